@@ -1,0 +1,429 @@
+/*
+ * CPU oracle for the batched dataflow-graph hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Only the tests, the smoke check and the benchmark's cpu-baseline leg may load
+ * this file.  It shares no code with the GPU path and the GPU path never calls it.
+ *
+ * What it computes.  Auto-batching changes *when* a cell is evaluated, never
+ * *what* is evaluated: lazy dataflow-graph construction plus batching of
+ * same-depth nodes is semantics preserving (paper section 2.2 "Dynamic
+ * Batching", section 4.1 goal G.1).  So the oracle is the plain definition:
+ * every input instance is evaluated on its own, node by node, by recursion over
+ * its structure, in double precision on the (exactly converted) fp32 inputs.
+ * No levels, no gathers, no arena, no blocking, no fusion.
+ *
+ * The paper prints no cell equations; it names the models (table 3: TreeLSTM,
+ * MV-RNN; listing 1: a recurrent cell applied along a list) and cites their
+ * source papers.  The cells below are the standard forms of those models:
+ *
+ *   binary TreeLSTM, gates (i, f_l, f_r, o, u), each with its own weight block:
+ *     leaf:      z = W_leaf x + b_leaf,  x = E[token],  children's h and c are the
+ *                shared constant zero state (section 7.2: the leaf state is a
+ *                constant tensor created once)
+ *     internal:  z = U [h_l ; h_r] + b   (the input transform only exists at
+ *                leaves: it is the hoisted, depth-0 part; appendix B.1)
+ *     i=s(z[0:H]) f_l=s(z[H:2H]) f_r=s(z[2H:3H]) o=s(z[3H:4H]) u=tanh(z[4H:5H])
+ *     c = i*u + f_l*c_l + f_r*c_r        h = o*tanh(c)       s(t)=1/(1+exp(-t))
+ *
+ *   MV-RNN (each node carries a vector and a matrix; left child (a,A), right (b,B)):
+ *     p = tanh(W [B a ; A b])     P = W_M [A ; B]     (section 7.2: the model
+ *     multiplies two intermediate activations); a leaf's (a,A) are table rows.
+ *
+ *   LSTM along a sequence (listing 1/2 structure, appendix B.3 "four gates"):
+ *     z = W_x x_t + W_h h_{t-1} + b, gates (i, f, o, u),
+ *     c_t = f*c_{t-1} + i*u,  h_t = o*tanh(c_t),  h_{-1} = c_{-1} = 0.
+ *
+ *   schedule: depth of a node = 0 if it consumes nothing produced inside the
+ *     graph, else 1 + max depth of its producers (footnote of section 4.1);
+ *     nodes run by increasing depth.  Order inside one depth is a convention
+ *     (ascending global node id): members of a batch are independent.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand
+ * computed 1- and 3-node trees, closed forms, library LSTM cells, brute force).
+ */
+#include <math.h>
+#include <pthread.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static double sigm(double t) { return 1.0 / (1.0 + exp(-t)); }
+
+/* y[r] = bias[r] + sum_k W[r*ld + k] * x[k],  r in [0,rows) */
+static void matvec(const float* W, int rows, int cols, int ld, const double* x,
+                   const float* bias, double* y) {
+  for (int r = 0; r < rows; ++r) {
+    double acc = bias ? (double)bias[r] : 0.0;
+    const float* w = W + (size_t)r * ld;
+    for (int k = 0; k < cols; ++k) acc += (double)w[k] * x[k];
+    y[r] = acc;
+  }
+}
+
+/* ------------------------------------------------------------------------- */
+/* TreeLSTM                                                                   */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+  int H, D;
+  const int32_t *left, *right, *token; /* global arrays, children tree-local */
+  const float *emb, *Wleaf, *bleaf, *U, *b;
+  double *h, *c; /* [N,H] */
+} tl_model;
+
+/* the cell of one node; its children (if any) must already be evaluated */
+static void treelstm_cell(const tl_model* m, int base, int j, double* z, double* in) {
+  const int H = m->H, D = m->D;
+  const int g = base + j;
+  const double *cl = NULL, *cr = NULL;
+  if (m->left[g] < 0) {
+    const float* x = m->emb + (size_t)m->token[g] * D;
+    for (int k = 0; k < D; ++k) in[k] = (double)x[k];
+    matvec(m->Wleaf, 5 * H, D, D, in, m->bleaf, z);
+  } else {
+    const int gl = base + m->left[g], gr = base + m->right[g];
+    for (int k = 0; k < H; ++k) in[k] = m->h[(size_t)gl * H + k];
+    for (int k = 0; k < H; ++k) in[H + k] = m->h[(size_t)gr * H + k];
+    matvec(m->U, 5 * H, 2 * H, 2 * H, in, m->b, z);
+    cl = m->c + (size_t)gl * H;
+    cr = m->c + (size_t)gr * H;
+  }
+  for (int q = 0; q < H; ++q) {
+    const double i = sigm(z[q]);
+    const double fl = sigm(z[H + q]);
+    const double fr = sigm(z[2 * H + q]);
+    const double o = sigm(z[3 * H + q]);
+    const double u = tanh(z[4 * H + q]);
+    const double c_l = cl ? cl[q] : 0.0;
+    const double c_r = cr ? cr[q] : 0.0;
+    const double c = i * u + fl * c_l + fr * c_r;
+    m->c[(size_t)g * H + q] = c;
+    m->h[(size_t)g * H + q] = o * tanh(c);
+  }
+}
+
+static void treelstm_rec(const tl_model* m, int base, int j, double* z, double* in) {
+  const int g = base + j;
+  if (m->left[g] >= 0) {
+    treelstm_rec(m, base, m->left[g], z, in);
+    treelstm_rec(m, base, m->right[g], z, in);
+  }
+  treelstm_cell(m, base, j, z, in);
+}
+
+/* root of a tree = the one node that is nobody's child; -1 if the tree is empty */
+static int find_root(const int32_t* left, const int32_t* right, int base, int n) {
+  if (n <= 0) return -1;
+  char* is_child = (char*)calloc((size_t)n, 1);
+  for (int j = 0; j < n; ++j) {
+    if (left[base + j] >= 0) is_child[left[base + j]] = 1;
+    if (right[base + j] >= 0) is_child[right[base + j]] = 1;
+  }
+  int root = -1;
+  for (int j = 0; j < n; ++j)
+    if (!is_child[j]) { root = j; break; }
+  free(is_child);
+  return root;
+}
+
+typedef struct {
+  const tl_model* m;
+  const int32_t* tree_off;
+  int n_trees, tid, nthreads;
+} tl_job;
+
+static void* treelstm_worker(void* p) {
+  const tl_job* jb = (const tl_job*)p;
+  const tl_model* m = jb->m;
+  const int zin = 5 * m->H, kin = (2 * m->H > m->D ? 2 * m->H : m->D);
+  double* z = (double*)malloc(sizeof(double) * (size_t)zin);
+  double* in = (double*)malloc(sizeof(double) * (size_t)kin);
+  for (int t = jb->tid; t < jb->n_trees; t += jb->nthreads) {
+    const int base = jb->tree_off[t], n = jb->tree_off[t + 1] - base;
+    const int root = find_root(m->left, m->right, base, n);
+    if (root >= 0) treelstm_rec(m, base, root, z, in);
+  }
+  free(z);
+  free(in);
+  return NULL;
+}
+
+/* Recursive per-tree evaluation.  nthreads > 1 only fans whole trees out over
+ * host threads (instances are independent); the per-tree code is the same. */
+int oracle_treelstm(int n_trees, const int32_t* tree_off, const int32_t* left,
+                    const int32_t* right, const int32_t* token, int H, int D,
+                    const float* emb, const float* Wleaf, const float* bleaf, const float* U,
+                    const float* b, double* h, double* c, int nthreads) {
+  tl_model m = {H, D, left, right, token, emb, Wleaf, bleaf, U, b, h, c};
+  if (nthreads < 1) nthreads = 1;
+  if (nthreads > 256) nthreads = 256;
+  tl_job jobs[256];
+  pthread_t th[256];
+  for (int i = 0; i < nthreads; ++i) {
+    jobs[i].m = &m; jobs[i].tree_off = tree_off; jobs[i].n_trees = n_trees;
+    jobs[i].tid = i; jobs[i].nthreads = nthreads;
+  }
+  if (nthreads == 1) { treelstm_worker(&jobs[0]); return 0; }
+  for (int i = 0; i < nthreads; ++i) pthread_create(&th[i], NULL, treelstm_worker, &jobs[i]);
+  for (int i = 0; i < nthreads; ++i) pthread_join(th[i], NULL);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* schedule oracle: depth by memoised recursion, then (depth, id) order       */
+/* ------------------------------------------------------------------------- */
+static int depth_rec(const int32_t* left, const int32_t* right, int base, int j, int32_t* depth) {
+  const int g = base + j;
+  if (depth[g] >= 0) return depth[g];
+  int d = 0;
+  if (left[g] >= 0) {
+    const int dl = depth_rec(left, right, base, left[g], depth);
+    const int dr = depth_rec(left, right, base, right[g], depth);
+    d = 1 + (dl > dr ? dl : dr);
+  }
+  depth[g] = d;
+  return d;
+}
+
+/* depth[N] out; returns the number of levels (max depth + 1), 0 if N == 0 */
+int oracle_tree_depths(int n_trees, const int32_t* tree_off, const int32_t* left,
+                       const int32_t* right, int32_t* depth) {
+  const int N = tree_off[n_trees];
+  int maxd = -1;
+  for (int g = 0; g < N; ++g) depth[g] = -1;
+  for (int t = 0; t < n_trees; ++t) {
+    const int base = tree_off[t], n = tree_off[t + 1] - base;
+    for (int j = 0; j < n; ++j) {
+      const int d = depth_rec(left, right, base, j, depth);
+      if (d > maxd) maxd = d;
+    }
+  }
+  return maxd + 1;
+}
+
+/* level_off[n_levels+1], level_nodes[N]: nodes by increasing depth, ascending id inside one.
+ * lrow/rrow[N] (optional): global child rows of the node at each list position, -1 at leaves */
+int oracle_tree_schedule(int n_trees, const int32_t* tree_off, const int32_t* left,
+                         const int32_t* right, int32_t* level_off, int32_t* level_nodes,
+                         int32_t* lrow, int32_t* rrow) {
+  const int N = tree_off[n_trees];
+  int32_t* depth = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+  int32_t* base_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N > 0 ? N : 1));
+  const int n_levels = oracle_tree_depths(n_trees, tree_off, left, right, depth);
+  for (int t = 0; t < n_trees; ++t)
+    for (int g = tree_off[t]; g < tree_off[t + 1]; ++g) base_of[g] = tree_off[t];
+  int pos = 0;
+  level_off[0] = 0;
+  for (int d = 0; d < n_levels; ++d) {
+    for (int g = 0; g < N; ++g)
+      if (depth[g] == d) {
+        level_nodes[pos] = g;
+        if (lrow) lrow[pos] = left[g] >= 0 ? base_of[g] + left[g] : -1;
+        if (rrow) rrow[pos] = right[g] >= 0 ? base_of[g] + right[g] : -1;
+        ++pos;
+      }
+    level_off[d + 1] = pos;
+  }
+  free(depth);
+  free(base_of);
+  return n_levels;
+}
+
+/* Same cell, but nodes visited in schedule order instead of by recursion
+ * (section 4.1, observation O.1: program order and depth order are both valid
+ * dependency orders, so both must give the same values). */
+int oracle_treelstm_topo(int n_trees, const int32_t* tree_off, const int32_t* left,
+                         const int32_t* right, const int32_t* token, int H, int D,
+                         const float* emb, const float* Wleaf, const float* bleaf,
+                         const float* U, const float* b, double* h, double* c) {
+  tl_model m = {H, D, left, right, token, emb, Wleaf, bleaf, U, b, h, c};
+  const int N = tree_off[n_trees];
+  if (N == 0) return 0;
+  int32_t* level_off = (int32_t*)malloc(sizeof(int32_t) * (size_t)(N + 1));
+  int32_t* level_nodes = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  int32_t* base_of = (int32_t*)malloc(sizeof(int32_t) * (size_t)N);
+  oracle_tree_schedule(n_trees, tree_off, left, right, level_off, level_nodes, NULL, NULL);
+  for (int t = 0; t < n_trees; ++t)
+    for (int g = tree_off[t]; g < tree_off[t + 1]; ++g) base_of[g] = tree_off[t];
+  const int zin = 5 * H, kin = (2 * H > D ? 2 * H : D);
+  double* z = (double*)malloc(sizeof(double) * (size_t)zin);
+  double* in = (double*)malloc(sizeof(double) * (size_t)kin);
+  for (int p = 0; p < N; ++p) {
+    const int g = level_nodes[p];
+    treelstm_cell(&m, base_of[g], g - base_of[g], z, in);
+  }
+  free(z); free(in); free(level_off); free(level_nodes); free(base_of);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* MV-RNN                                                                     */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+  int d;
+  const int32_t *left, *right, *token;
+  const float *vec_tab, *mat_tab, *W, *WM;
+  double *vec, *mat; /* [N,d], [N,d,d] */
+} mv_model;
+
+static void mvrnn_rec(const mv_model* m, int base, int j, double* v) {
+  const int d = m->d;
+  const int g = base + j;
+  double* p = m->vec + (size_t)g * d;
+  double* P = m->mat + (size_t)g * d * d;
+  if (m->left[g] < 0) {
+    const float* a = m->vec_tab + (size_t)m->token[g] * d;
+    const float* A = m->mat_tab + (size_t)m->token[g] * d * d;
+    for (int r = 0; r < d; ++r) p[r] = (double)a[r];
+    for (int e = 0; e < d * d; ++e) P[e] = (double)A[e];
+    return;
+  }
+  mvrnn_rec(m, base, m->left[g], v);
+  mvrnn_rec(m, base, m->right[g], v);
+  const int gl = base + m->left[g], gr = base + m->right[g];
+  const double *a = m->vec + (size_t)gl * d, *A = m->mat + (size_t)gl * d * d;
+  const double *b = m->vec + (size_t)gr * d, *B = m->mat + (size_t)gr * d * d;
+  /* v = [B a ; A b] */
+  for (int r = 0; r < d; ++r) {
+    double s0 = 0.0, s1 = 0.0;
+    for (int k = 0; k < d; ++k) s0 += B[r * d + k] * a[k];
+    for (int k = 0; k < d; ++k) s1 += A[r * d + k] * b[k];
+    v[r] = s0;
+    v[d + r] = s1;
+  }
+  /* p = tanh(W v) */
+  for (int r = 0; r < d; ++r) {
+    double s = 0.0;
+    for (int k = 0; k < 2 * d; ++k) s += (double)m->W[(size_t)r * 2 * d + k] * v[k];
+    p[r] = tanh(s);
+  }
+  /* P = W_M [A ; B]  ([d x 2d] times the vertical stack [2d x d]) */
+  for (int r = 0; r < d; ++r)
+    for (int q = 0; q < d; ++q) {
+      double s = 0.0;
+      for (int k = 0; k < d; ++k) s += (double)m->WM[(size_t)r * 2 * d + k] * A[k * d + q];
+      for (int k = 0; k < d; ++k) s += (double)m->WM[(size_t)r * 2 * d + d + k] * B[k * d + q];
+      P[r * d + q] = s;
+    }
+}
+
+typedef struct {
+  const mv_model* m;
+  const int32_t* tree_off;
+  int n_trees, tid, nthreads;
+} mv_job;
+
+static void* mvrnn_worker(void* p) {
+  const mv_job* jb = (const mv_job*)p;
+  double* v = (double*)malloc(sizeof(double) * 2 * (size_t)jb->m->d);
+  for (int t = jb->tid; t < jb->n_trees; t += jb->nthreads) {
+    const int base = jb->tree_off[t], n = jb->tree_off[t + 1] - base;
+    const int root = find_root(jb->m->left, jb->m->right, base, n);
+    if (root >= 0) mvrnn_rec(jb->m, base, root, v);
+  }
+  free(v);
+  return NULL;
+}
+
+int oracle_mvrnn(int n_trees, const int32_t* tree_off, const int32_t* left, const int32_t* right,
+                 const int32_t* token, int d, const float* vec_tab, const float* mat_tab,
+                 const float* W, const float* WM, double* vec, double* mat, int nthreads) {
+  mv_model m = {d, left, right, token, vec_tab, mat_tab, W, WM, vec, mat};
+  if (nthreads < 1) nthreads = 1;
+  if (nthreads > 256) nthreads = 256;
+  mv_job jobs[256];
+  pthread_t th[256];
+  for (int i = 0; i < nthreads; ++i) {
+    jobs[i].m = &m; jobs[i].tree_off = tree_off; jobs[i].n_trees = n_trees;
+    jobs[i].tid = i; jobs[i].nthreads = nthreads;
+  }
+  if (nthreads == 1) { mvrnn_worker(&jobs[0]); return 0; }
+  for (int i = 0; i < nthreads; ++i) pthread_create(&th[i], NULL, mvrnn_worker, &jobs[i]);
+  for (int i = 0; i < nthreads; ++i) pthread_join(th[i], NULL);
+  return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* variable-length LSTM: every sequence on its own                            */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+  int n_seq, H, D;
+  const int32_t* len;
+  const float *x, *Wx, *Wh, *b;
+  double *h, *c;
+  int tid, nthreads;
+} ls_job;
+
+static void* lstm_worker(void* p) {
+  const ls_job* jb = (const ls_job*)p;
+  const int H = jb->H, D = jb->D;
+  double* zx = (double*)malloc(sizeof(double) * 4 * (size_t)H);
+  double* zh = (double*)malloc(sizeof(double) * 4 * (size_t)H);
+  double* xin = (double*)malloc(sizeof(double) * (size_t)D);
+  double* hprev = (double*)malloc(sizeof(double) * (size_t)H);
+  double* cprev = (double*)malloc(sizeof(double) * (size_t)H);
+  size_t row0 = 0;
+  for (int s = 0; s < jb->n_seq; ++s) {
+    const int T = jb->len[s];
+    if (s % jb->nthreads == jb->tid) {
+      for (int q = 0; q < H; ++q) hprev[q] = cprev[q] = 0.0;
+      for (int t = 0; t < T; ++t) {
+        const size_t row = row0 + (size_t)t;
+        for (int k = 0; k < D; ++k) xin[k] = (double)jb->x[row * D + k];
+        matvec(jb->Wx, 4 * H, D, D, xin, jb->b, zx);
+        matvec(jb->Wh, 4 * H, H, H, hprev, NULL, zh);
+        for (int q = 0; q < H; ++q) {
+          const double i = sigm(zx[q] + zh[q]);
+          const double f = sigm(zx[H + q] + zh[H + q]);
+          const double o = sigm(zx[2 * H + q] + zh[2 * H + q]);
+          const double u = tanh(zx[3 * H + q] + zh[3 * H + q]);
+          const double c = f * cprev[q] + i * u;
+          jb->c[row * H + q] = c;
+          jb->h[row * H + q] = o * tanh(c);
+        }
+        for (int q = 0; q < H; ++q) {
+          hprev[q] = jb->h[row * H + q];
+          cprev[q] = jb->c[row * H + q];
+        }
+      }
+    }
+    row0 += (size_t)T;
+  }
+  free(zx); free(zh); free(xin); free(hprev); free(cprev);
+  return NULL;
+}
+
+int oracle_varlen_lstm(int n_seq, const int32_t* len, int H, int D, const float* x,
+                       const float* Wx, const float* Wh, const float* b, double* h, double* c,
+                       int nthreads) {
+  if (nthreads < 1) nthreads = 1;
+  if (nthreads > 256) nthreads = 256;
+  ls_job jobs[256];
+  pthread_t th[256];
+  for (int i = 0; i < nthreads; ++i) {
+    ls_job j = {n_seq, H, D, len, x, Wx, Wh, b, h, c, i, nthreads};
+    jobs[i] = j;
+  }
+  if (nthreads == 1) { lstm_worker(&jobs[0]); return 0; }
+  for (int i = 0; i < nthreads; ++i) pthread_create(&th[i], NULL, lstm_worker, &jobs[i]);
+  for (int i = 0; i < nthreads; ++i) pthread_join(th[i], NULL);
+  return 0;
+}
+
+/* sequence schedule: level t holds the rows (seq_off[s] + t) of all s with len[s] > t,
+ * ascending s.  Returns the number of levels (max len). */
+int oracle_seq_schedule(int n_seq, const int32_t* len, int32_t* level_off, int32_t* level_rows) {
+  int tmax = 0;
+  for (int s = 0; s < n_seq; ++s)
+    if (len[s] > tmax) tmax = len[s];
+  int pos = 0;
+  level_off[0] = 0;
+  for (int t = 0; t < tmax; ++t) {
+    int row0 = 0;
+    for (int s = 0; s < n_seq; ++s) {
+      if (len[s] > t) level_rows[pos++] = row0 + t;
+      row0 += len[s];
+    }
+    level_off[t + 1] = pos;
+  }
+  return tmax;
+}

@@ -1,0 +1,155 @@
+/*
+ * acrobat.h - C ABI of the MI355X batched dataflow-graph executor.
+ *
+ * The library runs the data-parallel hot path of compile-time-assisted auto-batching
+ * (paper sections 2.2, 4.1 and 5): a mini-batch of input structures (binary trees or
+ * variable-length sequences) is turned into a depth schedule (one batch per depth) and
+ * every batch is executed by one gather-fused cell kernel that reads its operands by
+ * index from the state arena, runs the dense cell contraction, applies the gate
+ * non-linearities and writes the new states back.
+ *
+ * General rules
+ *  - All sizes and indices are int32.  All floating point data is fp32, row-major.
+ *  - "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory
+ *    on the context's GPU.  The caller owns every buffer passed in; the library keeps
+ *    no caller pointer after a call returns.
+ *  - Host structure arrays are consumed before the call returns.  Device work is
+ *    enqueued on the given HIP stream (a hipStream_t passed as void*, NULL = the null
+ *    stream) and the call returns without synchronising, unless profiling is on.
+ *  - Every function returns ACROBAT_OK (0) or a negative code; nothing is launched
+ *    when validation fails.  acrobat_last_error() gives a human readable reason.
+ *  - No C++ exception crosses this boundary.
+ *  - A context must not be used from two threads at once.
+ */
+#ifndef ACROBAT_H
+#define ACROBAT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ACROBAT_OK 0
+#define ACROBAT_EINVAL (-1)  /* null pointer, negative size, unsupported shape            */
+#define ACROBAT_ESTRUCT (-2) /* malformed structure: bad child index, one child only, two  */
+                             /* parents, cycle, not exactly one root, token out of range   */
+#define ACROBAT_ENOMEM (-3)  /* host or device allocation failed                           */
+#define ACROBAT_EHIP (-4)    /* a HIP runtime call failed                                  */
+
+typedef struct acrobat_ctx acrobat_ctx;
+
+/* Create a context bound to HIP device `device`.  Owns the index staging buffers and
+ * scratch memory, which grow on demand and are freed by acrobat_destroy. */
+int acrobat_create(acrobat_ctx** out, int device);
+void acrobat_destroy(acrobat_ctx* ctx);
+/* Message of the last failing call on this context ("" if none); valid until the next call. */
+const char* acrobat_last_error(const acrobat_ctx* ctx);
+/* Static description of a return code. */
+const char* acrobat_strerror(int code);
+
+/* A mini-batch of binary trees (host memory, read-only).  Nodes of tree t occupy the global
+ * ids [tree_off[t], tree_off[t+1]); `left`/`right` hold tree-LOCAL child ids, both -1 for a
+ * leaf.  Any numbering of the nodes inside a tree is accepted.  `token` is the id of the
+ * table row a leaf reads (ignored for internal nodes). */
+typedef struct {
+  int32_t n_trees;
+  const int32_t* tree_off; /* [n_trees + 1], tree_off[0] == 0, non-decreasing */
+  const int32_t* left;     /* [N] */
+  const int32_t* right;    /* [N] */
+  const int32_t* token;    /* [N] */
+} acrobat_trees;
+
+/* ---- host level scheduler (no GPU needed) --------------------------------------------
+ * Depth schedule of section 4.1 (footnote: depth = 0 for a node that consumes nothing
+ * produced in the graph, else 1 + the largest producer depth; batches run by increasing
+ * depth).  One schedule node is one whole cell (grain-size coarsening, appendix B.2), all
+ * leaves sit in level 0 (hoisted input transforms, appendix B.1) and the two children of a
+ * node are concurrent.  Inside a level nodes are listed by ascending global id.
+ *
+ * Outputs are caller-allocated host arrays: level_off[N + 1] (only n_levels + 1 entries are
+ * written), level_nodes[N], and optionally lrow[N] / rrow[N] = global ids of the children of
+ * the node at the same list position (-1 at leaves); either may be NULL.
+ * vocab >= 0 additionally checks 0 <= token < vocab at every leaf; vocab < 0 skips that. */
+int acrobat_schedule_trees(const acrobat_trees* trees, int32_t vocab, int32_t* n_levels,
+                           int32_t* level_off, int32_t* level_nodes, int32_t* lrow, int32_t* rrow);
+
+/* Sequence schedule (listing 2: step t of every sequence has depth t).  Level t lists the
+ * rows seq_off[s] + t of all sequences with len[s] > t by ascending s, seq_off being the
+ * exclusive prefix sum of len.  level_off[max len + 1], level_rows[sum len] caller-allocated. */
+int acrobat_schedule_seqs(int32_t n_seq, const int32_t* len, int32_t* n_levels,
+                          int32_t* level_off, int32_t* level_rows);
+
+/* ---- forward calls --------------------------------------------------------------------
+ * Binary TreeLSTM (model of table 3).  Gate order of the 5H weight rows: (i, f_l, f_r, o, u).
+ *   leaf:      z = W_leaf E[token] + b_leaf ; child states are the shared zero state
+ *   internal:  z = U [h_l ; h_r] + b        ; U columns 0..H-1 act on h_l, H..2H-1 on h_r
+ *   c = s(z_i) tanh(z_u) + s(z_fl) c_l + s(z_fr) c_r ;  h = s(z_o) tanh(c)
+ * Level 0 is one batched kernel over all leaves that gathers embedding rows by token id
+ * (hoisting + gather fusion, section 5.2); each later level is one kernel that gathers the
+ * children's h and c rows by index, contracts [n_level x 2H] with U^T (all five gates in one
+ * pass: horizontal fusion, appendix B.3) and applies the gates (vertical fusion).
+ * Requires H, D multiples of 32.  d_h and d_c receive one row per node, row = global node id.
+ * Device pointers: d_emb [V,D], d_Wleaf [5H,D], d_bleaf [5H] or NULL (= 0), d_U [5H,2H],
+ * d_b [5H] or NULL, d_h / d_c [N,H] (written). */
+int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D,
+                             int32_t V, const float* d_emb, const float* d_Wleaf,
+                             const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
+                             float* d_c, void* hip_stream);
+
+/* MV-RNN (model of table 3; section 7.2: the cell multiplies two activations).  Every node
+ * carries a vector and a d x d matrix; with left child (a, A) and right child (b, B):
+ *   p = tanh(W [B a ; A b])      P = W_M [A ; B]      W, W_M: [d, 2d]
+ * A leaf's (a, A) are rows `token` of the tables and are read in place by the parent's kernel
+ * (no copy of leaf embeddings, section 7.4).  d_vec [N,d] / d_mat [N,d,d] receive the states of
+ * internal nodes at row = global node id; leaf rows are written (copied from the tables) only
+ * if copy_leaves != 0.  Requires d == 64.  Tables: d_vec_tab [V,d], d_mat_tab [V,d,d]. */
+int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t d, int32_t V,
+                          const float* d_vec_tab, const float* d_mat_tab, const float* d_W,
+                          const float* d_WM, float* d_vec, float* d_mat, int32_t copy_leaves,
+                          void* hip_stream);
+
+/* Variable-length LSTM (recurrence of listing 1 with the four-gate cell of appendix B.3).
+ * Gate order of the 4H rows: (i, f, o, u);  z = W_x x_t + W_h h_{t-1} + b ;
+ * c_t = s(z_f) c_{t-1} + s(z_i) tanh(z_u) ; h_t = s(z_o) tanh(c_t) ; h_{-1} = c_{-1} = 0.
+ * len[n_seq] (host, each >= 0).  Rows are packed sequence-major: row(s,t) = seq_off[s] + t.
+ * The input transform of all steps of all sequences runs first as one dense batch (hoisted,
+ * appendix B.1); then one kernel per time step over the still-active sequences.
+ * Requires H, D multiples of 32.  d_x [sum len, D], d_Wx [4H,D], d_Wh [4H,H], d_b [4H] or
+ * NULL, d_h / d_c [sum len, H] (written). */
+int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, int32_t H,
+                                int32_t D, const float* d_x, const float* d_Wx,
+                                const float* d_Wh, const float* d_b, float* d_h, float* d_c,
+                                void* hip_stream);
+
+/* ---- introspection --------------------------------------------------------------------
+ * Schedule built by the last forward call on this context (host arrays owned by the context,
+ * valid until the next forward call): level_off[n_levels + 1], level_nodes[level_off[n_levels]]. */
+int acrobat_last_schedule(const acrobat_ctx* ctx, int32_t* n_levels, const int32_t** level_off,
+                          const int32_t** level_nodes);
+
+/* Per-launch timing.  With profiling on, a forward call brackets every kernel launch with HIP
+ * events on the caller's stream and synchronises the stream before returning. */
+typedef struct {
+  int32_t kind;  /* ACROBAT_K_* */
+  int32_t level; /* depth of the batch */
+  int32_t n;     /* nodes (rows) in the batch */
+  float ms;      /* device time of the launch */
+} acrobat_launch_record;
+
+#define ACROBAT_K_TREE_LEAF 1
+#define ACROBAT_K_TREE_INTERNAL 2
+#define ACROBAT_K_MVRNN_LEVEL 3
+#define ACROBAT_K_MVRNN_LEAFCOPY 4
+#define ACROBAT_K_LSTM_INPUT 5
+#define ACROBAT_K_LSTM_STEP 6
+
+int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
+/* Records of the last forward call (context-owned, valid until the next forward call). */
+int acrobat_last_profile(const acrobat_ctx* ctx, int32_t* n_records,
+                         const acrobat_launch_record** records);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACROBAT_H */

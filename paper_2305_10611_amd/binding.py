@@ -1,0 +1,180 @@
+"""Thin ctypes binding of libacrobat.so: same names as include/acrobat.h, argument
+marshalling only.  Every step of the hot path runs inside the library; there is no Python
+or CPU fallback - if the library is missing, importing this module raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # noqa: F401  (first: the library must bind to the HIP runtime PyTorch ships, one runtime per process)
+
+from . import build as _build
+
+OK, EINVAL, ESTRUCT, ENOMEM, EHIP = 0, -1, -2, -3, -4
+K_TREE_LEAF, K_TREE_INTERNAL, K_MVRNN_LEVEL, K_MVRNN_LEAFCOPY, K_LSTM_INPUT, K_LSTM_STEP = 1, 2, 3, 4, 5, 6
+
+
+class AcrobatError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"acrobat error {code}: {msg}")
+        self.code = code
+
+
+class acrobat_trees(C.Structure):
+    _fields_ = [("n_trees", C.c_int32), ("tree_off", C.c_void_p), ("left", C.c_void_p),
+                ("right", C.c_void_p), ("token", C.c_void_p)]
+
+
+class acrobat_launch_record(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("level", C.c_int32), ("n", C.c_int32), ("ms", C.c_float)]
+
+
+EXPORTS = (
+    "acrobat_create", "acrobat_destroy", "acrobat_last_error", "acrobat_strerror",
+    "acrobat_schedule_trees", "acrobat_schedule_seqs", "acrobat_treelstm_forward",
+    "acrobat_mvrnn_forward", "acrobat_varlen_lstm_forward", "acrobat_last_schedule",
+    "acrobat_set_profiling", "acrobat_last_profile",
+)
+
+
+def _load():
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = C.CDLL(_build.LIB)
+    vp, i32 = C.c_void_p, C.c_int32
+    lib.acrobat_create.argtypes = [C.POINTER(vp), C.c_int]
+    lib.acrobat_destroy.argtypes = [vp]
+    lib.acrobat_destroy.restype = None
+    lib.acrobat_last_error.argtypes = [vp]
+    lib.acrobat_last_error.restype = C.c_char_p
+    lib.acrobat_strerror.argtypes = [C.c_int]
+    lib.acrobat_strerror.restype = C.c_char_p
+    lib.acrobat_schedule_trees.argtypes = [C.POINTER(acrobat_trees), i32, C.POINTER(i32), vp, vp, vp, vp]
+    lib.acrobat_schedule_seqs.argtypes = [i32, vp, C.POINTER(i32), vp, vp]
+    lib.acrobat_treelstm_forward.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32, i32] + [vp] * 8
+    lib.acrobat_mvrnn_forward.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32] + [vp] * 6 + [i32, vp]
+    lib.acrobat_varlen_lstm_forward.argtypes = [vp, i32, vp, i32, i32] + [vp] * 7
+    lib.acrobat_last_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
+    lib.acrobat_set_profiling.argtypes = [vp, i32]
+    lib.acrobat_last_profile.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(acrobat_launch_record))]
+    return lib
+
+
+lib = _load()
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _hp(a):  # host pointer of a numpy array (None -> NULL)
+    return None if a is None else a.ctypes.data
+
+
+def _dp(t):  # device pointer of a torch tensor (None -> NULL)
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous() and t.dtype.is_floating_point and t.element_size() == 4
+    return t.data_ptr()
+
+
+def _trees_struct(trees: dict):
+    keep = [_i32(trees["tree_off"]), _i32(trees["left"]), _i32(trees["right"]),
+            None if trees.get("token") is None else _i32(trees["token"])]
+    st = acrobat_trees(int(trees["n_trees"]), *(_hp(a) for a in keep))
+    return st, keep
+
+
+def acrobat_strerror(code: int) -> str:
+    return lib.acrobat_strerror(code).decode()
+
+
+def acrobat_schedule_trees(trees: dict, vocab: int = -1):
+    """-> (rc, level_off[n_levels+1], level_nodes[N], lrow[N], rrow[N])"""
+    st, keep = _trees_struct(trees)
+    N = int(keep[0][-1]) if keep[0].size else 0
+    level_off = np.zeros(max(N, 0) + 1, np.int32)
+    level_nodes, lrow, rrow = (np.empty(max(N, 0), np.int32) for _ in range(3))
+    n_levels = C.c_int32(0)
+    rc = lib.acrobat_schedule_trees(C.byref(st), vocab, C.byref(n_levels), _hp(level_off), _hp(level_nodes),
+                                    _hp(lrow), _hp(rrow))
+    if rc != OK:
+        return rc, None, None, None, None
+    return rc, level_off[: n_levels.value + 1].copy(), level_nodes, lrow, rrow
+
+
+def acrobat_schedule_seqs(lens):
+    """-> (rc, level_off[n_levels+1], level_rows[sum len])"""
+    lens = _i32(lens)
+    tmax = int(lens.max()) if lens.size and lens.max() > 0 else 0
+    total = int(np.maximum(lens, 0).sum())
+    level_off = np.zeros(tmax + 1, np.int32)
+    level_rows = np.empty(total, np.int32)
+    n_levels = C.c_int32(0)
+    rc = lib.acrobat_schedule_seqs(int(lens.size), _hp(lens), C.byref(n_levels), _hp(level_off), _hp(level_rows))
+    if rc != OK:
+        return rc, None, None
+    return rc, level_off, level_rows
+
+
+class Context:
+    """Owns one acrobat_ctx.  Methods mirror the C entry points and return the C return code."""
+
+    def __init__(self, device: int = 0):
+        self._h = C.c_void_p()
+        rc = lib.acrobat_create(C.byref(self._h), device)
+        if rc != OK:
+            raise AcrobatError(rc, acrobat_strerror(rc) + " (acrobat_create: is a GPU present?)")
+
+    def close(self):
+        if self._h:
+            lib.acrobat_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def acrobat_last_error(self) -> str:
+        return lib.acrobat_last_error(self._h).decode()
+
+    def check(self, rc):
+        if rc != OK:
+            raise AcrobatError(rc, self.acrobat_last_error() or acrobat_strerror(rc))
+
+    def acrobat_treelstm_forward(self, trees: dict, H, D, V, emb, W_leaf, b_leaf, U, b, h, c, stream=0) -> int:
+        st, keep = _trees_struct(trees)
+        return lib.acrobat_treelstm_forward(self._h, C.byref(st), H, D, V, _dp(emb), _dp(W_leaf), _dp(b_leaf),
+                                            _dp(U), _dp(b), _dp(h), _dp(c), stream)
+
+    def acrobat_mvrnn_forward(self, trees: dict, d, V, vec_tab, mat_tab, W, WM, vec, mat, copy_leaves=0,
+                              stream=0) -> int:
+        st, keep = _trees_struct(trees)
+        return lib.acrobat_mvrnn_forward(self._h, C.byref(st), d, V, _dp(vec_tab), _dp(mat_tab), _dp(W), _dp(WM),
+                                         _dp(vec), _dp(mat), int(copy_leaves), stream)
+
+    def acrobat_varlen_lstm_forward(self, lens, H, D, x, Wx, Wh, b, h, c, stream=0) -> int:
+        lens = _i32(lens)
+        return lib.acrobat_varlen_lstm_forward(self._h, int(lens.size), _hp(lens), H, D, _dp(x), _dp(Wx), _dp(Wh),
+                                               _dp(b), _dp(h), _dp(c), stream)
+
+    def acrobat_last_schedule(self):
+        n_levels, po, pn = C.c_int32(0), C.c_void_p(), C.c_void_p()
+        self.check(lib.acrobat_last_schedule(self._h, C.byref(n_levels), C.byref(po), C.byref(pn)))
+        L = n_levels.value
+        level_off = np.ctypeslib.as_array(C.cast(po, C.POINTER(C.c_int32)), shape=(L + 1,)).copy()
+        n = int(level_off[-1])
+        level_nodes = (np.ctypeslib.as_array(C.cast(pn, C.POINTER(C.c_int32)), shape=(n,)).copy()
+                       if n else np.zeros(0, np.int32))
+        return level_off, level_nodes
+
+    def acrobat_set_profiling(self, enabled: bool) -> int:
+        return lib.acrobat_set_profiling(self._h, int(bool(enabled)))
+
+    def acrobat_last_profile(self):
+        n, p = C.c_int32(0), C.POINTER(acrobat_launch_record)()
+        self.check(lib.acrobat_last_profile(self._h, C.byref(n), C.byref(p)))
+        return [(p[i].kind, p[i].level, p[i].n, p[i].ms) for i in range(n.value)]

@@ -1,0 +1,462 @@
+// C ABI of the batched dataflow-graph executor: context, index upload, level launch loop.
+//
+// Runtime pieces of the paper that live here (appendix C "Other Details"): arena-style reuse
+// of the index/scratch buffers across calls, asynchronous execution on the caller's stream,
+// and one batched host-to-device transfer per forward call for all index lists.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "acrobat.h"
+#include "cell_kernels.h"
+#include "scheduler.h"
+
+using namespace acrobat;
+
+struct acrobat_ctx {
+  int device = 0;
+  std::string err;
+  // last schedule (host)
+  int32_t n_levels = 0;
+  std::vector<int32_t> level_off, level_nodes;
+  // index staging: pinned host buffer -> device buffer, one copy per forward call
+  int32_t* h_stage = nullptr;
+  int32_t* d_idx = nullptr;
+  size_t stage_cap = 0, idx_cap = 0;  // in int32 elements
+  hipEvent_t stage_done = nullptr;    // the last upload out of h_stage has finished
+  bool stage_pending = false;
+  // scratch for the hoisted LSTM input transform
+  float* d_scratch = nullptr;
+  size_t scratch_cap = 0;  // in floats
+  // profiling
+  bool profiling = false;
+  std::vector<acrobat_launch_record> records;
+  std::vector<hipEvent_t> events;  // pool, two per record
+};
+
+namespace {
+
+int fail(acrobat_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg;
+  return code;
+}
+
+int fail_hip(acrobat_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, e == hipErrorOutOfMemory ? ACROBAT_ENOMEM : ACROBAT_EHIP,
+              std::string(what) + ": " + hipGetErrorString(e));
+}
+
+#define HIP_TRY(ctx, expr)                                   \
+  do {                                                       \
+    hipError_t e_ = (expr);                                  \
+    if (e_ != hipSuccess) return fail_hip(ctx, e_, #expr);   \
+  } while (0)
+
+// Makes room for `n` int32 in the pinned staging buffer and the device index buffer and waits
+// until a previous upload no longer reads the staging buffer.
+int reserve_indices(acrobat_ctx* ctx, size_t n) {
+  if (ctx->stage_pending) {
+    HIP_TRY(ctx, hipEventSynchronize(ctx->stage_done));
+    ctx->stage_pending = false;
+  }
+  if (n > ctx->stage_cap) {
+    const size_t cap = n + n / 2 + 1024;
+    if (ctx->h_stage) HIP_TRY(ctx, hipHostFree(ctx->h_stage));
+    ctx->h_stage = nullptr;
+    ctx->stage_cap = 0;
+    HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_stage), cap * sizeof(int32_t), hipHostMallocDefault));
+    ctx->stage_cap = cap;
+  }
+  if (n > ctx->idx_cap) {
+    const size_t cap = n + n / 2 + 1024;
+    if (ctx->d_idx) HIP_TRY(ctx, hipFree(ctx->d_idx));  // waits for kernels still using it
+    ctx->d_idx = nullptr;
+    ctx->idx_cap = 0;
+    HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_idx), cap * sizeof(int32_t)));
+    ctx->idx_cap = cap;
+  }
+  return ACROBAT_OK;
+}
+
+int upload_indices(acrobat_ctx* ctx, size_t n, hipStream_t stream) {
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->d_idx, ctx->h_stage, n * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+  HIP_TRY(ctx, hipEventRecord(ctx->stage_done, stream));
+  ctx->stage_pending = true;
+  return ACROBAT_OK;
+}
+
+int reserve_scratch(acrobat_ctx* ctx, size_t n_floats) {
+  if (n_floats <= ctx->scratch_cap) return ACROBAT_OK;
+  if (ctx->d_scratch) HIP_TRY(ctx, hipFree(ctx->d_scratch));
+  ctx->d_scratch = nullptr;
+  ctx->scratch_cap = 0;
+  HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_scratch), n_floats * sizeof(float)));
+  ctx->scratch_cap = n_floats;
+  return ACROBAT_OK;
+}
+
+// Brackets a launch with events when profiling is on.
+struct LaunchTimer {
+  acrobat_ctx* ctx;
+  hipStream_t stream;
+  int begin(int32_t kind, int32_t level, int32_t n) {
+    if (!ctx->profiling) return ACROBAT_OK;
+    const size_t need = 2 * (ctx->records.size() + 1);
+    while (ctx->events.size() < need) {
+      hipEvent_t e;
+      HIP_TRY(ctx, hipEventCreate(&e));
+      ctx->events.push_back(e);
+    }
+    ctx->records.push_back({kind, level, n, 0.0f});
+    HIP_TRY(ctx, hipEventRecord(ctx->events[need - 2], stream));
+    return ACROBAT_OK;
+  }
+  int end() {
+    if (!ctx->profiling) return ACROBAT_OK;
+    HIP_TRY(ctx, hipEventRecord(ctx->events[2 * ctx->records.size() - 1], stream));
+    return ACROBAT_OK;
+  }
+  int finish() {
+    if (!ctx->profiling) return ACROBAT_OK;
+    HIP_TRY(ctx, hipStreamSynchronize(stream));
+    for (size_t i = 0; i < ctx->records.size(); ++i)
+      HIP_TRY(ctx, hipEventElapsedTime(&ctx->records[i].ms, ctx->events[2 * i], ctx->events[2 * i + 1]));
+    return ACROBAT_OK;
+  }
+};
+
+#define TRY(expr)                        \
+  do {                                   \
+    int rc_ = (expr);                    \
+    if (rc_ != ACROBAT_OK) return rc_;   \
+  } while (0)
+
+int begin_call(acrobat_ctx* ctx) {
+  if (!ctx) return ACROBAT_EINVAL;
+  ctx->err.clear();
+  ctx->records.clear();
+  HIP_TRY(ctx, hipSetDevice(ctx->device));
+  return ACROBAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* acrobat_strerror(int code) {
+  switch (code) {
+    case ACROBAT_OK: return "ok";
+    case ACROBAT_EINVAL: return "invalid argument";
+    case ACROBAT_ESTRUCT: return "malformed input structure";
+    case ACROBAT_ENOMEM: return "out of memory";
+    case ACROBAT_EHIP: return "HIP runtime error";
+    default: return "unknown error code";
+  }
+}
+
+int acrobat_create(acrobat_ctx** out, int device) {
+  if (!out) return ACROBAT_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return ACROBAT_EHIP;
+  if (hipSetDevice(device) != hipSuccess) return ACROBAT_EHIP;
+  acrobat_ctx* ctx = new (std::nothrow) acrobat_ctx();
+  if (!ctx) return ACROBAT_ENOMEM;
+  ctx->device = device;
+  if (hipEventCreateWithFlags(&ctx->stage_done, hipEventDisableTiming) != hipSuccess) {
+    delete ctx;
+    return ACROBAT_EHIP;
+  }
+  *out = ctx;
+  return ACROBAT_OK;
+}
+
+void acrobat_destroy(acrobat_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->device);
+  if (ctx->stage_pending) (void)hipEventSynchronize(ctx->stage_done);
+  if (ctx->d_idx) (void)hipFree(ctx->d_idx);
+  if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+  if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+  if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
+  for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
+  delete ctx;
+}
+
+const char* acrobat_last_error(const acrobat_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int acrobat_schedule_trees(const acrobat_trees* trees, int32_t vocab, int32_t* n_levels,
+                           int32_t* level_off, int32_t* level_nodes, int32_t* lrow, int32_t* rrow) {
+  if (!trees || !n_levels || !level_off) return ACROBAT_EINVAL;
+  try {
+    TreeSchedule s;
+    std::string err;
+    const int rc = schedule_trees(*trees, vocab, s, err);
+    if (rc != ACROBAT_OK) return rc;
+    if (s.n_nodes > 0 && !level_nodes) return ACROBAT_EINVAL;
+    *n_levels = s.n_levels;
+    std::memcpy(level_off, s.level_off.data(), s.level_off.size() * sizeof(int32_t));
+    const size_t bytes = (size_t)s.n_nodes * sizeof(int32_t);
+    if (s.n_nodes > 0) {
+      std::memcpy(level_nodes, s.level_nodes.data(), bytes);
+      if (lrow) std::memcpy(lrow, s.lrow.data(), bytes);
+      if (rrow) std::memcpy(rrow, s.rrow.data(), bytes);
+    }
+    return ACROBAT_OK;
+  } catch (const std::bad_alloc&) {
+    return ACROBAT_ENOMEM;
+  } catch (...) {
+    return ACROBAT_EINVAL;
+  }
+}
+
+int acrobat_schedule_seqs(int32_t n_seq, const int32_t* len, int32_t* n_levels, int32_t* level_off,
+                          int32_t* level_rows) {
+  if (!n_levels || !level_off) return ACROBAT_EINVAL;
+  try {
+    SeqSchedule s;
+    std::string err;
+    const int rc = schedule_seqs(n_seq, len, s, err);
+    if (rc != ACROBAT_OK) return rc;
+    if (s.n_rows > 0 && !level_rows) return ACROBAT_EINVAL;
+    *n_levels = s.n_levels;
+    std::memcpy(level_off, s.level_off.data(), s.level_off.size() * sizeof(int32_t));
+    if (s.n_rows > 0) std::memcpy(level_rows, s.level_rows.data(), (size_t)s.n_rows * sizeof(int32_t));
+    return ACROBAT_OK;
+  } catch (const std::bad_alloc&) {
+    return ACROBAT_ENOMEM;
+  } catch (...) {
+    return ACROBAT_EINVAL;
+  }
+}
+
+int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D,
+                             int32_t V, const float* d_emb, const float* d_Wleaf,
+                             const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
+                             float* d_c, void* hip_stream) {
+  try {
+    TRY(begin_call(ctx));
+    if (!trees) return fail(ctx, ACROBAT_EINVAL, "trees is null");
+    if (H <= 0 || D <= 0 || H % 32 || D % 32) return fail(ctx, ACROBAT_EINVAL, "H and D must be positive multiples of 32");
+    if (V <= 0) return fail(ctx, ACROBAT_EINVAL, "V must be positive");
+    TreeSchedule s;
+    {
+      const int rc = schedule_trees(*trees, V, s, ctx->err);
+      if (rc != ACROBAT_OK) return rc;
+    }
+    ctx->n_levels = s.n_levels;
+    ctx->level_off = s.level_off;
+    ctx->level_nodes = s.level_nodes;
+    const int32_t N = s.n_nodes;
+    if (N == 0) return ACROBAT_OK;
+    if (!d_emb || !d_Wleaf || !d_U || !d_h || !d_c) return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    // index lists by schedule position: out row | first operand row | second operand row
+    TRY(reserve_indices(ctx, 3 * (size_t)N));
+    int32_t* st = ctx->h_stage;
+    std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
+    const int32_t n_leaf = s.level_off[1];
+    for (int32_t p = 0; p < n_leaf; ++p) st[N + p] = trees->token[s.level_nodes[p]];  // leaves gather by token
+    std::memcpy(st + N + n_leaf, s.lrow.data() + n_leaf, (size_t)(N - n_leaf) * sizeof(int32_t));
+    std::memcpy(st + 2 * (size_t)N, s.rrow.data(), (size_t)N * sizeof(int32_t));
+    TRY(upload_indices(ctx, 3 * (size_t)N, stream));
+    const int32_t* d_out = ctx->d_idx;
+    const int32_t* d_ia = ctx->d_idx + N;
+    const int32_t* d_ib = ctx->d_idx + 2 * (size_t)N;
+
+    LaunchTimer timer{ctx, stream};
+    for (int32_t lv = 0; lv < s.n_levels; ++lv) {
+      const int32_t off = s.level_off[lv], n = s.level_off[lv + 1] - off;
+      CellLevelArgs a{};
+      a.n = n;
+      a.H = H;
+      a.out_rows = d_out + off;
+      a.h = d_h;
+      a.c = d_c;
+      if (lv == 0) {
+        a.nseg = 1; a.kseg = D;
+        a.src0 = d_emb; a.idx0 = d_ia + off; a.ld0 = D;
+        a.W = d_Wleaf; a.ldw = D; a.bias = d_bleaf;
+      } else {
+        a.nseg = 2; a.kseg = H;
+        a.src0 = d_h; a.idx0 = d_ia + off; a.ld0 = H;
+        a.src1 = d_h; a.idx1 = d_ib + off; a.ld1 = H;
+        a.W = d_U; a.ldw = 2 * H; a.bias = d_b;
+        a.cprev_src = d_c;
+      }
+      TRY(timer.begin(lv == 0 ? ACROBAT_K_TREE_LEAF : ACROBAT_K_TREE_INTERNAL, lv, n));
+      HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream));
+      TRY(timer.end());
+    }
+    return timer.finish();
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
+}
+
+int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t d, int32_t V,
+                          const float* d_vec_tab, const float* d_mat_tab, const float* d_W,
+                          const float* d_WM, float* d_vec, float* d_mat, int32_t copy_leaves,
+                          void* hip_stream) {
+  try {
+    TRY(begin_call(ctx));
+    if (!trees) return fail(ctx, ACROBAT_EINVAL, "trees is null");
+    if (d != 64) return fail(ctx, ACROBAT_EINVAL, "only d == 64 is supported");
+    if (V <= 0) return fail(ctx, ACROBAT_EINVAL, "V must be positive");
+    TreeSchedule s;
+    {
+      const int rc = schedule_trees(*trees, V, s, ctx->err);
+      if (rc != ACROBAT_OK) return rc;
+    }
+    ctx->n_levels = s.n_levels;
+    ctx->level_off = s.level_off;
+    ctx->level_nodes = s.level_nodes;
+    const int32_t N = s.n_nodes;
+    if (N == 0) return ACROBAT_OK;
+    if (!d_vec_tab || !d_mat_tab || !d_W || !d_WM || !d_vec || !d_mat)
+      return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    // child source codes: arena row of an internal child, -(token + 1) for a leaf child
+    TRY(reserve_indices(ctx, 3 * (size_t)N));
+    int32_t* st = ctx->h_stage;
+    std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
+    const int32_t n_leaf = s.level_off[1];
+    for (int32_t p = 0; p < n_leaf; ++p) {
+      st[N + p] = trees->token[s.level_nodes[p]];
+      st[2 * (size_t)N + p] = -1;
+    }
+    auto code = [&](int32_t g) { return trees->left[g] < 0 ? -(trees->token[g] + 1) : g; };
+    for (int32_t p = n_leaf; p < N; ++p) {
+      st[N + p] = code(s.lrow[p]);
+      st[2 * (size_t)N + p] = code(s.rrow[p]);
+    }
+    TRY(upload_indices(ctx, 3 * (size_t)N, stream));
+    const int32_t* d_out = ctx->d_idx;
+    const int32_t* d_ia = ctx->d_idx + N;
+    const int32_t* d_ib = ctx->d_idx + 2 * (size_t)N;
+
+    LaunchTimer timer{ctx, stream};
+    if (copy_leaves) {
+      TRY(timer.begin(ACROBAT_K_MVRNN_LEAFCOPY, 0, n_leaf));
+      HIP_TRY(ctx, launch_mvrnn_leaf_copy(n_leaf, d_out, d_ia, d_vec_tab, d_mat_tab, d_vec, d_mat, stream));
+      TRY(timer.end());
+    }
+    for (int32_t lv = 1; lv < s.n_levels; ++lv) {
+      const int32_t off = s.level_off[lv], n = s.level_off[lv + 1] - off;
+      MvrnnLevelArgs a{};
+      a.n = n;
+      a.out_rows = d_out + off;
+      a.lsrc = d_ia + off;
+      a.rsrc = d_ib + off;
+      a.vec_tab = d_vec_tab; a.mat_tab = d_mat_tab;
+      a.W = d_W; a.WM = d_WM;
+      a.vec = d_vec; a.mat = d_mat;
+      TRY(timer.begin(ACROBAT_K_MVRNN_LEVEL, lv, n));
+      HIP_TRY(ctx, launch_mvrnn_level(a, stream));
+      TRY(timer.end());
+    }
+    return timer.finish();
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
+}
+
+int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, int32_t H,
+                                int32_t D, const float* d_x, const float* d_Wx,
+                                const float* d_Wh, const float* d_b, float* d_h, float* d_c,
+                                void* hip_stream) {
+  try {
+    TRY(begin_call(ctx));
+    if (H <= 0 || D <= 0 || H % 32 || D % 32) return fail(ctx, ACROBAT_EINVAL, "H and D must be positive multiples of 32");
+    SeqSchedule s;
+    {
+      const int rc = schedule_seqs(n_seq, len, s, ctx->err);
+      if (rc != ACROBAT_OK) return rc;
+    }
+    ctx->n_levels = s.n_levels;
+    ctx->level_off = s.level_off;
+    ctx->level_nodes = s.level_rows;
+    const int32_t R = (int32_t)s.n_rows;
+    if (R == 0) return ACROBAT_OK;
+    if (!d_x || !d_Wx || !d_Wh || !d_h || !d_c) return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    // by schedule position: row written | row of the previous step (unused at t = 0)
+    TRY(reserve_indices(ctx, 2 * (size_t)R));
+    int32_t* st = ctx->h_stage;
+    std::memcpy(st, s.level_rows.data(), (size_t)R * sizeof(int32_t));
+    for (int32_t p = 0; p < R; ++p) st[R + p] = s.level_rows[p] - 1;
+    for (int32_t p = 0; p < s.level_off[1]; ++p) st[R + p] = s.level_rows[p];  // keep in range
+    TRY(reserve_scratch(ctx, (size_t)R * 4 * (size_t)H));
+    TRY(upload_indices(ctx, 2 * (size_t)R, stream));
+    const int32_t* d_out = ctx->d_idx;
+    const int32_t* d_prev = ctx->d_idx + R;
+
+    LaunchTimer timer{ctx, stream};
+    {  // hoisted input transform of every step of every sequence: one dense batch
+      CellLevelArgs a{};
+      a.n = R; a.H = H; a.nseg = 1; a.kseg = D;
+      a.src0 = d_x; a.ld0 = D;
+      a.W = d_Wx; a.ldw = D; a.bias = d_b;
+      a.zout = ctx->d_scratch;
+      TRY(timer.begin(ACROBAT_K_LSTM_INPUT, 0, R));
+      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z, a, stream));
+      TRY(timer.end());
+    }
+    for (int32_t t = 0; t < s.n_levels; ++t) {
+      const int32_t off = s.level_off[t], n = s.level_off[t + 1] - off;
+      CellLevelArgs a{};
+      a.n = n; a.H = H;
+      a.out_rows = d_out + off;
+      a.h = d_h; a.c = d_c;
+      a.zadd = ctx->d_scratch;
+      a.W = d_Wh; a.ldw = H;
+      if (t > 0) {
+        a.nseg = 1; a.kseg = H;
+        a.src0 = d_h; a.idx0 = d_prev + off; a.ld0 = H;
+        a.cprev_src = d_c;
+      }
+      TRY(timer.begin(ACROBAT_K_LSTM_STEP, t, n));
+      HIP_TRY(ctx, launch_cell_level(EPI_LSTM_STEP, a, stream));
+      TRY(timer.end());
+    }
+    return timer.finish();
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
+}
+
+int acrobat_last_schedule(const acrobat_ctx* ctx, int32_t* n_levels, const int32_t** level_off,
+                          const int32_t** level_nodes) {
+  if (!ctx || !n_levels || !level_off || !level_nodes) return ACROBAT_EINVAL;
+  *n_levels = ctx->n_levels;
+  *level_off = ctx->level_off.data();
+  *level_nodes = ctx->level_nodes.data();
+  return ACROBAT_OK;
+}
+
+int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled) {
+  if (!ctx) return ACROBAT_EINVAL;
+  ctx->profiling = enabled != 0;
+  return ACROBAT_OK;
+}
+
+int acrobat_last_profile(const acrobat_ctx* ctx, int32_t* n_records, const acrobat_launch_record** records) {
+  if (!ctx || !n_records || !records) return ACROBAT_EINVAL;
+  *n_records = (int32_t)ctx->records.size();
+  *records = ctx->records.data();
+  return ACROBAT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Launch interface of the gather-fused cell kernels (device code in cell_kernels.hip,
+// mvrnn_kernels.hip).  Plain structs and functions only; no HIP types besides hipStream_t.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace acrobat {
+
+enum CellEpilogue : int {
+  EPI_TREE_LEAF = 0,      // gates (i, o, u): c = s(i) tanh(u), h = s(o) tanh(c)
+  EPI_TREE_INTERNAL = 1,  // gates (i, f_l, f_r, o, u) + gathered child c rows
+  EPI_LSTM_STEP = 2,      // gates (i, f, o, u) + precomputed input transform + previous c
+  EPI_STORE_Z = 3,        // plain pre-activation store (hoisted input transform)
+};
+
+// One batch (one depth level) of a cell whose contraction is
+//   z[node, g*H + j] = sum_k in[node, k] * W[(gate_row[g]*H + j) * ldw + k]
+// where in[node, :] is the concatenation of `nseg` row segments of length kseg, segment s
+// being row idx_s[node] (or `node` itself when idx_s is null) of the matrix src_s.
+struct CellLevelArgs {
+  int32_t n;     // nodes in this batch (> 0)
+  int32_t H;     // hidden size (multiple of 32)
+  int32_t nseg;  // 0 (no contraction), 1 or 2
+  int32_t kseg;  // columns per segment (multiple of 32)
+  const float* src0; const int32_t* idx0; int32_t ld0;
+  const float* src1; const int32_t* idx1; int32_t ld1;
+  const float* W; int32_t ldw;  // weight rows are contiguous in k
+  const float* bias;            // indexed like W's rows, or null
+  const int32_t* out_rows;      // [n] arena row written by each node, null = node index
+  float* h; float* c;           // arena [rows, H]
+  const float* cprev_src;       // tree/LSTM: c rows gathered with idx0 (and idx1); null = zero state
+  const float* zadd;            // LSTM step: [rows, 4H] pre-activations added to z (row = out row)
+  float* zout;                  // STORE_Z: [rows, G*H]
+};
+
+// Launches the kernel for one level; picks the node-tile height from n.  Returns hipGetLastError().
+hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream);
+
+// MV-RNN level: for each of the n nodes at list positions [0,n):
+//   p = tanh(W [B a ; A b]),  P = W_M [A ; B]  with (a,A) / (b,B) the left / right child state.
+// A child source code s >= 0 means arena row s of (vec, mat); s < 0 means table row -(s+1).
+struct MvrnnLevelArgs {
+  int32_t n;
+  const int32_t* out_rows;  // [n]
+  const int32_t* lsrc;      // [n] encoded left child source
+  const int32_t* rsrc;      // [n]
+  const float* vec_tab; const float* mat_tab;
+  const float* W; const float* WM;  // [64,128] each
+  float* vec; float* mat;           // arena [rows,64], [rows,64,64]
+};
+hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream);
+
+// Copies table rows `token[i]` into arena rows out_rows[i] (vector and matrix), i in [0,n).
+hipError_t launch_mvrnn_leaf_copy(int32_t n, const int32_t* out_rows, const int32_t* token,
+                                  const float* vec_tab, const float* mat_tab, float* vec, float* mat,
+                                  hipStream_t stream);
+
+}  // namespace acrobat

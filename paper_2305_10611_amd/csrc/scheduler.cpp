@@ -1,0 +1,163 @@
+// Host level scheduler.
+//
+// Depth schedule of section 4.1: a node that consumes nothing produced inside the graph
+// has depth 0, any other node 1 + the largest depth among its producers; batches run by
+// increasing depth and the members of one depth are independent.  One schedule node is a
+// whole cell (appendix B.2), every leaf cell only consumes its embedding row so all leaves
+// land in depth 0 (the hoisted input transform of appendix B.1), and sibling subtrees are
+// concurrent (section 4.1, "instance parallelism").
+//
+// The paper computes depths inline while the unbatched program runs, relying on program
+// order being a valid dependency order.  Here the structure arrives as index arrays in an
+// arbitrary numbering, so depths are propagated upwards from the leaves through parent links
+// (one pass, O(N)), which also detects malformed input; a counting sort by depth then
+// produces the per-level lists.
+#include "scheduler.h"
+
+#include <algorithm>
+#include <limits>
+
+namespace acrobat {
+
+namespace {
+std::string at_node(const char* what, int32_t tree, int32_t local) {
+  return std::string(what) + " (tree " + std::to_string(tree) + ", node " + std::to_string(local) + ")";
+}
+}  // namespace
+
+int schedule_trees(const acrobat_trees& tr, int32_t vocab, TreeSchedule& out, std::string& err) {
+  out = TreeSchedule();
+  if (tr.n_trees < 0) { err = "n_trees is negative"; return ACROBAT_EINVAL; }
+  if (!tr.tree_off) { err = "tree_off is null"; return ACROBAT_EINVAL; }
+  if (tr.tree_off[0] != 0) { err = "tree_off[0] must be 0"; return ACROBAT_EINVAL; }
+  for (int32_t t = 0; t < tr.n_trees; ++t)
+    if (tr.tree_off[t + 1] < tr.tree_off[t]) { err = "tree_off is decreasing"; return ACROBAT_EINVAL; }
+  const int32_t N = tr.tree_off[tr.n_trees];
+  out.n_nodes = N;
+  if (N == 0) { out.level_off.assign(1, 0); return ACROBAT_OK; }
+  if (!tr.left || !tr.right) { err = "left/right is null"; return ACROBAT_EINVAL; }
+  if (vocab >= 0 && !tr.token) { err = "token is null"; return ACROBAT_EINVAL; }
+
+  std::vector<int32_t> parent(N, -1), depth(N, 0), stack;
+  std::vector<uint8_t> pending(N, 0);
+  stack.reserve(64);
+  int32_t max_depth = 0;
+  for (int32_t t = 0; t < tr.n_trees; ++t) {
+    const int32_t base = tr.tree_off[t], n = tr.tree_off[t + 1] - base;
+    if (n == 0) continue;
+    // pass 1: validate child links, record parents
+    for (int32_t j = 0; j < n; ++j) {
+      const int32_t l = tr.left[base + j], r = tr.right[base + j];
+      if (l == -1 && r == -1) {
+        if (vocab >= 0) {
+          const int32_t tok = tr.token[base + j];
+          if (tok < 0 || tok >= vocab) { err = at_node("leaf token out of range", t, j); return ACROBAT_ESTRUCT; }
+        }
+        continue;
+      }
+      if (l < 0 || r < 0) {
+        err = at_node((l < -1 || r < -1) ? "child index out of range" : "node has exactly one child", t, j);
+        return ACROBAT_ESTRUCT;
+      }
+      if (l >= n || r >= n) { err = at_node("child index out of range", t, j); return ACROBAT_ESTRUCT; }
+      if (l == j || r == j) { err = at_node("node is its own child", t, j); return ACROBAT_ESTRUCT; }
+      if (l == r) { err = at_node("both children are the same node", t, j); return ACROBAT_ESTRUCT; }
+      if (parent[base + l] != -1) { err = at_node("node has two parents", t, l); return ACROBAT_ESTRUCT; }
+      parent[base + l] = base + j;
+      if (parent[base + r] != -1) { err = at_node("node has two parents", t, r); return ACROBAT_ESTRUCT; }
+      parent[base + r] = base + j;
+      pending[base + j] = 2;
+    }
+    int32_t roots = 0;
+    for (int32_t j = 0; j < n; ++j) roots += parent[base + j] == -1;
+    if (roots != 1) {
+      err = "tree " + std::to_string(t) + " has " + std::to_string(roots) + " roots (need exactly 1)";
+      return ACROBAT_ESTRUCT;
+    }
+    // pass 2: push depths upwards from the leaves; a node is final once both children are
+    int32_t done = 0;
+    for (int32_t j = 0; j < n; ++j) {
+      if (tr.left[base + j] >= 0) continue;
+      int32_t g = base + j;  // a leaf: walk up while we complete parents
+      ++done;
+      while (true) {
+        const int32_t p = parent[g];
+        if (p < 0) break;
+        depth[p] = std::max(depth[p], depth[g] + 1);
+        if (--pending[p]) break;
+        ++done;
+        g = p;
+      }
+    }
+    if (done != n) { err = "tree " + std::to_string(t) + " contains a cycle"; return ACROBAT_ESTRUCT; }
+    for (int32_t j = 0; j < n; ++j) max_depth = std::max(max_depth, depth[base + j]);
+  }
+
+  // counting sort by depth; visiting ids in ascending order keeps each level ascending
+  out.n_levels = max_depth + 1;
+  out.level_off.assign(out.n_levels + 1, 0);
+  for (int32_t g = 0; g < N; ++g) ++out.level_off[depth[g] + 1];
+  for (int32_t d = 0; d < out.n_levels; ++d) out.level_off[d + 1] += out.level_off[d];
+  std::vector<int32_t> cursor(out.level_off.begin(), out.level_off.end() - 1);
+  out.level_nodes.resize(N);
+  out.lrow.resize(N);
+  out.rrow.resize(N);
+  for (int32_t t = 0; t < tr.n_trees; ++t) {
+    const int32_t base = tr.tree_off[t];
+    for (int32_t g = base; g < tr.tree_off[t + 1]; ++g) {
+      const int32_t pos = cursor[depth[g]]++;
+      out.level_nodes[pos] = g;
+      const int32_t l = tr.left[g], r = tr.right[g];
+      out.lrow[pos] = l >= 0 ? base + l : -1;
+      out.rrow[pos] = r >= 0 ? base + r : -1;
+    }
+  }
+  return ACROBAT_OK;
+}
+
+int schedule_seqs(int32_t n_seq, const int32_t* len, SeqSchedule& out, std::string& err) {
+  out = SeqSchedule();
+  out.level_off.assign(1, 0);
+  if (n_seq < 0) { err = "n_seq is negative"; return ACROBAT_EINVAL; }
+  if (n_seq == 0) return ACROBAT_OK;
+  if (!len) { err = "len is null"; return ACROBAT_EINVAL; }
+  int64_t total = 0;
+  int32_t tmax = 0;
+  for (int32_t s = 0; s < n_seq; ++s) {
+    if (len[s] < 0) { err = "negative sequence length at " + std::to_string(s); return ACROBAT_EINVAL; }
+    total += len[s];
+    tmax = std::max(tmax, len[s]);
+  }
+  if (total > std::numeric_limits<int32_t>::max()) { err = "more than 2^31-1 rows"; return ACROBAT_EINVAL; }
+  out.n_rows = total;
+  out.n_levels = tmax;
+  out.level_off.assign(tmax + 1, 0);
+  out.level_rows.resize(static_cast<size_t>(total));
+  // active sequences (ascending s) with their first row; filtered in place as steps run out
+  std::vector<int32_t> act_seq, act_row0;
+  act_seq.reserve(n_seq);
+  act_row0.reserve(n_seq);
+  int32_t row0 = 0;
+  for (int32_t s = 0; s < n_seq; ++s) {
+    if (len[s] > 0) { act_seq.push_back(s); act_row0.push_back(row0); }
+    row0 += len[s];
+  }
+  int32_t pos = 0;
+  for (int32_t t = 0; t < tmax; ++t) {
+    size_t keep = 0;
+    for (size_t a = 0; a < act_seq.size(); ++a) {
+      if (len[act_seq[a]] > t) {
+        out.level_rows[pos++] = act_row0[a] + t;
+        act_seq[keep] = act_seq[a];
+        act_row0[keep] = act_row0[a];
+        ++keep;
+      }
+    }
+    act_seq.resize(keep);
+    act_row0.resize(keep);
+    out.level_off[t + 1] = pos;
+  }
+  return ACROBAT_OK;
+}
+
+}  // namespace acrobat

@@ -1,0 +1,31 @@
+// Host level scheduler: structures -> per-depth node lists (no GPU code here).
+#pragma once
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "acrobat.h"
+
+namespace acrobat {
+
+struct TreeSchedule {
+  int32_t n_nodes = 0;
+  int32_t n_levels = 0;
+  std::vector<int32_t> level_off;    // [n_levels + 1]
+  std::vector<int32_t> level_nodes;  // [N] global ids, ascending inside a level
+  std::vector<int32_t> lrow, rrow;   // [N] global child ids by list position, -1 at leaves
+};
+
+// Returns ACROBAT_OK / EINVAL / ESTRUCT; `err` explains a failure.
+int schedule_trees(const acrobat_trees& trees, int32_t vocab, TreeSchedule& out, std::string& err);
+
+struct SeqSchedule {
+  int64_t n_rows = 0;
+  int32_t n_levels = 0;
+  std::vector<int32_t> level_off;   // [n_levels + 1]
+  std::vector<int32_t> level_rows;  // [sum len]
+};
+
+int schedule_seqs(int32_t n_seq, const int32_t* len, SeqSchedule& out, std::string& err);
+
+}  // namespace acrobat

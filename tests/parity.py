@@ -1,0 +1,74 @@
+"""Helpers of the GPU parity tests: run a workload through the C-ABI binding, compare with
+the oracle under the stated tolerances."""
+import numpy as np
+import torch
+
+ABS_TOL = 1e-4  # max abs error on every element of every node's state
+REL_TOL = 1e-3  # per node: max-norm of the error over max-norm of the oracle's row
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def stream_handle():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def nan_filled(*shape):
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+
+def run_treelstm(ctx, w, use_bias=True, stream=None):
+    N, H = int(w["tree_off"][-1]), int(w["H"])
+    t = {k: dev(w[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")}
+    h, c = nan_filled(max(N, 1), H), nan_filled(max(N, 1), H)
+    rc = ctx.acrobat_treelstm_forward(w, H, int(w["D"]), int(w["V"]), t["emb"], t["W_leaf"],
+                                      t["b_leaf"] if use_bias else None, t["U"], t["b"] if use_bias else None,
+                                      h, c, stream_handle() if stream is None else stream)
+    ctx.check(rc)
+    torch.cuda.synchronize()
+    return h[:N].cpu().numpy(), c[:N].cpu().numpy()
+
+
+def run_mvrnn(ctx, w, copy_leaves=1):
+    N, d = int(w["tree_off"][-1]), int(w["d"])
+    t = {k: dev(w[k]) for k in ("vec_tab", "mat_tab", "W", "WM")}
+    vec, mat = nan_filled(max(N, 1), d), nan_filled(max(N, 1), d, d)
+    rc = ctx.acrobat_mvrnn_forward(w, d, int(w["V"]), t["vec_tab"], t["mat_tab"], t["W"], t["WM"], vec, mat,
+                                   copy_leaves, stream_handle())
+    ctx.check(rc)
+    torch.cuda.synchronize()
+    return vec[:N].cpu().numpy(), mat[:N].cpu().numpy()
+
+
+def run_lstm(ctx, w, use_bias=True):
+    R, H = int(np.sum(w["len"])), int(w["H"])
+    t = {k: dev(w[k]) for k in ("x", "Wx", "Wh", "b")}
+    h, c = nan_filled(max(R, 1), H), nan_filled(max(R, 1), H)
+    rc = ctx.acrobat_varlen_lstm_forward(w["len"], H, int(w["D"]), t["x"], t["Wx"], t["Wh"],
+                                         t["b"] if use_bias else None, h, c, stream_handle())
+    ctx.check(rc)
+    torch.cuda.synchronize()
+    return h[:R].cpu().numpy(), c[:R].cpu().numpy()
+
+
+def errors(got, want):
+    """(max abs error, max over rows of max-norm relative error)."""
+    got = np.asarray(got, np.float64).reshape(want.shape[0], -1)
+    want = np.asarray(want, np.float64).reshape(want.shape[0], -1)
+    if want.size == 0:
+        return 0.0, 0.0
+    diff = np.abs(got - want)
+    row_err = diff.max(axis=1)
+    row_ref = np.maximum(np.abs(want).max(axis=1), 1e-30)
+    return float(diff.max()), float((row_err / row_ref).max())
+
+
+def assert_close(got, want, what=""):
+    assert got.shape[0] == want.shape[0]
+    assert not np.isnan(got).any(), f"{what}: NaN in the GPU result (a row was read before it was written, or never written)"
+    abs_err, rel_err = errors(got, want)
+    assert abs_err <= ABS_TOL, f"{what}: max abs error {abs_err:.3e} > {ABS_TOL}"
+    assert rel_err <= REL_TOL, f"{what}: max per-node relative error {rel_err:.3e} > {REL_TOL}"
+    return abs_err, rel_err

@@ -1,0 +1,228 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Schedules bit exact; fp32 states within 1e-4 abs and 1e-3 per-node relative."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import generators as gen
+from workloads import make_config
+
+pytestmark = pytest.mark.gpu
+
+NT = oracle.default_threads()
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_2305_10611_amd as A
+    c = A.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.fixture(scope="module")
+def P():
+    from tests import parity
+    return parity
+
+
+def check_tree_schedule(ctx, w):
+    level_off, level_nodes = ctx.acrobat_last_schedule()
+    o_off, o_nodes, _, _ = oracle.tree_schedule(w)
+    assert np.array_equal(level_off, o_off) and np.array_equal(level_nodes, o_nodes)
+
+
+# ---------------------------------------------------------------- TreeLSTM
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_treelstm_benchmark_configs(ctx, P, cfg):
+    w = make_config(cfg)
+    h, c = P.run_treelstm(ctx, w)
+    check_tree_schedule(ctx, w)
+    oh, oc = oracle.treelstm(w, nthreads=NT)
+    eh = P.assert_close(h, oh, f"cfg{cfg} h")
+    ec = P.assert_close(c, oc, f"cfg{cfg} c")
+    print(f"cfg{cfg}: N={w['n_nodes']} h abs/rel {eh[0]:.2e}/{eh[1]:.2e}  c abs/rel {ec[0]:.2e}/{ec[1]:.2e}")
+
+
+@pytest.mark.parametrize("H,n_trees,lo,hi", [(32, 5, 1, 9), (64, 37, 1, 33), (96, 3, 50, 70), (256, 130, 1, 12),
+                                             (512, 9, 1, 40)])
+def test_treelstm_ragged_shapes_with_bias(ctx, P, H, n_trees, lo, hi):
+    w = gen.treelstm_workload(n_trees, lo, hi, H, 101, "zipf1.1", seed=H + n_trees, bias_scale=0.3)
+    h, c = P.run_treelstm(ctx, w)
+    check_tree_schedule(ctx, w)
+    oh, oc = oracle.treelstm(w, nthreads=NT)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+
+
+def test_treelstm_null_bias_equals_zero_bias(ctx, P):
+    w = gen.treelstm_workload(6, 2, 20, 64, 50, "uniform", seed=8)
+    h0, c0 = P.run_treelstm(ctx, w, use_bias=True)
+    h1, c1 = P.run_treelstm(ctx, w, use_bias=False)
+    assert np.array_equal(h0, h1) and np.array_equal(c0, c1)
+
+
+def test_treelstm_random_node_numbering(ctx, P):
+    w = gen.treelstm_workload(20, 1, 30, 64, 77, "uniform", seed=9, bias_scale=0.2)
+    w2, perm = gen.relabel_trees(w, gen.make_rng(10), extra={"token": w["token"]})
+    h, c = P.run_treelstm(ctx, w2)
+    check_tree_schedule(ctx, w2)
+    oh, oc = oracle.treelstm(w2, nthreads=NT)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+    # and the relabelled batch gives the original batch's states, row for row
+    h0, c0 = P.run_treelstm(ctx, w)
+    P.assert_close(h[perm], h0.astype(np.float64), "h vs original numbering")
+
+
+def test_treelstm_tree_order_invariance(ctx, P):
+    w = make_config(1)
+    h0, c0 = P.run_treelstm(ctx, w)
+    order = gen.make_rng(3).permutation(w["n_trees"])
+    w2, src = gen.reorder_trees(w, order, per_node={"token": w["token"]})
+    h1, c1 = P.run_treelstm(ctx, w2)
+    P.assert_close(h1, h0[src].astype(np.float64), "h")
+    P.assert_close(c1, c0[src].astype(np.float64), "c")
+    print("bitwise equal under tree reordering:", np.array_equal(h1, h0[src]) and np.array_equal(c1, c0[src]))
+
+
+def test_treelstm_degenerate_batches(ctx, P):
+    import paper_2305_10611_amd as A
+    # empty batch: OK, nothing launched
+    w = gen.treelstm_workload(2, 1, 1, 32, 10, "uniform", seed=1)
+    empty = dict(w, n_trees=0, tree_off=np.array([0], np.int32), left=np.zeros(0, np.int32),
+                 right=np.zeros(0, np.int32), token=np.zeros(0, np.int32))
+    h, c = P.run_treelstm(ctx, empty)
+    assert h.shape[0] == 0
+    # only single-leaf trees: one level
+    h, c = P.run_treelstm(ctx, w)
+    oh, oc = oracle.treelstm(w)
+    P.assert_close(h, oh, "h")
+    level_off, _ = ctx.acrobat_last_schedule()
+    assert list(level_off) == [0, 2]
+    # malformed structure is refused and nothing is written
+    bad = dict(w, left=np.array([0, -1], np.int32))
+    hh, cc = P.nan_filled(2, 32), P.nan_filled(2, 32)
+    t = {k: P.dev(w[k]) for k in ("emb", "W_leaf", "U")}
+    rc = ctx.acrobat_treelstm_forward(bad, 32, 32, 10, t["emb"], t["W_leaf"], None, t["U"], None, hh, cc, 0)
+    assert rc == A.ESTRUCT and ctx.acrobat_last_error() != ""
+    assert bool(hh.isnan().all())
+    rc = ctx.acrobat_treelstm_forward(w, 33, 32, 10, t["emb"], t["W_leaf"], None, t["U"], None, hh, cc, 0)
+    assert rc == A.EINVAL
+    rc = ctx.acrobat_treelstm_forward(w, 32, 32, 10, None, t["W_leaf"], None, t["U"], None, hh, cc, 0)
+    assert rc == A.EINVAL
+
+
+def test_treelstm_deep_chain(ctx, P):
+    """Many tiny levels in a row (launch-order dependence between consecutive levels)."""
+    H, L = 64, 150
+    rng = gen.make_rng(12)
+    n = 2 * L - 1
+    left = np.full(n, -1, np.int32)
+    right = np.full(n, -1, np.int32)
+    for t in range(L - 1):
+        left[L + t] = 0 if t == 0 else L + t - 1
+        right[L + t] = t + 1
+    w = gen.treelstm_workload(1, 1, 1, H, 40, "uniform", seed=13, bias_scale=0.2)
+    token = np.where(left < 0, rng.integers(0, 40, n), -1).astype(np.int32)
+    w.update(n_trees=1, tree_off=np.array([0, n], np.int32), left=left, right=right, token=token, n_nodes=n)
+    h, c = P.run_treelstm(ctx, w)
+    oh, oc = oracle.treelstm(w)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+
+
+# ---------------------------------------------------------------- MV-RNN
+def test_mvrnn_benchmark_config(ctx, P):
+    w = make_config(3)
+    vec, mat = P.run_mvrnn(ctx, w, copy_leaves=1)
+    check_tree_schedule(ctx, w)
+    ov, om = oracle.mvrnn(w, nthreads=NT)
+    ev = P.assert_close(vec, ov, "vec")
+    em = P.assert_close(mat, om, "mat")
+    print(f"cfg3: N={w['n_nodes']} vec abs/rel {ev[0]:.2e}/{ev[1]:.2e} mat abs/rel {em[0]:.2e}/{em[1]:.2e}")
+    # without the leaf copy: internal rows identical, leaf rows untouched
+    vec2, mat2 = P.run_mvrnn(ctx, w, copy_leaves=0)
+    internal = w["left"] >= 0
+    assert np.array_equal(vec2[internal], vec[internal]) and np.array_equal(mat2[internal], mat[internal])
+    assert np.isnan(vec2[~internal]).all() and np.isnan(mat2[~internal]).all()
+
+
+def test_mvrnn_small_ragged_and_relabelled(ctx, P):
+    w = gen.mvrnn_workload(11, 1, 9, 64, seed=31)
+    w2, perm = gen.relabel_trees(w, gen.make_rng(32), extra={"token": w["token"]})
+    for ww in (w, w2):
+        vec, mat = P.run_mvrnn(ctx, ww)
+        check_tree_schedule(ctx, ww)
+        ov, om = oracle.mvrnn(ww, nthreads=NT)
+        P.assert_close(vec, ov, "vec")
+        P.assert_close(mat, om, "mat")
+    # shared table rows: two leaves reading the same row
+    w3 = dict(w)
+    w3["token"] = np.where(w["token"] >= 0, w["token"] % 3, -1).astype(np.int32)
+    vec, mat = P.run_mvrnn(ctx, w3)
+    ov, om = oracle.mvrnn(w3)
+    P.assert_close(vec, ov, "vec")
+    P.assert_close(mat, om, "mat")
+
+
+def test_mvrnn_rejects_unsupported_d(ctx, P):
+    import paper_2305_10611_amd as A
+    w = gen.mvrnn_workload(2, 2, 3, 32, seed=33)
+    t = {k: P.dev(w[k]) for k in ("vec_tab", "mat_tab", "W", "WM")}
+    N = w["n_nodes"]
+    rc = ctx.acrobat_mvrnn_forward(w, 32, w["V"], t["vec_tab"], t["mat_tab"], t["W"], t["WM"],
+                                   P.nan_filled(N, 32), P.nan_filled(N, 32, 32), 1, 0)
+    assert rc == A.EINVAL
+
+
+# ---------------------------------------------------------------- variable-length LSTM
+def check_seq_schedule(ctx, lens):
+    level_off, level_rows = ctx.acrobat_last_schedule()
+    o_off, o_rows = oracle.seq_schedule(lens)
+    assert np.array_equal(level_off, o_off) and np.array_equal(level_rows, o_rows)
+
+
+def test_lstm_benchmark_config(ctx, P):
+    w = make_config(4)
+    h, c = P.run_lstm(ctx, w)
+    check_seq_schedule(ctx, w["len"])
+    oh, oc = oracle.varlen_lstm(w, nthreads=NT)
+    eh = P.assert_close(h, oh, "h")
+    ec = P.assert_close(c, oc, "c")
+    print(f"cfg4: rows={w['n_nodes']} h abs/rel {eh[0]:.2e}/{eh[1]:.2e}  c abs/rel {ec[0]:.2e}/{ec[1]:.2e}")
+
+
+@pytest.mark.parametrize("H,D,n_seq,lo,hi", [(32, 32, 3, 0, 5), (64, 96, 70, 0, 20), (256, 128, 300, 1, 7)])
+def test_lstm_ragged_with_bias_and_empty_sequences(ctx, P, H, D, n_seq, lo, hi):
+    w = gen.lstm_workload(n_seq, lo, hi, H, D, seed=H + D, bias_scale=0.3)
+    h, c = P.run_lstm(ctx, w)
+    check_seq_schedule(ctx, w["len"])
+    oh, oc = oracle.varlen_lstm(w, nthreads=NT)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+
+
+def test_lstm_degenerate(ctx, P):
+    w = gen.lstm_workload(4, 1, 3, 32, 32, seed=5)
+    w0 = dict(w, len=np.zeros(4, np.int32))
+    h, c = P.run_lstm(ctx, w0)
+    assert h.shape[0] == 0
+    w1 = dict(w, n_seq=0, len=np.zeros(0, np.int32))
+    h, c = P.run_lstm(ctx, w1)
+    assert h.shape[0] == 0
+
+
+# ---------------------------------------------------------------- profiling mode
+def test_profiling_records_every_launch(ctx, P):
+    w = make_config(0)
+    ctx.acrobat_set_profiling(True)
+    try:
+        P.run_treelstm(ctx, w)
+        rec = ctx.acrobat_last_profile()
+    finally:
+        ctx.acrobat_set_profiling(False)
+    level_off, _ = ctx.acrobat_last_schedule()
+    assert len(rec) == len(level_off) - 1
+    assert [r[2] for r in rec] == list(np.diff(level_off))
+    assert all(r[3] > 0 for r in rec)

@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Throughput of the batched dataflow-graph hot path on one MI355X.
+
+A step is one whole forward pass over one synthetic mini-batch: host level scheduling, the
+single index upload and every level kernel.  Weights, tables and inputs are resident in HBM
+before the timed region; the host structure arrays (tree child indices / sequence lengths)
+are consumed by the call itself, as the library's boundary defines.
+
+Prints ONE JSON line.  `roofline` is measured live with HIP events recorded by the library
+on the launch stream around every launch of the dominant kernel; `cpu_baseline` is the CPU
+oracle timed on this machine's host cores on the same inputs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (2 = headline)")
+    ap.add_argument("--profile-steps", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (instances are independent, so more GPUs would "
+              "simply take disjoint sets of trees; no collective is part of the path). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2305_10611_amd as A
+    from workloads import make_config
+
+    torch.cuda.set_device(0)
+    w = make_config(args.config)
+    kind = w["kind"]
+    ctx = A.Context(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    stream = torch.cuda.current_stream().cuda_stream
+    n_nodes = int(w["n_nodes"])
+
+    if kind == "treelstm":
+        H, D, V = int(w["H"]), int(w["D"]), int(w["V"])
+        t = {k: dev(w[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")}
+        out = [torch.empty(n_nodes, H, device="cuda"), torch.empty(n_nodes, H, device="cuda")]
+        step = lambda: ctx.check(ctx.acrobat_treelstm_forward(w, H, D, V, t["emb"], t["W_leaf"], t["b_leaf"], t["U"],
+                                                              t["b"], out[0], out[1], stream))
+        sched = lambda: A.acrobat_schedule_trees(w, V)
+        n_leaf = int((w["left"] < 0).sum())
+        flops_per = {A.binding.K_TREE_LEAF: 2.0 * D * 3 * H, A.binding.K_TREE_INTERNAL: 2.0 * 2 * H * 5 * H}
+        # strict-minimum bytes per node (states + indices), weights extra per launch
+        bytes_per = {A.binding.K_TREE_LEAF: 4.0 * D + 4 + 8.0 * H, A.binding.K_TREE_INTERNAL: 24.0 * H + 12}
+        weight_bytes = {A.binding.K_TREE_LEAF: 12.0 * H * D, A.binding.K_TREE_INTERNAL: 40.0 * H * H}
+        dominant = A.binding.K_TREE_INTERNAL
+        total_flops = n_leaf * flops_per[A.binding.K_TREE_LEAF] + (n_nodes - n_leaf) * flops_per[dominant]
+        dtype, bound = "f32", "mfma"
+    elif kind == "mvrnn":
+        d, V = int(w["d"]), int(w["V"])
+        t = {k: dev(w[k]) for k in ("vec_tab", "mat_tab", "W", "WM")}
+        out = [torch.empty(n_nodes, d, device="cuda"), torch.empty(n_nodes, d, d, device="cuda")]
+        step = lambda: ctx.check(ctx.acrobat_mvrnn_forward(w, d, V, t["vec_tab"], t["mat_tab"], t["W"], t["WM"],
+                                                           out[0], out[1], 0, stream))
+        sched = lambda: A.acrobat_schedule_trees(w, V)
+        n_int = int((w["left"] >= 0).sum())
+        flops_per = {A.binding.K_MVRNN_LEVEL: 4.0 * d * d + 4.0 * d * d + 4.0 * d ** 3}
+        bytes_per = {A.binding.K_MVRNN_LEVEL: 12.0 * (d * d + d) + 12}
+        weight_bytes = {A.binding.K_MVRNN_LEVEL: 16.0 * d * d}
+        dominant = A.binding.K_MVRNN_LEVEL
+        total_flops = n_int * flops_per[dominant]
+        dtype, bound = "f32", "hbm"
+    else:
+        H, D = int(w["H"]), int(w["D"])
+        t = {k: dev(w[k]) for k in ("x", "Wx", "Wh", "b")}
+        out = [torch.empty(n_nodes, H, device="cuda"), torch.empty(n_nodes, H, device="cuda")]
+        step = lambda: ctx.check(ctx.acrobat_varlen_lstm_forward(w["len"], H, D, t["x"], t["Wx"], t["Wh"], t["b"],
+                                                                 out[0], out[1], stream))
+        sched = lambda: A.acrobat_schedule_seqs(w["len"])
+        flops_per = {A.binding.K_LSTM_INPUT: 2.0 * D * 4 * H, A.binding.K_LSTM_STEP: 2.0 * H * 4 * H}
+        bytes_per = {A.binding.K_LSTM_INPUT: 4.0 * D + 16.0 * H, A.binding.K_LSTM_STEP: 16.0 * H + 8.0 * H + 8.0 * H + 8}
+        weight_bytes = {A.binding.K_LSTM_INPUT: 16.0 * H * D, A.binding.K_LSTM_STEP: 16.0 * H * H}
+        dominant = A.binding.K_LSTM_STEP
+        total_flops = n_nodes * (flops_per[A.binding.K_LSTM_INPUT] + flops_per[A.binding.K_LSTM_STEP])
+        dtype, bound = "f32", "mfma"
+
+    # ---- timed region: W warm-up steps, then exactly K steps between two synchronisations
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = n_nodes / (ms_per_step * 1e-3)
+
+    # ---- host scheduler alone
+    ts = []
+    for _ in range(20):
+        a0 = time.perf_counter()
+        sched()
+        ts.append(time.perf_counter() - a0)
+    t_schedule_ms = float(np.median(ts)) * 1e3
+
+    # ---- per-launch device times (HIP events on the launch stream, recorded by the library)
+    ctx.acrobat_set_profiling(True)
+    recs = []
+    for _ in range(max(1, args.profile_steps)):
+        step()
+        recs.append(ctx.acrobat_last_profile())
+    ctx.acrobat_set_profiling(False)
+    n_rep = len(recs)
+    per_launch = []  # (kind, level, n, tile, mean ms, ksplit)
+    for i, r in enumerate(recs[0]):
+        per_launch.append((r[0], r[1], r[2], r[4], float(np.mean([rr[i][3] for rr in recs])), r[5]))
+    t_device_ms = sum(p[4] for p in per_launch)
+    # dominant kernel = the variant of the dominant kind that accounts for most device time
+    by_tile = {}
+    for k, lv, n, tile, ms, _ in per_launch:
+        if k == dominant:
+            e = by_tile.setdefault(tile, [0, 0, 0.0])
+            e[0] += 1
+            e[1] += n
+            e[2] += ms
+    dom_tile = max(by_tile, key=lambda q: by_tile[q][2])
+    launches, units, ms_sum = by_tile[dom_tile]
+    if bound == "mfma":
+        achieved = units * flops_per[dominant] / (ms_sum * 1e-3) / 1e12
+        peak, unit = PEAK_FP32_MFMA_TFLOPS, "TFLOP/s"
+    else:
+        achieved = (units * bytes_per[dominant] + launches * weight_bytes[dominant]) / (ms_sum * 1e-3) / 1e9
+        peak, unit = PEAK_HBM_GBS, "GB/s"
+    roofline = {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": None,
+                "kernel": f"kind={dominant} tile={dom_tile}", "launches_per_step": launches,
+                "units_per_step": units, "avg_launch_us": round(ms_sum / launches * 1e3, 2)}
+
+    if args.verbose:
+        print(f"{'kind':>4} {'lvl':>4} {'n':>6} {'tile':>4} {'ks':>3} {'us':>9} {'TFLOP/s':>8} {'GB/s':>8}", file=sys.stderr)
+        for k, lv, n, tile, ms, ks in per_launch:
+            fl = n * flops_per[k]
+            by = n * bytes_per[k] + weight_bytes[k]
+            print(f"{k:>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f} {fl / ms / 1e9:>8.2f} {by / ms / 1e6:>8.1f}",
+                  file=sys.stderr)
+        print(f"device sum {t_device_ms:.3f} ms, end-to-end {ms_per_step:.3f} ms/step, schedule {t_schedule_ms:.3f} ms",
+              file=sys.stderr)
+
+    # ---- the CPU oracle on this machine's host cores, same inputs, run once
+    cpu_baseline = None
+    err = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nt = oracle.default_threads()
+        c0 = time.perf_counter()
+        if kind == "treelstm":
+            ref = oracle.treelstm(w, nthreads=nt)
+        elif kind == "mvrnn":
+            ref = oracle.mvrnn(w, nthreads=nt)
+        else:
+            ref = oracle.varlen_lstm(w, nthreads=nt)
+        c1 = time.perf_counter()
+        cpu_baseline = {"value": round(n_nodes / (c1 - c0), 1), "unit": "nodes/s", "cores": nt, "kind": "oracle",
+                        "sample": f"the whole {w['name']} batch ({n_nodes} nodes), evaluated once with whole "
+                                  f"instances fanned out over {nt} host threads"}
+        torch.cuda.synchronize()
+        got = [o.cpu().numpy().astype(np.float64) for o in out]
+        mask = slice(None) if kind != "mvrnn" else (w["left"] >= 0)
+        err = max(float(np.abs(g[mask] - r[mask]).max()) for g, r in zip(got, ref))
+
+    line = {
+        "metric": "node evals/sec", "value": round(value, 1), "unit": "nodes/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": w["name"], "index": args.config, "nodes": n_nodes, "seed": int(w["seed"])},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
+                      "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),
+                      "device_tflops": round(total_flops / (t_device_ms * 1e-3) / 1e12, 3),
+                      "max_abs_err_vs_oracle": err},
+    }
+    print(json.dumps(line), flush=True)
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -134,6 +134,8 @@ typedef struct {
   int32_t kind;  /* ACROBAT_K_* */
   int32_t level; /* depth of the batch */
   int32_t n;     /* nodes (rows) in the batch */
+  int32_t tile;  /* nodes per workgroup tile of the kernel variant that was launched */
+  int32_t ksplit; /* workgroups sharing the contraction range of one tile */
   float ms;      /* device time of the launch */
 } acrobat_launch_record;
 

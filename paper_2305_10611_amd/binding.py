@@ -27,7 +27,7 @@ class acrobat_trees(C.Structure):
 
 
 class acrobat_launch_record(C.Structure):
-    _fields_ = [("kind", C.c_int32), ("level", C.c_int32), ("n", C.c_int32), ("ms", C.c_float)]
+    _fields_ = [("kind", C.c_int32), ("level", C.c_int32), ("n", C.c_int32), ("tile", C.c_int32), ("ksplit", C.c_int32), ("ms", C.c_float)]
 
 
 EXPORTS = (
@@ -177,4 +177,4 @@ class Context:
     def acrobat_last_profile(self):
         n, p = C.c_int32(0), C.POINTER(acrobat_launch_record)()
         self.check(lib.acrobat_last_profile(self._h, C.byref(n), C.byref(p)))
-        return [(p[i].kind, p[i].level, p[i].n, p[i].ms) for i in range(n.value)]
+        return [(p[i].kind, p[i].level, p[i].n, p[i].ms, p[i].tile, p[i].ksplit) for i in range(n.value)]

@@ -5,6 +5,7 @@
 // and one batched host-to-device transfer per forward call for all index lists.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -31,6 +32,8 @@ struct acrobat_ctx {
   // scratch for the hoisted LSTM input transform
   float* d_scratch = nullptr;
   size_t scratch_cap = 0;  // in floats
+  // split-k workspace of the cell kernels (allocated at the first forward call)
+  SplitKWorkspace splitk;
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
@@ -98,6 +101,32 @@ int reserve_scratch(acrobat_ctx* ctx, size_t n_floats) {
   return ACROBAT_OK;
 }
 
+// Partial-tile workspace: 32 MiB of partial accumulators and 16 Ki arrival counters.  Counters
+// start at zero and every launch leaves them at zero.
+int reserve_splitk(acrobat_ctx* ctx) {
+  if (ctx->splitk.partial) return ACROBAT_OK;
+  constexpr size_t kPartialFloats = (size_t)8 << 20;
+  constexpr int32_t kCounters = 16384;
+  float* p = nullptr;
+  unsigned* c = nullptr;
+  HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c), kCounters * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(c, 0, kCounters * sizeof(unsigned));
+  if (e != hipSuccess) {
+    (void)hipFree(p);
+    if (c) (void)hipFree(c);
+    return fail_hip(ctx, e, "split-k workspace");
+  }
+  ctx->splitk.partial = p;
+  ctx->splitk.partial_floats = kPartialFloats;
+  ctx->splitk.counters = c;
+  ctx->splitk.n_counters = kCounters;
+  // tuning override for experiments: ACROBAT_FORCE_TILE=128|64|32, ACROBAT_FORCE_KSPLIT=1..32
+  if (const char* v = std::getenv("ACROBAT_FORCE_TILE")) ctx->splitk.force_bm = std::atoi(v);
+  if (const char* v = std::getenv("ACROBAT_FORCE_KSPLIT")) ctx->splitk.force_ksplit = std::atoi(v);
+  return ACROBAT_OK;
+}
+
 // Brackets a launch with events when profiling is on.
 struct LaunchTimer {
   acrobat_ctx* ctx;
@@ -110,10 +139,12 @@ struct LaunchTimer {
       HIP_TRY(ctx, hipEventCreate(&e));
       ctx->events.push_back(e);
     }
-    ctx->records.push_back({kind, level, n, 0.0f});
+    ctx->records.push_back({kind, level, n, 0, 1, 0.0f});
     HIP_TRY(ctx, hipEventRecord(ctx->events[need - 2], stream));
     return ACROBAT_OK;
   }
+  int32_t* tile() { return ctx->profiling ? &ctx->records.back().tile : nullptr; }
+  int32_t* ksplit() { return ctx->profiling ? &ctx->records.back().ksplit : nullptr; }
   int end() {
     if (!ctx->profiling) return ACROBAT_OK;
     HIP_TRY(ctx, hipEventRecord(ctx->events[2 * ctx->records.size() - 1], stream));
@@ -180,6 +211,8 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->stage_pending) (void)hipEventSynchronize(ctx->stage_done);
   if (ctx->d_idx) (void)hipFree(ctx->d_idx);
   if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
+  if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
+  if (ctx->splitk.counters) (void)hipFree(ctx->splitk.counters);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
@@ -255,6 +288,9 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
     if (!d_emb || !d_Wleaf || !d_U || !d_h || !d_c) return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
+    if ((double)5 * H * 2 * H >= 2147483648.0 || (double)5 * H * D >= 2147483648.0)
+      return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
+    TRY(reserve_splitk(ctx));
     // index lists by schedule position: out row | first operand row | second operand row
     TRY(reserve_indices(ctx, 3 * (size_t)N));
     int32_t* st = ctx->h_stage;
@@ -289,7 +325,8 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
         a.cprev_src = d_c;
       }
       TRY(timer.begin(lv == 0 ? ACROBAT_K_TREE_LEAF : ACROBAT_K_TREE_INTERNAL, lv, n));
-      HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream));
+      HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream, ctx->splitk,
+                                     timer.tile(), timer.ksplit()));
       TRY(timer.end());
     }
     return timer.finish();
@@ -359,7 +396,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
       a.W = d_W; a.WM = d_WM;
       a.vec = d_vec; a.mat = d_mat;
       TRY(timer.begin(ACROBAT_K_MVRNN_LEVEL, lv, n));
-      HIP_TRY(ctx, launch_mvrnn_level(a, stream));
+      HIP_TRY(ctx, launch_mvrnn_level(a, stream, timer.tile()));
       TRY(timer.end());
     }
     return timer.finish();
@@ -390,6 +427,9 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
     if (!d_x || !d_Wx || !d_Wh || !d_h || !d_c) return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
+    if ((double)4 * H * H >= 2147483648.0 || (double)4 * H * D >= 2147483648.0)
+      return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
+    TRY(reserve_splitk(ctx));
     // by schedule position: row written | row of the previous step (unused at t = 0)
     TRY(reserve_indices(ctx, 2 * (size_t)R));
     int32_t* st = ctx->h_stage;
@@ -409,7 +449,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       a.W = d_Wx; a.ldw = D; a.bias = d_b;
       a.zout = ctx->d_scratch;
       TRY(timer.begin(ACROBAT_K_LSTM_INPUT, 0, R));
-      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z, a, stream));
+      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
       TRY(timer.end());
     }
     for (int32_t t = 0; t < s.n_levels; ++t) {
@@ -426,7 +466,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
         a.cprev_src = d_c;
       }
       TRY(timer.begin(ACROBAT_K_LSTM_STEP, t, n));
-      HIP_TRY(ctx, launch_cell_level(EPI_LSTM_STEP, a, stream));
+      HIP_TRY(ctx, launch_cell_level(EPI_LSTM_STEP, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
       TRY(timer.end());
     }
     return timer.finish();

@@ -34,8 +34,20 @@ struct CellLevelArgs {
   float* zout;                  // STORE_Z: [rows, G*H]
 };
 
-// Launches the kernel for one level; picks the node-tile height from n.  Returns hipGetLastError().
-hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream);
+// Device workspace for levels whose k range is split over several workgroups: partial
+// accumulator tiles and one arrival counter per output tile (all zero between launches).
+struct SplitKWorkspace {
+  float* partial = nullptr;
+  size_t partial_floats = 0;
+  unsigned* counters = nullptr;
+  int32_t n_counters = 0;
+  int32_t force_bm = 0, force_ksplit = 0;  // tuning override, 0 = automatic
+};
+
+// Launches the kernel for one level; picks the node-tile height and k split from the level's
+// size and reports them in *tile / *ksplit (may be null).  Returns hipGetLastError().
+hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,
+                             const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit);
 
 // MV-RNN level: for each of the n nodes at list positions [0,n):
 //   p = tanh(W [B a ; A b]),  P = W_M [A ; B]  with (a,A) / (b,B) the left / right child state.
@@ -49,7 +61,7 @@ struct MvrnnLevelArgs {
   const float* W; const float* WM;  // [64,128] each
   float* vec; float* mat;           // arena [rows,64], [rows,64,64]
 };
-hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream);
+hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile);
 
 // Copies table rows `token[i]` into arena rows out_rows[i] (vector and matrix), i in [0,n).
 hipError_t launch_mvrnn_leaf_copy(int32_t n, const int32_t* out_rows, const int32_t* token,

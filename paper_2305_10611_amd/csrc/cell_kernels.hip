@@ -16,6 +16,12 @@
 // next slab.  Wavefronts are arranged WM (node blocks) x WK (k split inside a slab); small
 // levels use WK > 1 so that all four matrix pipes of the CU work on a 32-node tile.
 //
+// Small levels cannot fill 256 compute units with (node tile, j tile) pairs alone, so the
+// k range is additionally split over `ksplit` workgroups.  Each writes its partial tile to
+// a workspace; the workgroup that arrives last at the tile's counter sums the partials in
+// fixed order (results do not depend on arrival order) and runs the epilogue.  Nobody waits
+// for anybody: there is no spinning, the last arriver is simply the one that finishes.
+//
 // Matrix instruction: v_mfma_f32_32x32x2_f32.  Lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; the 16 result registers of lane l hold column j = l%32 and rows
 // i = 8*(v/4) + 4*(l/32) + v%4.  Rows are nodes, columns are hidden units, so stores are
@@ -23,6 +29,10 @@
 // with one 16-byte LDS read and feeds them to four instructions; lanes 32..63 take the
 // upper four k of an 8-k group, which is just a permutation of the summation order applied
 // to both operands alike.
+//
+// Workgroup order: the j tile is the fastest index of the linear workgroup id.  Workgroups
+// go round-robin to the 8 XCDs, so with 8 or 16 j tiles every XCD only ever touches the
+// weight rows of one or two j tiles and keeps them in its own L2 for the whole level.
 #include "cell_kernels.h"
 
 namespace acrobat {
@@ -32,8 +42,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kBK = 32;        // k columns per slab
-constexpr int kLdT = kBK + 4;  // LDS row stride (floats): 16-byte aligned, conflict-free b128 reads
 constexpr int kThreads = 256;
+constexpr int kBlockFloats = 16 * 64;  // one 32x32 accumulator block of one wavefront
 
 __device__ __forceinline__ float fast_sigmoid(float x) {
   return __builtin_amdgcn_rcpf(1.0f + __expf(-x));  // exp -> inf gives 0, exp -> 0 gives 1
@@ -49,22 +59,27 @@ __device__ __forceinline__ constexpr int gate_row(int g) {
 }
 
 template <int G, int EPI, int WM, int WK>
-__global__ __launch_bounds__(kThreads) void cell_level_kernel(const CellLevelArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelArgs a, const int ksplit,
+                                                              float* __restrict__ partial,
+                                                              unsigned* __restrict__ counters) {
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
   constexpr int BM = 32 * WM;
   constexpr int BROWS = 32 * G;
-  constexpr int TILE_FLOATS = (BM + BROWS) * kLdT;
-  constexpr int RED_FLOATS = WK > 1 ? WM * G * 16 * 64 : 0;
-  constexpr int SMEM_FLOATS = TILE_FLOATS > RED_FLOATS ? TILE_FLOATS : RED_FLOATS;
+  constexpr int Q = 4 / WK;  // 8-k groups of a slab handled by one wavefront
+  constexpr int TILE_FLOATS = (BM + BROWS) * kBK;
+  constexpr int RED_FLOATS = WK > 1 ? WM * G * kBlockFloats : 0;
+  constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
+  constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
   __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
-  float* As = smem;
-  float* Bs = smem + BM * kLdT;
+  __shared__ int s_is_last;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wk = wave / WM;
   const int H = a.H, n = a.n;
   const int n_jt = H >> 5;
-  const int jt = blockIdx.x % n_jt, mt = blockIdx.x / n_jt;
+  const int jt = blockIdx.x % n_jt;
+  const int rest = blockIdx.x / n_jt;
+  const int ks = rest % ksplit, mt = rest / ksplit;
   const int j0 = jt * 32, m0 = mt * BM;
 
   // ---- global -> LDS staging assignment: 16-byte chunk `tid & 7` of tile row `tid >> 3` (+32 i)
@@ -85,10 +100,9 @@ __global__ __launch_bounds__(kThreads) void cell_level_kernel(const CellLevelArg
       aptr1[i] = a.src1 + r1 * (size_t)a.ld1 + lpart;
     }
   }
-  const float* bptr[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-    bptr[g] = a.W + (size_t)(gate_row<EPI>(g) * H + j0 + lrow) * (size_t)a.ldw + lpart;
+  // weights: one per-lane offset; gate and slab offsets are uniform (fit 32 bits: host-checked)
+  const unsigned boff = (unsigned)(j0 + lrow) * (unsigned)a.ldw + (unsigned)lpart;
+  const unsigned gate_stride = (unsigned)H * (unsigned)a.ldw;
 
   floatx16 acc[G];
 #pragma unroll
@@ -97,143 +111,355 @@ __global__ __launch_bounds__(kThreads) void cell_level_kernel(const CellLevelArg
     for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 
   const int slabs_per_seg = a.kseg / kBK;
-  const int n_slabs = a.nseg * slabs_per_seg;
+  const int my_slabs = (a.nseg * slabs_per_seg) / ksplit;  // host guarantees divisibility
+  const int slab0 = ks * my_slabs;
 
-  floatx4 ra[WM], rb[G];
-  auto load_slab = [&](int kb) {
+  // Software pipeline, written so that one wavefront per SIMD can keep the matrix pipe busy
+  // and two workgroups fit a compute unit (<= 80 KB LDS, <= 256 registers):
+  //  * global -> registers: NS staging sets hold slabs in flight;
+  //  * registers -> LDS: slab buffers of 32 floats per row without padding; the 16-byte chunk
+  //    c of row r sits at chunk position c ^ ((r >> 1) & 7), which makes both the row-wise
+  //    stores and the column-wise 16-byte operand reads free of bank conflicts;
+  //  * LDS -> operand registers: two fragment sets, the fragments of the next 8-k group are
+  //    read while the matrix instructions of the current group issue.
+  // Q == 1 (each wavefront has one group per slab): three buffers - read / complete / being
+  // filled - and one barrier at the end of a slab.  Q >= 2: two buffers; slab kb+1 is written
+  // during the first group of slab kb, the barrier sits before the LAST group of slab kb, and
+  // that group's shadow hides the first operand read of slab kb+1.
+  // Inside a group none of the memory instructions depends on the matrix instructions, and
+  // the scheduling hints interleave them one to one.  Slab indices past the end are clamped:
+  // the last slab is fetched again into a buffer nothing reads, so the loop has no branches.
+  constexpr int NS = WM == 1 ? 4 : 2;
+  constexpr int AHEAD = Q == 1 ? 2 : 1;  // a slab is stored to LDS AHEAD iterations before its use
+  floatx4 ra[NS][WM], rb[NS][G];
+  floatx4 fa[2], fb[2][G];
+  auto load_slab = [&](int set, int i) {
+    const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
     const int seg = kb >= slabs_per_seg;
     const int koff = (kb - (seg ? slabs_per_seg : 0)) * kBK;
 #pragma unroll
-    for (int i = 0; i < WM; ++i)
-      ra[i] = *reinterpret_cast<const floatx4*>((seg ? aptr1[i] : aptr0[i]) + koff);
-#pragma unroll
-    for (int g = 0; g < G; ++g) rb[g] = *reinterpret_cast<const floatx4*>(bptr[g] + kb * kBK);
-  };
-  auto store_slab = [&]() {
-#pragma unroll
-    for (int i = 0; i < WM; ++i)
-      *reinterpret_cast<floatx4*>(&As[(lrow + 32 * i) * kLdT + lpart]) = ra[i];
+    for (int r = 0; r < WM; ++r)
+      ra[set][r] = *reinterpret_cast<const floatx4*>((seg ? aptr1[r] : aptr0[r]) + koff);
 #pragma unroll
     for (int g = 0; g < G; ++g)
-      *reinterpret_cast<floatx4*>(&Bs[(lrow + 32 * g) * kLdT + lpart]) = rb[g];
+      rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
   };
-
-  if (n_slabs > 0) {
-    load_slab(0);
-    store_slab();
-    __syncthreads();
-    const int frag = (lane & 31) * kLdT + (lane >> 5) * 4;
-    for (int kb = 0; kb < n_slabs; ++kb) {
-      if (kb + 1 < n_slabs) load_slab(kb + 1);
+  const int st_off = lrow * kBK + (((tid & 7) ^ ((lrow >> 1) & 7)) << 2);
+  auto store_slab = [&](int set, int buf) {
+    float* As = smem + buf * TILE_FLOATS;
+    float* Bs = As + BM * kBK;
 #pragma unroll
-      for (int q = 0; q < 4 / WK; ++q) {
-        const int kk = wk * (4 / WK) + q;  // 8-k group of the slab handled by this wavefront
-        const floatx4 av = *reinterpret_cast<const floatx4*>(&As[wm * 32 * kLdT + frag + kk * 8]);
+    for (int r = 0; r < WM; ++r) *reinterpret_cast<floatx4*>(&As[32 * r * kBK + st_off]) = ra[set][r];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-          const floatx4 bv = *reinterpret_cast<const floatx4*>(&Bs[g * 32 * kLdT + frag + kk * 8]);
+    for (int g = 0; g < G; ++g) *reinterpret_cast<floatx4*>(&Bs[32 * g * kBK + st_off]) = rb[set][g];
+  };
+  int fr_off[Q];  // operand fragment of group q: row lane%32, chunk 2*(wk*Q + q) + lane/32
 #pragma unroll
-          for (int s = 0; s < 4; ++s)
-            acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[s], bv[s], acc[g], 0, 0, 0);
+  for (int q = 0; q < Q; ++q)
+    fr_off[q] = (lane & 31) * kBK + (((2 * (wk * Q + q) + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 2);
+  auto read_frag = [&](int fset, int buf, int q) {
+    const float* As = smem + buf * TILE_FLOATS;
+    const float* Bs = As + BM * kBK;
+    fa[fset] = *reinterpret_cast<const floatx4*>(&As[wm * 32 * kBK + fr_off[q]]);
+#pragma unroll
+    for (int g = 0; g < G; ++g) fb[fset][g] = *reinterpret_cast<const floatx4*>(&Bs[g * 32 * kBK + fr_off[q]]);
+  };
+  auto mfma_group = [&](int fset) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+      for (int g = 0; g < G; ++g)  // G independent accumulators between dependent issues
+        acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[fset][s], fb[fset][g][s], acc[g], 0, 0, 0);
+  };
+  // one slab; `set` = (kb + AHEAD) % NS is the staging set that holds slab kb + AHEAD,
+  // `par` = kb & 1 the fragment set when Q == 1, `bc` = kb % NBUF the buffer of slab kb
+  auto iteration = [&](int kb, int set, int par, int bc) {
+    const int b_next = bc + 1 == NBUF ? 0 : bc + 1;
+    const int b_fill = Q == 1 ? (bc == 0 ? 2 : bc - 1) : b_next;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+      const int fcur = Q == 1 ? par : (q & 1);
+      if (Q > 1 && q == Q - 1) __syncthreads();  // slab kb + 1 is complete in b_next
+      if (q + 1 < Q) read_frag(fcur ^ 1, bc, q + 1);
+      else read_frag(fcur ^ 1, b_next, 0);
+      if (q == 0) {
+        store_slab(set, b_fill);  // slab kb + AHEAD
+        load_slab(set, kb + AHEAD + NS);
+      }
+      mfma_group(fcur);
+      // interleave: one memory instruction after each matrix instruction
+      constexpr int n_mfma = 4 * G, n_rd = 1 + G, n_st = WM + G;
+      constexpr int w = n_st > (n_mfma - n_rd) / 2 ? 2 : 1;
+#pragma unroll
+      for (int i = 0; i < n_rd; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // DS read
+      }
+      if (q == 0) {
+#pragma unroll
+        for (int i = 0; i < (n_st + w - 1) / w; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x200, w, 0);  // DS write
+        }
+#pragma unroll
+        for (int i = 0; i < (n_st + w - 1) / w; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x020, w, 0);  // VMEM read
         }
       }
-      __syncthreads();  // everyone is done reading this slab
-      if (kb + 1 < n_slabs) {
-        store_slab();
+      constexpr int rest0 = n_mfma - n_rd - 2 * ((n_st + w - 1) / w), rest = n_mfma - n_rd;
+      static_assert(rest0 >= 0, "more memory slots than matrix instructions");
+      if (q == 0) {
+        if (rest0 > 0) __builtin_amdgcn_sched_group_barrier(0x008, rest0, 0);  // the remaining MFMAs
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x008, rest, 0);
+      }
+    }
+    if (Q == 1) __syncthreads();
+  };
+
+  if (my_slabs > 0) {
+    // slabs 0 .. AHEAD-1 go to LDS now, slabs AHEAD .. AHEAD+NS-1 into the staging sets
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) load_slab(i, i);
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i) store_slab(i, i);
+#pragma unroll
+    for (int i = 0; i < NS; ++i) load_slab((AHEAD + i) % NS, AHEAD + i);
+    __syncthreads();
+    read_frag(0, 0, 0);
+    int kb = 0, bc = 0;
+    for (; kb + NS <= my_slabs; kb += NS) {
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        iteration(kb + i, (i + AHEAD) % NS, i & 1, bc);
+        bc = bc + 1 == NBUF ? 0 : bc + 1;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) {
+      if (kb + i < my_slabs) {
+        iteration(kb + i, (i + AHEAD) % NS, i & 1, bc);
+        bc = bc + 1 == NBUF ? 0 : bc + 1;
+      }
+    }
+    if (Q > 1) __syncthreads();  // the last group's barrier pairs: LDS is reused by the reductions
+  }
+
+  // sums the partial tiles of the WK wavefronts of a node block into its wk == 0 wavefront
+  // (fixed order wk = 1, 2, ...)
+  auto reduce_over_wk = [&]() {
+    if constexpr (WK > 1) {
+      float* red = smem + wm * (G * kBlockFloats);
+      for (int r = 1; r < WK; ++r) {
         __syncthreads();
+        if (wk == r) {
+#pragma unroll
+          for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[(g * 16 + v) * 64 + lane] = acc[g][v];
+        }
+        __syncthreads();
+        if (wk == 0) {
+#pragma unroll
+          for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[g][v] += red[(g * 16 + v) * 64 + lane];
+        }
       }
     }
-  }
+  };
+  reduce_over_wk();
 
-  // ---- sum the k-split partial tiles into the wk == 0 wavefront of each node block
-  if constexpr (WK > 1) {
-    float* red = smem + wm * (G * 16 * 64);
-    for (int r = 1; r < WK; ++r) {
-      __syncthreads();
-      if (wk == r) {
+  // ---- k split over workgroups: publish the partial tile; the last arriver reduces
+  if (ksplit > 1) {
+    const int tile = mt * n_jt + jt;
+    float* mine = partial + ((size_t)(tile * ksplit + ks) * WM + wm) * (G * kBlockFloats);
+    if (wk == 0) {
 #pragma unroll
-        for (int g = 0; g < G; ++g)
+      for (int g = 0; g < G; ++g)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) red[(g * 16 + v) * 64 + lane] = acc[g][v];
-      }
-      __syncthreads();
-      if (wk == 0) {
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[g][v] += red[(g * 16 + v) * 64 + lane];
-      }
+        for (int v = 0; v < 16; ++v) mine[(g * 16 + v) * 64 + lane] = acc[g][v];
     }
-    if (wk != 0) return;
+    __threadfence();  // release: partial tile visible device-wide before the counter moves
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned prev = atomicAdd(&counters[tile], 1u);
+      const int last = prev == (unsigned)(ksplit - 1);
+      if (last) counters[tile] = 0u;  // every arrival is in: leave the counter ready for the next launch
+      s_is_last = last;
+    }
+    __syncthreads();
+    if (!s_is_last) return;
+    __threadfence();  // acquire: the other workgroups' partial tiles
+    // wavefront (wm, wk) sums the partial tiles wk, wk + WK, ... (own workgroup's included, so
+    // the order is the same whoever arrives last), then the WK sums are combined as above
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
+    for (int s = wk; s < ksplit; s += WK) {
+      const float* p = partial + ((size_t)(tile * ksplit + s) * WM + wm) * (G * kBlockFloats);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[g][v] += p[(g * 16 + v) * 64 + lane];
+    }
+    reduce_over_wk();
   }
+  if (wk != 0) return;
 
-  // ---- fused epilogue: bias, gates, state update, scatter to the arena
+  // ---- fused epilogue: bias, gates, state update, scatter to the arena.
+  // Three passes over the 16 accumulator rows of a lane - indices, then every gathered
+  // operand, then arithmetic and stores - so that all loads of a pass are in flight together
+  // instead of one dependent chain per row (the stores may alias the loads as far as the
+  // compiler can tell, which would otherwise serialise the rows).
   const int j = j0 + (lane & 31);
   float bz[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
 
+  size_t orow[16];
+  int ia[16], ib[16];
+  bool live[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int node = m0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-    if (node >= n) continue;
-    const size_t orow = a.out_rows ? (size_t)a.out_rows[node] : (size_t)node;
-    float z[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) z[g] = acc[g][v] + bz[g];
+    live[v] = node < n;
+    const int nd = live[v] ? node : n - 1;  // tail rows read what the last node reads, store nothing
+    orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
+    ia[v] = ib[v] = 0;
+    if constexpr (EPI == EPI_TREE_INTERNAL) {
+      ia[v] = a.idx0[nd];
+      ib[v] = a.idx1[nd];
+    }
+    if constexpr (EPI == EPI_LSTM_STEP) {
+      if (a.cprev_src) ia[v] = a.idx0[nd];
+    }
+  }
 
-    if constexpr (EPI == EPI_STORE_Z) {
+  if constexpr (EPI == EPI_STORE_Z) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) a.zout[orow * (size_t)(G * H) + g * H + j] = z[g];
-    } else if constexpr (EPI == EPI_TREE_LEAF) {
-      const float c = fast_sigmoid(z[0]) * fast_tanh(z[2]);
-      a.c[orow * H + j] = c;
-      a.h[orow * H + j] = fast_sigmoid(z[1]) * fast_tanh(c);
-    } else if constexpr (EPI == EPI_TREE_INTERNAL) {
-      const float cl = a.cprev_src[(size_t)a.idx0[node] * H + j];
-      const float cr = a.cprev_src[(size_t)a.idx1[node] * H + j];
-      const float c = fast_sigmoid(z[0]) * fast_tanh(z[4]) + fast_sigmoid(z[1]) * cl +
-                      fast_sigmoid(z[2]) * cr;
-      a.c[orow * H + j] = c;
-      a.h[orow * H + j] = fast_sigmoid(z[3]) * fast_tanh(c);
-    } else {  // EPI_LSTM_STEP
+    for (int v = 0; v < 16; ++v) {
+      if (!live[v]) continue;
 #pragma unroll
-      for (int g = 0; g < G; ++g) z[g] += a.zadd[orow * (size_t)(G * H) + g * H + j];
-      const float cp = a.cprev_src ? a.cprev_src[(size_t)a.idx0[node] * H + j] : 0.0f;
-      const float c = fast_sigmoid(z[1]) * cp + fast_sigmoid(z[0]) * fast_tanh(z[3]);
-      a.c[orow * H + j] = c;
-      a.h[orow * H + j] = fast_sigmoid(z[2]) * fast_tanh(c);
+      for (int g = 0; g < G; ++g) a.zout[orow[v] * (size_t)(G * H) + g * H + j] = acc[g][v] + bz[g];
+    }
+  } else if constexpr (EPI == EPI_TREE_LEAF) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (!live[v]) continue;
+      const float c = fast_sigmoid(acc[0][v] + bz[0]) * fast_tanh(acc[2][v] + bz[2]);
+      a.c[orow[v] * H + j] = c;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc[1][v] + bz[1]) * fast_tanh(c);
+    }
+  } else if constexpr (EPI == EPI_TREE_INTERNAL) {
+    float cl[16], cr[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      cl[v] = a.cprev_src[(size_t)ia[v] * H + j];
+      cr[v] = a.cprev_src[(size_t)ib[v] * H + j];
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (!live[v]) continue;
+      const float c = fast_sigmoid(acc[0][v] + bz[0]) * fast_tanh(acc[4][v] + bz[4]) +
+                      fast_sigmoid(acc[1][v] + bz[1]) * cl[v] + fast_sigmoid(acc[2][v] + bz[2]) * cr[v];
+      a.c[orow[v] * H + j] = c;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc[3][v] + bz[3]) * fast_tanh(c);
+    }
+  } else {  // EPI_LSTM_STEP
+    float cp[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      cp[v] = a.cprev_src ? a.cprev_src[(size_t)ia[v] * H + j] : 0.0f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) acc[g][v] += a.zadd[orow[v] * (size_t)(G * H) + g * H + j];
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (!live[v]) continue;
+      const float c = fast_sigmoid(acc[1][v] + bz[1]) * cp[v] +
+                      fast_sigmoid(acc[0][v] + bz[0]) * fast_tanh(acc[3][v] + bz[3]);
+      a.c[orow[v] * H + j] = c;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc[2][v] + bz[2]) * fast_tanh(c);
     }
   }
 }
 
-template <int G, int EPI>
-hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream) {
+struct Shape {
+  int bm, ksplit;
+};
+
+// Picks the node-tile height and the k split for a level from a small cost model.
+template <int G>
+Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   const int n_jt = a.H / 32;
-  // largest node tile that still gives the 256 compute units at least one workgroup each
-  auto wgs = [&](int bm) { return (long)((a.n + bm - 1) / bm) * n_jt; };
-  if (wgs(128) >= 256) {
-    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3((unsigned)wgs(128)), dim3(kThreads), 0,
-                       stream, a);
-  } else if (wgs(64) >= 256) {
-    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3((unsigned)wgs(64)), dim3(kThreads), 0,
-                       stream, a);
+  const int n_slabs = a.nseg * (a.kseg / kBK);
+  auto fits = [&](int bm, int s) {
+    if (s < 1 || s > 32 || (s & (s - 1))) return false;
+    if (s == 1) return true;
+    if (n_slabs == 0 || n_slabs % s != 0) return false;
+    const long tiles = (long)((a.n + bm - 1) / bm) * n_jt;
+    return tiles <= ws.n_counters && (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
+  };
+  if (ws.force_bm == 128 || ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
+    Shape f{ws.force_bm, ws.force_ksplit > 0 ? ws.force_ksplit : 1};
+    if (fits(f.bm, f.ksplit)) return f;
+  }
+  // Measured on MI355X (H = 512, five gates): a workgroup alone on its compute unit takes about
+  // 8 us + 0.6 us * bm * (slabs / 32); the 256 units work through ceil(workgroups / 256) such
+  // rounds (two resident workgroups share one matrix pipe), and smaller tiles pay for their
+  // larger operand traffic.  Splitting k over workgroups costs a device-wide release/acquire
+  // per workgroup (~9 us), which only pays for the very smallest levels.
+  Shape best{32, 1};
+  double best_cost = 1e300;
+  const int bms[3] = {128, 64, 32};
+  for (int bm : bms) {
+    const long tiles = (long)((a.n + bm - 1) / bm) * n_jt;
+    const double rounds = (double)((tiles + 255) / 256);
+    const double traffic = bm == 128 ? 1.0 : bm == 64 ? 1.08 : 1.25;
+    const double cost = 8.0 + 0.6 * bm * traffic * rounds * (n_slabs / 32.0) * (G / 5.0);
+    if (cost < best_cost * 0.999) {
+      best_cost = cost;
+      best = Shape{bm, 1};
+    }
+  }
+  if (best.bm == 32 && a.n <= 48 && n_slabs >= 16 && fits(32, 4)) best.ksplit = 4;
+  return best;
+}
+
+template <int G, int EPI>
+hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitKWorkspace& ws,
+                        int32_t* tile, int32_t* ksplit) {
+  const Shape sh = pick_shape<G>(a, ws);
+  const int n_jt = a.H / 32;
+  const unsigned grid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
+  if (tile) *tile = sh.bm;
+  if (ksplit) *ksplit = sh.ksplit;
+  if (sh.bm == 128) {
+    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
+                       ws.partial, ws.counters);
+  } else if (sh.bm == 64) {
+    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
+                       ws.partial, ws.counters);
   } else {
-    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3((unsigned)wgs(32)), dim3(kThreads), 0,
-                       stream, a);
+    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
+                       ws.partial, ws.counters);
   }
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream) {
+hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,
+                             const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit) {
   if (a.n <= 0) return hipSuccess;
   switch (epi) {
-    case EPI_TREE_LEAF: return launch_shape<3, EPI_TREE_LEAF>(a, stream);
-    case EPI_TREE_INTERNAL: return launch_shape<5, EPI_TREE_INTERNAL>(a, stream);
-    case EPI_LSTM_STEP: return launch_shape<4, EPI_LSTM_STEP>(a, stream);
-    case EPI_STORE_Z: return launch_shape<4, EPI_STORE_Z>(a, stream);
+    case EPI_TREE_LEAF: return launch_shape<3, EPI_TREE_LEAF>(a, stream, ws, tile, ksplit);
+    case EPI_TREE_INTERNAL: return launch_shape<5, EPI_TREE_INTERNAL>(a, stream, ws, tile, ksplit);
+    case EPI_LSTM_STEP: return launch_shape<4, EPI_LSTM_STEP>(a, stream, ws, tile, ksplit);
+    case EPI_STORE_Z: return launch_shape<4, EPI_STORE_Z>(a, stream, ws, tile, ksplit);
   }
   return hipErrorInvalidValue;
 }

@@ -101,27 +101,15 @@ int reserve_scratch(acrobat_ctx* ctx, size_t n_floats) {
   return ACROBAT_OK;
 }
 
-// Partial-tile workspace: 32 MiB of partial accumulators and 16 Ki arrival counters.  Counters
-// start at zero and every launch leaves them at zero.
+// Partial-tile workspace of the k-split levels: 32 MiB.
 int reserve_splitk(acrobat_ctx* ctx) {
   if (ctx->splitk.partial) return ACROBAT_OK;
   constexpr size_t kPartialFloats = (size_t)8 << 20;
-  constexpr int32_t kCounters = 16384;
   float* p = nullptr;
-  unsigned* c = nullptr;
   HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
-  hipError_t e = hipMalloc(reinterpret_cast<void**>(&c), kCounters * sizeof(unsigned));
-  if (e == hipSuccess) e = hipMemset(c, 0, kCounters * sizeof(unsigned));
-  if (e != hipSuccess) {
-    (void)hipFree(p);
-    if (c) (void)hipFree(c);
-    return fail_hip(ctx, e, "split-k workspace");
-  }
   ctx->splitk.partial = p;
   ctx->splitk.partial_floats = kPartialFloats;
-  ctx->splitk.counters = c;
-  ctx->splitk.n_counters = kCounters;
-  // tuning override for experiments: ACROBAT_FORCE_TILE=128|64|32, ACROBAT_FORCE_KSPLIT=1..32
+  // tuning override for experiments: ACROBAT_FORCE_TILE=128|64|32|16, ACROBAT_FORCE_KSPLIT=1..32
   if (const char* v = std::getenv("ACROBAT_FORCE_TILE")) ctx->splitk.force_bm = std::atoi(v);
   if (const char* v = std::getenv("ACROBAT_FORCE_KSPLIT")) ctx->splitk.force_ksplit = std::atoi(v);
   return ACROBAT_OK;
@@ -212,7 +200,6 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->d_idx) (void)hipFree(ctx->d_idx);
   if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
-  if (ctx->splitk.counters) (void)hipFree(ctx->splitk.counters);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);

@@ -35,12 +35,11 @@ struct CellLevelArgs {
 };
 
 // Device workspace for levels whose k range is split over several workgroups: partial
-// accumulator tiles and one arrival counter per output tile (all zero between launches).
+// accumulator tiles, written by the contraction kernel and summed by the reduction kernel
+// that follows it on the stream.
 struct SplitKWorkspace {
   float* partial = nullptr;
   size_t partial_floats = 0;
-  unsigned* counters = nullptr;
-  int32_t n_counters = 0;
   int32_t force_bm = 0, force_ksplit = 0;  // tuning override, 0 = automatic
 };
 

@@ -58,10 +58,90 @@ __device__ __forceinline__ constexpr int gate_row(int g) {
   return EPI == EPI_TREE_LEAF ? (g == 0 ? 0 : g + 2) : g;  // leaf: i, o, u = blocks 0, 3, 4
 }
 
+// Fused epilogue of one lane: bias, gates, state update, scatter to the arena, for NV
+// accumulator rows (node_of(v)) of hidden unit j; acc(g, v) is the pre-activation of gate g.
+// Three passes - indices, then every gathered operand, then arithmetic and stores - so that
+// all loads of a pass are in flight together instead of one dependent chain per row (the
+// stores may alias the loads as far as the compiler can tell, which would otherwise serialise
+// the rows).
+template <int G, int EPI, int NV, class Acc, class NodeOf>
+__device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int j, Acc&& acc, NodeOf&& node_of) {
+  const int H = a.H, n = a.n;
+  float bz[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
+
+  size_t orow[NV];
+  int ia[NV], ib[NV];
+  bool live[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    const int node = node_of(v);
+    live[v] = node < n;
+    const int nd = live[v] ? node : n - 1;  // tail rows read what the last node reads, store nothing
+    orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
+    ia[v] = ib[v] = 0;
+    if constexpr (EPI == EPI_TREE_INTERNAL) {
+      ia[v] = a.idx0[nd];
+      ib[v] = a.idx1[nd];
+    }
+    if constexpr (EPI == EPI_LSTM_STEP) {
+      if (a.cprev_src) ia[v] = a.idx0[nd];
+    }
+  }
+
+  if constexpr (EPI == EPI_STORE_Z) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      if (!live[v]) continue;
+#pragma unroll
+      for (int g = 0; g < G; ++g) a.zout[orow[v] * (size_t)(G * H) + g * H + j] = acc(g, v) + bz[g];
+    }
+  } else if constexpr (EPI == EPI_TREE_LEAF) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      if (!live[v]) continue;
+      const float c = fast_sigmoid(acc(0, v) + bz[0]) * fast_tanh(acc(2, v) + bz[2]);
+      a.c[orow[v] * H + j] = c;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc(1, v) + bz[1]) * fast_tanh(c);
+    }
+  } else if constexpr (EPI == EPI_TREE_INTERNAL) {
+    float cl[NV], cr[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      cl[v] = a.cprev_src[(size_t)ia[v] * H + j];
+      cr[v] = a.cprev_src[(size_t)ib[v] * H + j];
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      if (!live[v]) continue;
+      const float c = fast_sigmoid(acc(0, v) + bz[0]) * fast_tanh(acc(4, v) + bz[4]) +
+                      fast_sigmoid(acc(1, v) + bz[1]) * cl[v] + fast_sigmoid(acc(2, v) + bz[2]) * cr[v];
+      a.c[orow[v] * H + j] = c;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc(3, v) + bz[3]) * fast_tanh(c);
+    }
+  } else {  // EPI_LSTM_STEP
+    float cp[NV], zx[G][NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      cp[v] = a.cprev_src ? a.cprev_src[(size_t)ia[v] * H + j] : 0.0f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) zx[g][v] = a.zadd[orow[v] * (size_t)(G * H) + g * H + j];
+    }
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      if (!live[v]) continue;
+      const float c = fast_sigmoid(acc(1, v) + zx[1][v] + bz[1]) * cp[v] +
+                      fast_sigmoid(acc(0, v) + zx[0][v] + bz[0]) * fast_tanh(acc(3, v) + zx[3][v] + bz[3]);
+      a.c[orow[v] * H + j] = c;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc(2, v) + zx[2][v] + bz[2]) * fast_tanh(c);
+    }
+  }
+}
+
 template <int G, int EPI, int WM, int WK>
 __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelArgs a, const int ksplit,
-                                                              float* __restrict__ partial,
-                                                              unsigned* __restrict__ counters) {
+                                                                 float* __restrict__ partial) {
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
   constexpr int BM = 32 * WM;
   constexpr int BROWS = 32 * G;
@@ -71,7 +151,6 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
   constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
   __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
-  __shared__ int s_is_last;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wk = wave / WM;
@@ -271,120 +350,52 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   };
   reduce_over_wk();
 
-  // ---- k split over workgroups: publish the partial tile; the last arriver reduces
+  if (wk != 0) return;
+
+  // ---- k split over workgroups: store the partial tile in register layout and stop; the
+  // reduction kernel that follows on the stream adds the partial tiles and runs the epilogue
   if (ksplit > 1) {
     const int tile = mt * n_jt + jt;
     float* mine = partial + ((size_t)(tile * ksplit + ks) * WM + wm) * (G * kBlockFloats);
-    if (wk == 0) {
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mine[(g * 16 + v) * 64 + lane] = acc[g][v];
-    }
-    __threadfence();  // release: partial tile visible device-wide before the counter moves
-    __syncthreads();
-    if (tid == 0) {
-      const unsigned prev = atomicAdd(&counters[tile], 1u);
-      const int last = prev == (unsigned)(ksplit - 1);
-      if (last) counters[tile] = 0u;  // every arrival is in: leave the counter ready for the next launch
-      s_is_last = last;
-    }
-    __syncthreads();
-    if (!s_is_last) return;
-    __threadfence();  // acquire: the other workgroups' partial tiles
-    // wavefront (wm, wk) sums the partial tiles wk, wk + WK, ... (own workgroup's included, so
-    // the order is the same whoever arrives last), then the WK sums are combined as above
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
-    for (int s = wk; s < ksplit; s += WK) {
-      const float* p = partial + ((size_t)(tile * ksplit + s) * WM + wm) * (G * kBlockFloats);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[g][v] += p[(g * 16 + v) * 64 + lane];
-    }
-    reduce_over_wk();
-  }
-  if (wk != 0) return;
-
-  // ---- fused epilogue: bias, gates, state update, scatter to the arena.
-  // Three passes over the 16 accumulator rows of a lane - indices, then every gathered
-  // operand, then arithmetic and stores - so that all loads of a pass are in flight together
-  // instead of one dependent chain per row (the stores may alias the loads as far as the
-  // compiler can tell, which would otherwise serialise the rows).
-  const int j = j0 + (lane & 31);
-  float bz[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
-
-  size_t orow[16];
-  int ia[16], ib[16];
-  bool live[16];
-#pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int node = m0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-    live[v] = node < n;
-    const int nd = live[v] ? node : n - 1;  // tail rows read what the last node reads, store nothing
-    orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
-    ia[v] = ib[v] = 0;
-    if constexpr (EPI == EPI_TREE_INTERNAL) {
-      ia[v] = a.idx0[nd];
-      ib[v] = a.idx1[nd];
-    }
-    if constexpr (EPI == EPI_LSTM_STEP) {
-      if (a.cprev_src) ia[v] = a.idx0[nd];
-    }
+      for (int v = 0; v < 16; ++v) mine[(g * 16 + v) * 64 + lane] = acc[g][v];
+    return;
   }
 
-  if constexpr (EPI == EPI_STORE_Z) {
+  // ---- fused epilogue (rows of lane: node = m0 + 32 wm + 8 (v / 4) + 4 (lane / 32) + v % 4)
+  cell_epilogue<G, EPI, 16>(
+      a, j0 + (lane & 31), [&](int g, int v) { return acc[g][v]; },
+      [&](int v) { return m0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3); });
+}
+
+// Second half of a level whose k range was split over `ksplit` workgroups: one wavefront per
+// (tile, node block, accumulator row v) adds the partial tiles in fixed order and runs the fused
+// epilogue.  The kernel boundary between the two launches is the only synchronisation: a
+// device-wide fence inside a kernel costs far more on this part (about 15 us with 256
+// workgroups) than a launch (about 3 us).
+template <int G, int EPI>
+__global__ __launch_bounds__(64) void cell_splitk_reduce_kernel(const CellLevelArgs a, const int ksplit, const int wm_count,
+                                                                const float* __restrict__ partial) {
+  const int lane = threadIdx.x;
+  const int v = blockIdx.x & 15;
+  const int rest = blockIdx.x >> 4;
+  const int wm = rest % wm_count, tile = rest / wm_count;
+  const int n_jt = a.H >> 5;
+  const int jt = tile % n_jt, mt = tile / n_jt;
+  float acc[G];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (!live[v]) continue;
+  for (int g = 0; g < G; ++g) acc[g] = 0.0f;
+#pragma unroll 4
+  for (int s = 0; s < ksplit; ++s) {
+    const float* p = partial + ((size_t)(tile * ksplit + s) * wm_count + wm) * (G * kBlockFloats) + v * 64 + lane;
 #pragma unroll
-      for (int g = 0; g < G; ++g) a.zout[orow[v] * (size_t)(G * H) + g * H + j] = acc[g][v] + bz[g];
-    }
-  } else if constexpr (EPI == EPI_TREE_LEAF) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (!live[v]) continue;
-      const float c = fast_sigmoid(acc[0][v] + bz[0]) * fast_tanh(acc[2][v] + bz[2]);
-      a.c[orow[v] * H + j] = c;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc[1][v] + bz[1]) * fast_tanh(c);
-    }
-  } else if constexpr (EPI == EPI_TREE_INTERNAL) {
-    float cl[16], cr[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      cl[v] = a.cprev_src[(size_t)ia[v] * H + j];
-      cr[v] = a.cprev_src[(size_t)ib[v] * H + j];
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (!live[v]) continue;
-      const float c = fast_sigmoid(acc[0][v] + bz[0]) * fast_tanh(acc[4][v] + bz[4]) +
-                      fast_sigmoid(acc[1][v] + bz[1]) * cl[v] + fast_sigmoid(acc[2][v] + bz[2]) * cr[v];
-      a.c[orow[v] * H + j] = c;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc[3][v] + bz[3]) * fast_tanh(c);
-    }
-  } else {  // EPI_LSTM_STEP
-    float cp[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      cp[v] = a.cprev_src ? a.cprev_src[(size_t)ia[v] * H + j] : 0.0f;
-#pragma unroll
-      for (int g = 0; g < G; ++g) acc[g][v] += a.zadd[orow[v] * (size_t)(G * H) + g * H + j];
-    }
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (!live[v]) continue;
-      const float c = fast_sigmoid(acc[1][v] + bz[1]) * cp[v] +
-                      fast_sigmoid(acc[0][v] + bz[0]) * fast_tanh(acc[3][v] + bz[3]);
-      a.c[orow[v] * H + j] = c;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc[2][v] + bz[2]) * fast_tanh(c);
-    }
+    for (int g = 0; g < G; ++g) acc[g] += p[g * kBlockFloats];
   }
+  const int node = mt * 32 * wm_count + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+  cell_epilogue<G, EPI, 1>(
+      a, jt * 32 + (lane & 31), [&](int g, int) { return acc[g]; }, [&](int) { return node; });
 }
 
 struct Shape {
@@ -401,31 +412,26 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
     if (s == 1) return true;
     if (n_slabs == 0 || n_slabs % s != 0) return false;
     const long tiles = (long)((a.n + bm - 1) / bm) * n_jt;
-    return tiles <= ws.n_counters && (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
+    return (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
   };
   if (ws.force_bm == 128 || ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
     Shape f{ws.force_bm, ws.force_ksplit > 0 ? ws.force_ksplit : 1};
     if (fits(f.bm, f.ksplit)) return f;
   }
-  // Measured on MI355X (H = 512, five gates): a workgroup alone on its compute unit takes about
-  // 8 us + 0.6 us * bm * (slabs / 32); the 256 units work through ceil(workgroups / 256) such
-  // rounds (two resident workgroups share one matrix pipe), and smaller tiles pay for their
-  // larger operand traffic.  Splitting k over workgroups costs a device-wide release/acquire
-  // per workgroup (~9 us), which only pays for the very smallest levels.
-  Shape best{32, 1};
-  double best_cost = 1e300;
-  const int bms[3] = {128, 64, 32};
-  for (int bm : bms) {
-    const long tiles = (long)((a.n + bm - 1) / bm) * n_jt;
-    const double rounds = (double)((tiles + 255) / 256);
-    const double traffic = bm == 128 ? 1.0 : bm == 64 ? 1.08 : 1.25;
-    const double cost = 8.0 + 0.6 * bm * traffic * rounds * (n_slabs / 32.0) * (G / 5.0);
-    if (cost < best_cost * 0.999) {
-      best_cost = cost;
-      best = Shape{bm, 1};
-    }
-  }
-  if (best.bm == 32 && a.n <= 48 && n_slabs >= 16 && fits(32, 4)) best.ksplit = 4;
+  // Rules fitted to sweeps on MI355X (TreeLSTM H = 512 and 256, LSTM H = 512):
+  //  * 64-node tiles for all but the smallest levels (128-node tiles leave too few workgroups
+  //    at these level sizes, 32-node tiles re-read the weights too often);
+  //  * one compute unit streams its operand slabs at only ~40 GB/s, so a level with fewer
+  //    tiles than compute units is latency bound: split k until about 256 workgroups exist
+  //    (at least 4 slabs each, at most 8 ways - the reduction kernel costs a launch, ~3 us,
+  //    and reads ksplit partial tiles);
+  //  * slightly more tiles than compute units: split in two for balance.
+  Shape best{a.n > 128 ? 64 : 32, 1};
+  const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
+  int s = 1;
+  while (s * 2 <= 8 && tiles * s * 2 <= 256 && n_slabs % (s * 2) == 0 && n_slabs / (s * 2) >= 4) s *= 2;
+  if (s == 1 && tiles > 256 && tiles <= 384 && n_slabs % 2 == 0 && n_slabs >= 8) s = 2;
+  if (fits(best.bm, s)) best.ksplit = s;
   return best;
 }
 
@@ -439,13 +445,19 @@ hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitK
   if (ksplit) *ksplit = sh.ksplit;
   if (sh.bm == 128) {
     hipLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
-                       ws.partial, ws.counters);
+                       ws.partial);
   } else if (sh.bm == 64) {
     hipLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
-                       ws.partial, ws.counters);
+                       ws.partial);
   } else {
     hipLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
-                       ws.partial, ws.counters);
+                       ws.partial);
+  }
+  if (sh.ksplit > 1) {
+    const int wm_count = sh.bm / 32;
+    const unsigned rgrid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * wm_count * 16);
+    hipLaunchKernelGGL((cell_splitk_reduce_kernel<G, EPI>), dim3(rgrid), dim3(64), 0, stream, a, sh.ksplit,
+                       wm_count, ws.partial);
   }
   return hipGetLastError();
 }

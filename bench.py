@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="only run one plain device-to-device copy of this many MiB (a kernel of known traffic "
+                         "for scaling hardware-counter readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (instances are independent, so more GPUs would "
@@ -48,6 +51,15 @@ def main():
     from workloads import make_config
 
     torch.cuda.set_device(0)
+    if args.copy_calibration_mib > 0:
+        n = args.copy_calibration_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_mib": args.copy_calibration_mib, "launches": 3}))
+        return
     w = make_config(args.config)
     kind = w["kind"]
     ctx = A.Context(0)

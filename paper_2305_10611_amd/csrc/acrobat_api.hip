@@ -101,10 +101,10 @@ int reserve_scratch(acrobat_ctx* ctx, size_t n_floats) {
   return ACROBAT_OK;
 }
 
-// Partial-tile workspace of the k-split levels: 32 MiB.
+// Partial-tile workspace of the k-split levels: 128 MiB.
 int reserve_splitk(acrobat_ctx* ctx) {
   if (ctx->splitk.partial) return ACROBAT_OK;
-  constexpr size_t kPartialFloats = (size_t)8 << 20;
+  constexpr size_t kPartialFloats = (size_t)32 << 20;
   float* p = nullptr;
   HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
   ctx->splitk.partial = p;

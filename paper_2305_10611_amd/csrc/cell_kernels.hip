@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   constexpr int BROWS = 32 * G;
   constexpr int Q = 4 / WK;  // 8-k groups of a slab handled by one wavefront
   constexpr int TILE_FLOATS = (BM + BROWS) * kBK;
-  constexpr int RED_FLOATS = WK > 1 ? WM * G * kBlockFloats : 0;
+  constexpr int RED_FLOATS = WM * (WK - 1) * G * kBlockFloats;
   constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
   constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
   __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
@@ -298,13 +298,15 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   };
 
   if (my_slabs > 0) {
-    // slabs 0 .. AHEAD-1 go to LDS now, slabs AHEAD .. AHEAD+NS-1 into the staging sets
+    // all NS staging sets are requested at once (slab i -> set i); slabs 0 .. AHEAD-1 then go
+    // to LDS and their sets are refilled with slabs NS .. NS+AHEAD-1
 #pragma unroll
-    for (int i = 0; i < AHEAD; ++i) load_slab(i, i);
+    for (int i = 0; i < NS; ++i) load_slab(i, i);
 #pragma unroll
-    for (int i = 0; i < AHEAD; ++i) store_slab(i, i);
-#pragma unroll
-    for (int i = 0; i < NS; ++i) load_slab((AHEAD + i) % NS, AHEAD + i);
+    for (int i = 0; i < AHEAD; ++i) {
+      store_slab(i, i);
+      load_slab(i, NS + i);
+    }
     __syncthreads();
     read_frag(0, 0, 0);
     int kb = 0, bc = 0;
@@ -326,25 +328,25 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   }
 
   // sums the partial tiles of the WK wavefronts of a node block into its wk == 0 wavefront
-  // (fixed order wk = 1, 2, ...)
+  // (fixed order wk = 1, 2, ...): one round through LDS
   auto reduce_over_wk = [&]() {
     if constexpr (WK > 1) {
-      float* red = smem + wm * (G * kBlockFloats);
-      for (int r = 1; r < WK; ++r) {
-        __syncthreads();
-        if (wk == r) {
+      float* red = smem + (wm * (WK - 1)) * (G * kBlockFloats);
+      __syncthreads();
+      if (wk > 0) {
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) red[(wk - 1) * (G * kBlockFloats) + (g * 16 + v) * 64 + lane] = acc[g][v];
+      }
+      __syncthreads();
+      if (wk == 0) {
+#pragma unroll
+        for (int r = 0; r < WK - 1; ++r)
 #pragma unroll
           for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[(g * 16 + v) * 64 + lane] = acc[g][v];
-        }
-        __syncthreads();
-        if (wk == 0) {
-#pragma unroll
-          for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[g][v] += red[(g * 16 + v) * 64 + lane];
-        }
+            for (int v = 0; v < 16; ++v) acc[g][v] += red[r * (G * kBlockFloats) + (g * 16 + v) * 64 + lane];
       }
     }
   };

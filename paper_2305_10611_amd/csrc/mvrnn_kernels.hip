@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void mvrnn_leaf_copy_kernel(int n, const int32
 hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile) {
   if (tile) *tile = 1;
   if (a.n <= 0) return hipSuccess;
-  const int grid = a.n < 1024 ? a.n : 1024;  // up to four resident workgroups per compute unit
+  const int grid = a.n < 512 ? a.n : 512;  // two resident workgroups per compute unit, each strides over the level
   hipLaunchKernelGGL(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, a);
   return hipGetLastError();
 }

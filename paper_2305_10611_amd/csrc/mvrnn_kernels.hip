@@ -19,8 +19,13 @@
 //    wavefront); the even columns feed one accumulator block and the odd columns another,
 //    so every lane ends up with adjacent output columns and stores them as one float2.
 //    The two k halves are summed through LDS.
-//  * the three small mat-vecs run on the vector ALUs: four lanes per output row, 16-wide
-//    partial dot products, quad reduction with lane shuffles.
+//  * B a and A b reuse the same registers: a wavefront holds its whole child matrix (64
+//    registers x 64 lanes), multiplies its two columns per row by the other child's vector
+//    and sums over the 32 lanes of a half wavefront with a reduce-scatter butterfly (16 rows
+//    per wavefront -> 16 exchanges instead of 16 x 5).  W [B a ; A b] runs on the vector
+//    ALUs, four lanes per output row.
+//  * the loop is software pipelined over nodes: the next node's indices and matrix loads
+//    are issued before the current node's matrix instructions.
 #include "cell_kernels.h"
 
 namespace acrobat {
@@ -32,6 +37,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kD = 64;
 constexpr int kDD = kD * kD;
+constexpr int kWld = 2 * kD + 4;  // LDS row stride of W
 
 __device__ __forceinline__ float fast_tanh(float x) {
   return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * x) + 1.0f);
@@ -43,10 +49,16 @@ __device__ __forceinline__ float quad_sum(float x) {
   return x;
 }
 
-__global__ __launch_bounds__(256) void mvrnn_level_kernel(const MvrnnLevelArgs a) {
-  __shared__ float s_ab[2 * kD];  // a | b
-  __shared__ float s_v[2 * kD];   // B a | A b
-  __shared__ float s_red[2][32 * 64];
+struct NodeRef {  // where one node's operands live and where its results go
+  const float* mat;  // this wavefront's child matrix (left child for kh = 0, right for kh = 1)
+  const float* vec;  // the OTHER child's vector
+  size_t orow;
+};
+
+__global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArgs a) {
+  __shared__ float s_v[2 * kD];  // B a | A b
+  __shared__ float s_red[2][2][16 * 64];  // [row block][k half of the writer][8 rows x even/odd x lane]
+  __shared__ __attribute__((aligned(16))) float s_W[kD * kWld];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int mb = wave & 1, kh = wave >> 1;
@@ -56,85 +68,149 @@ __global__ __launch_bounds__(256) void mvrnn_level_kernel(const MvrnnLevelArgs a
   float wm[32];  // W_M[32*mb + lcol][64*kh + 2s + lhi]
 #pragma unroll
   for (int s = 0; s < 32; ++s) wm[s] = a.WM[(mb * 32 + lcol) * (2 * kD) + kh * kD + 2 * s + lhi];
-  const int vr = tid >> 2, vq = tid & 3;  // mat-vec: output row, quarter of the columns
-  floatx4 wv[8];                          // W[vr][32*vq .. +31]
-#pragma unroll
-  for (int k = 0; k < 8; ++k)
-    wv[k] = *reinterpret_cast<const floatx4*>(a.W + vr * (2 * kD) + vq * 32 + k * 4);
+  const int vr = tid >> 2, vq = tid & 3;  // p = tanh(W v): output row, quarter of the columns
+  for (int i = tid; i < kD * 2 * kD / 4; i += 256) {  // W -> LDS (rows padded to 132 floats)
+    const int r = i >> 5, c4 = i & 31;
+    *reinterpret_cast<floatx4*>(&s_W[r * kWld + c4 * 4]) = *reinterpret_cast<const floatx4*>(a.W + r * (2 * kD) + c4 * 4);
+  }
 
-  for (int node = blockIdx.x; node < a.n; node += gridDim.x) {
-    const int ls = a.lsrc[node], rs = a.rsrc[node];
-    const size_t orow = (size_t)a.out_rows[node];
-    const float* va = ls >= 0 ? a.vec + (size_t)ls * kD : a.vec_tab + (size_t)(-(ls + 1)) * kD;
-    const float* mA = ls >= 0 ? a.mat + (size_t)ls * kDD : a.mat_tab + (size_t)(-(ls + 1)) * kDD;
-    const float* vb = rs >= 0 ? a.vec + (size_t)rs * kD : a.vec_tab + (size_t)(-(rs + 1)) * kD;
-    const float* mB = rs >= 0 ? a.mat + (size_t)rs * kDD : a.mat_tab + (size_t)(-(rs + 1)) * kDD;
-
-    // ---- matrix path: issue the operand loads first, they are the long latency
-    const float* X = (kh ? mB : mA) + lhi * kD + 2 * lcol;
-    floatx2 x[32];
+  struct RawIdx { int ls, rs, orow; };
+  // the index lists are only read in this kernel and `node` is uniform in the workgroup
+  const int32_t* __restrict__ lsrc = a.lsrc;
+  const int32_t* __restrict__ rsrc = a.rsrc;
+  const int32_t* __restrict__ orows = a.out_rows;
+  auto load_idx = [&](int node) {
+    const int u = __builtin_amdgcn_readfirstlane(node);
+    RawIdx r;
+    r.ls = lsrc[u];
+    r.rs = rsrc[u];
+    r.orow = orows[u];
+    return r;
+  };
+  auto resolve = [&](const RawIdx& i) {
+    const int ms = kh ? i.rs : i.ls, vs = kh ? i.ls : i.rs;
+    NodeRef r;
+    r.mat = ms >= 0 ? a.mat + (size_t)ms * kDD : a.mat_tab + (size_t)(-(ms + 1)) * kDD;
+    r.vec = vs >= 0 ? a.vec + (size_t)vs * kD : a.vec_tab + (size_t)(-(vs + 1)) * kD;
+    r.orow = (size_t)i.orow;
+    return r;
+  };
+  auto load_node = [&](const NodeRef& r, floatx2 (&x)[32], floatx2& vv) {
+    const float* X = r.mat + lhi * kD + 2 * lcol;
 #pragma unroll
     for (int s = 0; s < 32; ++s) x[s] = *reinterpret_cast<const floatx2*>(X + 2 * s * kD);
+    vv = *reinterpret_cast<const floatx2*>(r.vec + 2 * lcol);
+  };
 
-    // ---- vector path
-    if (tid < kD) s_ab[tid] = va[tid];
-    else if (tid < 2 * kD) s_ab[tid] = vb[tid - kD];
-    __syncthreads();
-    float s0 = 0.0f, s1 = 0.0f;
+  // one node: `x`, `vv` hold its operands; `xn`, `vvn` receive the next node's, whose indices
+  // (`raw`) were fetched one iteration ago; the indices of the node after that are fetched now
+  auto process = [&](int node, NodeRef& cur, RawIdx& raw, floatx2 (&x)[32], floatx2& vv, floatx2 (&xn)[32],
+                     floatx2& vvn) {
+    // (indices past the end are clamped to the last node: a harmless re-read keeps the loop body
+    // free of branches, so the compiler can leave these loads in flight)
+    const int next2 = min(node + 2 * (int)gridDim.x, a.n - 1);
+    // (opaque to the optimiser: nothing derived from these indices may be computed, and so
+    // waited for, before this point - they were requested a whole iteration ago)
+    asm volatile("" : "+v"(raw.ls), "+v"(raw.rs), "+v"(raw.orow));
+    const NodeRef nxt = resolve(raw);
+    raw = load_idx(next2);
+
+    // ---- mat-vec rows 2*(16 mb + i) + lhi, i < 16: partial over this lane's two columns,
+    // then reduce-scatter over the 32 lanes of the half wavefront
+    float v[16];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const floatx4 rb = *reinterpret_cast<const floatx4*>(mB + vr * kD + vq * 16 + k * 4);
-      const floatx4 ra = *reinterpret_cast<const floatx4*>(mA + vr * kD + vq * 16 + k * 4);
+    for (int i = 0; i < 16; ++i) {
+      const floatx2 xi = mb ? x[16 + i] : x[i];  // (a select, not a runtime register index)
+      v[i] = xi[0] * vv[0] + xi[1] * vv[1];
+    }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        s0 += rb[e] * s_ab[vq * 16 + k * 4 + e];
-        s1 += ra[e] * s_ab[kD + vq * 16 + k * 4 + e];
+    for (int half = 8, bit = 16; half >= 1; half >>= 1, bit >>= 1) {
+      const bool up = (lcol & bit) != 0;  // upper lanes keep the upper half of the rows
+#pragma unroll
+      for (int i = 0; i < half; ++i) {
+        const float send = up ? v[i] : v[i + half];
+        const float keep = up ? v[i + half] : v[i];
+        v[i] = keep + __shfl_xor(send, bit);
       }
     }
-    s0 = quad_sum(s0);
-    s1 = quad_sum(s1);
-    if (vq == 0) {
-      s_v[vr] = s0;
-      s_v[kD + vr] = s1;
-    }
-    __syncthreads();
-    float t = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) t += wv[k][e] * s_v[vq * 32 + k * 4 + e];
-    t = quad_sum(t);
-    if (vq == 0) a.vec[orow * kD + vr] = fast_tanh(t);
+    v[0] += __shfl_xor(v[0], 1);  // lanes 2i, 2i+1 both hold row i's sum now
+    if ((lcol & 1) == 0) s_v[(kh ? 0 : kD) + 2 * (16 * mb + (lcol >> 1)) + lhi] = v[0];
 
-    // ---- matrix path: 32 k-steps of two 32x32 blocks (even / odd output columns)
+    // ---- next node's operands: in flight during this node's matrix instructions
+    load_node(nxt, xn, vvn);
+
+    // ---- P: 32 k-steps of two 32x32 blocks (even / odd output columns)
     floatx16 acc_e, acc_o;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc_e[v] = acc_o[v] = 0.0f;
+    for (int q = 0; q < 16; ++q) acc_e[q] = acc_o[q] = 0.0f;
 #pragma unroll
     for (int s = 0; s < 32; ++s) {
       acc_e = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], x[s][0], acc_e, 0, 0, 0);
       acc_o = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], x[s][1], acc_o, 0, 0, 0);
     }
-    if (kh == 1) {
+    // the 33 operand loads of the next node go out first, one per matrix instruction
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        s_red[mb][(2 * v) * 64 + lane] = acc_e[v];
-        s_red[mb][(2 * v + 1) * 64 + lane] = acc_o[v];
-      }
+    for (int i = 0; i < 33; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // VMEM read
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
     }
-    __syncthreads();
-    if (kh == 0) {
-      float* P = a.mat + orow * kDD;
+    __builtin_amdgcn_sched_group_barrier(0x008, 31, 0);
+    // the two k halves exchange half of their accumulator rows through LDS (kh = 0 hands over
+    // rows q >= 8, kh = 1 rows q < 8), so both finish and store 8 rows: the same number of
+    // stores on every wavefront keeps the memory counters of the two paths alike
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = mb * 32 + (v >> 2) * 8 + lhi * 4 + (v & 3);
-        floatx2 o;
-        o[0] = acc_e[v] + s_red[mb][(2 * v) * 64 + lane];
-        o[1] = acc_o[v] + s_red[mb][(2 * v + 1) * 64 + lane];
+    for (int q = 0; q < 8; ++q) {
+      const int qs = kh ? q : q + 8;
+      s_red[mb][kh][(2 * q) * 64 + lane] = kh ? acc_e[q] : acc_e[q + 8];
+      s_red[mb][kh][(2 * q + 1) * 64 + lane] = kh ? acc_o[q] : acc_o[q + 8];
+      (void)qs;
+    }
+    __syncthreads();  // s_v and s_red complete
+
+    // ---- p = tanh(W [B a ; A b])
+    float t = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const floatx4 wk4 = *reinterpret_cast<const floatx4*>(&s_W[vr * kWld + vq * 32 + k * 4]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) t += wk4[e] * s_v[vq * 32 + k * 4 + e];
+    }
+    t = quad_sum(t);
+    if (vq == 0) a.vec[cur.orow * kD + vr] = fast_tanh(t);
+
+    {
+      float* P = a.mat + cur.orow * kDD;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int qq = kh ? q + 8 : q;  // accumulator row finished by this wavefront
+        const int i = mb * 32 + (qq >> 2) * 8 + lhi * 4 + (qq & 3);
+        const float mine_e = kh ? acc_e[q + 8] : acc_e[q], mine_o = kh ? acc_o[q + 8] : acc_o[q];
+        const float other_e = s_red[mb][kh ^ 1][(2 * q) * 64 + lane];
+        const float other_o = s_red[mb][kh ^ 1][(2 * q + 1) * 64 + lane];
+        floatx2 o;  // always (k half 0) + (k half 1)
+        o[0] = kh ? other_e + mine_e : mine_e + other_e;
+        o[1] = kh ? other_o + mine_o : mine_o + other_o;
         *reinterpret_cast<floatx2*>(P + i * kD + 2 * lcol) = o;
       }
     }
-    __syncthreads();  // s_ab / s_v / s_red are reused by the next node
+    __syncthreads();  // s_v / s_red are reused by the next node
+    cur = nxt;
+  };
+
+  int node = blockIdx.x;
+  if (node >= a.n) return;
+  RawIdx raw = load_idx(node);
+  NodeRef cur = resolve(raw);
+  raw = load_idx(min(node + (int)gridDim.x, a.n - 1));
+  floatx2 x0[32], x1[32], vv0, vv1;
+  load_node(cur, x0, vv0);
+  while (true) {
+    process(node, cur, raw, x0, vv0, x1, vv1);
+    node += gridDim.x;
+    if (node >= a.n) break;
+    process(node, cur, raw, x1, vv1, x0, vv0);
+    node += gridDim.x;
+    if (node >= a.n) break;
   }
 }
 

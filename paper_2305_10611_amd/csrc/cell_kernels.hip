@@ -425,13 +425,13 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //    at these level sizes, 32-node tiles re-read the weights too often);
   //  * one compute unit streams its operand slabs at only ~40 GB/s, so a level with fewer
   //    tiles than compute units is latency bound: split k until about 256 workgroups exist
-  //    (at least 4 slabs each, at most 8 ways - the reduction kernel costs a launch, ~3 us,
+  //    (at least 2 slabs each, at most 8 ways - the reduction kernel costs a launch, ~3 us,
   //    and reads ksplit partial tiles);
   //  * slightly more tiles than compute units: split in two for balance.
   Shape best{a.n > 128 ? 64 : 32, 1};
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
   int s = 1;
-  while (s * 2 <= 8 && tiles * s * 2 <= 256 && n_slabs % (s * 2) == 0 && n_slabs / (s * 2) >= 4) s *= 2;
+  while (s * 2 <= 8 && tiles * s * 2 <= 256 && n_slabs % (s * 2) == 0 && n_slabs / (s * 2) >= 2) s *= 2;
   if (s == 1 && tiles > 256 && tiles <= 384 && n_slabs % 2 == 0 && n_slabs >= 8) s = 2;
   if (fits(best.bm, s)) best.ksplit = s;
   return best;

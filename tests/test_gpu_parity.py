@@ -226,3 +226,27 @@ def test_profiling_records_every_launch(ctx, P):
     assert len(rec) == len(level_off) - 1
     assert [r[2] for r in rec] == list(np.diff(level_off))
     assert all(r[3] > 0 for r in rec)
+
+
+# ---------------------------------------------------------------- every kernel variant
+@pytest.mark.parametrize("tile,ksplit", [(128, 1), (64, 1), (32, 1), (128, 2), (64, 4), (32, 8), (32, 2)])
+def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit, monkeypatch):
+    """The launcher normally picks the node-tile height and k split from the level size; the
+    tuning override forces one variant for every level (leaf, internal, LSTM input and steps)."""
+    import paper_2305_10611_amd as A
+    monkeypatch.setenv("ACROBAT_FORCE_TILE", str(tile))
+    monkeypatch.setenv("ACROBAT_FORCE_KSPLIT", str(ksplit))
+    c = A.Context(0)  # the override is read when the context allocates its workspace
+    try:
+        w = gen.treelstm_workload(23, 1, 40, 256, 300, "zipf1.1", seed=tile + ksplit, bias_scale=0.2)
+        h, cc = P.run_treelstm(c, w)
+        oh, oc = oracle.treelstm(w, nthreads=NT)
+        P.assert_close(h, oh, "h")
+        P.assert_close(cc, oc, "c")
+        s = gen.lstm_workload(150, 0, 9, 128, 64, seed=tile * 3 + ksplit, bias_scale=0.2)
+        h, cc = P.run_lstm(c, s)
+        oh, oc = oracle.varlen_lstm(s, nthreads=NT)
+        P.assert_close(h, oh, "lstm h")
+        P.assert_close(cc, oc, "lstm c")
+    finally:
+        c.close()

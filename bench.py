@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
+    ap.add_argument("--no-overlap-streams", dest="overlap_streams", action="store_false",
+                    help="skip the informational two-stream throughput measurement")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="only run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "for scaling hardware-counter readings) and exit")
@@ -70,9 +72,9 @@ def main():
     if kind == "treelstm":
         H, D, V = int(w["H"]), int(w["D"]), int(w["V"])
         t = {k: dev(w[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")}
-        out = [torch.empty(n_nodes, H, device="cuda"), torch.empty(n_nodes, H, device="cuda")]
-        step = lambda: ctx.check(ctx.acrobat_treelstm_forward(w, H, D, V, t["emb"], t["W_leaf"], t["b_leaf"], t["U"],
-                                                              t["b"], out[0], out[1], stream))
+        new_out = lambda: [torch.empty(n_nodes, H, device="cuda"), torch.empty(n_nodes, H, device="cuda")]
+        make_step = lambda c, o, st: (lambda: c.check(c.acrobat_treelstm_forward(
+            w, H, D, V, t["emb"], t["W_leaf"], t["b_leaf"], t["U"], t["b"], o[0], o[1], st)))
         sched = lambda: A.acrobat_schedule_trees(w, V)
         n_leaf = int((w["left"] < 0).sum())
         flops_per = {A.binding.K_TREE_LEAF: 2.0 * D * 3 * H, A.binding.K_TREE_INTERNAL: 2.0 * 2 * H * 5 * H}
@@ -85,9 +87,9 @@ def main():
     elif kind == "mvrnn":
         d, V = int(w["d"]), int(w["V"])
         t = {k: dev(w[k]) for k in ("vec_tab", "mat_tab", "W", "WM")}
-        out = [torch.empty(n_nodes, d, device="cuda"), torch.empty(n_nodes, d, d, device="cuda")]
-        step = lambda: ctx.check(ctx.acrobat_mvrnn_forward(w, d, V, t["vec_tab"], t["mat_tab"], t["W"], t["WM"],
-                                                           out[0], out[1], 0, stream))
+        new_out = lambda: [torch.empty(n_nodes, d, device="cuda"), torch.empty(n_nodes, d, d, device="cuda")]
+        make_step = lambda c, o, st: (lambda: c.check(c.acrobat_mvrnn_forward(
+            w, d, V, t["vec_tab"], t["mat_tab"], t["W"], t["WM"], o[0], o[1], 0, st)))
         sched = lambda: A.acrobat_schedule_trees(w, V)
         n_int = int((w["left"] >= 0).sum())
         flops_per = {A.binding.K_MVRNN_LEVEL: 4.0 * d * d + 4.0 * d * d + 4.0 * d ** 3}
@@ -99,9 +101,9 @@ def main():
     else:
         H, D = int(w["H"]), int(w["D"])
         t = {k: dev(w[k]) for k in ("x", "Wx", "Wh", "b")}
-        out = [torch.empty(n_nodes, H, device="cuda"), torch.empty(n_nodes, H, device="cuda")]
-        step = lambda: ctx.check(ctx.acrobat_varlen_lstm_forward(w["len"], H, D, t["x"], t["Wx"], t["Wh"], t["b"],
-                                                                 out[0], out[1], stream))
+        new_out = lambda: [torch.empty(n_nodes, H, device="cuda"), torch.empty(n_nodes, H, device="cuda")]
+        make_step = lambda c, o, st: (lambda: c.check(c.acrobat_varlen_lstm_forward(
+            w["len"], H, D, t["x"], t["Wx"], t["Wh"], t["b"], o[0], o[1], st)))
         sched = lambda: A.acrobat_schedule_seqs(w["len"])
         flops_per = {A.binding.K_LSTM_INPUT: 2.0 * D * 4 * H, A.binding.K_LSTM_STEP: 2.0 * H * 4 * H}
         bytes_per = {A.binding.K_LSTM_INPUT: 4.0 * D + 16.0 * H, A.binding.K_LSTM_STEP: 16.0 * H + 8.0 * H + 8.0 * H + 8}
@@ -109,6 +111,9 @@ def main():
         dominant = A.binding.K_LSTM_STEP
         total_flops = n_nodes * (flops_per[A.binding.K_LSTM_INPUT] + flops_per[A.binding.K_LSTM_STEP])
         dtype, bound = "f32", "mfma"
+
+    out = new_out()
+    step = make_step(ctx, out, stream)
 
     # ---- timed region: W warm-up steps, then exactly K steps between two synchronisations
     for _ in range(args.warmup):
@@ -121,6 +126,27 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = n_nodes / (ms_per_step * 1e-3)
+
+    # ---- information only: the same K steps alternating between two streams (two contexts, two
+    # output buffers), so that the latency-bound small levels of one mini-batch overlap the
+    # compute-bound wide levels of the next.  `value` above stays the single-stream figure.
+    overlap = None
+    if args.overlap_streams:
+        ctx2 = A.Context(0)
+        s2 = torch.cuda.Stream()
+        step2 = make_step(ctx2, new_out(), s2.cuda_stream)
+        s2.wait_stream(torch.cuda.current_stream())
+        for i in range(args.warmup):
+            (step if i % 2 == 0 else step2)()
+        torch.cuda.synchronize()
+        o0 = time.perf_counter()
+        for i in range(args.steps):
+            (step if i % 2 == 0 else step2)()
+        torch.cuda.synchronize()
+        o1 = time.perf_counter()
+        oms = (o1 - o0) * 1e3 / args.steps
+        overlap = {"streams": 2, "ms_per_step": round(oms, 4), "value": round(n_nodes / (oms * 1e-3), 1)}
+        ctx2.close()
 
     # ---- host scheduler alone
     ts = []
@@ -200,7 +226,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w["name"], "index": args.config, "nodes": n_nodes, "seed": int(w["seed"])},
-        "roofline": roofline, "cpu_baseline": cpu_baseline,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap,
         "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
                       "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),
                       "device_tflops": round(total_flops / (t_device_ms * 1e-3) / 1e12, 3),

@@ -331,13 +331,19 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   // (fixed order wk = 1, 2, ...): one round through LDS
   auto reduce_over_wk = [&]() {
     if constexpr (WK > 1) {
-      float* red = smem + (wm * (WK - 1)) * (G * kBlockFloats);
+      // 16-byte LDS accesses: register quad (g, v4) of lane l sits at float4 slot (g*4 + v4)*64 + l
+      floatx4* red = reinterpret_cast<floatx4*>(smem) + (wm * (WK - 1)) * (G * 4 * 64);
       __syncthreads();
       if (wk > 0) {
 #pragma unroll
         for (int g = 0; g < G; ++g)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) red[(wk - 1) * (G * kBlockFloats) + (g * 16 + v) * 64 + lane] = acc[g][v];
+          for (int v4 = 0; v4 < 4; ++v4) {
+            floatx4 q;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) q[e] = acc[g][v4 * 4 + e];
+            red[(wk - 1) * (G * 4 * 64) + (g * 4 + v4) * 64 + lane] = q;
+          }
       }
       __syncthreads();
       if (wk == 0) {
@@ -346,7 +352,11 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
 #pragma unroll
           for (int g = 0; g < G; ++g)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[g][v] += red[r * (G * kBlockFloats) + (g * 16 + v) * 64 + lane];
+            for (int v4 = 0; v4 < 4; ++v4) {
+              const floatx4 q = red[r * (G * 4 * 64) + (g * 4 + v4) * 64 + lane];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[g][v4 * 4 + e] += q[e];
+            }
       }
     }
   };

@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (2 = headline)")
+    ap.add_argument("--paper-grid", default=None, metavar="MODEL:SIZE:BATCH",
+                    help="instead of --config: a mini-batch shaped like the paper's grid, e.g. treelstm:small:64")
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
@@ -62,7 +64,13 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_mib": args.copy_calibration_mib, "launches": 3}))
         return
-    w = make_config(args.config)
+    if args.paper_grid:
+        from workloads.generators import paper_grid_workload
+        model, size, batch = args.paper_grid.split(":")
+        w = paper_grid_workload(model, size, int(batch))
+        args.config = -1
+    else:
+        w = make_config(args.config)
     kind = w["kind"]
     ctx = A.Context(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()

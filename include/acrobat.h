@@ -103,7 +103,7 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
  * A leaf's (a, A) are rows `token` of the tables and are read in place by the parent's kernel
  * (no copy of leaf embeddings, section 7.4).  d_vec [N,d] / d_mat [N,d,d] receive the states of
  * internal nodes at row = global node id; leaf rows are written (copied from the tables) only
- * if copy_leaves != 0.  Requires d == 64.  Tables: d_vec_tab [V,d], d_mat_tab [V,d,d]. */
+ * if copy_leaves != 0.  Requires d == 64 or d == 128.  Tables: d_vec_tab [V,d], d_mat_tab [V,d,d]. */
 int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t d, int32_t V,
                           const float* d_vec_tab, const float* d_mat_tab, const float* d_W,
                           const float* d_WM, float* d_vec, float* d_mat, int32_t copy_leaves,

@@ -34,6 +34,7 @@ struct acrobat_ctx {
   size_t scratch_cap = 0;  // in floats
   // split-k workspace of the cell kernels (allocated at the first forward call)
   SplitKWorkspace splitk;
+  int mvrnn_variant = 0;  // d == 64: which level kernel (tuning override ACROBAT_MVRNN_VARIANT)
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
@@ -185,6 +186,7 @@ int acrobat_create(acrobat_ctx** out, int device) {
   acrobat_ctx* ctx = new (std::nothrow) acrobat_ctx();
   if (!ctx) return ACROBAT_ENOMEM;
   ctx->device = device;
+  if (const char* v = std::getenv("ACROBAT_MVRNN_VARIANT")) ctx->mvrnn_variant = std::atoi(v);
   if (hipEventCreateWithFlags(&ctx->stage_done, hipEventDisableTiming) != hipSuccess) {
     delete ctx;
     return ACROBAT_EHIP;
@@ -331,7 +333,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
   try {
     TRY(begin_call(ctx));
     if (!trees) return fail(ctx, ACROBAT_EINVAL, "trees is null");
-    if (d != 64) return fail(ctx, ACROBAT_EINVAL, "only d == 64 is supported");
+    if (d != 64 && d != 128) return fail(ctx, ACROBAT_EINVAL, "only d == 64 and d == 128 are supported");
     if (V <= 0) return fail(ctx, ACROBAT_EINVAL, "V must be positive");
     TreeSchedule s;
     {
@@ -369,13 +371,15 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
     LaunchTimer timer{ctx, stream};
     if (copy_leaves) {
       TRY(timer.begin(ACROBAT_K_MVRNN_LEAFCOPY, 0, n_leaf));
-      HIP_TRY(ctx, launch_mvrnn_leaf_copy(n_leaf, d_out, d_ia, d_vec_tab, d_mat_tab, d_vec, d_mat, stream));
+      HIP_TRY(ctx, launch_mvrnn_leaf_copy(n_leaf, d, d_out, d_ia, d_vec_tab, d_mat_tab, d_vec, d_mat, stream));
       TRY(timer.end());
     }
     for (int32_t lv = 1; lv < s.n_levels; ++lv) {
       const int32_t off = s.level_off[lv], n = s.level_off[lv + 1] - off;
       MvrnnLevelArgs a{};
       a.n = n;
+      a.d = d;
+      a.variant = ctx->mvrnn_variant;
       a.out_rows = d_out + off;
       a.lsrc = d_ia + off;
       a.rsrc = d_ib + off;

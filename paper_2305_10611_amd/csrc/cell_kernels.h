@@ -53,17 +53,19 @@ hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream
 // A child source code s >= 0 means arena row s of (vec, mat); s < 0 means table row -(s+1).
 struct MvrnnLevelArgs {
   int32_t n;
+  int32_t d;        // 64 or 128
+  int32_t variant;  // d == 64 only: 0 = register-resident kernel, 1 = streaming kernel
   const int32_t* out_rows;  // [n]
   const int32_t* lsrc;      // [n] encoded left child source
   const int32_t* rsrc;      // [n]
   const float* vec_tab; const float* mat_tab;
-  const float* W; const float* WM;  // [64,128] each
-  float* vec; float* mat;           // arena [rows,64], [rows,64,64]
+  const float* W; const float* WM;  // [d,2d] each
+  float* vec; float* mat;           // arena [rows,d], [rows,d,d]
 };
 hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile);
 
 // Copies table rows `token[i]` into arena rows out_rows[i] (vector and matrix), i in [0,n).
-hipError_t launch_mvrnn_leaf_copy(int32_t n, const int32_t* out_rows, const int32_t* token,
+hipError_t launch_mvrnn_leaf_copy(int32_t n, int32_t d, const int32_t* out_rows, const int32_t* token,
                                   const float* vec_tab, const float* mat_tab, float* vec, float* mat,
                                   hipStream_t stream);
 

@@ -1,4 +1,4 @@
-// MV-RNN level kernel for gfx950, d = 64.
+// MV-RNN level kernels for gfx950 (d = 64: register-resident kernel; d = 64 or 128: streaming kernel).
 //
 // Per node with left child (a, A) and right child (b, B):
 //   p = tanh(W [B a ; A b]),   P = W_M [A ; B]          (W, W_M: [64,128])
@@ -214,19 +214,202 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   }
 }
 
-__global__ __launch_bounds__(256) void mvrnn_leaf_copy_kernel(int n, const int32_t* out_rows,
-                                                              const int32_t* token,
-                                                              const float* vec_tab,
-                                                              const float* mat_tab, float* vec,
-                                                              float* mat) {
+// Streaming variant, any D in {64, 128}: P = W_M [A ; B] with v_mfma_f32_16x16x4_f32.
+// Lane l = 16 r4 + c loads 16 bytes: columns 4c..4c+3 (of a 64-column group) of row 4s + r4 of
+// the stacked child matrices - exactly the B-operand layout of the instruction (k = l/16,
+// n = l%16) for four output column blocks at once, block e taking column 4c + e, so a lane
+// ends up with four adjacent output columns per accumulator row and stores them as one float4.
+// Wavefront w owns output rows [D/4 * w, D/4 * (w+1)) and streams ALL rows of [A ; B] through
+// a ring of PF load slots (the four wavefronts read the same lines; no reduction through LDS
+// is needed).  Its rows of W_M are the A operand and stay in registers for the whole launch.
+// B a and A b are formed from the streamed rows (wavefront w takes the steps s = w mod 4) and
+// summed over the 16 lanes of a row group with a reduce-scatter butterfly.  The ring runs
+// across node boundaries: the first PF steps of the next node are requested while the
+// current node's last matrix instructions issue.
+template <int D>
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mvrnn_stream_kernel(const MvrnnLevelArgs a) {
+  constexpr int CG = D / 64;     // 64-column groups
+  constexpr int MB = D / 64;     // 16-row output blocks per wavefront
+  constexpr int S = 2 * D / 4;   // 4-row steps over [A ; B]
+  constexpr int SA = D / 4;      // steps inside A
+  constexpr int PF = 8;          // load slots in flight
+  constexpr int NV = S / 4;      // mat-vec rows groups handled by one wavefront
+  constexpr int WLD = 2 * D + 4; // LDS row stride of W
+  constexpr int LPR = 256 / D;   // lanes per output row of p = tanh(W v)
+  constexpr int DD = D * D;
+  __shared__ float s_v[2 * D];  // B a | A b
+  __shared__ __attribute__((aligned(16))) float s_W[D * WLD];
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int c = lane & 15, r4 = lane >> 4;
+
+  float wm[MB][S];  // W_M[16 (MB w + mb) + c][4 s + r4]
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int s = 0; s < S; ++s) wm[mb][s] = a.WM[(size_t)(16 * (MB * w + mb) + c) * (2 * D) + 4 * s + r4];
+  for (int i = tid; i < D * 2 * D / 4; i += 256) {
+    const int r = i / (2 * D / 4), c4 = i % (2 * D / 4);
+    *reinterpret_cast<floatx4*>(&s_W[r * WLD + c4 * 4]) = *reinterpret_cast<const floatx4*>(a.W + (size_t)r * (2 * D) + c4 * 4);
+  }
+
+  const int32_t* __restrict__ lsrc = a.lsrc;
+  const int32_t* __restrict__ rsrc = a.rsrc;
+  const int32_t* __restrict__ orows = a.out_rows;
+  struct Raw { int ls, rs, orow; };
+  struct Ref { const float* mA; const float* mB; const float* va; const float* vb; size_t orow; };
+  auto load_idx = [&](int node) {
+    Raw r;
+    r.ls = lsrc[node];
+    r.rs = rsrc[node];
+    r.orow = orows[node];
+    return r;
+  };
+  auto resolve = [&](const Raw& i) {
+    Ref r;
+    r.mA = i.ls >= 0 ? a.mat + (size_t)i.ls * DD : a.mat_tab + (size_t)(-(i.ls + 1)) * DD;
+    r.va = i.ls >= 0 ? a.vec + (size_t)i.ls * D : a.vec_tab + (size_t)(-(i.ls + 1)) * D;
+    r.mB = i.rs >= 0 ? a.mat + (size_t)i.rs * DD : a.mat_tab + (size_t)(-(i.rs + 1)) * DD;
+    r.vb = i.rs >= 0 ? a.vec + (size_t)i.rs * D : a.vec_tab + (size_t)(-(i.rs + 1)) * D;
+    r.orow = (size_t)i.orow;
+    return r;
+  };
+  floatx4 ring[PF][CG];
+  auto load_step = [&](const Ref& r, int s, int slot) {  // s, slot: compile-time at every call site
+    const float* base = (s < SA ? r.mA + (size_t)(4 * s + r4) * D : r.mB + (size_t)(4 * (s - SA) + r4) * D) + 4 * c;
+#pragma unroll
+    for (int g = 0; g < CG; ++g) ring[slot][g] = *reinterpret_cast<const floatx4*>(base + 64 * g);
+  };
+
+  int node = blockIdx.x;
+  if (node >= a.n) return;
+  Raw raw = load_idx(node);
+  Ref cur = resolve(raw);
+  raw = load_idx(min(node + (int)gridDim.x, a.n - 1));
+#pragma unroll
+  for (int s = 0; s < PF; ++s) load_step(cur, s, s);
+
+  for (; node < a.n; node += gridDim.x) {
+    asm volatile("" : "+v"(raw.ls), "+v"(raw.rs), "+v"(raw.orow));  // fetched one node ago; consumed here
+    const Ref nxt = resolve(raw);
+    raw = load_idx(min(node + 2 * (int)gridDim.x, a.n - 1));
+    floatx4 va4[CG], vb4[CG];  // the children's vectors, this lane's columns
+#pragma unroll
+    for (int g = 0; g < CG; ++g) {
+      va4[g] = *reinterpret_cast<const floatx4*>(cur.va + 64 * g + 4 * c);
+      vb4[g] = *reinterpret_cast<const floatx4*>(cur.vb + 64 * g + 4 * c);
+    }
+
+    floatx4 acc[MB][CG][4];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[mb][g][e] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float mv[NV];
+
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      floatx4 x[CG];
+#pragma unroll
+      for (int g = 0; g < CG; ++g) x[g] = ring[s % PF][g];
+      if (s + PF < S) load_step(cur, s + PF, s % PF);
+      else load_step(nxt, s + PF - S, s % PF);  // next node (a re-read of the last node at the very end)
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int g = 0; g < CG; ++g)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            acc[mb][g][e] = __builtin_amdgcn_mfma_f32_16x16x4f32(wm[mb][s], x[g][e], acc[mb][g][e], 0, 0, 0);
+      // mat-vec partial of rows 4s + r4 (every wavefront computes it, wavefront s % 4 keeps it)
+      float d = 0.0f;
+#pragma unroll
+      for (int g = 0; g < CG; ++g) {
+        const floatx4 v4 = s < SA ? vb4[g] : va4[g];  // A rows meet b, B rows meet a
+#pragma unroll
+        for (int e = 0; e < 4; ++e) d += x[g][e] * v4[e];
+      }
+      if ((s & 3) == 0) mv[s >> 2] = d;
+      else mv[s >> 2] = (s & 3) == w ? d : mv[s >> 2];
+    }
+    // mv[i] belongs to step s = 4 i + w for w > 0 ... and to s = 4 i for w == 0 (set first, kept)
+    // reduce over the 16 lanes of a row group
+    int nv = NV;
+#pragma unroll
+    for (int bit = 8; bit >= 1; bit >>= 1) {
+      if (nv > 1) {
+        const int half = nv / 2;
+        const bool up = (c & bit) != 0;
+#pragma unroll
+        for (int i = 0; i < NV / 2; ++i) {
+          if (i < half) {
+            const float send = up ? mv[i] : mv[i + half];
+            const float keep = up ? mv[i + half] : mv[i];
+            mv[i] = keep + __shfl_xor(send, bit);
+          }
+        }
+        nv = half;
+      } else {
+        mv[0] += __shfl_xor(mv[0], bit);
+      }
+    }
+    {
+      // value index held by this lane: the bits of c at which a halving took place
+      constexpr int HALVINGS = NV >= 16 ? 4 : NV >= 8 ? 3 : NV >= 4 ? 2 : 1;
+      const int idx = c >> (4 - HALVINGS);
+      const bool writer = (c & ((1 << (4 - HALVINGS)) - 1)) == 0;
+      const int s = 4 * idx + w;
+      const int row = 4 * s + r4;  // row of [A ; B]
+      if (writer) s_v[row < D ? D + row : row - D] = mv[0];  // A b goes below B a
+    }
+    __syncthreads();
+
+    // p = tanh(W [B a ; A b])
+    {
+      const int pr = tid / LPR, pq = tid % LPR;
+      constexpr int COLS = 2 * D / LPR;
+      float t = 0.0f;
+#pragma unroll
+      for (int k = 0; k < COLS / 4; ++k) {
+        const floatx4 w4 = *reinterpret_cast<const floatx4*>(&s_W[pr * WLD + pq * COLS + k * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t += w4[e] * s_v[pq * COLS + k * 4 + e];
+      }
+#pragma unroll
+      for (int bit = 1; bit < LPR; bit <<= 1) t += __shfl_xor(t, bit);
+      if (pq == 0) a.vec[cur.orow * D + pr] = fast_tanh(t);
+    }
+    // P rows 16 (MB w + mb) + 4 r4 + v, columns 64 g + 4 c .. +3
+    float* P = a.mat + cur.orow * DD;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int g = 0; g < CG; ++g)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          floatx4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = acc[mb][g][e][v];
+          *reinterpret_cast<floatx4*>(P + (size_t)(16 * (MB * w + mb) + 4 * r4 + v) * D + 64 * g + 4 * c) = o;
+        }
+    __syncthreads();  // s_v is reused by the next node
+    cur = nxt;
+  }
+}
+
+__global__ __launch_bounds__(256) void mvrnn_leaf_copy_kernel(int n, int d, const int32_t* out_rows,
+                                                              const int32_t* token, const float* vec_tab,
+                                                              const float* mat_tab, float* vec, float* mat) {
   const int tid = threadIdx.x;
+  const int dd4 = d * d / 4;
   for (int i = blockIdx.x; i < n; i += gridDim.x) {
     const size_t src = (size_t)token[i], dst = (size_t)out_rows[i];
-    const floatx4* ms = reinterpret_cast<const floatx4*>(mat_tab + src * kDD);
-    floatx4* md = reinterpret_cast<floatx4*>(mat + dst * kDD);
-#pragma unroll
-    for (int k = 0; k < 4; ++k) md[tid + 256 * k] = ms[tid + 256 * k];
-    if (tid < kD) vec[dst * kD + tid] = vec_tab[src * kD + tid];
+    const floatx4* ms = reinterpret_cast<const floatx4*>(mat_tab + src * d * d);
+    floatx4* md = reinterpret_cast<floatx4*>(mat + dst * d * d);
+    for (int k = tid; k < dd4; k += 256) md[k] = ms[k];
+    if (tid < d) vec[dst * d + tid] = vec_tab[src * d + tid];
   }
 }
 
@@ -236,16 +419,22 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
   if (tile) *tile = 1;
   if (a.n <= 0) return hipSuccess;
   const int grid = a.n < 512 ? a.n : 512;  // two resident workgroups per compute unit, each strides over the level
-  hipLaunchKernelGGL(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, a);
+  if (a.d == 128) {
+    hipLaunchKernelGGL(mvrnn_stream_kernel<128>, dim3(a.n < 256 ? a.n : 256), dim3(256), 0, stream, a);
+  } else if (a.variant == 1) {
+    hipLaunchKernelGGL(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, a);
+  } else {
+    hipLaunchKernelGGL(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, a);
+  }
   return hipGetLastError();
 }
 
-hipError_t launch_mvrnn_leaf_copy(int32_t n, const int32_t* out_rows, const int32_t* token,
+hipError_t launch_mvrnn_leaf_copy(int32_t n, int32_t d, const int32_t* out_rows, const int32_t* token,
                                   const float* vec_tab, const float* mat_tab, float* vec, float* mat,
                                   hipStream_t stream) {
   if (n <= 0) return hipSuccess;
   const int grid = n < 2048 ? n : 2048;
-  hipLaunchKernelGGL(mvrnn_leaf_copy_kernel, dim3(grid), dim3(256), 0, stream, n, out_rows, token,
+  hipLaunchKernelGGL(mvrnn_leaf_copy_kernel, dim3(grid), dim3(256), 0, stream, n, d, out_rows, token,
                      vec_tab, mat_tab, vec, mat);
   return hipGetLastError();
 }

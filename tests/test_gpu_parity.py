@@ -166,6 +166,44 @@ def test_mvrnn_small_ragged_and_relabelled(ctx, P):
     P.assert_close(mat, om, "mat")
 
 
+def test_mvrnn_d128_ragged_and_relabelled(ctx, P):
+    """The paper's large MV-RNN size (section 7.1): 128-d vectors, 128 x 128 matrices."""
+    w = gen.mvrnn_workload(13, 1, 12, 128, seed=41)
+    w2, perm = gen.relabel_trees(w, gen.make_rng(42), extra={"token": w["token"]})
+    for ww in (w, w2):
+        vec, mat = P.run_mvrnn(ctx, ww)
+        check_tree_schedule(ctx, ww)
+        ov, om = oracle.mvrnn(ww, nthreads=NT)
+        P.assert_close(vec, ov, "vec")
+        P.assert_close(mat, om, "mat")
+
+
+def test_mvrnn_d128_paper_batch(ctx, P):
+    from workloads.generators import paper_grid_workload
+    w = paper_grid_workload("mvrnn", "large", 64)
+    vec, mat = P.run_mvrnn(ctx, w, copy_leaves=0)
+    ov, om = oracle.mvrnn(w, nthreads=NT)
+    internal = w["left"] >= 0
+    P.assert_close(vec[internal], ov[internal], "vec")
+    P.assert_close(mat[internal], om[internal], "mat")
+    assert np.isnan(vec[~internal]).all()
+
+
+def test_mvrnn_d64_streaming_variant(P, monkeypatch):
+    """d = 64 has two level kernels; the tuning override selects the streaming one."""
+    import paper_2305_10611_amd as A
+    monkeypatch.setenv("ACROBAT_MVRNN_VARIANT", "1")
+    c = A.Context(0)
+    try:
+        w = gen.mvrnn_workload(40, 1, 30, 64, seed=43)
+        vec, mat = P.run_mvrnn(c, w)
+        ov, om = oracle.mvrnn(w, nthreads=NT)
+        P.assert_close(vec, ov, "vec")
+        P.assert_close(mat, om, "mat")
+    finally:
+        c.close()
+
+
 def test_mvrnn_rejects_unsupported_d(ctx, P):
     import paper_2305_10611_amd as A
     w = gen.mvrnn_workload(2, 2, 3, 32, seed=33)

@@ -55,6 +55,27 @@ def test_treelstm_ragged_shapes_with_bias(ctx, P, H, n_trees, lo, hi):
     P.assert_close(c, oc, "c")
 
 
+def test_treelstm_embedding_width_differs_from_hidden_size(ctx, P):
+    for H, D in ((64, 160), (128, 32)):
+        w = gen.treelstm_workload(12, 1, 25, H, 90, "zipf1.1", seed=H + D, bias_scale=0.3, D=D)
+        assert w["emb"].shape[1] == D and w["W_leaf"].shape == (5 * H, D)
+        h, c = P.run_treelstm(ctx, w)
+        oh, oc = oracle.treelstm(w, nthreads=NT)
+        P.assert_close(h, oh, "h")
+        P.assert_close(c, oc, "c")
+
+
+def test_treelstm_many_tiles_per_level(ctx, P):
+    """A wide, shallow batch: tens of thousands of nodes per level, several dispatch rounds."""
+    w = gen.treelstm_workload(9000, 2, 6, 64, 500, "zipf1.1", seed=77, bias_scale=0.2)
+    assert w["n_nodes"] > 60000
+    h, c = P.run_treelstm(ctx, w)
+    check_tree_schedule(ctx, w)
+    oh, oc = oracle.treelstm(w, nthreads=NT)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+
+
 def test_treelstm_null_bias_equals_zero_bias(ctx, P):
     w = gen.treelstm_workload(6, 2, 20, 64, 50, "uniform", seed=8)
     h0, c0 = P.run_treelstm(ctx, w, use_bias=True)

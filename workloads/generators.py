@@ -162,14 +162,14 @@ def leaf_mask(trees: dict):
 # --------------------------------------------------------------------------
 # workloads
 # --------------------------------------------------------------------------
-def treelstm_workload(n_trees, leaf_lo, leaf_hi, H, V, token_dist, seed, bias_scale=0.0):
+def treelstm_workload(n_trees, leaf_lo, leaf_hi, H, V, token_dist, seed, bias_scale=0.0, D=None):
     """Binary TreeLSTM batch: trees, leaf token ids, embedding table and weights.
 
     Gate order of the 5H weight rows: (i, f_l, f_r, o, u).  U columns 0..H-1 act
     on the left child's h, H..2H-1 on the right child's.
     """
     rng = make_rng(seed)
-    D = H
+    D = H if D is None else D  # embedding width (the benchmark configs use D == H)
     counts = rng.integers(leaf_lo, leaf_hi + 1, size=n_trees)
     trees = tree_batch(counts, rng)
     N = int(trees["tree_off"][-1])

@@ -135,3 +135,35 @@ def seq_schedule(lens):
     n = lib.oracle_seq_schedule(C.c_int(lens.size), _p(lens), _p(level_off), _p(level_rows))
     assert n == tmax
     return level_off, level_rows
+
+
+def birnn(w: dict, nthreads: int = 1):
+    """Evaluate a bidirectional-RNN batch. Returns hf, hb [sum len, H] and y [sum len, n_out] (f64)."""
+    lib = _load()
+    H, D, n_out = int(w["H"]), int(w["D"]), int(w["n_out"])
+    lens = _i32(w["len"])
+    total = int(lens.sum())
+    names = ("x", "fWx", "fWh", "fb", "finit", "bWx", "bWh", "bb", "binit", "C", "cb")
+    arrs = [_f32(w[k]) for k in names]
+    hf = np.full((total, H), np.nan, dtype=np.float64)
+    hb = np.full((total, H), np.nan, dtype=np.float64)
+    y = np.full((total, n_out), np.nan, dtype=np.float64)
+    lib.oracle_birnn(C.c_int(int(w["n_seq"])), _p(lens), C.c_int(H), C.c_int(D), C.c_int(n_out),
+                     *[_p(a) for a in arrs], _p(hf), _p(hb), _p(y), C.c_int(int(nthreads)))
+    return hf, hb, y
+
+
+def phase_schedule(prod_lists, phase):
+    """Generic (phase, depth, id) schedule of an explicit dataflow graph.
+    prod_lists[n] = producers of node n.  Returns (depth[n], order[n], batch_off)."""
+    lib = _load()
+    n = len(prod_lists)
+    prod_off = np.zeros(n + 1, np.int32)
+    prod_off[1:] = np.cumsum([len(p) for p in prod_lists])
+    prod = _i32(np.concatenate([np.asarray(p, np.int32) for p in prod_lists]) if prod_off[-1] else np.zeros(0, np.int32))
+    phase = _i32(phase)
+    depth = np.empty(n, np.int32)
+    order = np.empty(n, np.int32)
+    batch_off = np.zeros(n + 1, np.int32)
+    nb = lib.oracle_phase_schedule(C.c_int(n), _p(prod_off), _p(prod), _p(phase), _p(depth), _p(order), _p(batch_off))
+    return depth, order, batch_off[: nb + 1].copy()

@@ -33,10 +33,21 @@
  *     z = W_x x_t + W_h h_{t-1} + b, gates (i, f, o, u),
  *     c_t = f*c_{t-1} + i*u,  h_t = o*tanh(c_t),  h_{-1} = c_{-1} = 0.
  *
+ *   bidirectional RNN with a per-token output layer (listing 1's cell in both directions,
+ *   appendix C.1; output operators as in token classification, section 7.5):
+ *     forward:   hf_t = s(Wf_x x_t + bf + Wf_h hf_{t-1}),  hf_{-1} = f_init (a parameter)
+ *     backward:  hb_t = s(Wb_x x_t + bb + Wb_h hb_{t+1}),  hb_{len} = b_init (same cell on the
+ *                reversed sequence, own parameters)
+ *     output:    y_t = relu(c_b + C [hf_t ; hb_t])
+ *
  *   schedule: depth of a node = 0 if it consumes nothing produced inside the
  *     graph, else 1 + max depth of its producers (footnote of section 4.1);
  *     nodes run by increasing depth.  Order inside one depth is a convention
  *     (ascending global node id): members of a batch are independent.
+ *
+ *   program phases (section 4.1, appendix B.4): operators of a phase are scheduled and
+ *     executed before any operator of the next phase, so depth is counted inside a phase: a
+ *     node's depth is 0 if it has no producer in its own phase.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand
  * computed 1- and 3-node trees, closed forms, library LSTM cells, brute force).
@@ -426,4 +437,117 @@ int oracle_seq_schedule(int n_seq, const int32_t* len, int32_t* level_off, int32
     level_off[t + 1] = pos;
   }
   return tmax;
+}
+
+/* ------------------------------------------------------------------------- */
+/* bidirectional RNN with per-token output layer                              */
+/* ------------------------------------------------------------------------- */
+typedef struct {
+  int n_seq, H, D, n_out;
+  const int32_t* len;
+  const float *x, *fWx, *fWh, *fb, *finit, *bWx, *bWh, *bb, *binit, *C, *cb;
+  double *hf, *hb, *y;
+  int tid, nthreads;
+} bi_job;
+
+/* one direction of one sequence: rows row0 .. row0+T-1, visited in the order given by `step` */
+static void rnn_chain(const bi_job* jb, size_t row0, int T, int backward, const float* Wx,
+                      const float* Wh, const float* b, const float* init, double* hout,
+                      double* zx, double* zh, double* xin, double* hprev) {
+  const int H = jb->H, D = jb->D;
+  for (int q = 0; q < H; ++q) hprev[q] = (double)init[q];
+  for (int i = 0; i < T; ++i) {
+    const int t = backward ? T - 1 - i : i;
+    const size_t row = row0 + (size_t)t;
+    for (int k = 0; k < D; ++k) xin[k] = (double)jb->x[row * D + k];
+    matvec(Wx, H, D, D, xin, b, zx);
+    matvec(Wh, H, H, H, hprev, NULL, zh);
+    for (int q = 0; q < H; ++q) hout[row * H + q] = sigm(zx[q] + zh[q]);
+    for (int q = 0; q < H; ++q) hprev[q] = hout[row * H + q];
+  }
+}
+
+static void* birnn_worker(void* p) {
+  const bi_job* jb = (const bi_job*)p;
+  const int H = jb->H, D = jb->D;
+  double* zx = (double*)malloc(sizeof(double) * (size_t)H);
+  double* zh = (double*)malloc(sizeof(double) * (size_t)H);
+  double* xin = (double*)malloc(sizeof(double) * (size_t)D);
+  double* hprev = (double*)malloc(sizeof(double) * (size_t)H);
+  double* pin = (double*)malloc(sizeof(double) * 2 * (size_t)H);
+  double* yo = (double*)malloc(sizeof(double) * (size_t)jb->n_out);
+  size_t row0 = 0;
+  for (int s = 0; s < jb->n_seq; ++s) {
+    const int T = jb->len[s];
+    if (s % jb->nthreads == jb->tid) {
+      rnn_chain(jb, row0, T, 0, jb->fWx, jb->fWh, jb->fb, jb->finit, jb->hf, zx, zh, xin, hprev);
+      rnn_chain(jb, row0, T, 1, jb->bWx, jb->bWh, jb->bb, jb->binit, jb->hb, zx, zh, xin, hprev);
+      for (int t = 0; t < T; ++t) {
+        const size_t row = row0 + (size_t)t;
+        for (int q = 0; q < H; ++q) pin[q] = jb->hf[row * H + q];
+        for (int q = 0; q < H; ++q) pin[H + q] = jb->hb[row * H + q];
+        matvec(jb->C, jb->n_out, 2 * H, 2 * H, pin, jb->cb, yo);
+        for (int o = 0; o < jb->n_out; ++o) jb->y[row * jb->n_out + o] = yo[o] > 0.0 ? yo[o] : 0.0;
+      }
+    }
+    row0 += (size_t)T;
+  }
+  free(zx); free(zh); free(xin); free(hprev); free(pin); free(yo);
+  return NULL;
+}
+
+int oracle_birnn(int n_seq, const int32_t* len, int H, int D, int n_out, const float* x,
+                 const float* fWx, const float* fWh, const float* fb, const float* finit,
+                 const float* bWx, const float* bWh, const float* bb, const float* binit,
+                 const float* C, const float* cb, double* hf, double* hb, double* y, int nthreads) {
+  if (nthreads < 1) nthreads = 1;
+  if (nthreads > 256) nthreads = 256;
+  bi_job jobs[256];
+  pthread_t th[256];
+  for (int i = 0; i < nthreads; ++i) {
+    bi_job j = {n_seq, H, D, n_out, len, x, fWx, fWh, fb, finit, bWx, bWh, bb, binit, C, cb, hf, hb, y, i, nthreads};
+    jobs[i] = j;
+  }
+  if (nthreads == 1) { birnn_worker(&jobs[0]); return 0; }
+  for (int i = 0; i < nthreads; ++i) pthread_create(&th[i], NULL, birnn_worker, &jobs[i]);
+  for (int i = 0; i < nthreads; ++i) pthread_join(th[i], NULL);
+  return 0;
+}
+
+/* Generic phase-aware depth schedule of an explicit dataflow graph.  Node n has producers
+ * prod[prod_off[n] .. prod_off[n+1]) and phase phase[n] (producers never sit in a later phase).
+ * depth[n] = 0 if n has no producer in its own phase, else 1 + the largest such producer's
+ * depth.  order[] lists the nodes by (phase, depth, id); batch_off[] marks the batches.
+ * Returns the number of batches. */
+static int phase_depth(int n, const int32_t* prod_off, const int32_t* prod, const int32_t* phase, int32_t* depth) {
+  if (depth[n] >= 0) return depth[n];
+  int d = 0;
+  for (int e = prod_off[n]; e < prod_off[n + 1]; ++e)
+    if (phase[prod[e]] == phase[n]) {
+      const int dp = 1 + phase_depth(prod[e], prod_off, prod, phase, depth);
+      if (dp > d) d = dp;
+    }
+  depth[n] = d;
+  return d;
+}
+
+int oracle_phase_schedule(int n_nodes, const int32_t* prod_off, const int32_t* prod, const int32_t* phase,
+                          int32_t* depth, int32_t* order, int32_t* batch_off) {
+  int max_phase = 0, max_depth = 0;
+  for (int n = 0; n < n_nodes; ++n) depth[n] = -1;
+  for (int n = 0; n < n_nodes; ++n) {
+    const int d = phase_depth(n, prod_off, prod, phase, depth);
+    if (d > max_depth) max_depth = d;
+    if (phase[n] > max_phase) max_phase = phase[n];
+  }
+  int pos = 0, nb = 0;
+  batch_off[0] = 0;
+  for (int ph = 0; ph <= max_phase; ++ph)
+    for (int d = 0; d <= max_depth; ++d) {
+      const int before = pos;
+      for (int n = 0; n < n_nodes; ++n)
+        if (phase[n] == ph && depth[n] == d) order[pos++] = n;
+      if (pos > before) batch_off[++nb] = pos;
+    }
+  return nb;
 }

@@ -237,6 +237,28 @@ def lstm_workload(n_seq, len_lo, len_hi, H, D, seed, bias_scale=0.0):
                 Wx=Wx, Wh=Wh, b=b, seed=seed, n_nodes=total)
 
 
+def birnn_workload(n_seq, len_lo, len_hi, H, D, n_out, seed, bias_scale=0.1):
+    """Bidirectional RNN batch with a per-token output layer.  Rows of x are packed
+    sequence-major (row(s, t) = seq_off[s] + t).  Each direction has its own Wx [H,D], Wh [H,H],
+    b [H] and initial state [H]; the output layer is C [n_out, 2H] (columns 0..H-1 act on the
+    forward state), cb [n_out]."""
+    rng = make_rng(seed)
+    lens = rng.integers(len_lo, len_hi + 1, size=n_seq).astype(np.int32)
+    seq_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    total = int(seq_off[-1])
+    out = dict(kind="birnn", n_seq=n_seq, len=lens, seq_off=seq_off, H=H, D=D, n_out=n_out, seed=seed,
+               n_nodes=total, x=normal_f32((total, D), rng))
+    bound = 1.0 / np.sqrt(H)
+    for p in ("f", "b"):
+        out[p + "Wx"] = uniform_f32((H, D), bound, rng)
+        out[p + "Wh"] = uniform_f32((H, H), bound, rng)
+        out[p + "b"] = uniform_f32((H,), bias_scale, rng)
+        out[p + "init"] = uniform_f32((H,), 1.0, rng) * np.float32(0.5) + np.float32(0.5)
+    out["C"] = uniform_f32((n_out, 2 * H), 1.0 / np.sqrt(2 * H), rng)
+    out["cb"] = uniform_f32((n_out,), bias_scale, rng)
+    return out
+
+
 def paper_grid_workload(model: str, size: str, batch: int, seed: int | None = None):
     """Mini-batches shaped like the paper's evaluation grid (section 7.1): model size small /
     large (hidden 256 / 512; MV-RNN 64 / 128) and batch size 8 / 64.  The treebank itself is not

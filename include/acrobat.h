@@ -80,6 +80,16 @@ int acrobat_schedule_trees(const acrobat_trees* trees, int32_t vocab, int32_t* n
 int acrobat_schedule_seqs(int32_t n_seq, const int32_t* len, int32_t* n_levels,
                           int32_t* level_off, int32_t* level_rows);
 
+/* Bidirectional-RNN schedule with program phases (section 4.1, appendix B.4): operators of a phase
+ * are scheduled and executed before any operator of the next phase, so depth counts inside a
+ * phase.  Phase 0 holds the two recurrences (listing 2: step k of a direction has depth k), phase 1
+ * every per-token output operator - all of them in ONE batch although the sequences differ in
+ * length.  Nodes are coded  fwd(row) = row,  bwd(row) = R + row,  out(row) = 2R + row  with
+ * R = sum len and row = seq_off[s] + t; a level lists its codes in ascending order.
+ * level_off[max len + 2], level_codes[3 R] caller-allocated; n_levels = max len + 1 (0 if R == 0). */
+int acrobat_schedule_birnn(int32_t n_seq, const int32_t* len, int32_t* n_levels, int32_t* level_off,
+                           int32_t* level_codes);
+
 /* ---- forward calls --------------------------------------------------------------------
  * Binary TreeLSTM (model of table 3).  Gate order of the 5H weight rows: (i, f_l, f_r, o, u).
  *   leaf:      z = W_leaf E[token] + b_leaf ; child states are the shared zero state
@@ -122,6 +132,30 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
                                 const float* d_Wh, const float* d_b, float* d_h, float* d_c,
                                 void* hip_stream);
 
+/* Bidirectional RNN with a per-token output layer (the BiRNN of table 3; cell of listing 1 used
+ * in both directions with separate parameters, appendix C.1; output operators batched by program
+ * phases, section 7.5).  With p = forward or backward:
+ *   hf_t = s(Wf_x x_t + bf + Wf_h hf_{t-1}), hf_{-1} = f.h_init     (steps t = 0 .. len-1)
+ *   hb_t = s(Wb_x x_t + bb + Wb_h hb_{t+1}), hb_{len} = b.h_init    (steps t = len-1 .. 0)
+ *   y_t  = relu(cb + C [hf_t ; hb_t])                               (C: [n_out, 2H])
+ * The input transforms of both directions are hoisted (one dense batch each); the two
+ * recurrences are independent and run on the caller's stream and on a context-owned second
+ * stream, joined before the single output batch.  Rows are packed as for the LSTM.
+ * Requires H, D multiples of 32, 1 <= n_out.  All pointers in acrobat_rnn_dir are device
+ * pointers: Wx [H,D], Wh [H,H], b [H] or NULL, h_init [H].  d_hf / d_hb [sum len, H] and
+ * d_y [sum len, n_out] are written. */
+typedef struct {
+  const float* Wx;
+  const float* Wh;
+  const float* b;
+  const float* h_init;
+} acrobat_rnn_dir;
+
+int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, int32_t H, int32_t D,
+                          int32_t n_out, const float* d_x, const acrobat_rnn_dir* fwd,
+                          const acrobat_rnn_dir* bwd, const float* d_C, const float* d_cb,
+                          float* d_hf, float* d_hb, float* d_y, void* hip_stream);
+
 /* ---- introspection --------------------------------------------------------------------
  * Schedule built by the last forward call on this context (host arrays owned by the context,
  * valid until the next forward call): level_off[n_levels + 1], level_nodes[level_off[n_levels]]. */
@@ -145,6 +179,9 @@ typedef struct {
 #define ACROBAT_K_MVRNN_LEAFCOPY 4
 #define ACROBAT_K_LSTM_INPUT 5
 #define ACROBAT_K_LSTM_STEP 6
+#define ACROBAT_K_RNN_INPUT 7
+#define ACROBAT_K_RNN_STEP 8
+#define ACROBAT_K_RNN_OUTPUT 9
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 /* Records of the last forward call (context-owned, valid until the next forward call). */

@@ -13,6 +13,7 @@ from . import build as _build
 
 OK, EINVAL, ESTRUCT, ENOMEM, EHIP = 0, -1, -2, -3, -4
 K_TREE_LEAF, K_TREE_INTERNAL, K_MVRNN_LEVEL, K_MVRNN_LEAFCOPY, K_LSTM_INPUT, K_LSTM_STEP = 1, 2, 3, 4, 5, 6
+K_RNN_INPUT, K_RNN_STEP, K_RNN_OUTPUT = 7, 8, 9
 
 
 class AcrobatError(RuntimeError):
@@ -30,11 +31,15 @@ class acrobat_launch_record(C.Structure):
     _fields_ = [("kind", C.c_int32), ("level", C.c_int32), ("n", C.c_int32), ("tile", C.c_int32), ("ksplit", C.c_int32), ("ms", C.c_float)]
 
 
+class acrobat_rnn_dir(C.Structure):
+    _fields_ = [("Wx", C.c_void_p), ("Wh", C.c_void_p), ("b", C.c_void_p), ("h_init", C.c_void_p)]
+
+
 EXPORTS = (
     "acrobat_create", "acrobat_destroy", "acrobat_last_error", "acrobat_strerror",
     "acrobat_schedule_trees", "acrobat_schedule_seqs", "acrobat_treelstm_forward",
     "acrobat_mvrnn_forward", "acrobat_varlen_lstm_forward", "acrobat_last_schedule",
-    "acrobat_set_profiling", "acrobat_last_profile",
+    "acrobat_set_profiling", "acrobat_last_profile", "acrobat_schedule_birnn", "acrobat_birnn_forward",
 )
 
 
@@ -55,6 +60,9 @@ def _load():
     lib.acrobat_treelstm_forward.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32, i32] + [vp] * 8
     lib.acrobat_mvrnn_forward.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32] + [vp] * 6 + [i32, vp]
     lib.acrobat_varlen_lstm_forward.argtypes = [vp, i32, vp, i32, i32] + [vp] * 7
+    lib.acrobat_schedule_birnn.argtypes = [i32, vp, C.POINTER(i32), vp, vp]
+    lib.acrobat_birnn_forward.argtypes = ([vp, i32, vp, i32, i32, i32, vp, C.POINTER(acrobat_rnn_dir),
+                                           C.POINTER(acrobat_rnn_dir)] + [vp] * 6)
     lib.acrobat_last_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
     lib.acrobat_set_profiling.argtypes = [vp, i32]
     lib.acrobat_last_profile.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(acrobat_launch_record))]
@@ -118,6 +126,20 @@ def acrobat_schedule_seqs(lens):
     return rc, level_off, level_rows
 
 
+def acrobat_schedule_birnn(lens):
+    """-> (rc, level_off[n_levels+1], level_codes[3 sum len])"""
+    lens = _i32(lens)
+    tmax = int(lens.max()) if lens.size and lens.max() > 0 else 0
+    total = int(np.maximum(lens, 0).sum())
+    level_off = np.zeros(tmax + 2, np.int32)
+    level_codes = np.empty(3 * total, np.int32)
+    n_levels = C.c_int32(0)
+    rc = lib.acrobat_schedule_birnn(int(lens.size), _hp(lens), C.byref(n_levels), _hp(level_off), _hp(level_codes))
+    if rc != OK:
+        return rc, None, None
+    return rc, level_off[: n_levels.value + 1].copy(), level_codes
+
+
 class Context:
     """Owns one acrobat_ctx.  Methods mirror the C entry points and return the C return code."""
 
@@ -160,6 +182,14 @@ class Context:
         lens = _i32(lens)
         return lib.acrobat_varlen_lstm_forward(self._h, int(lens.size), _hp(lens), H, D, _dp(x), _dp(Wx), _dp(Wh),
                                                _dp(b), _dp(h), _dp(c), stream)
+
+    def acrobat_birnn_forward(self, lens, H, D, n_out, x, fwd, bwd, Cw, cb, hf, hb, y, stream=0) -> int:
+        """fwd / bwd: (Wx, Wh, b, h_init) device tensors of one direction."""
+        lens = _i32(lens)
+        f = acrobat_rnn_dir(*(_dp(t) for t in fwd))
+        b = acrobat_rnn_dir(*(_dp(t) for t in bwd))
+        return lib.acrobat_birnn_forward(self._h, int(lens.size), _hp(lens), H, D, n_out, _dp(x), C.byref(f),
+                                         C.byref(b), _dp(Cw), _dp(cb), _dp(hf), _dp(hb), _dp(y), stream)
 
     def acrobat_last_schedule(self):
         n_levels, po, pn = C.c_int32(0), C.c_void_p(), C.c_void_p()

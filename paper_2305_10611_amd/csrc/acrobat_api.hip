@@ -34,6 +34,9 @@ struct acrobat_ctx {
   size_t scratch_cap = 0;  // in floats
   // split-k workspace of the cell kernels (allocated at the first forward call)
   SplitKWorkspace splitk;
+  // second stream for the backward recurrence of the bidirectional RNN (default priority)
+  hipStream_t aux_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   int mvrnn_variant = 0;  // d == 64: which level kernel (tuning override ACROBAT_MVRNN_VARIANT)
   // profiling
   bool profiling = false;
@@ -113,6 +116,14 @@ int reserve_splitk(acrobat_ctx* ctx) {
   // tuning override for experiments: ACROBAT_FORCE_TILE=128|64|32|16, ACROBAT_FORCE_KSPLIT=1..32
   if (const char* v = std::getenv("ACROBAT_FORCE_TILE")) ctx->splitk.force_bm = std::atoi(v);
   if (const char* v = std::getenv("ACROBAT_FORCE_KSPLIT")) ctx->splitk.force_ksplit = std::atoi(v);
+  return ACROBAT_OK;
+}
+
+int reserve_aux_stream(acrobat_ctx* ctx) {
+  if (ctx->aux_stream) return ACROBAT_OK;
+  HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
+  HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming));
+  HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
   return ACROBAT_OK;
 }
 
@@ -204,6 +215,12 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
+  if (ctx->aux_stream) {
+    (void)hipStreamSynchronize(ctx->aux_stream);
+    (void)hipStreamDestroy(ctx->aux_stream);
+  }
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   delete ctx;
 }
@@ -458,6 +475,140 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       }
       TRY(timer.begin(ACROBAT_K_LSTM_STEP, t, n));
       HIP_TRY(ctx, launch_cell_level(EPI_LSTM_STEP, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
+      TRY(timer.end());
+    }
+    return timer.finish();
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
+}
+
+int acrobat_schedule_birnn(int32_t n_seq, const int32_t* len, int32_t* n_levels, int32_t* level_off,
+                           int32_t* level_codes) {
+  if (!n_levels || !level_off) return ACROBAT_EINVAL;
+  try {
+    BirnnSchedule s;
+    std::string err;
+    const int rc = schedule_birnn(n_seq, len, s, err);
+    if (rc != ACROBAT_OK) return rc;
+    if (s.n_rows > 0 && !level_codes) return ACROBAT_EINVAL;
+    *n_levels = s.n_levels;
+    std::memcpy(level_off, s.level_off.data(), s.level_off.size() * sizeof(int32_t));
+    if (s.n_rows > 0) std::memcpy(level_codes, s.level_codes.data(), s.level_codes.size() * sizeof(int32_t));
+    return ACROBAT_OK;
+  } catch (const std::bad_alloc&) {
+    return ACROBAT_ENOMEM;
+  } catch (...) {
+    return ACROBAT_EINVAL;
+  }
+}
+
+int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, int32_t H, int32_t D,
+                          int32_t n_out, const float* d_x, const acrobat_rnn_dir* fwd,
+                          const acrobat_rnn_dir* bwd, const float* d_C, const float* d_cb,
+                          float* d_hf, float* d_hb, float* d_y, void* hip_stream) {
+  try {
+    TRY(begin_call(ctx));
+    if (H <= 0 || D <= 0 || H % 32 || D % 32) return fail(ctx, ACROBAT_EINVAL, "H and D must be positive multiples of 32");
+    if (n_out < 1) return fail(ctx, ACROBAT_EINVAL, "n_out must be positive");
+    BirnnSchedule s;
+    {
+      const int rc = schedule_birnn(n_seq, len, s, ctx->err);
+      if (rc != ACROBAT_OK) return rc;
+    }
+    ctx->n_levels = s.n_levels;
+    ctx->level_off = s.level_off;
+    ctx->level_nodes = s.level_codes;
+    const int32_t R = (int32_t)s.n_rows;
+    if (R == 0) return ACROBAT_OK;
+    if (!fwd || !bwd) return fail(ctx, ACROBAT_EINVAL, "a direction's parameter block is null");
+    if (!d_x || !d_C || !d_hf || !d_hb || !d_y || !fwd->Wx || !fwd->Wh || !fwd->h_init || !bwd->Wx || !bwd->Wh ||
+        !bwd->h_init)
+      return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
+    if ((double)H * H >= 2147483648.0 || (double)H * D >= 2147483648.0 || (double)n_out * 2 * H >= 2147483648.0)
+      return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int32_t T = s.n_levels - 1;  // recurrence steps; level T is the output batch
+    TRY(reserve_splitk(ctx));
+    TRY(reserve_aux_stream(ctx));
+    // per direction, by position in the direction's step lists: row written | row of the previous
+    // step of that direction (step 0 gathers row 0 of the initial-state vector)
+    TRY(reserve_indices(ctx, 4 * (size_t)R));
+    int32_t* st = ctx->h_stage;
+    for (int32_t k = 0; k < T; ++k) {
+      const int32_t f0 = s.fwd_off[k], nf = s.fwd_off[k + 1] - f0;
+      const int32_t* codes = s.level_codes.data() + s.level_off[k];
+      for (int32_t p = 0; p < nf; ++p) {
+        const int32_t rf = codes[p], rb = codes[nf + p] - R;
+        st[f0 + p] = rf;
+        st[(size_t)R + f0 + p] = k == 0 ? 0 : rf - 1;
+        st[2 * (size_t)R + f0 + p] = rb;
+        st[3 * (size_t)R + f0 + p] = k == 0 ? 0 : rb + 1;
+      }
+    }
+    TRY(reserve_scratch(ctx, 2 * (size_t)R * (size_t)H));
+    TRY(upload_indices(ctx, 4 * (size_t)R, stream));
+
+    // The two recurrences share nothing but x: the backward one runs on the second stream, forked
+    // after the index upload and joined before the output batch.  With profiling on everything
+    // is serialised on the caller's stream so that the per-launch times mean something.
+    const bool two_streams = !ctx->profiling;
+    hipStream_t sdir[2] = {stream, two_streams ? ctx->aux_stream : stream};
+    if (two_streams) {
+      HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, stream));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+    }
+    SplitKWorkspace ws[2] = {ctx->splitk, ctx->splitk};  // each stream its own half
+    ws[0].partial_floats = ws[1].partial_floats = ctx->splitk.partial_floats / 2;
+    ws[1].partial = ctx->splitk.partial + ws[0].partial_floats;
+    const acrobat_rnn_dir* par[2] = {fwd, bwd};
+    float* hdir[2] = {d_hf, d_hb};
+    float* xp[2] = {ctx->d_scratch, ctx->d_scratch + (size_t)R * H};
+
+    LaunchTimer timer{ctx, stream};
+    for (int dir = 0; dir < 2; ++dir) {  // hoisted input transforms: one dense batch per direction
+      CellLevelArgs a{};
+      a.n = R; a.H = H; a.nseg = 1; a.kseg = D;
+      a.src0 = d_x; a.ld0 = D;
+      a.W = par[dir]->Wx; a.ldw = D; a.bias = par[dir]->b;
+      a.zout = xp[dir];
+      TRY(timer.begin(ACROBAT_K_RNN_INPUT, dir, R));
+      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z1, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit()));
+      TRY(timer.end());
+    }
+    for (int32_t k = 0; k < T; ++k) {
+      const int32_t off = s.fwd_off[k], n = s.fwd_off[k + 1] - off;
+      for (int dir = 0; dir < 2; ++dir) {
+        CellLevelArgs a{};
+        a.n = n; a.H = H; a.nseg = 1; a.kseg = H;
+        a.out_rows = ctx->d_idx + 2 * (size_t)dir * R + off;
+        a.idx0 = ctx->d_idx + (2 * (size_t)dir + 1) * R + off;
+        a.src0 = k == 0 ? par[dir]->h_init : hdir[dir];
+        a.ld0 = H;
+        a.W = par[dir]->Wh; a.ldw = H;
+        a.zadd = xp[dir];
+        a.h = hdir[dir];
+        TRY(timer.begin(ACROBAT_K_RNN_STEP, k, n));
+        HIP_TRY(ctx, launch_cell_level(EPI_RNN_STEP, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit()));
+        TRY(timer.end());
+      }
+    }
+    if (two_streams) {
+      HIP_TRY(ctx, hipEventRecord(ctx->ev_join, ctx->aux_stream));
+      HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
+    }
+    {  // phase 1: every token's output operator in one batch; [hf_t ; hb_t] is read in place
+      CellLevelArgs a{};
+      a.n = R; a.H = (n_out + 31) / 32 * 32; a.n_cols = n_out;
+      a.nseg = 2; a.kseg = H;
+      a.src0 = d_hf; a.ld0 = H;
+      a.src1 = d_hb; a.ld1 = H;
+      a.W = d_C; a.ldw = 2 * H; a.bias = d_cb;
+      a.y = d_y; a.ldo = n_out;
+      TRY(timer.begin(ACROBAT_K_RNN_OUTPUT, T, R));
+      HIP_TRY(ctx, launch_cell_level(EPI_RELU_OUT, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
       TRY(timer.end());
     }
     return timer.finish();

@@ -11,7 +11,10 @@ enum CellEpilogue : int {
   EPI_TREE_LEAF = 0,      // gates (i, o, u): c = s(i) tanh(u), h = s(o) tanh(c)
   EPI_TREE_INTERNAL = 1,  // gates (i, f_l, f_r, o, u) + gathered child c rows
   EPI_LSTM_STEP = 2,      // gates (i, f, o, u) + precomputed input transform + previous c
-  EPI_STORE_Z = 3,        // plain pre-activation store (hoisted input transform)
+  EPI_STORE_Z = 3,        // plain pre-activation store (hoisted input transform), 4 gates
+  EPI_RNN_STEP = 4,       // single gate: h = s(z + precomputed input transform)
+  EPI_RELU_OUT = 5,       // single gate: y = relu(z + bias), n_cols <= H valid columns
+  EPI_STORE_Z1 = 6,       // EPI_STORE_Z with a single gate
 };
 
 // One batch (one depth level) of a cell whose contraction is
@@ -30,8 +33,12 @@ struct CellLevelArgs {
   const int32_t* out_rows;      // [n] arena row written by each node, null = node index
   float* h; float* c;           // arena [rows, H]
   const float* cprev_src;       // tree/LSTM: c rows gathered with idx0 (and idx1); null = zero state
-  const float* zadd;            // LSTM step: [rows, 4H] pre-activations added to z (row = out row)
+  const float* zadd;            // LSTM / RNN step: [rows, G*H] pre-activations added to z (row = out row)
   float* zout;                  // STORE_Z: [rows, G*H]
+  // RELU_OUT only: the weight matrix has n_cols <= H rows (H = n_cols rounded up to 32 sizes the
+  // grid), y[row * ldo + j] is written for j < n_cols.  0 elsewhere (= H).
+  int32_t n_cols;
+  float* y; int32_t ldo;
 };
 
 // Device workspace for levels whose k range is split over several workgroups: partial

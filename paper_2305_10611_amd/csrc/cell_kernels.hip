@@ -1,5 +1,5 @@
-// Gather-fused cell kernels for gfx950 (TreeLSTM leaf / internal level, LSTM input
-// transform and step).
+// Gather-fused cell kernels for gfx950 (TreeLSTM leaf / internal level, LSTM and RNN input
+// transform and step, RNN output layer).
 //
 // One launch executes one depth level of the schedule (section 4.1).  The kernel reads the
 // level's operand rows straight from the arena through index lists instead of from a
@@ -18,9 +18,8 @@
 //
 // Small levels cannot fill 256 compute units with (node tile, j tile) pairs alone, so the
 // k range is additionally split over `ksplit` workgroups.  Each writes its partial tile to
-// a workspace; the workgroup that arrives last at the tile's counter sums the partials in
-// fixed order (results do not depend on arrival order) and runs the epilogue.  Nobody waits
-// for anybody: there is no spinning, the last arriver is simply the one that finishes.
+// a workspace; a second, small kernel launched behind it sums the partial tiles in fixed
+// order and runs the epilogue.
 //
 // Matrix instruction: v_mfma_f32_32x32x2_f32.  Lane l supplies A[i = l%32][k = l/32] and
 // B[k = l/32][j = l%32]; the 16 result registers of lane l hold column j = l%32 and rows
@@ -69,7 +68,10 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
   const int H = a.H, n = a.n;
   float bz[G];
 #pragma unroll
-  for (int g = 0; g < G; ++g) bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
+  for (int g = 0; g < G; ++g) {
+    if constexpr (EPI == EPI_RELU_OUT) bz[g] = a.bias && j < a.n_cols ? a.bias[j] : 0.0f;
+    else bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
+  }
 
   size_t orow[NV];
   int ia[NV], ib[NV];
@@ -119,6 +121,23 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
                       fast_sigmoid(acc(1, v) + bz[1]) * cl[v] + fast_sigmoid(acc(2, v) + bz[2]) * cr[v];
       a.c[orow[v] * H + j] = c;
       a.h[orow[v] * H + j] = fast_sigmoid(acc(3, v) + bz[3]) * fast_tanh(c);
+    }
+  } else if constexpr (EPI == EPI_RNN_STEP) {
+    float zx[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) zx[v] = a.zadd[orow[v] * (size_t)H + j];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      if (!live[v]) continue;
+      a.h[orow[v] * H + j] = fast_sigmoid(acc(0, v) + zx[v] + bz[0]);
+    }
+  } else if constexpr (EPI == EPI_RELU_OUT) {
+    if (j < a.n_cols) {
+#pragma unroll
+      for (int v = 0; v < NV; ++v) {
+        if (!live[v]) continue;
+        a.y[orow[v] * (size_t)a.ldo + j] = fmaxf(acc(0, v) + bz[0], 0.0f);
+      }
     }
   } else {  // EPI_LSTM_STEP
     float cp[NV], zx[G][NV];
@@ -180,7 +199,9 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     }
   }
   // weights: one per-lane offset; gate and slab offsets are uniform (fit 32 bits: host-checked)
-  const unsigned boff = (unsigned)(j0 + lrow) * (unsigned)a.ldw + (unsigned)lpart;
+  // (RELU_OUT: rows past the last weight row re-read it; their columns are never stored)
+  const int wrow = EPI == EPI_RELU_OUT ? (j0 + lrow < a.n_cols ? j0 + lrow : a.n_cols - 1) : j0 + lrow;
+  const unsigned boff = (unsigned)wrow * (unsigned)a.ldw + (unsigned)lpart;
   const unsigned gate_stride = (unsigned)H * (unsigned)a.ldw;
 
   floatx16 acc[G];
@@ -268,7 +289,9 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
       mfma_group(fcur);
       // interleave: one memory instruction after each matrix instruction
       constexpr int n_mfma = 4 * G, n_rd = 1 + G, n_st = WM + G;
-      constexpr int w = n_st > (n_mfma - n_rd) / 2 ? 2 : 1;
+      // the stores and the loads of a slab each get at most half of the slots left by the reads
+      constexpr int half = (n_mfma - n_rd) / 2;
+      constexpr int w = (n_st + half - 1) / half;
 #pragma unroll
       for (int i = 0; i < n_rd; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // MFMA
@@ -484,6 +507,9 @@ hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream
     case EPI_TREE_INTERNAL: return launch_shape<5, EPI_TREE_INTERNAL>(a, stream, ws, tile, ksplit);
     case EPI_LSTM_STEP: return launch_shape<4, EPI_LSTM_STEP>(a, stream, ws, tile, ksplit);
     case EPI_STORE_Z: return launch_shape<4, EPI_STORE_Z>(a, stream, ws, tile, ksplit);
+    case EPI_STORE_Z1: return launch_shape<1, EPI_STORE_Z>(a, stream, ws, tile, ksplit);
+    case EPI_RNN_STEP: return launch_shape<1, EPI_RNN_STEP>(a, stream, ws, tile, ksplit);
+    case EPI_RELU_OUT: return launch_shape<1, EPI_RELU_OUT>(a, stream, ws, tile, ksplit);
   }
   return hipErrorInvalidValue;
 }

@@ -160,4 +160,44 @@ int schedule_seqs(int32_t n_seq, const int32_t* len, SeqSchedule& out, std::stri
   return ACROBAT_OK;
 }
 
+int schedule_birnn(int32_t n_seq, const int32_t* len, BirnnSchedule& out, std::string& err) {
+  out = BirnnSchedule();
+  out.level_off.assign(1, 0);
+  out.fwd_off.assign(1, 0);
+  SeqSchedule f;
+  const int rc = schedule_seqs(n_seq, len, f, err);  // forward recurrence: step k = time k
+  if (rc != ACROBAT_OK) return rc;
+  const int64_t R = f.n_rows;
+  if (R == 0) return ACROBAT_OK;
+  if (3 * R > std::numeric_limits<int32_t>::max()) { err = "more than (2^31-1)/3 rows"; return ACROBAT_EINVAL; }
+  out.n_rows = R;
+  out.n_levels = f.n_levels + 1;
+  out.level_off.assign(out.n_levels + 1, 0);
+  out.fwd_off.assign(f.n_levels + 1, 0);
+  out.level_codes.resize(static_cast<size_t>(3 * R));
+  // last row of every sequence, by the sequence's first row (for the mirrored backward step)
+  std::vector<int32_t> last_of_first(static_cast<size_t>(R), 0);
+  {
+    int32_t row0 = 0;
+    for (int32_t s = 0; s < n_seq; ++s) {
+      if (len[s] > 0) last_of_first[row0] = row0 + len[s] - 1;
+      row0 += len[s];
+    }
+  }
+  int32_t pos = 0;
+  for (int32_t k = 0; k < f.n_levels; ++k) {
+    const int32_t b = f.level_off[k], e = f.level_off[k + 1];
+    for (int32_t p = b; p < e; ++p) out.level_codes[pos++] = f.level_rows[p];  // forward: row0 + k
+    for (int32_t p = b; p < e; ++p) {                                          // backward: last - k
+      const int32_t row0 = f.level_rows[p] - k;
+      out.level_codes[pos++] = static_cast<int32_t>(R) + last_of_first[row0] - k;
+    }
+    out.fwd_off[k + 1] = out.fwd_off[k] + (e - b);
+    out.level_off[k + 1] = pos;
+  }
+  for (int32_t r = 0; r < R; ++r) out.level_codes[pos++] = static_cast<int32_t>(2 * R) + r;
+  out.level_off[out.n_levels] = pos;
+  return ACROBAT_OK;
+}
+
 }  // namespace acrobat

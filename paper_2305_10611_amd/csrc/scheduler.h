@@ -28,4 +28,17 @@ struct SeqSchedule {
 
 int schedule_seqs(int32_t n_seq, const int32_t* len, SeqSchedule& out, std::string& err);
 
+// Bidirectional RNN with an output phase: levels 0 .. max len - 1 hold step k of both directions
+// (codes: forward row, then R + backward row), the last level holds every output operator (2R + row).
+struct BirnnSchedule {
+  int64_t n_rows = 0;
+  int32_t n_levels = 0;              // max len + 1, or 0
+  std::vector<int32_t> level_off;    // [n_levels + 1] into level_codes
+  std::vector<int32_t> level_codes;  // [3 R]
+  std::vector<int32_t> fwd_off;      // [max len + 1]: forward entries of level k are
+                                     // level_codes[level_off[k] .. level_off[k] + fwd_off[k+1] - fwd_off[k])
+};
+
+int schedule_birnn(int32_t n_seq, const int32_t* len, BirnnSchedule& out, std::string& err);
+
 }  // namespace acrobat

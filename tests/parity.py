@@ -53,22 +53,37 @@ def run_lstm(ctx, w, use_bias=True):
     return h[:R].cpu().numpy(), c[:R].cpu().numpy()
 
 
-def errors(got, want):
-    """(max abs error, max over rows of max-norm relative error)."""
+def run_birnn(ctx, w, use_bias=True):
+    R, H, n_out = int(np.sum(w["len"])), int(w["H"]), int(w["n_out"])
+    names = ("x", "fWx", "fWh", "fb", "finit", "bWx", "bWh", "bb", "binit", "C", "cb")
+    t = {k: dev(np.asarray(w[k], np.float32)) for k in names}
+    hf, hb, y = nan_filled(max(R, 1), H), nan_filled(max(R, 1), H), nan_filled(max(R, 1), n_out)
+    fwd = (t["fWx"], t["fWh"], t["fb"] if use_bias else None, t["finit"])
+    bwd = (t["bWx"], t["bWh"], t["bb"] if use_bias else None, t["binit"])
+    rc = ctx.acrobat_birnn_forward(w["len"], H, int(w["D"]), n_out, t["x"], fwd, bwd, t["C"],
+                                   t["cb"] if use_bias else None, hf, hb, y, stream_handle())
+    ctx.check(rc)
+    torch.cuda.synchronize()
+    return hf[:R].cpu().numpy(), hb[:R].cpu().numpy(), y[:R].cpu().numpy()
+
+
+def errors(got, want, ref_floor=1e-30):
+    """(max abs error, max over rows of max-norm relative error).  ref_floor bounds a row's
+    reference norm from below: rows a ReLU clamps to exactly zero have no relative error."""
     got = np.asarray(got, np.float64).reshape(want.shape[0], -1)
     want = np.asarray(want, np.float64).reshape(want.shape[0], -1)
     if want.size == 0:
         return 0.0, 0.0
     diff = np.abs(got - want)
     row_err = diff.max(axis=1)
-    row_ref = np.maximum(np.abs(want).max(axis=1), 1e-30)
+    row_ref = np.maximum(np.abs(want).max(axis=1), ref_floor)
     return float(diff.max()), float((row_err / row_ref).max())
 
 
-def assert_close(got, want, what=""):
+def assert_close(got, want, what="", ref_floor=1e-30):
     assert got.shape[0] == want.shape[0]
     assert not np.isnan(got).any(), f"{what}: NaN in the GPU result (a row was read before it was written, or never written)"
-    abs_err, rel_err = errors(got, want)
+    abs_err, rel_err = errors(got, want, ref_floor)
     assert abs_err <= ABS_TOL, f"{what}: max abs error {abs_err:.3e} > {ABS_TOL}"
     assert rel_err <= REL_TOL, f"{what}: max per-node relative error {rel_err:.3e} > {REL_TOL}"
     return abs_err, rel_err

@@ -272,6 +272,70 @@ def test_lstm_degenerate(ctx, P):
     assert h.shape[0] == 0
 
 
+# ---------------------------------------------------------------- bidirectional RNN (program phases)
+def check_birnn_schedule(ctx, lens):
+    from tests.test_oracle_birnn import birnn_graph
+    level_off, level_codes = ctx.acrobat_last_schedule()
+    prods, R = birnn_graph(np.asarray(lens))
+    if R == 0:
+        assert list(level_off) == [0]
+        return
+    _, order, batch_off = oracle.phase_schedule(prods, np.array([0] * (2 * R) + [1] * R, np.int32))
+    assert np.array_equal(level_off, batch_off) and np.array_equal(level_codes, order)
+
+
+def check_birnn(P, got, want, tag=""):
+    for name, g, o in zip(("hf", "hb", "y"), got, want):
+        # y = relu(.) has rows that are exactly zero: their error is judged by the absolute bound only
+        P.assert_close(g, o, f"{tag} {name}", ref_floor=0.1 if name == "y" else 1e-30)
+
+
+@pytest.mark.parametrize("H,D,n_out,n_seq,lo,hi", [(32, 32, 1, 3, 0, 5), (64, 96, 16, 70, 0, 20), (256, 256, 16, 64, 5, 50),
+                                                  (128, 64, 40, 300, 1, 7), (96, 32, 64, 33, 2, 12)])
+def test_birnn_ragged_with_bias_and_empty_sequences(ctx, P, H, D, n_out, n_seq, lo, hi):
+    w = gen.birnn_workload(n_seq, lo, hi, H, D, n_out, seed=H + D + n_out, bias_scale=0.3)
+    got = P.run_birnn(ctx, w)
+    check_birnn_schedule(ctx, w["len"])
+    check_birnn(P, got, oracle.birnn(w, nthreads=NT))
+    # a second call right behind the first reuses the second stream and both workspace halves
+    got2 = P.run_birnn(ctx, w)
+    assert all(np.array_equal(a, b) for a, b in zip(got, got2))
+
+
+def test_birnn_serialised_profiling_path_and_null_bias(ctx, P):
+    w = gen.birnn_workload(40, 0, 15, 64, 64, 10, seed=91, bias_scale=0.2)
+    got = P.run_birnn(ctx, w)
+    ctx.acrobat_set_profiling(True)
+    try:
+        got_serial = P.run_birnn(ctx, w)
+        rec = ctx.acrobat_last_profile()
+    finally:
+        ctx.acrobat_set_profiling(False)
+    assert all(np.array_equal(a, b) for a, b in zip(got, got_serial))
+    T = int(w["len"].max())
+    assert len(rec) == 2 + 2 * T + 1 and all(r[3] > 0 for r in rec)
+    wz = dict(w)
+    for k in ("fb", "bb", "cb"):
+        wz[k] = np.zeros_like(w[k])
+    g0 = P.run_birnn(ctx, wz, use_bias=True)
+    g1 = P.run_birnn(ctx, wz, use_bias=False)
+    assert all(np.array_equal(a, b) for a, b in zip(g0, g1))
+    check_birnn(P, g1, oracle.birnn(wz, nthreads=NT))
+
+
+def test_birnn_degenerate(ctx, P):
+    w = gen.birnn_workload(4, 1, 3, 32, 32, 4, seed=5)
+    w0 = dict(w, len=np.zeros(4, np.int32))
+    hf, hb, y = P.run_birnn(ctx, w0)
+    assert hf.shape[0] == 0 and y.shape[0] == 0
+    w1 = gen.birnn_workload(1, 1, 1, 32, 32, 3, seed=6, bias_scale=0.5)  # one token: both directions start and end on it
+    check_birnn(P, P.run_birnn(ctx, w1), oracle.birnn(w1))
+    import paper_2305_10611_amd as A
+    t = P.nan_filled(4, 32)
+    rc = ctx.acrobat_birnn_forward(np.array([2], np.int32), 32, 32, 0, t, (t, t, None, t), (t, t, None, t), t, None, t, t, t)
+    assert rc == A.EINVAL
+
+
 # ---------------------------------------------------------------- profiling mode
 def test_profiling_records_every_launch(ctx, P):
     w = make_config(0)
@@ -307,5 +371,7 @@ def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit, monkey
         oh, oc = oracle.varlen_lstm(s, nthreads=NT)
         P.assert_close(h, oh, "lstm h")
         P.assert_close(cc, oc, "lstm c")
+        b = gen.birnn_workload(90, 0, 9, 128, 64, 20, seed=tile * 5 + ksplit, bias_scale=0.2)
+        check_birnn(P, P.run_birnn(c, b), oracle.birnn(b, nthreads=NT), "birnn")
     finally:
         c.close()

@@ -120,3 +120,32 @@ def test_sequence_schedule_edge_cases():
     rc, level_off, rows = A.acrobat_schedule_seqs(w["len"])
     sizes = np.diff(level_off)
     assert sizes[0] == (w["len"] > 0).sum() and sizes.sum() == w["len"].sum() and np.all(np.diff(sizes) <= 0)
+
+
+# ---------------------------------------------------------------- bidirectional RNN with phases
+@pytest.mark.parametrize("lens", [[3, 1, 4, 0, 2], [1], [0, 0], [], [7, 7, 7], [1, 9, 2, 9, 1, 0, 5]])
+def test_birnn_schedule_is_bit_exact_against_the_phase_schedule_oracle(lens):
+    from tests.test_oracle_birnn import birnn_graph
+    lens = np.asarray(lens, np.int32)
+    rc, level_off, level_codes = A.acrobat_schedule_birnn(lens)
+    assert rc == A.OK
+    prods, R = birnn_graph(lens)
+    if R == 0:
+        assert list(level_off) == [0] and level_codes.size == 0
+        return
+    phase = np.array([0] * (2 * R) + [1] * R, np.int32)
+    _, order, batch_off = oracle.phase_schedule(prods, phase)
+    assert np.array_equal(level_off, batch_off) and np.array_equal(level_codes, order)
+
+
+def test_birnn_schedule_on_a_random_batch_and_bad_input():
+    rng = gen.make_rng(77)
+    lens = rng.integers(0, 40, size=200).astype(np.int32)
+    from tests.test_oracle_birnn import birnn_graph
+    rc, level_off, level_codes = A.acrobat_schedule_birnn(lens)
+    assert rc == A.OK
+    prods, R = birnn_graph(lens)
+    _, order, batch_off = oracle.phase_schedule(prods, np.array([0] * (2 * R) + [1] * R, np.int32))
+    assert np.array_equal(level_off, batch_off) and np.array_equal(level_codes, order)
+    rc, _, _ = A.acrobat_schedule_birnn(np.array([3, -1], np.int32))
+    assert rc == A.ESTRUCT or rc == A.EINVAL

@@ -106,6 +106,25 @@ def main():
         dominant = A.binding.K_MVRNN_LEVEL
         total_flops = n_int * flops_per[dominant]
         dtype, bound = "f32", "hbm"
+    elif kind == "birnn":
+        H, D, n_out = int(w["H"]), int(w["D"]), int(w["n_out"])
+        R = n_nodes
+        n_nodes = 3 * R  # dataflow-graph nodes per token: forward cell, backward cell, output operator
+        names = ("x", "fWx", "fWh", "fb", "finit", "bWx", "bWh", "bb", "binit", "C", "cb")
+        t = {k: dev(np.asarray(w[k], np.float32)) for k in names}
+        new_out = lambda: [torch.empty(R, H, device="cuda"), torch.empty(R, H, device="cuda"),
+                           torch.empty(R, n_out, device="cuda")]
+        make_step = lambda c, o, st: (lambda: c.check(c.acrobat_birnn_forward(
+            w["len"], H, D, n_out, t["x"], (t["fWx"], t["fWh"], t["fb"], t["finit"]),
+            (t["bWx"], t["bWh"], t["bb"], t["binit"]), t["C"], t["cb"], o[0], o[1], o[2], st)))
+        sched = lambda: A.acrobat_schedule_birnn(w["len"])
+        B = A.binding
+        flops_per = {B.K_RNN_INPUT: 2.0 * D * H, B.K_RNN_STEP: 2.0 * H * H, B.K_RNN_OUTPUT: 4.0 * H * n_out}
+        bytes_per = {B.K_RNN_INPUT: 4.0 * D + 4.0 * H, B.K_RNN_STEP: 12.0 * H + 8, B.K_RNN_OUTPUT: 8.0 * H + 4.0 * n_out}
+        weight_bytes = {B.K_RNN_INPUT: 4.0 * H * D, B.K_RNN_STEP: 4.0 * H * H, B.K_RNN_OUTPUT: 8.0 * H * n_out}
+        dominant = B.K_RNN_STEP
+        total_flops = R * (2 * flops_per[B.K_RNN_INPUT] + 2 * flops_per[B.K_RNN_STEP] + flops_per[B.K_RNN_OUTPUT])
+        dtype, bound = "f32", "mfma"
     else:
         H, D = int(w["H"]), int(w["D"])
         t = {k: dev(w[k]) for k in ("x", "Wx", "Wh", "b")}
@@ -218,6 +237,8 @@ def main():
             ref = oracle.treelstm(w, nthreads=nt)
         elif kind == "mvrnn":
             ref = oracle.mvrnn(w, nthreads=nt)
+        elif kind == "birnn":
+            ref = oracle.birnn(w, nthreads=nt)
         else:
             ref = oracle.varlen_lstm(w, nthreads=nt)
         c1 = time.perf_counter()

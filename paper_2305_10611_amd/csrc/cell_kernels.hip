@@ -465,6 +465,11 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
   int s = 1;
   while (s * 2 <= 8 && tiles * s * 2 <= 256 && n_slabs % (s * 2) == 0 && n_slabs / (s * 2) >= 2) s *= 2;
+  //  * the reduction kernel adds about 4.4 us to the level's dependent chain while one workgroup
+  //    streams about 50 KB/us: splitting must take at least that much streaming time off the
+  //    workgroup, or the level runs unsplit (single-gate RNN steps, narrow LSTMs).
+  const double wg_kb = (double)(32 * G + best.bm) * n_slabs * kBK * sizeof(float) / 1024.0;
+  if (s > 1 && wg_kb * (1.0 - 1.0 / s) < 4.4 * 50.0) s = 1;
   if (s == 1 && tiles > 256 && tiles <= 384 && n_slabs % 2 == 0 && n_slabs >= 8) s = 2;
   if (fits(best.bm, s)) best.ksplit = s;
   return best;

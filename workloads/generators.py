@@ -261,13 +261,18 @@ def birnn_workload(n_seq, len_lo, len_hi, H, D, n_out, seed, bias_scale=0.1):
 
 def paper_grid_workload(model: str, size: str, batch: int, seed: int | None = None):
     """Mini-batches shaped like the paper's evaluation grid (section 7.1): model size small /
-    large (hidden 256 / 512; MV-RNN 64 / 128) and batch size 8 / 64.  The treebank itself is not
-    available: sentence lengths are drawn uniformly from [5, 35] (mean 20) and parsed by random
-    binary splits; parameters are random, as in the paper."""
-    assert size in ("small", "large") and model in ("treelstm", "mvrnn")
-    s = SEED_BASE + 100 + (0 if model == "treelstm" else 10) + (0 if size == "small" else 5) + batch if seed is None else seed
+    large (hidden 256 / 512; MV-RNN 64 / 128) and batch size 8 / 64.  The treebank and the
+    sentence-pair corpus themselves are not available: sentence lengths are drawn uniformly from
+    [5, 35] (mean 20), trees are random binary splits; parameters are random, as in the paper.
+    The BiRNN's output layer has 16 units."""
+    assert size in ("small", "large") and model in ("treelstm", "mvrnn", "birnn")
+    s = (SEED_BASE + 100 + {"treelstm": 0, "mvrnn": 10, "birnn": 20}[model] + (0 if size == "small" else 5) + batch
+         if seed is None else seed)
     if model == "treelstm":
         w = treelstm_workload(batch, 5, 35, 256 if size == "small" else 512, 20000, "zipf1.1", s)
+    elif model == "birnn":
+        H = 256 if size == "small" else 512
+        w = birnn_workload(batch, 5, 35, H, H, 16, s)
     else:
         w = mvrnn_workload(batch, 5, 35, 64 if size == "small" else 128, s)
     w["name"] = f"paper_{model}_{size}_bs{batch}"

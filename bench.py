@@ -6,8 +6,8 @@ single index upload and every level kernel.  Weights, tables and inputs are resi
 before the timed region; the host structure arrays (tree child indices / sequence lengths)
 are consumed by the call itself, as the library's boundary defines.
 
-Prints ONE JSON line.  `roofline` is measured live with HIP events recorded by the library
-on the launch stream around every launch of the dominant kernel; `cpu_baseline` is the CPU
+Prints ONE JSON line.  `roofline` is measured live with HIP events that the library hands to
+every launch on its stream (stamped with the kernel's own begin and end); `cpu_baseline` is the CPU
 oracle timed on this machine's host cores on the same inputs.
 """
 from __future__ import annotations
@@ -25,6 +25,15 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summaries
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB per dispatch, factors from a plain copy of known size).
+# Hardware counters cannot be read from inside this process; workloads without a summary report null.
+MEASURED_TRAFFIC = {
+    ("treelstm_h512_256", "kind=2 tile=64"): (56.9e6, "profiles/treelstm_h512_256_cell_level_kernel.md"),
+    ("mvrnn_d64_64", "kind=3 tile=1"): (6.9e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md"),
+    ("lstm_h512_256", "kind=6 tile=64"): (14.5e6, "profiles/lstm_h512_256_cell_level_kernel.md"),
+}
 
 
 def main():
@@ -195,6 +204,8 @@ def main():
     for i, r in enumerate(recs[0]):
         per_launch.append((r[0], r[1], r[2], r[4], float(np.mean([rr[i][3] for rr in recs])), r[5]))
     t_device_ms = sum(p[4] for p in per_launch)
+    K_REDUCE = A.binding.K_SPLITK_REDUCE
+    t_reduce_ms = sum(p[4] for p in per_launch if p[0] == K_REDUCE)
     # dominant kernel = the variant of the dominant kind that accounts for most device time
     by_tile = {}
     for k, lv, n, tile, ms, _ in per_launch:
@@ -211,14 +222,21 @@ def main():
     else:
         achieved = (units * bytes_per[dominant] + launches * weight_bytes[dominant]) / (ms_sum * 1e-3) / 1e9
         peak, unit = PEAK_HBM_GBS, "GB/s"
+    kname = f"kind={dominant} tile={dom_tile}"
+    traffic, traffic_src = MEASURED_TRAFFIC.get((w["name"], kname), (None, None))
     roofline = {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
-                "frac": round(achieved / peak, 4), "traffic": None,
-                "kernel": f"kind={dominant} tile={dom_tile}", "launches_per_step": launches,
+                "frac": round(achieved / peak, 4), "traffic": traffic, "traffic_unit": "bytes/launch",
+                "traffic_source": traffic_src,
+                "algorithmic_bytes_per_launch": round((units * bytes_per[dominant] + launches * weight_bytes[dominant]) / launches),
+                "kernel": kname, "launches_per_step": launches,
                 "units_per_step": units, "avg_launch_us": round(ms_sum / launches * 1e3, 2)}
 
     if args.verbose:
         print(f"{'kind':>4} {'lvl':>4} {'n':>6} {'tile':>4} {'ks':>3} {'us':>9} {'TFLOP/s':>8} {'GB/s':>8}", file=sys.stderr)
         for k, lv, n, tile, ms, ks in per_launch:
+            if k == K_REDUCE:
+                print(f"{'red':>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f}", file=sys.stderr)
+                continue
             fl = n * flops_per[k]
             by = n * bytes_per[k] + weight_bytes[k]
             print(f"{k:>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f} {fl / ms / 1e9:>8.2f} {by / ms / 1e6:>8.1f}",
@@ -257,6 +275,7 @@ def main():
         "config": {"workload": w["name"], "index": args.config, "nodes": n_nodes, "seed": int(w["seed"])},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap,
         "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
+                      "t_splitk_reduce_ms": round(t_reduce_ms, 4),
                       "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),
                       "device_tflops": round(total_flops / (t_device_ms * 1e-3) / 1e12, 3),
                       "max_abs_err_vs_oracle": err},

@@ -162,15 +162,18 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
 int acrobat_last_schedule(const acrobat_ctx* ctx, int32_t* n_levels, const int32_t** level_off,
                           const int32_t** level_nodes);
 
-/* Per-launch timing.  With profiling on, a forward call brackets every kernel launch with HIP
- * events on the caller's stream and synchronises the stream before returning. */
+/* Per-launch timing.  With profiling on, a forward call gives every kernel launch a start and a
+ * stop event of its own (stamped by the runtime with the kernel's begin and end, so `ms` is the
+ * kernel's execution time without launch gaps) and synchronises the stream before returning.
+ * The reduction kernel of a k-split level has its own record (ACROBAT_K_SPLITK_REDUCE) directly
+ * behind the record of its level. */
 typedef struct {
   int32_t kind;  /* ACROBAT_K_* */
   int32_t level; /* depth of the batch */
   int32_t n;     /* nodes (rows) in the batch */
   int32_t tile;  /* nodes per workgroup tile of the kernel variant that was launched */
   int32_t ksplit; /* workgroups sharing the contraction range of one tile */
-  float ms;      /* device time of the launch */
+  float ms;      /* execution time of the kernel */
 } acrobat_launch_record;
 
 #define ACROBAT_K_TREE_LEAF 1
@@ -182,6 +185,7 @@ typedef struct {
 #define ACROBAT_K_RNN_INPUT 7
 #define ACROBAT_K_RNN_STEP 8
 #define ACROBAT_K_RNN_OUTPUT 9
+#define ACROBAT_K_SPLITK_REDUCE 10
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 /* Records of the last forward call (context-owned, valid until the next forward call). */

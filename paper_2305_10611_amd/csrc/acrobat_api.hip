@@ -127,27 +127,35 @@ int reserve_aux_stream(acrobat_ctx* ctx) {
   return ACROBAT_OK;
 }
 
-// Brackets a launch with events when profiling is on.
+// Per-launch timing when profiling is on: every launch gets its own start/stop events, which the
+// runtime stamps with the kernel's begin and end (the k-split reduction kernel gets a record of its
+// own, kind ACROBAT_K_SPLITK_REDUCE, right behind its level's record).
 struct LaunchTimer {
   acrobat_ctx* ctx;
   hipStream_t stream;
+  LaunchEvents ev;  // events of the launch that begin() announced (all null when profiling is off)
   int begin(int32_t kind, int32_t level, int32_t n) {
+    ev = LaunchEvents();
     if (!ctx->profiling) return ACROBAT_OK;
-    const size_t need = 2 * (ctx->records.size() + 1);
-    while (ctx->events.size() < need) {
+    const size_t first = 2 * ctx->records.size();
+    while (ctx->events.size() < first + 4) {
       hipEvent_t e;
       HIP_TRY(ctx, hipEventCreate(&e));
       ctx->events.push_back(e);
     }
     ctx->records.push_back({kind, level, n, 0, 1, 0.0f});
-    HIP_TRY(ctx, hipEventRecord(ctx->events[need - 2], stream));
+    ev.start = ctx->events[first];
+    ev.stop = ctx->events[first + 1];
+    ev.reduce_start = ctx->events[first + 2];
+    ev.reduce_stop = ctx->events[first + 3];
     return ACROBAT_OK;
   }
   int32_t* tile() { return ctx->profiling ? &ctx->records.back().tile : nullptr; }
   int32_t* ksplit() { return ctx->profiling ? &ctx->records.back().ksplit : nullptr; }
   int end() {
     if (!ctx->profiling) return ACROBAT_OK;
-    HIP_TRY(ctx, hipEventRecord(ctx->events[2 * ctx->records.size() - 1], stream));
+    const acrobat_launch_record r = ctx->records.back();
+    if (r.ksplit > 1) ctx->records.push_back({ACROBAT_K_SPLITK_REDUCE, r.level, r.n, r.tile, r.ksplit, 0.0f});
     return ACROBAT_OK;
   }
   int finish() {
@@ -332,7 +340,7 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
       }
       TRY(timer.begin(lv == 0 ? ACROBAT_K_TREE_LEAF : ACROBAT_K_TREE_INTERNAL, lv, n));
       HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream, ctx->splitk,
-                                     timer.tile(), timer.ksplit()));
+                                     timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
     return timer.finish();
@@ -388,7 +396,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
     LaunchTimer timer{ctx, stream};
     if (copy_leaves) {
       TRY(timer.begin(ACROBAT_K_MVRNN_LEAFCOPY, 0, n_leaf));
-      HIP_TRY(ctx, launch_mvrnn_leaf_copy(n_leaf, d, d_out, d_ia, d_vec_tab, d_mat_tab, d_vec, d_mat, stream));
+      HIP_TRY(ctx, launch_mvrnn_leaf_copy(n_leaf, d, d_out, d_ia, d_vec_tab, d_mat_tab, d_vec, d_mat, stream, timer.ev));
       TRY(timer.end());
     }
     for (int32_t lv = 1; lv < s.n_levels; ++lv) {
@@ -404,7 +412,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
       a.W = d_W; a.WM = d_WM;
       a.vec = d_vec; a.mat = d_mat;
       TRY(timer.begin(ACROBAT_K_MVRNN_LEVEL, lv, n));
-      HIP_TRY(ctx, launch_mvrnn_level(a, stream, timer.tile()));
+      HIP_TRY(ctx, launch_mvrnn_level(a, stream, timer.tile(), timer.ev));
       TRY(timer.end());
     }
     return timer.finish();
@@ -457,7 +465,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       a.W = d_Wx; a.ldw = D; a.bias = d_b;
       a.zout = ctx->d_scratch;
       TRY(timer.begin(ACROBAT_K_LSTM_INPUT, 0, R));
-      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
+      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z, a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
     for (int32_t t = 0; t < s.n_levels; ++t) {
@@ -474,7 +482,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
         a.cprev_src = d_c;
       }
       TRY(timer.begin(ACROBAT_K_LSTM_STEP, t, n));
-      HIP_TRY(ctx, launch_cell_level(EPI_LSTM_STEP, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
+      HIP_TRY(ctx, launch_cell_level(EPI_LSTM_STEP, a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
     return timer.finish();
@@ -575,7 +583,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
       a.W = par[dir]->Wx; a.ldw = D; a.bias = par[dir]->b;
       a.zout = xp[dir];
       TRY(timer.begin(ACROBAT_K_RNN_INPUT, dir, R));
-      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z1, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit()));
+      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z1, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
     for (int32_t k = 0; k < T; ++k) {
@@ -591,7 +599,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
         a.zadd = xp[dir];
         a.h = hdir[dir];
         TRY(timer.begin(ACROBAT_K_RNN_STEP, k, n));
-        HIP_TRY(ctx, launch_cell_level(EPI_RNN_STEP, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit()));
+        HIP_TRY(ctx, launch_cell_level(EPI_RNN_STEP, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit(), timer.ev));
         TRY(timer.end());
       }
     }
@@ -608,7 +616,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
       a.W = d_C; a.ldw = 2 * H; a.bias = d_cb;
       a.y = d_y; a.ldo = n_out;
       TRY(timer.begin(ACROBAT_K_RNN_OUTPUT, T, R));
-      HIP_TRY(ctx, launch_cell_level(EPI_RELU_OUT, a, stream, ctx->splitk, timer.tile(), timer.ksplit()));
+      HIP_TRY(ctx, launch_cell_level(EPI_RELU_OUT, a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
     return timer.finish();

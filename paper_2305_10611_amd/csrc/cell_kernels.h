@@ -2,6 +2,7 @@
 // mvrnn_kernels.hip).  Plain structs and functions only; no HIP types besides hipStream_t.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 
@@ -50,10 +51,19 @@ struct SplitKWorkspace {
   int32_t force_bm = 0, force_ksplit = 0;  // tuning override, 0 = automatic
 };
 
+// Optional events handed to the launches themselves: the runtime stamps them with the kernel's
+// own begin and end, so their elapsed time is the kernel's execution time without the idle gaps
+// that events recorded on the stream add around a launch.  Null = plain launch.
+struct LaunchEvents {
+  hipEvent_t start = nullptr, stop = nullptr;                // the level kernel
+  hipEvent_t reduce_start = nullptr, reduce_stop = nullptr;  // the reduction kernel of a k-split level
+};
+
 // Launches the kernel for one level; picks the node-tile height and k split from the level's
 // size and reports them in *tile / *ksplit (may be null).  Returns hipGetLastError().
 hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,
-                             const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit);
+                             const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit,
+                             const LaunchEvents& ev = LaunchEvents());
 
 // MV-RNN level: for each of the n nodes at list positions [0,n):
 //   p = tanh(W [B a ; A b]),  P = W_M [A ; B]  with (a,A) / (b,B) the left / right child state.
@@ -69,11 +79,12 @@ struct MvrnnLevelArgs {
   const float* W; const float* WM;  // [d,2d] each
   float* vec; float* mat;           // arena [rows,d], [rows,d,d]
 };
-hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile);
+hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile,
+                              const LaunchEvents& ev = LaunchEvents());
 
 // Copies table rows `token[i]` into arena rows out_rows[i] (vector and matrix), i in [0,n).
 hipError_t launch_mvrnn_leaf_copy(int32_t n, int32_t d, const int32_t* out_rows, const int32_t* token,
                                   const float* vec_tab, const float* mat_tab, float* vec, float* mat,
-                                  hipStream_t stream);
+                                  hipStream_t stream, const LaunchEvents& ev = LaunchEvents());
 
 }  // namespace acrobat

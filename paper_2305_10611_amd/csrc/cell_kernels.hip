@@ -477,27 +477,27 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
 
 template <int G, int EPI>
 hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitKWorkspace& ws,
-                        int32_t* tile, int32_t* ksplit) {
+                        int32_t* tile, int32_t* ksplit, const LaunchEvents& ev) {
   const Shape sh = pick_shape<G>(a, ws);
   const int n_jt = a.H / 32;
   const unsigned grid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
   if (tile) *tile = sh.bm;
   if (ksplit) *ksplit = sh.ksplit;
   if (sh.bm == 128) {
-    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
-                       ws.partial);
+    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, 0, a, sh.ksplit, ws.partial);
   } else if (sh.bm == 64) {
-    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
-                       ws.partial);
+    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, 0, a, sh.ksplit, ws.partial);
   } else {
-    hipLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, a, sh.ksplit,
-                       ws.partial);
+    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, 0, a, sh.ksplit, ws.partial);
   }
   if (sh.ksplit > 1) {
     const int wm_count = sh.bm / 32;
     const unsigned rgrid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * wm_count * 16);
-    hipLaunchKernelGGL((cell_splitk_reduce_kernel<G, EPI>), dim3(rgrid), dim3(64), 0, stream, a, sh.ksplit,
-                       wm_count, ws.partial);
+    hipExtLaunchKernelGGL((cell_splitk_reduce_kernel<G, EPI>), dim3(rgrid), dim3(64), 0, stream, ev.reduce_start,
+                          ev.reduce_stop, 0, a, sh.ksplit, wm_count, (const float*)ws.partial);
   }
   return hipGetLastError();
 }
@@ -505,16 +505,16 @@ hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitK
 }  // namespace
 
 hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,
-                             const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit) {
+                             const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit, const LaunchEvents& ev) {
   if (a.n <= 0) return hipSuccess;
   switch (epi) {
-    case EPI_TREE_LEAF: return launch_shape<3, EPI_TREE_LEAF>(a, stream, ws, tile, ksplit);
-    case EPI_TREE_INTERNAL: return launch_shape<5, EPI_TREE_INTERNAL>(a, stream, ws, tile, ksplit);
-    case EPI_LSTM_STEP: return launch_shape<4, EPI_LSTM_STEP>(a, stream, ws, tile, ksplit);
-    case EPI_STORE_Z: return launch_shape<4, EPI_STORE_Z>(a, stream, ws, tile, ksplit);
-    case EPI_STORE_Z1: return launch_shape<1, EPI_STORE_Z>(a, stream, ws, tile, ksplit);
-    case EPI_RNN_STEP: return launch_shape<1, EPI_RNN_STEP>(a, stream, ws, tile, ksplit);
-    case EPI_RELU_OUT: return launch_shape<1, EPI_RELU_OUT>(a, stream, ws, tile, ksplit);
+    case EPI_TREE_LEAF: return launch_shape<3, EPI_TREE_LEAF>(a, stream, ws, tile, ksplit, ev);
+    case EPI_TREE_INTERNAL: return launch_shape<5, EPI_TREE_INTERNAL>(a, stream, ws, tile, ksplit, ev);
+    case EPI_LSTM_STEP: return launch_shape<4, EPI_LSTM_STEP>(a, stream, ws, tile, ksplit, ev);
+    case EPI_STORE_Z: return launch_shape<4, EPI_STORE_Z>(a, stream, ws, tile, ksplit, ev);
+    case EPI_STORE_Z1: return launch_shape<1, EPI_STORE_Z>(a, stream, ws, tile, ksplit, ev);
+    case EPI_RNN_STEP: return launch_shape<1, EPI_RNN_STEP>(a, stream, ws, tile, ksplit, ev);
+    case EPI_RELU_OUT: return launch_shape<1, EPI_RELU_OUT>(a, stream, ws, tile, ksplit, ev);
   }
   return hipErrorInvalidValue;
 }

@@ -415,27 +415,27 @@ __global__ __launch_bounds__(256) void mvrnn_leaf_copy_kernel(int n, int d, cons
 
 }  // namespace
 
-hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile) {
+hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile, const LaunchEvents& ev) {
   if (tile) *tile = 1;
   if (a.n <= 0) return hipSuccess;
   const int grid = a.n < 512 ? a.n : 512;  // two resident workgroups per compute unit, each strides over the level
   if (a.d == 128) {
-    hipLaunchKernelGGL(mvrnn_stream_kernel<128>, dim3(a.n < 256 ? a.n : 256), dim3(256), 0, stream, a);
+    hipExtLaunchKernelGGL(mvrnn_stream_kernel<128>, dim3(a.n < 256 ? a.n : 256), dim3(256), 0, stream, ev.start, ev.stop, 0, a);
   } else if (a.variant == 1) {
-    hipLaunchKernelGGL(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, a);
+    hipExtLaunchKernelGGL(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, 0, a);
   } else {
-    hipLaunchKernelGGL(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, a);
+    hipExtLaunchKernelGGL(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, 0, a);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_mvrnn_leaf_copy(int32_t n, int32_t d, const int32_t* out_rows, const int32_t* token,
                                   const float* vec_tab, const float* mat_tab, float* vec, float* mat,
-                                  hipStream_t stream) {
+                                  hipStream_t stream, const LaunchEvents& ev) {
   if (n <= 0) return hipSuccess;
   const int grid = n < 2048 ? n : 2048;
-  hipLaunchKernelGGL(mvrnn_leaf_copy_kernel, dim3(grid), dim3(256), 0, stream, n, d, out_rows, token,
-                     vec_tab, mat_tab, vec, mat);
+  hipExtLaunchKernelGGL(mvrnn_leaf_copy_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, 0, n, d,
+                        out_rows, token, vec_tab, mat_tab, vec, mat);
   return hipGetLastError();
 }
 

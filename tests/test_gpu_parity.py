@@ -312,8 +312,10 @@ def test_birnn_serialised_profiling_path_and_null_bias(ctx, P):
     finally:
         ctx.acrobat_set_profiling(False)
     assert all(np.array_equal(a, b) for a, b in zip(got, got_serial))
+    import paper_2305_10611_amd as A
     T = int(w["len"].max())
-    assert len(rec) == 2 + 2 * T + 1 and all(r[3] > 0 for r in rec)
+    assert all(r[3] > 0 for r in rec)
+    assert sum(r[0] != A.binding.K_SPLITK_REDUCE for r in rec) == 2 + 2 * T + 1
     wz = dict(w)
     for k in ("fb", "bb", "cb"):
         wz[k] = np.zeros_like(w[k])
@@ -345,10 +347,17 @@ def test_profiling_records_every_launch(ctx, P):
         rec = ctx.acrobat_last_profile()
     finally:
         ctx.acrobat_set_profiling(False)
+    import paper_2305_10611_amd as A
     level_off, _ = ctx.acrobat_last_schedule()
+    assert all(r[3] > 0 for r in rec)
+    # a k-split level has a second record for its reduction kernel right behind it
+    for prev, r in zip(rec, rec[1:]):
+        if r[0] == A.binding.K_SPLITK_REDUCE:
+            assert prev[0] != A.binding.K_SPLITK_REDUCE and prev[5] > 1 and prev[1:3] == r[1:3]
+    assert sum(r[0] == A.binding.K_SPLITK_REDUCE for r in rec) == sum(r[5] > 1 for r in rec if r[0] != A.binding.K_SPLITK_REDUCE)
+    rec = [r for r in rec if r[0] != A.binding.K_SPLITK_REDUCE]
     assert len(rec) == len(level_off) - 1
     assert [r[2] for r in rec] == list(np.diff(level_off))
-    assert all(r[3] > 0 for r in rec)
 
 
 # ---------------------------------------------------------------- every kernel variant

@@ -63,8 +63,13 @@ __device__ __forceinline__ constexpr int gate_row(int g) {
 // all loads of a pass are in flight together instead of one dependent chain per row (the
 // stores may alias the loads as far as the compiler can tell, which would otherwise serialise
 // the rows).
+//
+// `sidx` (may be null) is the tile's index table in LDS, [3][bm]: arena row written, first and
+// second operand row of tile row r = node - m0, as staged by the contraction kernel's prologue
+// (tail rows hold the entries of node n - 1); without it the indices come from global memory.
 template <int G, int EPI, int NV, class Acc, class NodeOf>
-__device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int j, Acc&& acc, NodeOf&& node_of) {
+__device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int j, Acc&& acc, NodeOf&& node_of,
+                                              const int* sidx = nullptr, const int bm = 0, const int m0 = 0) {
   const int H = a.H, n = a.n;
   float bz[G];
 #pragma unroll
@@ -81,14 +86,21 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
     const int node = node_of(v);
     live[v] = node < n;
     const int nd = live[v] ? node : n - 1;  // tail rows read what the last node reads, store nothing
-    orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
     ia[v] = ib[v] = 0;
-    if constexpr (EPI == EPI_TREE_INTERNAL) {
-      ia[v] = a.idx0[nd];
-      ib[v] = a.idx1[nd];
-    }
-    if constexpr (EPI == EPI_LSTM_STEP) {
-      if (a.cprev_src) ia[v] = a.idx0[nd];
+    if (sidx) {
+      const int r = node - m0;
+      orow[v] = (size_t)sidx[r];
+      if constexpr (EPI == EPI_TREE_INTERNAL || EPI == EPI_LSTM_STEP) ia[v] = sidx[bm + r];
+      if constexpr (EPI == EPI_TREE_INTERNAL) ib[v] = sidx[2 * bm + r];
+    } else {
+      orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
+      if constexpr (EPI == EPI_TREE_INTERNAL) {
+        ia[v] = a.idx0[nd];
+        ib[v] = a.idx1[nd];
+      }
+      if constexpr (EPI == EPI_LSTM_STEP) {
+        if (a.cprev_src) ia[v] = a.idx0[nd];
+      }
     }
   }
 
@@ -169,7 +181,8 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   constexpr int RED_FLOATS = WM * (WK - 1) * G * kBlockFloats;
   constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
   constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
-  __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS];
+  __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS + 3 * BM];
+  int* const sidx = reinterpret_cast<int*>(smem + SMEM_FLOATS);  // the tile's index table, see cell_epilogue
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wk = wave / WM;
@@ -182,21 +195,16 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
 
   // ---- global -> LDS staging assignment: 16-byte chunk `tid & 7` of tile row `tid >> 3` (+32 i)
   const int lrow = tid >> 3, lpart = (tid & 7) * 4;
-  const float* aptr0[WM];
-  const float* aptr1[WM];
+  // The tile's indices are read once: for the operand row pointers below and, through LDS, for
+  // the epilogue (which then starts with an LDS read instead of a dependent global load).
+  int row0[WM], row1[WM];
 #pragma unroll
   for (int i = 0; i < WM; ++i) {
     int node = m0 + lrow + 32 * i;
     node = node < n ? node : n - 1;  // tail rows re-read the last node; never stored
-    aptr0[i] = aptr1[i] = nullptr;
-    if (a.nseg > 0) {
-      const size_t r0 = a.idx0 ? (size_t)a.idx0[node] : (size_t)node;
-      aptr0[i] = a.src0 + r0 * (size_t)a.ld0 + lpart;
-    }
-    if (a.nseg > 1) {
-      const size_t r1 = a.idx1 ? (size_t)a.idx1[node] : (size_t)node;
-      aptr1[i] = a.src1 + r1 * (size_t)a.ld1 + lpart;
-    }
+    row0[i] = a.idx0 ? a.idx0[node] : node;
+    row1[i] = a.idx1 ? a.idx1[node] : node;
+    if ((tid & 7) == 2) sidx[lrow + 32 * i] = a.out_rows ? a.out_rows[node] : node;
   }
   // weights: one per-lane offset; gate and slab offsets are uniform (fit 32 bits: host-checked)
   // (RELU_OUT: rows past the last weight row re-read it; their columns are never stored)
@@ -233,16 +241,25 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   constexpr int AHEAD = Q == 1 ? 2 : 1;  // a slab is stored to LDS AHEAD iterations before its use
   floatx4 ra[NS][WM], rb[NS][G];
   floatx4 fa[2], fb[2][G];
-  auto load_slab = [&](int set, int i) {
+  const float* aptr0[WM];
+  const float* aptr1[WM];
+  auto load_slab_b = [&](int set, int i) {
+    const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
+  };
+  auto load_slab_a = [&](int set, int i) {
     const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
     const int seg = kb >= slabs_per_seg;
     const int koff = (kb - (seg ? slabs_per_seg : 0)) * kBK;
 #pragma unroll
     for (int r = 0; r < WM; ++r)
       ra[set][r] = *reinterpret_cast<const floatx4*>((seg ? aptr1[r] : aptr0[r]) + koff);
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-      rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
+  };
+  auto load_slab = [&](int set, int i) {
+    load_slab_a(set, i);
+    load_slab_b(set, i);
   };
   const int st_off = lrow * kBK + (((tid & 7) ^ ((lrow >> 1) & 7)) << 2);
   auto store_slab = [&](int set, int buf) {
@@ -320,11 +337,24 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     if (Q == 1) __syncthreads();
   };
 
+  // The weight slabs do not depend on the indices: they are requested first, the gathered rows as
+  // soon as the indices have arrived.
+  if (my_slabs > 0) {
+#pragma unroll
+    for (int i = 0; i < NS; ++i) load_slab_b(i, i);
+  }
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    aptr0[i] = a.nseg > 0 ? a.src0 + (size_t)row0[i] * (size_t)a.ld0 + lpart : nullptr;
+    aptr1[i] = a.nseg > 1 ? a.src1 + (size_t)row1[i] * (size_t)a.ld1 + lpart : nullptr;
+    if ((tid & 7) == 0) sidx[BM + lrow + 32 * i] = row0[i];
+    if ((tid & 7) == 1) sidx[2 * BM + lrow + 32 * i] = row1[i];
+  }
   if (my_slabs > 0) {
     // all NS staging sets are requested at once (slab i -> set i); slabs 0 .. AHEAD-1 then go
     // to LDS and their sets are refilled with slabs NS .. NS+AHEAD-1
 #pragma unroll
-    for (int i = 0; i < NS; ++i) load_slab(i, i);
+    for (int i = 0; i < NS; ++i) load_slab_a(i, i);
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i) {
       store_slab(i, i);
@@ -348,44 +378,71 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
       }
     }
     if (Q > 1) __syncthreads();  // the last group's barrier pairs: LDS is reused by the reductions
+  } else {
+    __syncthreads();  // no contraction (first step of a recurrence): publish the index table
   }
 
-  // sums the partial tiles of the WK wavefronts of a node block into its wk == 0 wavefront
-  // (fixed order wk = 1, 2, ...): one round through LDS
-  auto reduce_over_wk = [&]() {
-    if constexpr (WK > 1) {
-      // 16-byte LDS accesses: register quad (g, v4) of lane l sits at float4 slot (g*4 + v4)*64 + l
-      floatx4* red = reinterpret_cast<floatx4*>(smem) + (wm * (WK - 1)) * (G * 4 * 64);
-      __syncthreads();
-      if (wk > 0) {
+  // The WK wavefronts of a node block hold partial sums over their share of k.  They are added
+  // by a reduce-scatter through LDS: wavefront wk ends up with the complete sums of the QPW = 4/WK
+  // accumulator quads v4 = wk*QPW .. wk*QPW + QPW-1 (8 nodes each) and every wavefront runs the
+  // epilogue for the rows it owns, so the gate arithmetic is spread over all four SIMDs.  Each
+  // quad is summed in ascending wk order, whoever owns it.
+  constexpr int QPW = 4 / WK;  // quads owned per wavefront
+  constexpr int NV = 4 * QPW;  // accumulator rows owned per lane
+  float own[G][NV];
+  if constexpr (WK == 1) {
 #pragma unroll
-        for (int g = 0; g < G; ++g)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
-          for (int v4 = 0; v4 < 4; ++v4) {
-            floatx4 q;
+      for (int v = 0; v < 16; ++v) own[g][v] = acc[g][v];
+  } else {
+    // inbox of wavefront (wm, o): (WK-1) senders x G gates x QPW quads, one float4 per lane each
+    floatx4* red = reinterpret_cast<floatx4*>(smem);
+    auto inbox = [&](int o, int sender, int g, int qi) {
+      const int slot = sender < o ? sender : sender - 1;
+      return ((((wm * WK + o) * (WK - 1) + slot) * G + g) * QPW + qi) * 64 + lane;
+    };
+    __syncthreads();
 #pragma unroll
-            for (int e = 0; e < 4; ++e) q[e] = acc[g][v4 * 4 + e];
-            red[(wk - 1) * (G * 4 * 64) + (g * 4 + v4) * 64 + lane] = q;
-          }
-      }
-      __syncthreads();
-      if (wk == 0) {
+    for (int v4 = 0; v4 < 4; ++v4) {
+      const int o = v4 / QPW, qi = v4 % QPW;
+      if (o != wk) {
 #pragma unroll
-        for (int r = 0; r < WK - 1; ++r)
+        for (int g = 0; g < G; ++g) {
+          floatx4 q;
 #pragma unroll
-          for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-              const floatx4 q = red[r * (G * 4 * 64) + (g * 4 + v4) * 64 + lane];
-#pragma unroll
-              for (int e = 0; e < 4; ++e) acc[g][v4 * 4 + e] += q[e];
-            }
+          for (int e = 0; e < 4; ++e) q[e] = acc[g][v4 * 4 + e];
+          red[inbox(o, wk, g, qi)] = q;
+        }
       }
     }
-  };
-  reduce_over_wk();
-
-  if (wk != 0) return;
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int qi = 0; qi < QPW; ++qi) {
+        floatx4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int src = 0; src < WK; ++src) {  // ascending wk, own contribution in its place
+          floatx4 q;
+          if (src == wk) {
+#pragma unroll
+            for (int o = 0; o < WK; ++o)
+              if (o == wk) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q[e] = acc[g][(o * QPW + qi) * 4 + e];
+              }
+          } else {
+            q = red[inbox(wk, src, g, qi)];
+          }
+          sum += q;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) own[g][qi * 4 + e] = sum[e];
+      }
+  }
+  // accumulator row of owned row v: quad wk*QPW + v/4, element v%4
+  auto acc_row = [&](int v) { return (wk * QPW + (v >> 2)) * 4 + (v & 3); };
 
   // ---- k split over workgroups: store the partial tile in register layout and stop; the
   // reduction kernel that follows on the stream adds the partial tiles and runs the epilogue
@@ -395,14 +452,18 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mine[(g * 16 + v) * 64 + lane] = acc[g][v];
+      for (int v = 0; v < NV; ++v) mine[(g * 16 + acc_row(v)) * 64 + lane] = own[g][v];
     return;
   }
 
-  // ---- fused epilogue (rows of lane: node = m0 + 32 wm + 8 (v / 4) + 4 (lane / 32) + v % 4)
-  cell_epilogue<G, EPI, 16>(
-      a, j0 + (lane & 31), [&](int g, int v) { return acc[g][v]; },
-      [&](int v) { return m0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3); });
+  // ---- fused epilogue (accumulator row r of a lane: node = m0 + 32 wm + 8 (r / 4) + 4 (lane / 32) + r % 4)
+  cell_epilogue<G, EPI, NV>(
+      a, j0 + (lane & 31), [&](int g, int v) { return own[g][v]; },
+      [&](int v) {
+        const int r = acc_row(v);
+        return m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+      },
+      sidx, BM, m0);
 }
 
 // Second half of a level whose k range was split over `ksplit` workgroups: one wavefront per

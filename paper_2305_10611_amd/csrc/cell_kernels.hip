@@ -170,15 +170,28 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
   }
 }
 
-template <int G, int EPI, int WM, int WK>
+// PACK = false: the tile is 32 hidden units wide and has one 32-column block per gate (NB = G).
+// PACK = true (latency-bound levels; WM = 1, WK = 4 only): the tile is kPackJ = 8 hidden units wide
+// and its G*8 columns c = g*8 + jj are packed into NB = ceil(G*8 / 32) blocks, so a level has four
+// times as many workgroups, each streaming a quarter of the weight rows, and needs no k split
+// across workgroups (no second launch).  The gates of a (node, j) pair then sit in different lanes;
+// the reduction over the four wavefronts goes through LDS anyway and hands thread t the sums of
+// node t / 8, unit t % 8: one epilogue element per thread.
+constexpr int kPackJ = 8;
+
+template <int G, int EPI, int WM, int WK, bool PACK = false>
 __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelArgs a, const int ksplit,
                                                                  float* __restrict__ partial) {
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
+  static_assert(!PACK || (WM == 1 && WK == 4), "packed columns: one node block, k split over the wavefronts");
+  constexpr int NB = PACK ? (G * kPackJ + 31) / 32 : G;  // 32-column blocks of the weight tile
+  constexpr int JW = PACK ? kPackJ : 32;                 // hidden units per tile
   constexpr int BM = 32 * WM;
-  constexpr int BROWS = 32 * G;
+  constexpr int BROWS = 32 * NB;
   constexpr int Q = 4 / WK;  // 8-k groups of a slab handled by one wavefront
   constexpr int TILE_FLOATS = (BM + BROWS) * kBK;
-  constexpr int RED_FLOATS = WM * (WK - 1) * G * kBlockFloats;
+  constexpr int ZLD = NB * 32 + 8;  // PACK: row stride of the per-wavefront sums in LDS
+  constexpr int RED_FLOATS = PACK ? WK * 32 * ZLD : WM * (WK - 1) * G * kBlockFloats;
   constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
   constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
   __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS + 3 * BM];
@@ -187,11 +200,11 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wk = wave / WM;
   const int H = a.H, n = a.n;
-  const int n_jt = H >> 5;
+  const int n_jt = H / JW;
   const int jt = blockIdx.x % n_jt;
   const int rest = blockIdx.x / n_jt;
   const int ks = rest % ksplit, mt = rest / ksplit;
-  const int j0 = jt * 32, m0 = mt * BM;
+  const int j0 = jt * JW, m0 = mt * BM;
 
   // ---- global -> LDS staging assignment: 16-byte chunk `tid & 7` of tile row `tid >> 3` (+32 i)
   const int lrow = tid >> 3, lpart = (tid & 7) * 4;
@@ -211,10 +224,25 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   const int wrow = EPI == EPI_RELU_OUT ? (j0 + lrow < a.n_cols ? j0 + lrow : a.n_cols - 1) : j0 + lrow;
   const unsigned boff = (unsigned)wrow * (unsigned)a.ldw + (unsigned)lpart;
   const unsigned gate_stride = (unsigned)H * (unsigned)a.ldw;
-
-  floatx16 acc[G];
+  // PACK: tile row lrow of block b is column c = 32 b + lrow = g*8 + jj, i.e. weight row
+  // gate_row(g)*H + j0 + jj; columns past G*8 repeat the last one and are never read back
+  unsigned boffp[NB];
 #pragma unroll
-  for (int g = 0; g < G; ++g)
+  for (int b = 0; b < NB; ++b) {
+    int c = 32 * b + lrow;
+    c = c < G * kPackJ ? c : G * kPackJ - 1;
+    int wr = j0 + (c % kPackJ);
+    if (EPI == EPI_RELU_OUT) wr = wr < a.n_cols ? wr : a.n_cols - 1;
+    int grow = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (c / kPackJ == g) grow = gate_row<EPI>(g);
+    boffp[b] = ((unsigned)grow * (unsigned)H + (unsigned)wr) * (unsigned)a.ldw + (unsigned)lpart;
+  }
+
+  floatx16 acc[NB];
+#pragma unroll
+  for (int g = 0; g < NB; ++g)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 
@@ -237,17 +265,19 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   // Inside a group none of the memory instructions depends on the matrix instructions, and
   // the scheduling hints interleave them one to one.  Slab indices past the end are clamped:
   // the last slab is fetched again into a buffer nothing reads, so the loop has no branches.
-  constexpr int NS = WM == 1 ? 4 : 2;
+  constexpr int NS = PACK ? 8 : (WM == 1 ? 4 : 2);  // PACK: small slabs, more of them in flight
   constexpr int AHEAD = Q == 1 ? 2 : 1;  // a slab is stored to LDS AHEAD iterations before its use
-  floatx4 ra[NS][WM], rb[NS][G];
-  floatx4 fa[2], fb[2][G];
+  floatx4 ra[NS][WM], rb[NS][NB];
+  floatx4 fa[2], fb[2][NB];
   const float* aptr0[WM];
   const float* aptr1[WM];
   auto load_slab_b = [&](int set, int i) {
     const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-      rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
+    for (int g = 0; g < NB; ++g) {
+      if constexpr (PACK) rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + kb * kBK + boffp[g]);
+      else rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
+    }
   };
   auto load_slab_a = [&](int set, int i) {
     const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
@@ -268,7 +298,7 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
 #pragma unroll
     for (int r = 0; r < WM; ++r) *reinterpret_cast<floatx4*>(&As[32 * r * kBK + st_off]) = ra[set][r];
 #pragma unroll
-    for (int g = 0; g < G; ++g) *reinterpret_cast<floatx4*>(&Bs[32 * g * kBK + st_off]) = rb[set][g];
+    for (int g = 0; g < NB; ++g) *reinterpret_cast<floatx4*>(&Bs[32 * g * kBK + st_off]) = rb[set][g];
   };
   int fr_off[Q];  // operand fragment of group q: row lane%32, chunk 2*(wk*Q + q) + lane/32
 #pragma unroll
@@ -279,13 +309,13 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     const float* Bs = As + BM * kBK;
     fa[fset] = *reinterpret_cast<const floatx4*>(&As[wm * 32 * kBK + fr_off[q]]);
 #pragma unroll
-    for (int g = 0; g < G; ++g) fb[fset][g] = *reinterpret_cast<const floatx4*>(&Bs[g * 32 * kBK + fr_off[q]]);
+    for (int g = 0; g < NB; ++g) fb[fset][g] = *reinterpret_cast<const floatx4*>(&Bs[g * 32 * kBK + fr_off[q]]);
   };
   auto mfma_group = [&](int fset) {
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int g = 0; g < G; ++g)  // G independent accumulators between dependent issues
+      for (int g = 0; g < NB; ++g)  // NB independent accumulators between dependent issues
         acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[fset][s], fb[fset][g][s], acc[g], 0, 0, 0);
   };
   // one slab; `set` = (kb + AHEAD) % NS is the staging set that holds slab kb + AHEAD,
@@ -305,7 +335,7 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
       }
       mfma_group(fcur);
       // interleave: one memory instruction after each matrix instruction
-      constexpr int n_mfma = 4 * G, n_rd = 1 + G, n_st = WM + G;
+      constexpr int n_mfma = 4 * NB, n_rd = 1 + NB, n_st = WM + NB;
       // the stores and the loads of a slab each get at most half of the slots left by the reads
       constexpr int half = (n_mfma - n_rd) / 2;
       constexpr int w = (n_st + half - 1) / half;
@@ -382,6 +412,29 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     __syncthreads();  // no contraction (first step of a recurrence): publish the index table
   }
 
+  if constexpr (PACK) {
+    // every wavefront publishes its partial sums as z[wk][node row][column]; thread t then adds the
+    // four partial sums of each gate of (row t / 8, unit t % 8) in ascending wk order
+    float* z = smem;
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        z[(wk * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * ZLD + b * 32 + (lane & 31)] = acc[b][v];
+    __syncthreads();
+    const int row = tid >> 3, jj = tid & 7;
+    float zs[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float sum = 0.0f;
+#pragma unroll
+      for (int w = 0; w < WK; ++w) sum += z[(w * 32 + row) * ZLD + g * kPackJ + jj];
+      zs[g] = sum;
+    }
+    cell_epilogue<G, EPI, 1>(
+        a, j0 + jj, [&](int g, int) { return zs[g]; }, [&](int) { return m0 + row; }, sidx, BM, m0);
+  } else {
   // The WK wavefronts of a node block hold partial sums over their share of k.  They are added
   // by a reduce-scatter through LDS: wavefront wk ends up with the complete sums of the QPW = 4/WK
   // accumulator quads v4 = wk*QPW .. wk*QPW + QPW-1 (8 nodes each) and every wavefront runs the
@@ -464,6 +517,7 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
         return m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       },
       sidx, BM, m0);
+  }  // !PACK
 }
 
 // Second half of a level whose k range was split over `ksplit` workgroups: one wavefront per
@@ -495,7 +549,7 @@ __global__ __launch_bounds__(64) void cell_splitk_reduce_kernel(const CellLevelA
 }
 
 struct Shape {
-  int bm, ksplit;
+  int bm, ksplit;  // bm == 8 stands for the packed variant (32 nodes x 8 hidden units, no k split)
 };
 
 // Picks the node-tile height and the k split for a level from a small cost model.
@@ -510,6 +564,7 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
     const long tiles = (long)((a.n + bm - 1) / bm) * n_jt;
     return (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
   };
+  if (ws.force_bm == 8) return Shape{8, 1};
   if (ws.force_bm == 128 || ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
     Shape f{ws.force_bm, ws.force_ksplit > 0 ? ws.force_ksplit : 1};
     if (fits(f.bm, f.ksplit)) return f;
@@ -522,6 +577,9 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //    (at least 2 slabs each, at most 8 ways - the reduction kernel costs a launch, ~3 us,
   //    and reads ksplit partial tiles);
   //  * slightly more tiles than compute units: split in two for balance.
+  //  * latency-bound levels (n x K up to about 200 000) run the packed variant: four times as many
+  //    workgroups, a quarter of the weight rows each, one launch instead of two;
+  if ((long)a.n * n_slabs * kBK <= 200000) return Shape{8, 1};
   Shape best{a.n > 128 ? 64 : 32, 1};
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
   int s = 1;
@@ -540,10 +598,16 @@ template <int G, int EPI>
 hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitKWorkspace& ws,
                         int32_t* tile, int32_t* ksplit, const LaunchEvents& ev) {
   const Shape sh = pick_shape<G>(a, ws);
-  const int n_jt = a.H / 32;
-  const unsigned grid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
   if (tile) *tile = sh.bm;
   if (ksplit) *ksplit = sh.ksplit;
+  if (sh.bm == 8) {
+    const unsigned pgrid = (unsigned)((long)((a.n + 31) / 32) * (a.H / kPackJ));
+    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4, true>), dim3(pgrid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, 0, a, 1, ws.partial);
+    return hipGetLastError();
+  }
+  const int n_jt = a.H / 32;
+  const unsigned grid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
   if (sh.bm == 128) {
     hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
                           ev.stop, 0, a, sh.ksplit, ws.partial);

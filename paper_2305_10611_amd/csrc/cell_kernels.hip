@@ -16,7 +16,8 @@
 // next slab.  Wavefronts are arranged WM (node blocks) x WK (k split inside a slab); small
 // levels use WK > 1 so that all four matrix pipes of the CU work on a 32-node tile.
 //
-// Small levels cannot fill 256 compute units with (node tile, j tile) pairs alone, so the
+// Latency-bound levels (few nodes) go to cell_tiny_kernel further down.  Mid-size levels
+// cannot fill 256 compute units with (node tile, j tile) pairs alone, so the
 // k range is additionally split over `ksplit` workgroups.  Each writes its partial tile to
 // a workspace; a second, small kernel launched behind it sums the partial tiles in fixed
 // order and runs the epilogue.
@@ -170,28 +171,15 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
   }
 }
 
-// PACK = false: the tile is 32 hidden units wide and has one 32-column block per gate (NB = G).
-// PACK = true (latency-bound levels; WM = 1, WK = 4 only): the tile is kPackJ = 8 hidden units wide
-// and its G*8 columns c = g*8 + jj are packed into NB = ceil(G*8 / 32) blocks, so a level has four
-// times as many workgroups, each streaming a quarter of the weight rows, and needs no k split
-// across workgroups (no second launch).  The gates of a (node, j) pair then sit in different lanes;
-// the reduction over the four wavefronts goes through LDS anyway and hands thread t the sums of
-// node t / 8, unit t % 8: one epilogue element per thread.
-constexpr int kPackJ = 8;
-
-template <int G, int EPI, int WM, int WK, bool PACK = false>
+template <int G, int EPI, int WM, int WK>
 __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelArgs a, const int ksplit,
                                                                  float* __restrict__ partial) {
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
-  static_assert(!PACK || (WM == 1 && WK == 4), "packed columns: one node block, k split over the wavefronts");
-  constexpr int NB = PACK ? (G * kPackJ + 31) / 32 : G;  // 32-column blocks of the weight tile
-  constexpr int JW = PACK ? kPackJ : 32;                 // hidden units per tile
   constexpr int BM = 32 * WM;
-  constexpr int BROWS = 32 * NB;
+  constexpr int BROWS = 32 * G;
   constexpr int Q = 4 / WK;  // 8-k groups of a slab handled by one wavefront
   constexpr int TILE_FLOATS = (BM + BROWS) * kBK;
-  constexpr int ZLD = NB * 32 + 8;  // PACK: row stride of the per-wavefront sums in LDS
-  constexpr int RED_FLOATS = PACK ? WK * 32 * ZLD : WM * (WK - 1) * G * kBlockFloats;
+  constexpr int RED_FLOATS = WM * (WK - 1) * G * kBlockFloats;
   constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
   constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
   __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS + 3 * BM];
@@ -200,11 +188,11 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wk = wave / WM;
   const int H = a.H, n = a.n;
-  const int n_jt = H / JW;
+  const int n_jt = H >> 5;
   const int jt = blockIdx.x % n_jt;
   const int rest = blockIdx.x / n_jt;
   const int ks = rest % ksplit, mt = rest / ksplit;
-  const int j0 = jt * JW, m0 = mt * BM;
+  const int j0 = jt * 32, m0 = mt * BM;
 
   // ---- global -> LDS staging assignment: 16-byte chunk `tid & 7` of tile row `tid >> 3` (+32 i)
   const int lrow = tid >> 3, lpart = (tid & 7) * 4;
@@ -224,25 +212,10 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   const int wrow = EPI == EPI_RELU_OUT ? (j0 + lrow < a.n_cols ? j0 + lrow : a.n_cols - 1) : j0 + lrow;
   const unsigned boff = (unsigned)wrow * (unsigned)a.ldw + (unsigned)lpart;
   const unsigned gate_stride = (unsigned)H * (unsigned)a.ldw;
-  // PACK: tile row lrow of block b is column c = 32 b + lrow = g*8 + jj, i.e. weight row
-  // gate_row(g)*H + j0 + jj; columns past G*8 repeat the last one and are never read back
-  unsigned boffp[NB];
-#pragma unroll
-  for (int b = 0; b < NB; ++b) {
-    int c = 32 * b + lrow;
-    c = c < G * kPackJ ? c : G * kPackJ - 1;
-    int wr = j0 + (c % kPackJ);
-    if (EPI == EPI_RELU_OUT) wr = wr < a.n_cols ? wr : a.n_cols - 1;
-    int grow = 0;
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-      if (c / kPackJ == g) grow = gate_row<EPI>(g);
-    boffp[b] = ((unsigned)grow * (unsigned)H + (unsigned)wr) * (unsigned)a.ldw + (unsigned)lpart;
-  }
 
-  floatx16 acc[NB];
+  floatx16 acc[G];
 #pragma unroll
-  for (int g = 0; g < NB; ++g)
+  for (int g = 0; g < G; ++g)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 
@@ -265,19 +238,17 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   // Inside a group none of the memory instructions depends on the matrix instructions, and
   // the scheduling hints interleave them one to one.  Slab indices past the end are clamped:
   // the last slab is fetched again into a buffer nothing reads, so the loop has no branches.
-  constexpr int NS = PACK ? 8 : (WM == 1 ? 4 : 2);  // PACK: small slabs, more of them in flight
+  constexpr int NS = WM == 1 ? 4 : 2;
   constexpr int AHEAD = Q == 1 ? 2 : 1;  // a slab is stored to LDS AHEAD iterations before its use
-  floatx4 ra[NS][WM], rb[NS][NB];
-  floatx4 fa[2], fb[2][NB];
+  floatx4 ra[NS][WM], rb[NS][G];
+  floatx4 fa[2], fb[2][G];
   const float* aptr0[WM];
   const float* aptr1[WM];
   auto load_slab_b = [&](int set, int i) {
     const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
 #pragma unroll
-    for (int g = 0; g < NB; ++g) {
-      if constexpr (PACK) rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + kb * kBK + boffp[g]);
-      else rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
-    }
+    for (int g = 0; g < G; ++g)
+      rb[set][g] = *reinterpret_cast<const floatx4*>(a.W + (gate_row<EPI>(g) * gate_stride + kb * kBK) + boff);
   };
   auto load_slab_a = [&](int set, int i) {
     const int kb = slab0 + (i < my_slabs ? i : my_slabs - 1);
@@ -298,7 +269,7 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
 #pragma unroll
     for (int r = 0; r < WM; ++r) *reinterpret_cast<floatx4*>(&As[32 * r * kBK + st_off]) = ra[set][r];
 #pragma unroll
-    for (int g = 0; g < NB; ++g) *reinterpret_cast<floatx4*>(&Bs[32 * g * kBK + st_off]) = rb[set][g];
+    for (int g = 0; g < G; ++g) *reinterpret_cast<floatx4*>(&Bs[32 * g * kBK + st_off]) = rb[set][g];
   };
   int fr_off[Q];  // operand fragment of group q: row lane%32, chunk 2*(wk*Q + q) + lane/32
 #pragma unroll
@@ -309,13 +280,13 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     const float* Bs = As + BM * kBK;
     fa[fset] = *reinterpret_cast<const floatx4*>(&As[wm * 32 * kBK + fr_off[q]]);
 #pragma unroll
-    for (int g = 0; g < NB; ++g) fb[fset][g] = *reinterpret_cast<const floatx4*>(&Bs[g * 32 * kBK + fr_off[q]]);
+    for (int g = 0; g < G; ++g) fb[fset][g] = *reinterpret_cast<const floatx4*>(&Bs[g * 32 * kBK + fr_off[q]]);
   };
   auto mfma_group = [&](int fset) {
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-      for (int g = 0; g < NB; ++g)  // NB independent accumulators between dependent issues
+      for (int g = 0; g < G; ++g)  // G independent accumulators between dependent issues
         acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[fset][s], fb[fset][g][s], acc[g], 0, 0, 0);
   };
   // one slab; `set` = (kb + AHEAD) % NS is the staging set that holds slab kb + AHEAD,
@@ -335,7 +306,7 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
       }
       mfma_group(fcur);
       // interleave: one memory instruction after each matrix instruction
-      constexpr int n_mfma = 4 * NB, n_rd = 1 + NB, n_st = WM + NB;
+      constexpr int n_mfma = 4 * G, n_rd = 1 + G, n_st = WM + G;
       // the stores and the loads of a slab each get at most half of the slots left by the reads
       constexpr int half = (n_mfma - n_rd) / 2;
       constexpr int w = (n_st + half - 1) / half;
@@ -412,29 +383,6 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     __syncthreads();  // no contraction (first step of a recurrence): publish the index table
   }
 
-  if constexpr (PACK) {
-    // every wavefront publishes its partial sums as z[wk][node row][column]; thread t then adds the
-    // four partial sums of each gate of (row t / 8, unit t % 8) in ascending wk order
-    float* z = smem;
-    __syncthreads();
-#pragma unroll
-    for (int b = 0; b < NB; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        z[(wk * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * ZLD + b * 32 + (lane & 31)] = acc[b][v];
-    __syncthreads();
-    const int row = tid >> 3, jj = tid & 7;
-    float zs[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float sum = 0.0f;
-#pragma unroll
-      for (int w = 0; w < WK; ++w) sum += z[(w * 32 + row) * ZLD + g * kPackJ + jj];
-      zs[g] = sum;
-    }
-    cell_epilogue<G, EPI, 1>(
-        a, j0 + jj, [&](int g, int) { return zs[g]; }, [&](int) { return m0 + row; }, sidx, BM, m0);
-  } else {
   // The WK wavefronts of a node block hold partial sums over their share of k.  They are added
   // by a reduce-scatter through LDS: wavefront wk ends up with the complete sums of the QPW = 4/WK
   // accumulator quads v4 = wk*QPW .. wk*QPW + QPW-1 (8 nodes each) and every wavefront runs the
@@ -517,7 +465,6 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
         return m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       },
       sidx, BM, m0);
-  }  // !PACK
 }
 
 // Second half of a level whose k range was split over `ksplit` workgroups: one wavefront per
@@ -548,8 +495,196 @@ __global__ __launch_bounds__(64) void cell_splitk_reduce_kernel(const CellLevelA
       a, jt * 32 + (lane & 31), [&](int g, int) { return acc[g]; }, [&](int) { return node; });
 }
 
+// Latency-bound levels.  With few nodes a level is a skinny product: the time goes into streaming the
+// weight rows and into the chain of dependent steps, not into arithmetic.  This kernel therefore
+//  * gives a workgroup 32 nodes x JW hidden units x all G gates, the G*JW <= 32 columns c = g*JW + jj
+//    packed into ONE 32-column block (JW = 6 for five gates, else 8; the last tile may be partial):
+//    four to five times as many workgroups as 32-unit tiles, each streaming only G*JW weight rows,
+//    and no k split across workgroups, hence no second launch;
+//  * moves U 32-k slabs per step with one barrier per step (U = 8: 4 steps for K = 1024) and keeps
+//    two steps (up to 128 KB) in flight in registers, double buffered in LDS;
+//  * splits every slab's k over the four wavefronts as the large kernel does, publishes the four
+//    partial tiles in LDS and lets thread t add them (ascending wavefront order) for node t / 8,
+//    unit t % 8 and run the epilogue for that one element.
+// LDS layout of a slab and the operand fragments are those of cell_level_kernel.
+template <int G>
+constexpr int tiny_jw() { return G >= 5 ? 6 : 8; }
+
+template <int G, int EPI, int U>
+__global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelArgs a) {
+  constexpr int JW = tiny_jw<G>();
+  static_assert(G * JW <= 32 && JW <= 8, "one column block, one epilogue element per thread");
+  constexpr int SLAB = 64 * kBK;  // floats: tile rows 0..31 = nodes, 32..63 = columns
+  constexpr int ZLD = 32 + 8;
+  static_assert(4 * 32 * ZLD <= 2 * U * SLAB, "the partial tiles reuse the slab buffers");
+  extern __shared__ __attribute__((aligned(16))) float tiny_smem[];  // [2 buffers][U][SLAB], index table [3][32]
+  float* const smem = tiny_smem;
+  int* const sidx = reinterpret_cast<int*>(tiny_smem + 2 * U * SLAB);
+
+  const int tid = threadIdx.x, lane = tid & 63, wk = tid >> 6;
+  const int H = a.H, n = a.n;
+  const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
+  const int n_jt = (hlim + JW - 1) / JW;
+  const int jt = blockIdx.x % n_jt, mt = blockIdx.x / n_jt;
+  const int j0 = jt * JW, m0 = mt * 32;
+
+  const int lrow = tid >> 3, lpart = (tid & 7) * 4;
+  int node = m0 + lrow;
+  node = node < n ? node : n - 1;  // tail rows re-read the last node; never stored
+  const int row0 = a.idx0 ? a.idx0[node] : node;
+  const int row1 = a.idx1 ? a.idx1[node] : node;
+  if ((tid & 7) == 2) sidx[lrow] = a.out_rows ? a.out_rows[node] : node;
+  // tile row 32 + lrow is column c = lrow: gate c / JW, unit j0 + c % JW; columns and units past the
+  // end repeat the last valid one and are never read back
+  unsigned boff;
+  {
+    const int c = lrow < G * JW ? lrow : G * JW - 1;
+    int j = j0 + c % JW;
+    j = j < hlim ? j : hlim - 1;
+    int grow = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (c / JW == g) grow = gate_row<EPI>(g);
+    boff = ((unsigned)grow * (unsigned)H + (unsigned)j) * (unsigned)a.ldw + (unsigned)lpart;
+  }
+
+  floatx16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+
+  const int slabs_per_seg = a.kseg / kBK;
+  const int S = a.nseg * slabs_per_seg;
+  const int steps = (S + U - 1) / U;
+  const float* aptr0 = nullptr;
+  const float* aptr1 = nullptr;
+  floatx4 ra[2][U], rb[2][U];
+  auto load_b = [&](int slot, int s) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int kb = s * U + u;
+      kb = kb < S ? kb : S - 1;  // past the end: fetched again, never multiplied
+      rb[slot][u] = *reinterpret_cast<const floatx4*>(a.W + boff + kb * kBK);
+    }
+  };
+  auto load_a = [&](int slot, int s) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int kb = s * U + u;
+      kb = kb < S ? kb : S - 1;
+      const int seg = kb >= slabs_per_seg;
+      ra[slot][u] = *reinterpret_cast<const floatx4*>((seg ? aptr1 : aptr0) + (kb - (seg ? slabs_per_seg : 0)) * kBK);
+    }
+  };
+  const int st_off = lrow * kBK + (((tid & 7) ^ ((lrow >> 1) & 7)) << 2);
+  auto store_step = [&](int slot, int buf) {
+    float* base = smem + buf * (U * SLAB);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      *reinterpret_cast<floatx4*>(&base[u * SLAB + st_off]) = ra[slot][u];
+      *reinterpret_cast<floatx4*>(&base[u * SLAB + 32 * kBK + st_off]) = rb[slot][u];
+    }
+  };
+  // wavefront wk multiplies the 8-k group wk of every slab
+  const int fr_off = (lane & 31) * kBK + (((2 * wk + (lane >> 5)) ^ (((lane & 31) >> 1) & 7)) << 2);
+  auto compute_step = [&](int buf, int s) {
+    const float* base = smem + buf * (U * SLAB);
+    floatx4 fa[U], fb[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      fa[u] = *reinterpret_cast<const floatx4*>(&base[u * SLAB + fr_off]);
+      fb[u] = *reinterpret_cast<const floatx4*>(&base[u * SLAB + 32 * kBK + fr_off]);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (s * U + u < S) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[u][t], fb[u][t], acc, 0, 0, 0);
+      }
+    }
+  };
+
+  if (S > 0) {
+    // the weight slabs do not depend on the indices: requested first
+    load_b(0, 0);
+    if (steps > 1) load_b(1, 1);
+    aptr0 = a.src0 + (size_t)row0 * (size_t)a.ld0 + lpart;
+    aptr1 = a.nseg > 1 ? a.src1 + (size_t)row1 * (size_t)a.ld1 + lpart : aptr0;
+    if ((tid & 7) == 0) sidx[32 + lrow] = row0;
+    if ((tid & 7) == 1) sidx[64 + lrow] = row1;
+    load_a(0, 0);
+    if (steps > 1) load_a(1, 1);
+    store_step(0, 0);
+    if (steps > 2) {
+      load_a(0, 2);
+      load_b(0, 2);
+    }
+    __syncthreads();
+    // invariant at the top: buffer 0 holds step s, slot 1 step s + 1, slot 0 step s + 2
+    for (int s = 0; s < steps; s += 2) {
+      if (s + 1 < steps) {
+        store_step(1, 1);
+        if (s + 3 < steps) {
+          load_a(1, s + 3);
+          load_b(1, s + 3);
+        }
+      }
+      compute_step(0, s);
+      __syncthreads();
+      if (s + 1 < steps) {
+        if (s + 2 < steps) {
+          store_step(0, 0);
+          if (s + 4 < steps) {
+            load_a(0, s + 4);
+            load_b(0, s + 4);
+          }
+        }
+        compute_step(1, s + 1);
+        __syncthreads();
+      }
+    }
+  } else {
+    if ((tid & 7) == 0) sidx[32 + lrow] = row0;
+    if ((tid & 7) == 1) sidx[64 + lrow] = row1;
+    __syncthreads();
+  }
+
+  // partial tiles z[wk][node row][column], then one epilogue element per thread
+  float* z = smem;
+#pragma unroll
+  for (int v = 0; v < 16; ++v)
+    z[(wk * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * ZLD + (lane & 31)] = acc[v];
+  __syncthreads();
+  const int row = tid >> 3, jj = tid & 7;
+  if (jj >= JW || j0 + jj >= hlim) return;
+  float zs[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float sum = 0.0f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) sum += z[(w * 32 + row) * ZLD + g * JW + jj];
+    zs[g] = sum;
+  }
+  cell_epilogue<G, EPI, 1>(
+      a, j0 + jj, [&](int g, int) { return zs[g]; }, [&](int) { return m0 + row; }, sidx, 32, m0);
+}
+
+template <int G, int EPI, int U>
+hipError_t launch_tiny(const CellLevelArgs& a, unsigned grid, hipStream_t stream, const LaunchEvents& ev) {
+  constexpr size_t bytes = (size_t)(2 * U * 64 * kBK + 96) * sizeof(float);
+  static bool configured = false;  // more than 64 KB of dynamic LDS has to be asked for once
+  if (!configured) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cell_tiny_kernel<G, EPI, U>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipExtLaunchKernelGGL((cell_tiny_kernel<G, EPI, U>), dim3(grid), dim3(kThreads), bytes, stream, ev.start, ev.stop, 0,
+                        a);
+  return hipGetLastError();
+}
+
 struct Shape {
-  int bm, ksplit;  // bm == 8 stands for the packed variant (32 nodes x 8 hidden units, no k split)
+  int bm, ksplit;  // bm == 6 stands for cell_tiny_kernel (ksplit then carries its slabs per step, 0 = automatic)
 };
 
 // Picks the node-tile height and the k split for a level from a small cost model.
@@ -564,7 +699,7 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
     const long tiles = (long)((a.n + bm - 1) / bm) * n_jt;
     return (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
   };
-  if (ws.force_bm == 8) return Shape{8, 1};
+  if (ws.force_bm == 6) return Shape{6, ws.force_ksplit == 4 || ws.force_ksplit == 8 ? ws.force_ksplit : 0};
   if (ws.force_bm == 128 || ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
     Shape f{ws.force_bm, ws.force_ksplit > 0 ? ws.force_ksplit : 1};
     if (fits(f.bm, f.ksplit)) return f;
@@ -577,9 +712,8 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //    (at least 2 slabs each, at most 8 ways - the reduction kernel costs a launch, ~3 us,
   //    and reads ksplit partial tiles);
   //  * slightly more tiles than compute units: split in two for balance.
-  //  * latency-bound levels (n x K up to about 200 000) run the packed variant: four times as many
-  //    workgroups, a quarter of the weight rows each, one launch instead of two;
-  if ((long)a.n * n_slabs * kBK <= 200000) return Shape{8, 1};
+  //  * latency-bound levels (n x K up to about 256 000) run cell_tiny_kernel: one launch, no k split;
+  if ((long)a.n * n_slabs * kBK <= 256000) return Shape{6, 0};
   Shape best{a.n > 128 ? 64 : 32, 1};
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
   int s = 1;
@@ -600,11 +734,13 @@ hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitK
   const Shape sh = pick_shape<G>(a, ws);
   if (tile) *tile = sh.bm;
   if (ksplit) *ksplit = sh.ksplit;
-  if (sh.bm == 8) {
-    const unsigned pgrid = (unsigned)((long)((a.n + 31) / 32) * (a.H / kPackJ));
-    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4, true>), dim3(pgrid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, a, 1, ws.partial);
-    return hipGetLastError();
+  if (sh.bm == 6) {
+    const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : a.H;
+    const unsigned tgrid = (unsigned)((long)((a.n + 31) / 32) * ((hlim + tiny_jw<G>() - 1) / tiny_jw<G>()));
+    // 8 slabs per step need 128 KB of LDS, one workgroup per compute unit: only while all fit at once
+    const int u = sh.ksplit ? sh.ksplit : (tgrid <= 256 ? 8 : 4);
+    if (ksplit) *ksplit = 1;
+    return u == 8 ? launch_tiny<G, EPI, 8>(a, tgrid, stream, ev) : launch_tiny<G, EPI, 4>(a, tgrid, stream, ev);
   }
   const int n_jt = a.H / 32;
   const unsigned grid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);

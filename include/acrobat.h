@@ -138,9 +138,9 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
  *   hf_t = s(Wf_x x_t + bf + Wf_h hf_{t-1}), hf_{-1} = f.h_init     (steps t = 0 .. len-1)
  *   hb_t = s(Wb_x x_t + bb + Wb_h hb_{t+1}), hb_{len} = b.h_init    (steps t = len-1 .. 0)
  *   y_t  = relu(cb + C [hf_t ; hb_t])                               (C: [n_out, 2H])
- * The input transforms of both directions are hoisted (one dense batch each); the two
- * recurrences are independent and run on the caller's stream and on a context-owned second
- * stream, joined before the single output batch.  Rows are packed as for the LSTM.
+ * The input transforms of both directions are hoisted (one dense batch each, sharing a launch);
+ * the two recurrences are independent, step k of both directions shares one launch; the output
+ * batch follows.  Rows are packed as for the LSTM.
  * Requires H, D multiples of 32, 1 <= n_out.  All pointers in acrobat_rnn_dir are device
  * pointers: Wx [H,D], Wh [H,H], b [H] or NULL, h_init [H].  d_hf / d_hb [sum len, H] and
  * d_y [sum len, n_out] are written. */

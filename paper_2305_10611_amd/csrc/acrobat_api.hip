@@ -34,9 +34,6 @@ struct acrobat_ctx {
   size_t scratch_cap = 0;  // in floats
   // split-k workspace of the cell kernels (allocated at the first forward call)
   SplitKWorkspace splitk;
-  // second stream for the backward recurrence of the bidirectional RNN (default priority)
-  hipStream_t aux_stream = nullptr;
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   int mvrnn_variant = 0;  // d == 64: which level kernel (tuning override ACROBAT_MVRNN_VARIANT)
   // profiling
   bool profiling = false;
@@ -116,14 +113,6 @@ int reserve_splitk(acrobat_ctx* ctx) {
   // tuning override for experiments: ACROBAT_FORCE_TILE=128|64|32|16, ACROBAT_FORCE_KSPLIT=1..32
   if (const char* v = std::getenv("ACROBAT_FORCE_TILE")) ctx->splitk.force_bm = std::atoi(v);
   if (const char* v = std::getenv("ACROBAT_FORCE_KSPLIT")) ctx->splitk.force_ksplit = std::atoi(v);
-  return ACROBAT_OK;
-}
-
-int reserve_aux_stream(acrobat_ctx* ctx) {
-  if (ctx->aux_stream) return ACROBAT_OK;
-  HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming));
-  HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming));
-  HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking));
   return ACROBAT_OK;
 }
 
@@ -223,12 +212,6 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
-  if (ctx->aux_stream) {
-    (void)hipStreamSynchronize(ctx->aux_stream);
-    (void)hipStreamDestroy(ctx->aux_stream);
-  }
-  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
-  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   delete ctx;
 }
@@ -540,7 +523,6 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int32_t T = s.n_levels - 1;  // recurrence steps; level T is the output batch
     TRY(reserve_splitk(ctx));
-    TRY(reserve_aux_stream(ctx));
     // per direction, by position in the direction's step lists: row written | row of the previous
     // step of that direction (step 0 gathers row 0 of the initial-state vector)
     TRY(reserve_indices(ctx, 4 * (size_t)R));
@@ -559,53 +541,44 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
     TRY(reserve_scratch(ctx, 2 * (size_t)R * (size_t)H));
     TRY(upload_indices(ctx, 4 * (size_t)R, stream));
 
-    // The two recurrences share nothing but x: the backward one runs on the second stream, forked
-    // after the index upload and joined before the output batch.  With profiling on everything
-    // is serialised on the caller's stream so that the per-launch times mean something.
-    const bool two_streams = !ctx->profiling;
-    hipStream_t sdir[2] = {stream, two_streams ? ctx->aux_stream : stream};
-    if (two_streams) {
-      HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, stream));
-      HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
-    }
-    SplitKWorkspace ws[2] = {ctx->splitk, ctx->splitk};  // each stream its own half
-    ws[0].partial_floats = ws[1].partial_floats = ctx->splitk.partial_floats / 2;
-    ws[1].partial = ctx->splitk.partial + ws[0].partial_floats;
+    // The two recurrences share nothing but x and never wait for each other: step k of both
+    // directions goes out as ONE launch (workgroups of the forward batch, then of the backward
+    // batch), and so do the two hoisted input transforms.
     const acrobat_rnn_dir* par[2] = {fwd, bwd};
     float* hdir[2] = {d_hf, d_hb};
     float* xp[2] = {ctx->d_scratch, ctx->d_scratch + (size_t)R * H};
 
     LaunchTimer timer{ctx, stream};
-    for (int dir = 0; dir < 2; ++dir) {  // hoisted input transforms: one dense batch per direction
-      CellLevelArgs a{};
-      a.n = R; a.H = H; a.nseg = 1; a.kseg = D;
-      a.src0 = d_x; a.ld0 = D;
-      a.W = par[dir]->Wx; a.ldw = D; a.bias = par[dir]->b;
-      a.zout = xp[dir];
-      TRY(timer.begin(ACROBAT_K_RNN_INPUT, dir, R));
-      HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z1, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit(), timer.ev));
+    {  // hoisted input transforms: one dense batch per direction
+      CellLevelArgs a[2] = {};
+      for (int dir = 0; dir < 2; ++dir) {
+        a[dir].n = R; a[dir].H = H; a[dir].nseg = 1; a[dir].kseg = D;
+        a[dir].src0 = d_x; a[dir].ld0 = D;
+        a[dir].W = par[dir]->Wx; a[dir].ldw = D; a[dir].bias = par[dir]->b;
+        a[dir].zout = xp[dir];
+      }
+      TRY(timer.begin(ACROBAT_K_RNN_INPUT, 0, 2 * R));
+      HIP_TRY(ctx, launch_cell_level_pair(EPI_STORE_Z1, a[0], a[1], stream, ctx->splitk, timer.tile(), timer.ksplit(),
+                                          timer.ev));
       TRY(timer.end());
     }
     for (int32_t k = 0; k < T; ++k) {
       const int32_t off = s.fwd_off[k], n = s.fwd_off[k + 1] - off;
+      CellLevelArgs a[2] = {};
       for (int dir = 0; dir < 2; ++dir) {
-        CellLevelArgs a{};
-        a.n = n; a.H = H; a.nseg = 1; a.kseg = H;
-        a.out_rows = ctx->d_idx + 2 * (size_t)dir * R + off;
-        a.idx0 = ctx->d_idx + (2 * (size_t)dir + 1) * R + off;
-        a.src0 = k == 0 ? par[dir]->h_init : hdir[dir];
-        a.ld0 = H;
-        a.W = par[dir]->Wh; a.ldw = H;
-        a.zadd = xp[dir];
-        a.h = hdir[dir];
-        TRY(timer.begin(ACROBAT_K_RNN_STEP, k, n));
-        HIP_TRY(ctx, launch_cell_level(EPI_RNN_STEP, a, sdir[dir], ws[dir], timer.tile(), timer.ksplit(), timer.ev));
-        TRY(timer.end());
+        a[dir].n = n; a[dir].H = H; a[dir].nseg = 1; a[dir].kseg = H;
+        a[dir].out_rows = ctx->d_idx + 2 * (size_t)dir * R + off;
+        a[dir].idx0 = ctx->d_idx + (2 * (size_t)dir + 1) * R + off;
+        a[dir].src0 = k == 0 ? par[dir]->h_init : hdir[dir];
+        a[dir].ld0 = H;
+        a[dir].W = par[dir]->Wh; a[dir].ldw = H;
+        a[dir].zadd = xp[dir];
+        a[dir].h = hdir[dir];
       }
-    }
-    if (two_streams) {
-      HIP_TRY(ctx, hipEventRecord(ctx->ev_join, ctx->aux_stream));
-      HIP_TRY(ctx, hipStreamWaitEvent(stream, ctx->ev_join, 0));
+      TRY(timer.begin(ACROBAT_K_RNN_STEP, k, 2 * n));
+      HIP_TRY(ctx, launch_cell_level_pair(EPI_RNN_STEP, a[0], a[1], stream, ctx->splitk, timer.tile(), timer.ksplit(),
+                                          timer.ev));
+      TRY(timer.end());
     }
     {  // phase 1: every token's output operator in one batch; [hf_t ; hb_t] is read in place
       CellLevelArgs a{};

@@ -59,6 +59,14 @@ struct LaunchEvents {
   hipEvent_t reduce_start = nullptr, reduce_stop = nullptr;  // the reduction kernel of a k-split level
 };
 
+// Two independent batches of the same cell type (the two directions of a bidirectional recurrence)
+// can share one launch when both are handled by the same kernel variant without a k split:
+// workgroups [0, split) execute a[0], the others a[1].
+struct CellLevelPair {
+  CellLevelArgs a[2];
+  int32_t split;
+};
+
 // Launches the kernel for one level; picks the node-tile height and k split from the level's
 // size and reports them in *tile / *ksplit (may be null).  Returns hipGetLastError().
 hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,
@@ -79,6 +87,13 @@ struct MvrnnLevelArgs {
   const float* W; const float* WM;  // [d,2d] each
   float* vec; float* mat;           // arena [rows,d], [rows,d,d]
 };
+// Same for two independent batches: one shared launch where the variants agree (then *tile / *ksplit
+// describe it and ev brackets it), else two launches in a row on the stream (ev.start on the first,
+// ev.stop on the second; *tile / *ksplit describe the first).
+hipError_t launch_cell_level_pair(CellEpilogue epi, const CellLevelArgs& a0, const CellLevelArgs& a1, hipStream_t stream,
+                                  const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit,
+                                  const LaunchEvents& ev = LaunchEvents());
+
 hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile,
                               const LaunchEvents& ev = LaunchEvents());
 

@@ -35,6 +35,8 @@
 // weight rows of one or two j tiles and keeps them in its own L2 for the whole level.
 #include "cell_kernels.h"
 
+#include <type_traits>
+
 namespace acrobat {
 namespace {
 
@@ -172,8 +174,11 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
 }
 
 template <int G, int EPI, int WM, int WK>
-__global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelArgs a, const int ksplit,
+__global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelPair pr, const int ksplit,
                                                                  float* __restrict__ partial) {
+  const bool second = blockIdx.x >= (unsigned)pr.split;  // which of the two batches (uniform)
+  const CellLevelArgs& a = pr.a[second];
+  const int bid = (int)blockIdx.x - (second ? pr.split : 0);
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
   constexpr int BM = 32 * WM;
   constexpr int BROWS = 32 * G;
@@ -189,8 +194,8 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   const int wm = wave % WM, wk = wave / WM;
   const int H = a.H, n = a.n;
   const int n_jt = H >> 5;
-  const int jt = blockIdx.x % n_jt;
-  const int rest = blockIdx.x / n_jt;
+  const int jt = bid % n_jt;
+  const int rest = bid / n_jt;
   const int ks = rest % ksplit, mt = rest / ksplit;
   const int j0 = jt * 32, m0 = mt * BM;
 
@@ -511,7 +516,10 @@ template <int G>
 constexpr int tiny_jw() { return G >= 5 ? 6 : 8; }
 
 template <int G, int EPI, int U>
-__global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelArgs a) {
+__global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair pr) {
+  const bool second = blockIdx.x >= (unsigned)pr.split;  // which of the two batches (uniform)
+  const CellLevelArgs& a = pr.a[second];
+  const int bid = (int)blockIdx.x - (second ? pr.split : 0);
   constexpr int JW = tiny_jw<G>();
   static_assert(G * JW <= 32 && JW <= 8, "one column block, one epilogue element per thread");
   constexpr int SLAB = 64 * kBK;  // floats: tile rows 0..31 = nodes, 32..63 = columns
@@ -525,7 +533,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelArgs
   const int H = a.H, n = a.n;
   const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
   const int n_jt = (hlim + JW - 1) / JW;
-  const int jt = blockIdx.x % n_jt, mt = blockIdx.x / n_jt;
+  const int jt = bid % n_jt, mt = bid / n_jt;
   const int j0 = jt * JW, m0 = mt * 32;
 
   const int lrow = tid >> 3, lpart = (tid & 7) * 4;
@@ -669,7 +677,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelArgs
 }
 
 template <int G, int EPI, int U>
-hipError_t launch_tiny(const CellLevelArgs& a, unsigned grid, hipStream_t stream, const LaunchEvents& ev) {
+hipError_t launch_tiny(const CellLevelPair& pr, unsigned grid, hipStream_t stream, const LaunchEvents& ev) {
   constexpr size_t bytes = (size_t)(2 * U * 64 * kBK + 96) * sizeof(float);
   static bool configured = false;  // more than 64 KB of dynamic LDS has to be asked for once
   if (!configured) {
@@ -679,7 +687,7 @@ hipError_t launch_tiny(const CellLevelArgs& a, unsigned grid, hipStream_t stream
     configured = true;
   }
   hipExtLaunchKernelGGL((cell_tiny_kernel<G, EPI, U>), dim3(grid), dim3(kThreads), bytes, stream, ev.start, ev.stop, 0,
-                        a);
+                        pr);
   return hipGetLastError();
 }
 
@@ -728,31 +736,58 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   return best;
 }
 
+template <int G>
+unsigned tiny_grid(const CellLevelArgs& a, bool relu_out) {
+  const int hlim = relu_out ? a.n_cols : a.H;
+  return (unsigned)((long)((a.n + 31) / 32) * ((hlim + tiny_jw<G>() - 1) / tiny_jw<G>()));
+}
+
+// `b` (may be null) is a second, independent batch for the same launch.
 template <int G, int EPI>
-hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitKWorkspace& ws,
+hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStream_t stream, const SplitKWorkspace& ws,
                         int32_t* tile, int32_t* ksplit, const LaunchEvents& ev) {
   const Shape sh = pick_shape<G>(a, ws);
+  if (b) {
+    const Shape sh2 = pick_shape<G>(*b, ws);
+    const bool shareable = sh.bm == sh2.bm && (sh.bm == 6 ? sh.ksplit == sh2.ksplit : (sh.ksplit == 1 && sh2.ksplit == 1));
+    if (!shareable) {  // two launches in a row, bracketed as one: first kernel's begin .. last kernel's end
+      LaunchEvents e0, e1;
+      e0.start = ev.start;
+      if (sh2.bm != 6 && sh2.ksplit > 1) e1.reduce_stop = ev.stop;
+      else e1.stop = ev.stop;
+      const hipError_t err = launch_shape<G, EPI>(a, nullptr, stream, ws, tile, nullptr, e0);
+      if (err != hipSuccess) return err;
+      if (ksplit) *ksplit = 1;
+      return launch_shape<G, EPI>(*b, nullptr, stream, ws, nullptr, nullptr, e1);
+    }
+  }
   if (tile) *tile = sh.bm;
   if (ksplit) *ksplit = sh.ksplit;
+  CellLevelPair pr;
+  pr.a[0] = a;
+  pr.a[1] = b ? *b : a;
   if (sh.bm == 6) {
-    const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : a.H;
-    const unsigned tgrid = (unsigned)((long)((a.n + 31) / 32) * ((hlim + tiny_jw<G>() - 1) / tiny_jw<G>()));
+    const unsigned g0 = tiny_grid<G>(a, EPI == EPI_RELU_OUT), g1 = b ? tiny_grid<G>(*b, EPI == EPI_RELU_OUT) : 0;
+    pr.split = (int32_t)g0;
     // 8 slabs per step need 128 KB of LDS, one workgroup per compute unit: only while all fit at once
-    const int u = sh.ksplit ? sh.ksplit : (tgrid <= 256 ? 8 : 4);
+    const int u = sh.ksplit ? sh.ksplit : (g0 + g1 <= 256 ? 8 : 4);
     if (ksplit) *ksplit = 1;
-    return u == 8 ? launch_tiny<G, EPI, 8>(a, tgrid, stream, ev) : launch_tiny<G, EPI, 4>(a, tgrid, stream, ev);
+    return u == 8 ? launch_tiny<G, EPI, 8>(pr, g0 + g1, stream, ev) : launch_tiny<G, EPI, 4>(pr, g0 + g1, stream, ev);
   }
   const int n_jt = a.H / 32;
-  const unsigned grid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
+  const unsigned g0 = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
+  const unsigned g1 = b ? (unsigned)((long)((b->n + sh.bm - 1) / sh.bm) * (b->H / 32)) : 0;
+  pr.split = (int32_t)g0;
+  const unsigned grid = g0 + g1;
   if (sh.bm == 128) {
     hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, a, sh.ksplit, ws.partial);
+                          ev.stop, 0, pr, sh.ksplit, ws.partial);
   } else if (sh.bm == 64) {
     hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, a, sh.ksplit, ws.partial);
+                          ev.stop, 0, pr, sh.ksplit, ws.partial);
   } else {
     hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, a, sh.ksplit, ws.partial);
+                          ev.stop, 0, pr, sh.ksplit, ws.partial);
   }
   if (sh.ksplit > 1) {
     const int wm_count = sh.bm / 32;
@@ -763,21 +798,37 @@ hipError_t launch_shape(const CellLevelArgs& a, hipStream_t stream, const SplitK
   return hipGetLastError();
 }
 
+template <class F>
+hipError_t dispatch_epilogue(CellEpilogue epi, F&& f) {
+  switch (epi) {
+    case EPI_TREE_LEAF: return f(std::integral_constant<int, 3>(), std::integral_constant<int, EPI_TREE_LEAF>());
+    case EPI_TREE_INTERNAL: return f(std::integral_constant<int, 5>(), std::integral_constant<int, EPI_TREE_INTERNAL>());
+    case EPI_LSTM_STEP: return f(std::integral_constant<int, 4>(), std::integral_constant<int, EPI_LSTM_STEP>());
+    case EPI_STORE_Z: return f(std::integral_constant<int, 4>(), std::integral_constant<int, EPI_STORE_Z>());
+    case EPI_STORE_Z1: return f(std::integral_constant<int, 1>(), std::integral_constant<int, EPI_STORE_Z>());
+    case EPI_RNN_STEP: return f(std::integral_constant<int, 1>(), std::integral_constant<int, EPI_RNN_STEP>());
+    case EPI_RELU_OUT: return f(std::integral_constant<int, 1>(), std::integral_constant<int, EPI_RELU_OUT>());
+  }
+  return hipErrorInvalidValue;
+}
+
 }  // namespace
 
 hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,
                              const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit, const LaunchEvents& ev) {
   if (a.n <= 0) return hipSuccess;
-  switch (epi) {
-    case EPI_TREE_LEAF: return launch_shape<3, EPI_TREE_LEAF>(a, stream, ws, tile, ksplit, ev);
-    case EPI_TREE_INTERNAL: return launch_shape<5, EPI_TREE_INTERNAL>(a, stream, ws, tile, ksplit, ev);
-    case EPI_LSTM_STEP: return launch_shape<4, EPI_LSTM_STEP>(a, stream, ws, tile, ksplit, ev);
-    case EPI_STORE_Z: return launch_shape<4, EPI_STORE_Z>(a, stream, ws, tile, ksplit, ev);
-    case EPI_STORE_Z1: return launch_shape<1, EPI_STORE_Z>(a, stream, ws, tile, ksplit, ev);
-    case EPI_RNN_STEP: return launch_shape<1, EPI_RNN_STEP>(a, stream, ws, tile, ksplit, ev);
-    case EPI_RELU_OUT: return launch_shape<1, EPI_RELU_OUT>(a, stream, ws, tile, ksplit, ev);
-  }
-  return hipErrorInvalidValue;
+  return dispatch_epilogue(epi, [&](auto g, auto e) {
+    return launch_shape<decltype(g)::value, decltype(e)::value>(a, nullptr, stream, ws, tile, ksplit, ev);
+  });
+}
+
+hipError_t launch_cell_level_pair(CellEpilogue epi, const CellLevelArgs& a0, const CellLevelArgs& a1, hipStream_t stream,
+                                  const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit, const LaunchEvents& ev) {
+  if (a0.n <= 0) return launch_cell_level(epi, a1, stream, ws, tile, ksplit, ev);
+  if (a1.n <= 0) return launch_cell_level(epi, a0, stream, ws, tile, ksplit, ev);
+  return dispatch_epilogue(epi, [&](auto g, auto e) {
+    return launch_shape<decltype(g)::value, decltype(e)::value>(a0, &a1, stream, ws, tile, ksplit, ev);
+  });
 }
 
 }  // namespace acrobat

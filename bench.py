@@ -49,6 +49,9 @@ def main():
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
     ap.add_argument("--no-overlap-streams", dest="overlap_streams", action="store_false",
                     help="skip the informational two-stream throughput measurement")
+    ap.add_argument("--ablation", action="store_true",
+                    help="TreeLSTM only: also time the forward pass with gather fusion switched off (explicit "
+                         "gather launches), reported under \"ablation\"")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="only run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "for scaling hardware-counter readings) and exit")
@@ -184,6 +187,23 @@ def main():
         overlap = {"streams": 2, "ms_per_step": round(oms, 4), "value": round(n_nodes / (oms * 1e-3), 1)}
         ctx2.close()
 
+    # ---- information only: gather fusion off (explicit gather launch before every level)
+    ablation = None
+    if args.ablation and kind == "treelstm":
+        ctx.acrobat_set_gather_fusion(False)
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        a0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        a1 = time.perf_counter()
+        ctx.acrobat_set_gather_fusion(True)
+        ams = (a1 - a0) * 1e3 / args.steps
+        ablation = {"unfused_gather_ms_per_step": round(ams, 4), "fused_over_unfused_speedup": round(ams / ms_per_step, 3)}
+        step()  # the outputs checked further down come from the product path
+
     # ---- host scheduler alone
     ts = []
     for _ in range(20):
@@ -273,7 +293,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w["name"], "index": args.config, "nodes": n_nodes, "seed": int(w["seed"])},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap, "ablation": ablation,
         "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
                       "t_splitk_reduce_ms": round(t_reduce_ms, 4),
                       "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),

@@ -186,8 +186,16 @@ typedef struct {
 #define ACROBAT_K_RNN_STEP 8
 #define ACROBAT_K_RNN_OUTPUT 9
 #define ACROBAT_K_SPLITK_REDUCE 10
+#define ACROBAT_K_GATHER 11
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
+
+/* Ablation of gather fusion (section 5.2; measured in the paper's section 7.5).  Enabled (the
+ * default), the level kernels read their operand rows in place through the index lists.  Disabled,
+ * acrobat_treelstm_forward first copies every level's operand rows (embedding rows; child h and c
+ * rows) into contiguous scratch with an explicit gather launch and the level kernel reads the
+ * copies - the scheme of frameworks without gather fusion.  Results are bit-identical. */
+int acrobat_set_gather_fusion(acrobat_ctx* ctx, int32_t enabled);
 /* Records of the last forward call (context-owned, valid until the next forward call). */
 int acrobat_last_profile(const acrobat_ctx* ctx, int32_t* n_records,
                          const acrobat_launch_record** records);

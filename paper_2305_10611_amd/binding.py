@@ -14,6 +14,7 @@ from . import build as _build
 OK, EINVAL, ESTRUCT, ENOMEM, EHIP = 0, -1, -2, -3, -4
 K_TREE_LEAF, K_TREE_INTERNAL, K_MVRNN_LEVEL, K_MVRNN_LEAFCOPY, K_LSTM_INPUT, K_LSTM_STEP = 1, 2, 3, 4, 5, 6
 K_RNN_INPUT, K_RNN_STEP, K_RNN_OUTPUT, K_SPLITK_REDUCE = 7, 8, 9, 10
+K_GATHER = 11
 
 
 class AcrobatError(RuntimeError):
@@ -40,6 +41,7 @@ EXPORTS = (
     "acrobat_schedule_trees", "acrobat_schedule_seqs", "acrobat_treelstm_forward",
     "acrobat_mvrnn_forward", "acrobat_varlen_lstm_forward", "acrobat_last_schedule",
     "acrobat_set_profiling", "acrobat_last_profile", "acrobat_schedule_birnn", "acrobat_birnn_forward",
+    "acrobat_set_gather_fusion",
 )
 
 
@@ -65,6 +67,7 @@ def _load():
                                            C.POINTER(acrobat_rnn_dir)] + [vp] * 6)
     lib.acrobat_last_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
     lib.acrobat_set_profiling.argtypes = [vp, i32]
+    lib.acrobat_set_gather_fusion.argtypes = [vp, i32]
     lib.acrobat_last_profile.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(acrobat_launch_record))]
     return lib
 
@@ -203,6 +206,9 @@ class Context:
 
     def acrobat_set_profiling(self, enabled: bool) -> int:
         return lib.acrobat_set_profiling(self._h, int(bool(enabled)))
+
+    def acrobat_set_gather_fusion(self, enabled: bool) -> int:
+        return lib.acrobat_set_gather_fusion(self._h, int(bool(enabled)))
 
     def acrobat_last_profile(self):
         n, p = C.c_int32(0), C.POINTER(acrobat_launch_record)()

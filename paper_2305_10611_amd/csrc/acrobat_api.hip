@@ -5,6 +5,7 @@
 // and one batched host-to-device transfer per forward call for all index lists.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -34,6 +35,7 @@ struct acrobat_ctx {
   size_t scratch_cap = 0;  // in floats
   // split-k workspace of the cell kernels (allocated at the first forward call)
   SplitKWorkspace splitk;
+  bool gather_fusion = true;  // false: explicit gather launches (ablation)
   int mvrnn_variant = 0;  // d == 64: which level kernel (tuning override ACROBAT_MVRNN_VARIANT)
   // profiling
   bool profiling = false;
@@ -289,17 +291,25 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
     TRY(reserve_splitk(ctx));
     // index lists by schedule position: out row | first operand row | second operand row
-    TRY(reserve_indices(ctx, 3 * (size_t)N));
+    // (+ 0, 1, 2, ... for the unfused-gather ablation, whose level kernels read gathered copies)
+    const int32_t n_leaf = s.level_off[1];
+    int32_t n_wide = 0;  // widest internal level
+    for (int32_t lv = 1; lv < s.n_levels; ++lv) n_wide = std::max(n_wide, s.level_off[lv + 1] - s.level_off[lv]);
+    const bool unfused = !ctx->gather_fusion;
+    const size_t n_iota = unfused ? (size_t)std::max(n_leaf, 2 * n_wide) : 0;
+    TRY(reserve_indices(ctx, 3 * (size_t)N + n_iota));
     int32_t* st = ctx->h_stage;
     std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
-    const int32_t n_leaf = s.level_off[1];
     for (int32_t p = 0; p < n_leaf; ++p) st[N + p] = trees->token[s.level_nodes[p]];  // leaves gather by token
     std::memcpy(st + N + n_leaf, s.lrow.data() + n_leaf, (size_t)(N - n_leaf) * sizeof(int32_t));
     std::memcpy(st + 2 * (size_t)N, s.rrow.data(), (size_t)N * sizeof(int32_t));
-    TRY(upload_indices(ctx, 3 * (size_t)N, stream));
+    for (size_t i = 0; i < n_iota; ++i) st[3 * (size_t)N + i] = (int32_t)i;
+    if (unfused) TRY(reserve_scratch(ctx, std::max((size_t)n_leaf * D, 4 * (size_t)n_wide * H)));
+    TRY(upload_indices(ctx, 3 * (size_t)N + n_iota, stream));
     const int32_t* d_out = ctx->d_idx;
     const int32_t* d_ia = ctx->d_idx + N;
     const int32_t* d_ib = ctx->d_idx + 2 * (size_t)N;
+    const int32_t* d_iota = ctx->d_idx + 3 * (size_t)N;
 
     LaunchTimer timer{ctx, stream};
     for (int32_t lv = 0; lv < s.n_levels; ++lv) {
@@ -320,6 +330,28 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
         a.src1 = d_h; a.idx1 = d_ib + off; a.ld1 = H;
         a.W = d_U; a.ldw = 2 * H; a.bias = d_b;
         a.cprev_src = d_c;
+      }
+      if (unfused) {  // copy the operand rows first, then let the level kernel read the copies in order
+        GatherArgs g{};
+        g.n = n;
+        float* hbuf = ctx->d_scratch;                        // [2n, H]: left rows, right rows
+        float* cbuf = ctx->d_scratch + 2 * (size_t)n_wide * H;  // same for c
+        if (lv == 0) {
+          g.width = D; g.count = 1;
+          g.idx[0] = a.idx0; g.src[0] = d_emb; g.dst[0] = ctx->d_scratch;
+          a.src0 = ctx->d_scratch; a.idx0 = d_iota;
+        } else {
+          g.width = H; g.count = 4;
+          g.idx[0] = a.idx0; g.src[0] = d_h; g.dst[0] = hbuf;
+          g.idx[1] = a.idx1; g.src[1] = d_h; g.dst[1] = hbuf + (size_t)n * H;
+          g.idx[2] = a.idx0; g.src[2] = d_c; g.dst[2] = cbuf;
+          g.idx[3] = a.idx1; g.src[3] = d_c; g.dst[3] = cbuf + (size_t)n * H;
+          a.src0 = hbuf; a.src1 = hbuf; a.idx0 = d_iota; a.idx1 = d_iota + n;
+          a.cprev_src = cbuf;
+        }
+        TRY(timer.begin(ACROBAT_K_GATHER, lv, n));
+        HIP_TRY(ctx, launch_gather_rows(g, stream, timer.ev));
+        TRY(timer.end());
       }
       TRY(timer.begin(lv == 0 ? ACROBAT_K_TREE_LEAF : ACROBAT_K_TREE_INTERNAL, lv, n));
       HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream, ctx->splitk,
@@ -612,6 +644,12 @@ int acrobat_last_schedule(const acrobat_ctx* ctx, int32_t* n_levels, const int32
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled) {
   if (!ctx) return ACROBAT_EINVAL;
   ctx->profiling = enabled != 0;
+  return ACROBAT_OK;
+}
+
+int acrobat_set_gather_fusion(acrobat_ctx* ctx, int32_t enabled) {
+  if (!ctx) return ACROBAT_EINVAL;
+  ctx->gather_fusion = enabled != 0;
   return ACROBAT_OK;
 }
 

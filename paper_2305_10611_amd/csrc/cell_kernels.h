@@ -94,6 +94,16 @@ hipError_t launch_cell_level_pair(CellEpilogue epi, const CellLevelArgs& a0, con
                                   const SplitKWorkspace& ws, int32_t* tile, int32_t* ksplit,
                                   const LaunchEvents& ev = LaunchEvents());
 
+// Explicit gather (only for the unfused-gather ablation, section 5.2 / 7.5): copies rows idx[k][i] of
+// src[k] (row stride = width floats) to row i of dst[k], for up to four operand lists in one launch.
+struct GatherArgs {
+  int32_t n, width, count;
+  const int32_t* idx[4];
+  const float* src[4];
+  float* dst[4];
+};
+hipError_t launch_gather_rows(const GatherArgs& g, hipStream_t stream, const LaunchEvents& ev = LaunchEvents());
+
 hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile,
                               const LaunchEvents& ev = LaunchEvents());
 

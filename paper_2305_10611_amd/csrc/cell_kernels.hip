@@ -798,6 +798,18 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
   return hipGetLastError();
 }
 
+// one wavefront per (operand list, row): a contiguous 16-byte-vector copy of the row
+__global__ __launch_bounds__(kThreads) void gather_rows_kernel(const GatherArgs g) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int vec = g.width >> 2;
+  for (long r = (long)blockIdx.x * 4 + wave; r < (long)g.n * g.count; r += (long)gridDim.x * 4) {
+    const int k = (int)(r / g.n), i = (int)(r % g.n);
+    const floatx4* s = reinterpret_cast<const floatx4*>(g.src[k] + (size_t)g.idx[k][i] * g.width);
+    floatx4* d = reinterpret_cast<floatx4*>(g.dst[k] + (size_t)i * g.width);
+    for (int c = lane; c < vec; c += 64) d[c] = s[c];
+  }
+}
+
 template <class F>
 hipError_t dispatch_epilogue(CellEpilogue epi, F&& f) {
   switch (epi) {
@@ -829,6 +841,15 @@ hipError_t launch_cell_level_pair(CellEpilogue epi, const CellLevelArgs& a0, con
   return dispatch_epilogue(epi, [&](auto g, auto e) {
     return launch_shape<decltype(g)::value, decltype(e)::value>(a0, &a1, stream, ws, tile, ksplit, ev);
   });
+}
+
+hipError_t launch_gather_rows(const GatherArgs& g, hipStream_t stream, const LaunchEvents& ev) {
+  if (g.n <= 0 || g.count <= 0) return hipSuccess;
+  if (g.count > 4 || g.width % 4) return hipErrorInvalidValue;
+  const long rows = (long)g.n * g.count;
+  const unsigned grid = (unsigned)((rows + 3) / 4 < 4096 ? (rows + 3) / 4 : 4096);
+  hipExtLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, 0, g);
+  return hipGetLastError();
 }
 
 }  // namespace acrobat

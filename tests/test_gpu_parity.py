@@ -272,6 +272,29 @@ def test_lstm_degenerate(ctx, P):
     assert h.shape[0] == 0
 
 
+def test_treelstm_unfused_gather_ablation_is_bit_identical(ctx, P):
+    """With gather fusion off every level first copies its operand rows into contiguous scratch; the
+    level kernels then do the same arithmetic on the copies."""
+    import paper_2305_10611_amd as A
+    for w in (gen.treelstm_workload(40, 1, 30, 128, 300, "zipf1.1", seed=21, bias_scale=0.2, D=64), make_config(1)):
+        h0, c0 = P.run_treelstm(ctx, w)
+        ctx.acrobat_set_gather_fusion(False)
+        try:
+            h1, c1 = P.run_treelstm(ctx, w)
+            ctx.acrobat_set_profiling(True)
+            P.run_treelstm(ctx, w)
+            rec = ctx.acrobat_last_profile()
+        finally:
+            ctx.acrobat_set_profiling(False)
+            ctx.acrobat_set_gather_fusion(True)
+        level_off, _ = ctx.acrobat_last_schedule()
+        assert sum(r[0] == A.binding.K_GATHER for r in rec) == len(level_off) - 1
+        assert np.array_equal(h0, h1) and np.array_equal(c0, c1)
+        oh, oc = oracle.treelstm(w, nthreads=NT)
+        P.assert_close(h1, oh, "h")
+        P.assert_close(c1, oc, "c")
+
+
 # ---------------------------------------------------------------- bidirectional RNN (program phases)
 def check_birnn_schedule(ctx, lens):
     from tests.test_oracle_birnn import birnn_graph

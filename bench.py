@@ -52,6 +52,10 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="TreeLSTM only: also time the forward pass with gather fusion switched off (explicit "
                          "gather launches), reported under \"ablation\"")
+    ap.add_argument("--generic-runtime", action="store_true",
+                    help="TreeLSTM only: also time the same batch through the generic dataflow-graph runtime (the "
+                         "unbatched program calls invoke() per node with inline depths), reported under "
+                         "\"generic_runtime\"")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="only run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "for scaling hardware-counter readings) and exit")
@@ -204,6 +208,49 @@ def main():
         ablation = {"unfused_gather_ms_per_step": round(ams, 4), "fused_over_unfused_speedup": round(ams / ms_per_step, 3)}
         step()  # the outputs checked further down come from the product path
 
+    # ---- information only: the same batch through the generic runtime (DFG construction by the unbatched
+    # program + bucket scheduling + one launch per bucket), as in the activity breakdown of the paper's table 6
+    generic = None
+    if args.generic_runtime and kind == "treelstm":
+        B = A.binding
+        g = A.Dfg(ctx)
+        gh, gc = new_out()
+        rc, op_leaf = g.acrobat_dfg_register_op(B.EPI_TREE_LEAF, H, nseg=1, kseg=D, src0=t["emb"], ld0=D, W=t["W_leaf"],
+                                                ldw=D, bias=t["b_leaf"], h=gh, c=gc, src0_rows=V, out_rows=n_nodes)
+        ctx.check(rc)
+        rc, op_int = g.acrobat_dfg_register_op(B.EPI_TREE_INTERNAL, H, nseg=2, kseg=H, src0=gh, ld0=H, src1=gh, ld1=H,
+                                               W=t["U"], ldw=2 * H, bias=t["b"], h=gh, c=gc, cprev_src=gc,
+                                               src0_rows=n_nodes, src1_rows=n_nodes, out_rows=n_nodes)
+        ctx.check(rc)
+
+        def gstep():
+            g.acrobat_dfg_clear()
+            ctx.check(g.acrobat_dfg_build_treelstm(w, V, op_leaf, op_int))
+            ctx.check(g.acrobat_dfg_run(stream))
+        for _ in range(args.warmup):
+            gstep()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            gstep()
+        torch.cuda.synchronize()
+        g1 = time.perf_counter()
+        tb = []
+        for _ in range(20):
+            g.acrobat_dfg_clear()
+            b0 = time.perf_counter()
+            g.acrobat_dfg_build_treelstm(w, V, op_leaf, op_int)
+            b1 = time.perf_counter()
+            g.acrobat_dfg_schedule()
+            b2 = time.perf_counter()
+            tb.append((b1 - b0, b2 - b1))
+        gms = (g1 - g0) * 1e3 / args.steps
+        same = bool(torch.equal(gh, out[0]) and torch.equal(gc, out[1]))
+        generic = {"ms_per_step": round(gms, 4), "t_dfg_construction_ms": round(float(np.median([x[0] for x in tb])) * 1e3, 4),
+                   "t_bucket_schedule_ms": round(float(np.median([x[1] for x in tb])) * 1e3, 4),
+                   "bit_identical_to_specialised_path": same}
+        g.close()
+
     # ---- host scheduler alone
     ts = []
     for _ in range(20):
@@ -293,7 +340,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w["name"], "index": args.config, "nodes": n_nodes, "seed": int(w["seed"])},
-        "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap, "ablation": ablation,
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap, "ablation": ablation, "generic_runtime": generic,
         "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
                       "t_splitk_reduce_ms": round(t_reduce_ms, 4),
                       "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),

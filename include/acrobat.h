@@ -156,6 +156,87 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
                           const acrobat_rnn_dir* bwd, const float* d_C, const float* d_cb,
                           float* d_hf, float* d_hb, float* d_y, void* hip_stream);
 
+/* ---- generic runtime: batched execution of an explicit dataflow graph ---------------------
+ * The step before the specialised entry points above (section 4.1, listing 2; appendix C): the
+ * unbatched program of a mini-batch calls acrobat_dfg_invoke once per operator instance, passing
+ * the depth it computed inline, and acrobat_dfg_run executes the graph bucket by bucket - a
+ * bucket being all nodes of one (phase, depth, op), in ascending node id - with one batched
+ * index upload and one gather-fused kernel launch per bucket.  An op is one of the cell kernels
+ * of this library bound to its parameters and arenas; a new cell needs an op description, not a
+ * scheduler.
+ *
+ * acrobat_op_desc: the batch-independent arguments of a cell kernel.  For node i of a bucket the
+ * kernel computes z[g*H + j] = sum_k in[k] * W[(gate_row(g)*H + j)*ldw + k] with in = row arg0 of
+ * src0 (row stride ld0, kseg floats) followed, if nseg == 2, by row arg1 of src1, and then,
+ * by epilogue:
+ *   TREE_LEAF      (c, h)[out_row] from gates (i, o, u) = weight row blocks 0, 3, 4 of a [5H, kseg] matrix
+ *   TREE_INTERNAL  (c, h)[out_row] from gates (i, f_l, f_r, o, u) and rows arg0, arg1 of cprev_src
+ *   LSTM_STEP      (c, h)[out_row] from gates (i, f, o, u) + zadd[out_row, 4H] and row arg0 of cprev_src
+ *                  (cprev_src NULL: zero previous state)
+ *   STORE_Z / STORE_Z1   zout[out_row, 4H] / zout[out_row, H] = z + bias   (four gates / one)
+ *   RNN_STEP       h[out_row] = sigmoid(z + zadd[out_row, H])
+ *   RELU_OUT       y[out_row*ldo + j] = relu(z + bias[j]) for j < n_cols (W has n_cols rows; H = n_cols
+ *                  rounded up to a multiple of 32)
+ * All pointers are device pointers and must stay valid until the run has finished on its stream. */
+#define ACROBAT_EPI_TREE_LEAF 0
+#define ACROBAT_EPI_TREE_INTERNAL 1
+#define ACROBAT_EPI_LSTM_STEP 2
+#define ACROBAT_EPI_STORE_Z 3
+#define ACROBAT_EPI_RNN_STEP 4
+#define ACROBAT_EPI_RELU_OUT 5
+#define ACROBAT_EPI_STORE_Z1 6
+
+typedef struct {
+  int32_t epilogue; /* ACROBAT_EPI_* */
+  int32_t H;        /* hidden size, multiple of 32 */
+  int32_t nseg;     /* operand segments: 0 (no contraction), 1 or 2 */
+  int32_t kseg;     /* floats per segment, multiple of 32 */
+  const float* src0; int32_t ld0;
+  const float* src1; int32_t ld1;
+  const float* W; int32_t ldw;
+  const float* bias;
+  float* h; float* c;
+  const float* cprev_src;
+  const float* zadd;
+  float* zout;
+  int32_t n_cols; float* y; int32_t ldo;
+  /* row counts for the range check of acrobat_dfg_invoke's arguments: arg0 < src0_rows (also the
+   * rows of cprev_src), arg1 < src1_rows, out_row < out_rows (rows of h, c, zadd, zout, y) */
+  int32_t src0_rows, src1_rows, out_rows;
+} acrobat_op_desc;
+
+typedef struct acrobat_dfg acrobat_dfg;
+
+/* The graph uses the context's index buffers and workspace: one run at a time per context.
+ * ctx may be NULL for a graph that is only built and scheduled (acrobat_dfg_run then fails). */
+int acrobat_dfg_create(acrobat_ctx* ctx, acrobat_dfg** out);
+void acrobat_dfg_destroy(acrobat_dfg* g);
+/* Message of the last failed acrobat_dfg_* call on this graph (owned by the graph). */
+const char* acrobat_dfg_last_error(const acrobat_dfg* g);
+/* Binds a cell kernel to its parameters; *op_id counts from 0.  ACROBAT_EINVAL on bad shapes. */
+int acrobat_dfg_register_op(acrobat_dfg* g, const acrobat_op_desc* desc, int32_t* op_id);
+/* Drops all nodes, keeps the ops. */
+int acrobat_dfg_clear(acrobat_dfg* g);
+/* Adds one operator instance.  out_row / arg0 / arg1: rows as described above (arg1 ignored unless
+ * the op has two segments).  prod0 / prod1: node ids of the instances that produce the operands,
+ * -1 for graph inputs; they serve the check of the inline depth (section 4.1, goal G.1): a node
+ * must be in the same or a later phase than its producers and deeper than those of its own phase,
+ * else ACROBAT_ESTRUCT.  *node (may be NULL) receives the new node's id (0, 1, 2, ...). */
+int acrobat_dfg_invoke(acrobat_dfg* g, int32_t op, int32_t phase, int32_t depth, int32_t out_row,
+                       int32_t arg0, int32_t arg1, int32_t prod0, int32_t prod1, int32_t* node);
+/* The unbatched TreeLSTM program (recursive evaluation of every tree, depth computed inline,
+ * leaves hoisted to depth 0) written against acrobat_dfg_invoke: node (tree t, j) becomes an
+ * instance of op_leaf (arg0 = token) or op_internal (args = children's arena rows) writing arena
+ * row tree_off[t] + j.  Same structure checks and error codes as acrobat_schedule_trees. */
+int acrobat_dfg_build_treelstm(acrobat_dfg* g, const acrobat_trees* trees, int32_t vocab,
+                               int32_t op_leaf, int32_t op_internal);
+/* Executes all nodes on the stream (asynchronously unless profiling is on). */
+int acrobat_dfg_run(acrobat_dfg* g, void* hip_stream);
+/* Buckets of the last run or of acrobat_dfg_schedule (host arrays owned by the graph, valid until
+ * its next call): bucket_off[n_buckets + 1] into order[], bucket_op[n_buckets]. */
+int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** bucket_off,
+                         const int32_t** order, const int32_t** bucket_op);
+
 /* ---- introspection --------------------------------------------------------------------
  * Schedule built by the last forward call on this context (host arrays owned by the context,
  * valid until the next forward call): level_off[n_levels + 1], level_nodes[level_off[n_levels]]. */
@@ -187,6 +268,7 @@ typedef struct {
 #define ACROBAT_K_RNN_OUTPUT 9
 #define ACROBAT_K_SPLITK_REDUCE 10
 #define ACROBAT_K_GATHER 11
+#define ACROBAT_K_DFG_BUCKET 12 /* level = bucket index */
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 

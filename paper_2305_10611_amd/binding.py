@@ -36,12 +36,25 @@ class acrobat_rnn_dir(C.Structure):
     _fields_ = [("Wx", C.c_void_p), ("Wh", C.c_void_p), ("b", C.c_void_p), ("h_init", C.c_void_p)]
 
 
+class acrobat_op_desc(C.Structure):
+    _fields_ = [("epilogue", C.c_int32), ("H", C.c_int32), ("nseg", C.c_int32), ("kseg", C.c_int32),
+                ("src0", C.c_void_p), ("ld0", C.c_int32), ("src1", C.c_void_p), ("ld1", C.c_int32),
+                ("W", C.c_void_p), ("ldw", C.c_int32), ("bias", C.c_void_p), ("h", C.c_void_p), ("c", C.c_void_p),
+                ("cprev_src", C.c_void_p), ("zadd", C.c_void_p), ("zout", C.c_void_p),
+                ("n_cols", C.c_int32), ("y", C.c_void_p), ("ldo", C.c_int32),
+                ("src0_rows", C.c_int32), ("src1_rows", C.c_int32), ("out_rows", C.c_int32)]
+
+
+EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z, EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1 = range(7)
+
 EXPORTS = (
     "acrobat_create", "acrobat_destroy", "acrobat_last_error", "acrobat_strerror",
     "acrobat_schedule_trees", "acrobat_schedule_seqs", "acrobat_treelstm_forward",
     "acrobat_mvrnn_forward", "acrobat_varlen_lstm_forward", "acrobat_last_schedule",
     "acrobat_set_profiling", "acrobat_last_profile", "acrobat_schedule_birnn", "acrobat_birnn_forward",
     "acrobat_set_gather_fusion",
+    "acrobat_dfg_create", "acrobat_dfg_destroy", "acrobat_dfg_last_error", "acrobat_dfg_register_op", "acrobat_dfg_clear", "acrobat_dfg_invoke",
+    "acrobat_dfg_build_treelstm", "acrobat_dfg_run", "acrobat_dfg_schedule",
 )
 
 
@@ -65,6 +78,17 @@ def _load():
     lib.acrobat_schedule_birnn.argtypes = [i32, vp, C.POINTER(i32), vp, vp]
     lib.acrobat_birnn_forward.argtypes = ([vp, i32, vp, i32, i32, i32, vp, C.POINTER(acrobat_rnn_dir),
                                            C.POINTER(acrobat_rnn_dir)] + [vp] * 6)
+    lib.acrobat_dfg_create.argtypes = [vp, C.POINTER(vp)]
+    lib.acrobat_dfg_destroy.argtypes = [vp]
+    lib.acrobat_dfg_destroy.restype = None
+    lib.acrobat_dfg_last_error.argtypes = [vp]
+    lib.acrobat_dfg_last_error.restype = C.c_char_p
+    lib.acrobat_dfg_register_op.argtypes = [vp, C.POINTER(acrobat_op_desc), C.POINTER(i32)]
+    lib.acrobat_dfg_clear.argtypes = [vp]
+    lib.acrobat_dfg_invoke.argtypes = [vp] + [i32] * 8 + [C.POINTER(i32)]
+    lib.acrobat_dfg_build_treelstm.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32, i32]
+    lib.acrobat_dfg_run.argtypes = [vp, vp]
+    lib.acrobat_dfg_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     lib.acrobat_last_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
     lib.acrobat_set_profiling.argtypes = [vp, i32]
     lib.acrobat_set_gather_fusion.argtypes = [vp, i32]
@@ -141,6 +165,74 @@ def acrobat_schedule_birnn(lens):
     if rc != OK:
         return rc, None, None
     return rc, level_off[: n_levels.value + 1].copy(), level_codes
+
+
+class Dfg:
+    """Owns one acrobat_dfg of a Context.  Methods mirror the C entry points and return the C return code."""
+
+    def __init__(self, ctx: "Context | None"):
+        """ctx None: a graph that can be built and scheduled but not run (needs no GPU)."""
+        self.ctx = ctx
+        self._g = C.c_void_p()
+        rc = lib.acrobat_dfg_create(ctx._h if ctx else None, C.byref(self._g))
+        if rc != OK:
+            raise AcrobatError(rc, acrobat_strerror(rc))
+        self._keep = []
+
+    def acrobat_dfg_last_error(self) -> str:
+        return lib.acrobat_dfg_last_error(self._g).decode()
+
+    def acrobat_dfg_register_op_desc(self, desc: "acrobat_op_desc"):
+        """-> (rc, op_id) for a prepared descriptor (raw pointers)."""
+        op = C.c_int32(-1)
+        rc = lib.acrobat_dfg_register_op(self._g, C.byref(desc), C.byref(op))
+        return rc, op.value
+
+    def close(self):
+        if self._g:
+            lib.acrobat_dfg_destroy(self._g)
+            self._g = C.c_void_p()
+
+    def acrobat_dfg_register_op(self, epilogue, H, nseg=0, kseg=0, src0=None, ld0=0, src1=None, ld1=0, W=None, ldw=0,
+                                bias=None, h=None, c=None, cprev_src=None, zadd=None, zout=None, n_cols=0, y=None, ldo=0,
+                                src0_rows=0, src1_rows=0, out_rows=0):
+        """-> (rc, op_id); tensors are device tensors (kept alive by this object)."""
+        t = (src0, src1, W, bias, h, c, cprev_src, zadd, zout, y)
+        self._keep.append(t)
+        d = acrobat_op_desc(epilogue, H, nseg, kseg, _dp(src0), ld0, _dp(src1), ld1, _dp(W), ldw, _dp(bias), _dp(h),
+                            _dp(c), _dp(cprev_src), _dp(zadd), _dp(zout), n_cols, _dp(y), ldo, src0_rows, src1_rows,
+                            out_rows)
+        op = C.c_int32(-1)
+        rc = lib.acrobat_dfg_register_op(self._g, C.byref(d), C.byref(op))
+        return rc, op.value
+
+    def acrobat_dfg_clear(self) -> int:
+        return lib.acrobat_dfg_clear(self._g)
+
+    def acrobat_dfg_invoke(self, op, phase, depth, out_row, arg0=0, arg1=0, prod0=-1, prod1=-1):
+        """-> (rc, node id)"""
+        node = C.c_int32(-1)
+        rc = lib.acrobat_dfg_invoke(self._g, op, phase, depth, out_row, arg0, arg1, prod0, prod1, C.byref(node))
+        return rc, node.value
+
+    def acrobat_dfg_build_treelstm(self, trees: dict, vocab, op_leaf, op_internal) -> int:
+        st, keep = _trees_struct(trees)
+        return lib.acrobat_dfg_build_treelstm(self._g, C.byref(st), vocab, op_leaf, op_internal)
+
+    def acrobat_dfg_run(self, stream=0) -> int:
+        return lib.acrobat_dfg_run(self._g, stream)
+
+    def acrobat_dfg_schedule(self):
+        """-> (bucket_off, order, bucket_op)"""
+        nb, po, pn, pp = C.c_int32(0), C.c_void_p(), C.c_void_p(), C.c_void_p()
+        rc = lib.acrobat_dfg_schedule(self._g, C.byref(nb), C.byref(po), C.byref(pn), C.byref(pp))
+        if rc != OK:
+            raise AcrobatError(rc, self.acrobat_dfg_last_error())
+        B = nb.value
+        as_arr = lambda p, n: (np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_int32)), shape=(n,)).copy()
+                               if n else np.zeros(0, np.int32))
+        off = as_arr(po, B + 1) if B else np.zeros(1, np.int32)
+        return off, as_arr(pn, int(off[-1])), as_arr(pp, B)
 
 
 class Context:

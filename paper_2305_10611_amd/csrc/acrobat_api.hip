@@ -14,6 +14,7 @@
 
 #include "acrobat.h"
 #include "cell_kernels.h"
+#include "dfg_runtime.h"
 #include "scheduler.h"
 
 using namespace acrobat;
@@ -41,6 +42,13 @@ struct acrobat_ctx {
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
   std::vector<hipEvent_t> events;  // pool, two per record
+};
+
+struct acrobat_dfg {
+  acrobat_ctx* ctx = nullptr;
+  std::string err;
+  Dfg graph;
+  DfgBuckets buckets;
 };
 
 namespace {
@@ -622,6 +630,125 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
       a.y = d_y; a.ldo = n_out;
       TRY(timer.begin(ACROBAT_K_RNN_OUTPUT, T, R));
       HIP_TRY(ctx, launch_cell_level(EPI_RELU_OUT, a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
+      TRY(timer.end());
+    }
+    return timer.finish();
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
+}
+
+int acrobat_dfg_create(acrobat_ctx* ctx, acrobat_dfg** out) {
+  if (!out) return ACROBAT_EINVAL;
+  *out = new (std::nothrow) acrobat_dfg();
+  if (!*out) return ACROBAT_ENOMEM;
+  (*out)->ctx = ctx;
+  return ACROBAT_OK;
+}
+
+void acrobat_dfg_destroy(acrobat_dfg* g) { delete g; }
+
+const char* acrobat_dfg_last_error(const acrobat_dfg* g) { return g ? g->err.c_str() : "null graph"; }
+
+int acrobat_dfg_register_op(acrobat_dfg* g, const acrobat_op_desc* desc, int32_t* op_id) {
+  if (!g || !desc || !op_id) return ACROBAT_EINVAL;
+  try {
+    g->err.clear();
+    return g->graph.register_op(*desc, op_id, g->err);
+  } catch (...) {
+    g->err = "host allocation failed";
+    return ACROBAT_ENOMEM;
+  }
+}
+
+int acrobat_dfg_clear(acrobat_dfg* g) {
+  if (!g) return ACROBAT_EINVAL;
+  g->graph.clear();
+  return ACROBAT_OK;
+}
+
+int acrobat_dfg_invoke(acrobat_dfg* g, int32_t op, int32_t phase, int32_t depth, int32_t out_row,
+                       int32_t arg0, int32_t arg1, int32_t prod0, int32_t prod1, int32_t* node) {
+  if (!g) return ACROBAT_EINVAL;
+  try {
+    return g->graph.invoke(op, phase, depth, out_row, arg0, arg1, prod0, prod1, node, g->err);
+  } catch (...) {
+    g->err = "host allocation failed";
+    return ACROBAT_ENOMEM;
+  }
+}
+
+int acrobat_dfg_build_treelstm(acrobat_dfg* g, const acrobat_trees* trees, int32_t vocab,
+                               int32_t op_leaf, int32_t op_internal) {
+  if (!g || !trees) return ACROBAT_EINVAL;
+  try {
+    g->err.clear();
+    return dfg_build_treelstm(g->graph, *trees, vocab, op_leaf, op_internal, g->err);
+  } catch (...) {
+    g->err = "host allocation failed";
+    return ACROBAT_ENOMEM;
+  }
+}
+
+int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** bucket_off,
+                         const int32_t** order, const int32_t** bucket_op) {
+  if (!g || !n_buckets || !bucket_off || !order || !bucket_op) return ACROBAT_EINVAL;
+  try {
+    g->graph.bucket(g->buckets);
+  } catch (...) {
+    g->err = "host allocation failed";
+    return ACROBAT_ENOMEM;
+  }
+  *n_buckets = (int32_t)g->buckets.op.size();
+  *bucket_off = g->buckets.off.data();
+  *order = g->buckets.order.data();
+  *bucket_op = g->buckets.op.data();
+  return ACROBAT_OK;
+}
+
+int acrobat_dfg_run(acrobat_dfg* g, void* hip_stream) {
+  if (!g) return ACROBAT_EINVAL;
+  acrobat_ctx* ctx = g->ctx;
+  if (!ctx) {
+    g->err = "graph was created without a context";
+    return ACROBAT_EINVAL;
+  }
+  try {
+    TRY(begin_call(ctx));
+    g->graph.bucket(g->buckets);
+    const std::vector<DfgNode>& nodes = g->graph.nodes();
+    const size_t n = nodes.size();
+    if (n == 0) return ACROBAT_OK;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    TRY(reserve_splitk(ctx));
+    // by bucket position: row written | first operand row | second operand row
+    TRY(reserve_indices(ctx, 3 * n));
+    int32_t* st = ctx->h_stage;
+    for (size_t p = 0; p < n; ++p) {
+      const DfgNode& x = nodes[g->buckets.order[p]];
+      st[p] = x.out_row;
+      st[n + p] = x.arg0;
+      st[2 * n + p] = x.arg1;
+    }
+    TRY(upload_indices(ctx, 3 * n, stream));
+    LaunchTimer timer{ctx, stream};
+    for (size_t b = 0; b < g->buckets.op.size(); ++b) {
+      const int32_t off = g->buckets.off[b], cnt = g->buckets.off[b + 1] - off;
+      const acrobat_op_desc& d = g->graph.ops()[g->buckets.op[b]];
+      CellLevelArgs a{};
+      a.n = cnt; a.H = d.H; a.nseg = d.nseg; a.kseg = d.kseg;
+      a.src0 = d.src0; a.ld0 = d.ld0; a.idx0 = ctx->d_idx + n + off;
+      a.src1 = d.src1; a.ld1 = d.ld1; a.idx1 = ctx->d_idx + 2 * n + off;
+      a.W = d.W; a.ldw = d.ldw; a.bias = d.bias;
+      a.out_rows = ctx->d_idx + off;
+      a.h = d.h; a.c = d.c; a.cprev_src = d.cprev_src; a.zadd = d.zadd; a.zout = d.zout;
+      a.n_cols = d.n_cols; a.y = d.y; a.ldo = d.ldo;
+      static const CellEpilogue kEpi[] = {EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z,
+                                          EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1};
+      TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, cnt));
+      HIP_TRY(ctx, launch_cell_level(kEpi[d.epilogue], a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
     return timer.finish();

@@ -409,3 +409,96 @@ def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit, monkey
         check_birnn(P, P.run_birnn(c, b), oracle.birnn(b, nthreads=NT), "birnn")
     finally:
         c.close()
+
+
+# ---------------------------------------------------------------- generic dataflow-graph runtime
+def treelstm_ops(g, B, t, w, h, c, N):
+    H, D, V = int(w["H"]), int(w["D"]), int(w["V"])
+    rc, leaf = g.acrobat_dfg_register_op(B.EPI_TREE_LEAF, H, nseg=1, kseg=D, src0=t["emb"], ld0=D, W=t["W_leaf"], ldw=D,
+                                         bias=t["b_leaf"], h=h, c=c, src0_rows=V, out_rows=N)
+    assert rc == 0
+    rc, internal = g.acrobat_dfg_register_op(B.EPI_TREE_INTERNAL, H, nseg=2, kseg=H, src0=h, ld0=H, src1=h, ld1=H,
+                                             W=t["U"], ldw=2 * H, bias=t["b"], h=h, c=c, cprev_src=c, src0_rows=N,
+                                             src1_rows=N, out_rows=N)
+    assert rc == 0
+    return leaf, internal
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_generic_runtime_treelstm_program_is_bit_identical_to_the_specialised_path(ctx, P, cfg):
+    import torch
+    import paper_2305_10611_amd as A
+    from paper_2305_10611_amd import binding as B
+    w = make_config(cfg)
+    w, _ = gen.relabel_trees(w, gen.make_rng(cfg + 70), extra={"token": w["token"]})
+    N, H = int(w["tree_off"][-1]), int(w["H"])
+    t = {k: P.dev(w[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")}
+    h, c = P.nan_filled(N, H), P.nan_filled(N, H)
+    g = A.Dfg(ctx)
+    leaf, internal = treelstm_ops(g, B, t, w, h, c, N)
+    assert g.acrobat_dfg_build_treelstm(w, int(w["V"]), leaf, internal) == A.OK
+    ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+    torch.cuda.synchronize()
+    h_ref, c_ref = P.run_treelstm(ctx, w)
+    assert np.array_equal(h.cpu().numpy(), h_ref) and np.array_equal(c.cpu().numpy(), c_ref)
+    oh, oc = oracle.treelstm(w, nthreads=NT)
+    P.assert_close(h.cpu().numpy(), oh, "h")
+    P.assert_close(c.cpu().numpy(), oc, "c")
+    # a second run of the same graph, and a run after clear + rebuild
+    h.fill_(float("nan")); c.fill_(float("nan"))
+    g.acrobat_dfg_clear()
+    assert g.acrobat_dfg_build_treelstm(w, int(w["V"]), leaf, internal) == A.OK
+    ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+    torch.cuda.synchronize()
+    assert np.array_equal(h.cpu().numpy(), h_ref)
+    g.close()
+
+
+def test_generic_runtime_birnn_program_with_phases(ctx, P):
+    """The BiRNN written node by node against invoke(): hoisted input transforms (phase 0), the two
+    recurrences with inline depths (phase 1), every output operator in phase 2."""
+    import torch
+    import paper_2305_10611_amd as A
+    from paper_2305_10611_amd import binding as B
+    w = gen.birnn_workload(12, 0, 9, 64, 32, 5, seed=33, bias_scale=0.3)
+    R, H, D, n_out = int(w["len"].sum()), 64, 32, 5
+    names = ("x", "fWx", "fWh", "fb", "finit", "bWx", "bWh", "bb", "binit", "C", "cb")
+    t = {k: P.dev(np.asarray(w[k], np.float32)) for k in names}
+    hf, hb, y = P.nan_filled(R + 1, H), P.nan_filled(R + 1, H), P.nan_filled(R, n_out)
+    # row R of each state arena holds the direction's initial state, so step 0 reads it like any other row
+    hf[R] = t["finit"]; hb[R] = t["binit"]
+    xpf, xpb = P.nan_filled(R, H), P.nan_filled(R, H)
+    g = A.Dfg(ctx)
+    ok = lambda r: (r[0] == A.OK and r[1]) if isinstance(r, tuple) else r
+    reg = lambda *a, **k: (lambda r: (r[1] if r[0] == A.OK else pytest.fail(g.acrobat_dfg_last_error())))(g.acrobat_dfg_register_op(*a, **k))
+    proj = [reg(B.EPI_STORE_Z1, H, nseg=1, kseg=D, src0=t["x"], ld0=D, W=t[p + "Wx"], ldw=D, bias=t[p + "b"], zout=z,
+                src0_rows=R, out_rows=R) for p, z in (("f", xpf), ("b", xpb))]
+    step = [reg(B.EPI_RNN_STEP, H, nseg=1, kseg=H, src0=hh, ld0=H, W=t[p + "Wh"], ldw=H, zadd=z, h=hh, src0_rows=R + 1,
+                out_rows=R) for p, z, hh in (("f", xpf, hf), ("b", xpb, hb))]
+    out = reg(B.EPI_RELU_OUT, 32, nseg=2, kseg=H, src0=hf, ld0=H, src1=hb, ld1=H, W=t["C"], ldw=2 * H, bias=t["cb"],
+              n_cols=n_out, y=y, ldo=n_out, src0_rows=R, src1_rows=R, out_rows=R)
+    off = w["seq_off"]
+    for s in range(w["n_seq"]):
+        b, T = int(off[s]), int(w["len"][s])
+        pf = [g.acrobat_dfg_invoke(proj[0], 0, 0, b + i, b + i)[1] for i in range(T)]
+        pb = [g.acrobat_dfg_invoke(proj[1], 0, 0, b + i, b + i)[1] for i in range(T)]
+        nf, nb = [None] * T, [None] * T
+        for k in range(T):  # depth k in both directions
+            i = k
+            rc, nf[i] = g.acrobat_dfg_invoke(step[0], 1, k, b + i, R if k == 0 else b + i - 1, 0, pf[i], -1 if k == 0 else nf[i - 1])
+            assert rc == A.OK
+            i = T - 1 - k
+            rc, nb[i] = g.acrobat_dfg_invoke(step[1], 1, k, b + i, R if k == 0 else b + i + 1, 0, pb[i], -1 if k == 0 else nb[i + 1])
+            assert rc == A.OK
+        for i in range(T):
+            assert g.acrobat_dfg_invoke(out, 2, 0, b + i, b + i, b + i, nf[i], nb[i])[0] == A.OK
+    boff, order, bops = g.acrobat_dfg_schedule()
+    T_max = int(w["len"].max())
+    assert len(bops) == 2 + 2 * T_max + 1 and boff[-1] - boff[-2] == R
+    ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+    torch.cuda.synchronize()
+    ohf, ohb, oy = oracle.birnn(w, nthreads=NT)
+    P.assert_close(hf[:R].cpu().numpy(), ohf, "hf")
+    P.assert_close(hb[:R].cpu().numpy(), ohb, "hb")
+    P.assert_close(y.cpu().numpy(), oy, "y", ref_floor=0.1)
+    g.close()

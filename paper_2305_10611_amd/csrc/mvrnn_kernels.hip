@@ -64,15 +64,8 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   const int mb = wave & 1, kh = wave >> 1;
   const int lcol = lane & 31, lhi = lane >> 5;
 
-  // shared weights -> registers, once per workgroup
-  float wm[32];  // W_M[32*mb + lcol][64*kh + 2s + lhi]
-#pragma unroll
-  for (int s = 0; s < 32; ++s) wm[s] = a.WM[(mb * 32 + lcol) * (2 * kD) + kh * kD + 2 * s + lhi];
   const int vr = tid >> 2, vq = tid & 3;  // p = tanh(W v): output row, quarter of the columns
-  for (int i = tid; i < kD * 2 * kD / 4; i += 256) {  // W -> LDS (rows padded to 132 floats)
-    const int r = i >> 5, c4 = i & 31;
-    *reinterpret_cast<floatx4*>(&s_W[r * kWld + c4 * 4]) = *reinterpret_cast<const floatx4*>(a.W + r * (2 * kD) + c4 * 4);
-  }
+  float wm[32];  // W_M[32*mb + lcol][64*kh + 2s + lhi], in registers for the whole launch (loaded below)
 
   struct RawIdx { int ls, rs, orow; };
   // the index lists are only read in this kernel and `node` is uniform in the workgroup
@@ -199,11 +192,28 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
 
   int node = blockIdx.x;
   if (node >= a.n) return;
+  // The first node's indices head the longest dependent chain (indices -> operands -> matrix
+  // instructions), so they are requested before anything else; the shared weights, which depend on
+  // nothing, follow and arrive while the indices and then the operands are on their way.
   RawIdx raw = load_idx(node);
+  RawIdx raw_next = load_idx(min(node + (int)gridDim.x, a.n - 1));
+#pragma unroll
+  for (int s = 0; s < 32; ++s) wm[s] = a.WM[(mb * 32 + lcol) * (2 * kD) + kh * kD + 2 * s + lhi];
+  floatx4 wst[kD * 2 * kD / 4 / 256];  // W on its way to LDS (rows padded to 132 floats)
+#pragma unroll
+  for (int k = 0; k < kD * 2 * kD / 4 / 256; ++k) {
+    const int i = tid + 256 * k;
+    wst[k] = *reinterpret_cast<const floatx4*>(a.W + (i >> 5) * (2 * kD) + (i & 31) * 4);
+  }
   NodeRef cur = resolve(raw);
-  raw = load_idx(min(node + (int)gridDim.x, a.n - 1));
+  raw = raw_next;
   floatx2 x0[32], x1[32], vv0, vv1;
   load_node(cur, x0, vv0);
+#pragma unroll
+  for (int k = 0; k < kD * 2 * kD / 4 / 256; ++k) {
+    const int i = tid + 256 * k;
+    *reinterpret_cast<floatx4*>(&s_W[(i >> 5) * kWld + (i & 31) * 4]) = wst[k];
+  }
   while (true) {
     process(node, cur, raw, x0, vv0, x1, vv1);
     node += gridDim.x;

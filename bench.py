@@ -47,8 +47,9 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
-    ap.add_argument("--no-overlap-streams", dest="overlap_streams", action="store_false",
-                    help="skip the informational two-stream throughput measurement")
+    ap.add_argument("--two-streams", dest="overlap_streams", action="store_true",
+                    help="also measure, for information, the throughput when consecutive mini-batches alternate "
+                         "between two streams (reported under \"two_stream_throughput\")")
     ap.add_argument("--ablation", action="store_true",
                     help="TreeLSTM only: also time the forward pass with gather fusion switched off (explicit "
                          "gather launches), reported under \"ablation\"")

@@ -20,6 +20,14 @@
  *    when validation fails.  acrobat_last_error() gives a human readable reason.
  *  - No C++ exception crosses this boundary.
  *  - A context must not be used from two threads at once.
+ *  - Stream capture (hipStreamBeginCapture on the given stream): a forward call may be recorded
+ *    into a HIP graph once an uncaptured call of at least the same sizes has run on the context
+ *    (a captured call allocates nothing and waits for nothing; otherwise it fails with
+ *    ACROBAT_EINVAL), with profiling off.  The graph's upload node reads the context's staging
+ *    buffer at every replay: no other call may use the context until the graph is no longer
+ *    replayed.  Capturing and instantiating costs more than a forward call itself, so this pays
+ *    only for a mini-batch that is replayed unchanged; the schedule of a new mini-batch needs a
+ *    new graph.
  */
 #ifndef ACROBAT_H
 #define ACROBAT_H

@@ -69,9 +69,24 @@ int fail_hip(acrobat_ctx* ctx, hipError_t e, const char* what) {
     if (e_ != hipSuccess) return fail_hip(ctx, e_, #expr);   \
   } while (0)
 
+bool stream_is_capturing(hipStream_t stream) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  return hipStreamIsCapturing(stream, &st) == hipSuccess && st != hipStreamCaptureStatusNone;
+}
+
 // Makes room for `n` int32 in the pinned staging buffer and the device index buffer and waits
-// until a previous upload no longer reads the staging buffer.
-int reserve_indices(acrobat_ctx* ctx, size_t n) {
+// until a previous upload no longer reads the staging buffer.  While `stream` is being captured
+// into a graph nothing may be allocated or waited for: the buffers must already be large enough
+// (one uncaptured call of the same size beforehand does that), and the caller must keep other
+// calls away from this context until it has finished with the graph, whose upload node reads the
+// staging buffer at every replay.
+int reserve_indices(acrobat_ctx* ctx, size_t n, hipStream_t stream) {
+  const bool capturing = stream_is_capturing(stream);
+  if (capturing) {
+    if (n > ctx->stage_cap || n > ctx->idx_cap)
+      return fail(ctx, ACROBAT_EINVAL, "stream capture: index buffers too small, run once without capture first");
+    return ACROBAT_OK;
+  }
   if (ctx->stage_pending) {
     HIP_TRY(ctx, hipEventSynchronize(ctx->stage_done));
     ctx->stage_pending = false;
@@ -97,13 +112,15 @@ int reserve_indices(acrobat_ctx* ctx, size_t n) {
 
 int upload_indices(acrobat_ctx* ctx, size_t n, hipStream_t stream) {
   HIP_TRY(ctx, hipMemcpyAsync(ctx->d_idx, ctx->h_stage, n * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+  if (stream_is_capturing(stream)) return ACROBAT_OK;
   HIP_TRY(ctx, hipEventRecord(ctx->stage_done, stream));
   ctx->stage_pending = true;
   return ACROBAT_OK;
 }
 
-int reserve_scratch(acrobat_ctx* ctx, size_t n_floats) {
+int reserve_scratch(acrobat_ctx* ctx, size_t n_floats, hipStream_t stream) {
   if (n_floats <= ctx->scratch_cap) return ACROBAT_OK;
+  if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "stream capture: scratch too small, run once without capture first");
   if (ctx->d_scratch) HIP_TRY(ctx, hipFree(ctx->d_scratch));
   ctx->d_scratch = nullptr;
   ctx->scratch_cap = 0;
@@ -113,8 +130,9 @@ int reserve_scratch(acrobat_ctx* ctx, size_t n_floats) {
 }
 
 // Partial-tile workspace of the k-split levels: 128 MiB.
-int reserve_splitk(acrobat_ctx* ctx) {
+int reserve_splitk(acrobat_ctx* ctx, hipStream_t stream) {
   if (ctx->splitk.partial) return ACROBAT_OK;
+  if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "stream capture: workspace not allocated, run once without capture first");
   constexpr size_t kPartialFloats = (size_t)32 << 20;
   float* p = nullptr;
   HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
@@ -136,6 +154,7 @@ struct LaunchTimer {
   int begin(int32_t kind, int32_t level, int32_t n) {
     ev = LaunchEvents();
     if (!ctx->profiling) return ACROBAT_OK;
+    if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "profiling cannot be combined with stream capture");
     const size_t first = 2 * ctx->records.size();
     while (ctx->events.size() < first + 4) {
       hipEvent_t e;
@@ -297,7 +316,7 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
 
     if ((double)5 * H * 2 * H >= 2147483648.0 || (double)5 * H * D >= 2147483648.0)
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
-    TRY(reserve_splitk(ctx));
+    TRY(reserve_splitk(ctx, stream));
     // index lists by schedule position: out row | first operand row | second operand row
     // (+ 0, 1, 2, ... for the unfused-gather ablation, whose level kernels read gathered copies)
     const int32_t n_leaf = s.level_off[1];
@@ -305,14 +324,14 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
     for (int32_t lv = 1; lv < s.n_levels; ++lv) n_wide = std::max(n_wide, s.level_off[lv + 1] - s.level_off[lv]);
     const bool unfused = !ctx->gather_fusion;
     const size_t n_iota = unfused ? (size_t)std::max(n_leaf, 2 * n_wide) : 0;
-    TRY(reserve_indices(ctx, 3 * (size_t)N + n_iota));
+    TRY(reserve_indices(ctx, 3 * (size_t)N + n_iota, stream));
     int32_t* st = ctx->h_stage;
     std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
     for (int32_t p = 0; p < n_leaf; ++p) st[N + p] = trees->token[s.level_nodes[p]];  // leaves gather by token
     std::memcpy(st + N + n_leaf, s.lrow.data() + n_leaf, (size_t)(N - n_leaf) * sizeof(int32_t));
     std::memcpy(st + 2 * (size_t)N, s.rrow.data(), (size_t)N * sizeof(int32_t));
     for (size_t i = 0; i < n_iota; ++i) st[3 * (size_t)N + i] = (int32_t)i;
-    if (unfused) TRY(reserve_scratch(ctx, std::max((size_t)n_leaf * D, 4 * (size_t)n_wide * H)));
+    if (unfused) TRY(reserve_scratch(ctx, std::max((size_t)n_leaf * D, 4 * (size_t)n_wide * H), stream));
     TRY(upload_indices(ctx, 3 * (size_t)N + n_iota, stream));
     const int32_t* d_out = ctx->d_idx;
     const int32_t* d_ia = ctx->d_idx + N;
@@ -398,7 +417,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
     // child source codes: arena row of an internal child, -(token + 1) for a leaf child
-    TRY(reserve_indices(ctx, 3 * (size_t)N));
+    TRY(reserve_indices(ctx, 3 * (size_t)N, stream));
     int32_t* st = ctx->h_stage;
     std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
     const int32_t n_leaf = s.level_off[1];
@@ -468,14 +487,14 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
 
     if ((double)4 * H * H >= 2147483648.0 || (double)4 * H * D >= 2147483648.0)
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
-    TRY(reserve_splitk(ctx));
+    TRY(reserve_splitk(ctx, stream));
     // by schedule position: row written | row of the previous step (unused at t = 0)
-    TRY(reserve_indices(ctx, 2 * (size_t)R));
+    TRY(reserve_indices(ctx, 2 * (size_t)R, stream));
     int32_t* st = ctx->h_stage;
     std::memcpy(st, s.level_rows.data(), (size_t)R * sizeof(int32_t));
     for (int32_t p = 0; p < R; ++p) st[R + p] = s.level_rows[p] - 1;
     for (int32_t p = 0; p < s.level_off[1]; ++p) st[R + p] = s.level_rows[p];  // keep in range
-    TRY(reserve_scratch(ctx, (size_t)R * 4 * (size_t)H));
+    TRY(reserve_scratch(ctx, (size_t)R * 4 * (size_t)H, stream));
     TRY(upload_indices(ctx, 2 * (size_t)R, stream));
     const int32_t* d_out = ctx->d_idx;
     const int32_t* d_prev = ctx->d_idx + R;
@@ -562,10 +581,10 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int32_t T = s.n_levels - 1;  // recurrence steps; level T is the output batch
-    TRY(reserve_splitk(ctx));
+    TRY(reserve_splitk(ctx, stream));
     // per direction, by position in the direction's step lists: row written | row of the previous
     // step of that direction (step 0 gathers row 0 of the initial-state vector)
-    TRY(reserve_indices(ctx, 4 * (size_t)R));
+    TRY(reserve_indices(ctx, 4 * (size_t)R, stream));
     int32_t* st = ctx->h_stage;
     for (int32_t k = 0; k < T; ++k) {
       const int32_t f0 = s.fwd_off[k], nf = s.fwd_off[k + 1] - f0;
@@ -578,7 +597,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
         st[3 * (size_t)R + f0 + p] = k == 0 ? 0 : rb + 1;
       }
     }
-    TRY(reserve_scratch(ctx, 2 * (size_t)R * (size_t)H));
+    TRY(reserve_scratch(ctx, 2 * (size_t)R * (size_t)H, stream));
     TRY(upload_indices(ctx, 4 * (size_t)R, stream));
 
     // The two recurrences share nothing but x and never wait for each other: step k of both
@@ -722,9 +741,9 @@ int acrobat_dfg_run(acrobat_dfg* g, void* hip_stream) {
     const size_t n = nodes.size();
     if (n == 0) return ACROBAT_OK;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    TRY(reserve_splitk(ctx));
+    TRY(reserve_splitk(ctx, stream));
     // by bucket position: row written | first operand row | second operand row
-    TRY(reserve_indices(ctx, 3 * n));
+    TRY(reserve_indices(ctx, 3 * n, stream));
     int32_t* st = ctx->h_stage;
     for (size_t p = 0; p < n; ++p) {
       const DfgNode& x = nodes[g->buckets.order[p]];

@@ -67,6 +67,15 @@ struct CellLevelPair {
   int32_t split;
 };
 
+// One launch: with events through the extended launch call (which stamps them), without events
+// through the plain one (which, unlike the extended call, can be recorded by a stream capture).
+template <class Kernel, class... Args>
+inline void launch_with_events(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, hipEvent_t start,
+                               hipEvent_t stop, Args... args) {
+  if (start || stop) hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, start, stop, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args...);
+}
+
 // Launches the kernel for one level; picks the node-tile height and k split from the level's
 // size and reports them in *tile / *ksplit (may be null).  Returns hipGetLastError().
 hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream_t stream,

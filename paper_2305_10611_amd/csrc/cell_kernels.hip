@@ -686,7 +686,7 @@ hipError_t launch_tiny(const CellLevelPair& pr, unsigned grid, hipStream_t strea
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipExtLaunchKernelGGL((cell_tiny_kernel<G, EPI, U>), dim3(grid), dim3(kThreads), bytes, stream, ev.start, ev.stop, 0,
+  launch_with_events((cell_tiny_kernel<G, EPI, U>), dim3(grid), dim3(kThreads), bytes, stream, ev.start, ev.stop, 
                         pr);
   return hipGetLastError();
 }
@@ -780,20 +780,20 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
   pr.split = (int32_t)g0;
   const unsigned grid = g0 + g1;
   if (sh.bm == 128) {
-    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, pr, sh.ksplit, ws.partial);
+    launch_with_events((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, pr, sh.ksplit, ws.partial);
   } else if (sh.bm == 64) {
-    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, pr, sh.ksplit, ws.partial);
+    launch_with_events((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, pr, sh.ksplit, ws.partial);
   } else {
-    hipExtLaunchKernelGGL((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, 0, pr, sh.ksplit, ws.partial);
+    launch_with_events((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
+                          ev.stop, pr, sh.ksplit, ws.partial);
   }
   if (sh.ksplit > 1) {
     const int wm_count = sh.bm / 32;
     const unsigned rgrid = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * wm_count * 16);
-    hipExtLaunchKernelGGL((cell_splitk_reduce_kernel<G, EPI>), dim3(rgrid), dim3(64), 0, stream, ev.reduce_start,
-                          ev.reduce_stop, 0, a, sh.ksplit, wm_count, (const float*)ws.partial);
+    launch_with_events((cell_splitk_reduce_kernel<G, EPI>), dim3(rgrid), dim3(64), 0, stream, ev.reduce_start,
+                          ev.reduce_stop, a, sh.ksplit, wm_count, (const float*)ws.partial);
   }
   return hipGetLastError();
 }
@@ -848,7 +848,7 @@ hipError_t launch_gather_rows(const GatherArgs& g, hipStream_t stream, const Lau
   if (g.count > 4 || g.width % 4) return hipErrorInvalidValue;
   const long rows = (long)g.n * g.count;
   const unsigned grid = (unsigned)((rows + 3) / 4 < 4096 ? (rows + 3) / 4 : 4096);
-  hipExtLaunchKernelGGL(gather_rows_kernel, dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, 0, g);
+  launch_with_events(gather_rows_kernel, dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, g);
   return hipGetLastError();
 }
 

@@ -430,11 +430,11 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
   if (a.n <= 0) return hipSuccess;
   const int grid = a.n < 512 ? a.n : 512;  // two resident workgroups per compute unit, each strides over the level
   if (a.d == 128) {
-    hipExtLaunchKernelGGL(mvrnn_stream_kernel<128>, dim3(a.n < 256 ? a.n : 256), dim3(256), 0, stream, ev.start, ev.stop, 0, a);
+    launch_with_events(mvrnn_stream_kernel<128>, dim3(a.n < 256 ? a.n : 256), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else if (a.variant == 1) {
-    hipExtLaunchKernelGGL(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, 0, a);
+    launch_with_events(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else {
-    hipExtLaunchKernelGGL(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, 0, a);
+    launch_with_events(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
   }
   return hipGetLastError();
 }
@@ -444,7 +444,7 @@ hipError_t launch_mvrnn_leaf_copy(int32_t n, int32_t d, const int32_t* out_rows,
                                   hipStream_t stream, const LaunchEvents& ev) {
   if (n <= 0) return hipSuccess;
   const int grid = n < 2048 ? n : 2048;
-  hipExtLaunchKernelGGL(mvrnn_leaf_copy_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, 0, n, d,
+  launch_with_events(mvrnn_leaf_copy_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, n, d,
                         out_rows, token, vec_tab, mat_tab, vec, mat);
   return hipGetLastError();
 }

@@ -411,6 +411,50 @@ def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit, monkey
         c.close()
 
 
+# ---------------------------------------------------------------- stream capture
+def test_forward_recorded_into_a_graph_replays_the_eager_result():
+    """A captured forward call (index upload + every level launch) replayed several times, with eager work
+    on another context and synchronisations between the replays, gives the eager result each time."""
+    import torch
+    import paper_2305_10611_amd as A
+    from tests import parity as P
+    w = gen.treelstm_workload(30, 1, 25, 128, 200, "zipf1.1", seed=44, bias_scale=0.2)
+    other = gen.treelstm_workload(9, 1, 12, 64, 50, "uniform", seed=45)
+    N, H = int(w["tree_off"][-1]), int(w["H"])
+    t = {k: P.dev(w[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")}
+    ctx, ctx2 = A.Context(0), A.Context(0)
+    try:
+        h_ref, c_ref = P.run_treelstm(ctx, w)          # also sizes the context's buffers
+        h, c = P.nan_filled(N, H), P.nan_filled(N, H)
+        s = torch.cuda.Stream()
+        fwd = lambda: ctx.acrobat_treelstm_forward(w, H, int(w["D"]), int(w["V"]), t["emb"], t["W_leaf"], t["b_leaf"],
+                                                   t["U"], t["b"], h, c, s.cuda_stream)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s, capture_error_mode="relaxed"):
+            rc = fwd()
+        assert rc == A.OK, ctx.acrobat_last_error()
+        assert torch.isnan(h).all()                      # capture launches nothing
+        for _ in range(3):
+            h.fill_(float("nan")); c.fill_(float("nan"))
+            P.run_treelstm(ctx2, other)                  # eager work in between, on its own context
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(h.cpu().numpy(), h_ref) and np.array_equal(c.cpu().numpy(), c_ref)
+        # a capture that would have to allocate is refused, not attempted
+        big = gen.treelstm_workload(400, 20, 40, 128, 200, "zipf1.1", seed=46)
+        tb = {k: P.dev(big[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")}
+        Nb = int(big["tree_off"][-1])
+        hb, cb = P.nan_filled(Nb, H), P.nan_filled(Nb, H)
+        g2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g2, stream=s, capture_error_mode="relaxed"):
+            rc = ctx.acrobat_treelstm_forward(big, H, int(big["D"]), int(big["V"]), tb["emb"], tb["W_leaf"], tb["b_leaf"],
+                                              tb["U"], tb["b"], hb, cb, s.cuda_stream)
+        assert rc == A.EINVAL and "capture" in ctx.acrobat_last_error()
+    finally:
+        ctx.close(); ctx2.close()
+
+
 # ---------------------------------------------------------------- generic dataflow-graph runtime
 def treelstm_ops(g, B, t, w, h, c, N):
     H, D, V = int(w["H"]), int(w["D"]), int(w["V"])

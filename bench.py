@@ -25,6 +25,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix peak
 PEAK_HBM_GBS = 8000.0
+# ceilings measured on this machine: a loop of nothing but fp32 matrix instructions on all compute
+# units, and a plain streaming read by 256 workgroups
+MEASURED_MFMA_TFLOPS = 155.0
+MEASURED_HBM_GBS = 5800.0
 
 # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summaries
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB per dispatch, factors from a plain copy of known size).
@@ -299,16 +303,30 @@ def main():
                 "kernel": kname, "launches_per_step": launches,
                 "units_per_step": units, "avg_launch_us": round(ms_sum / launches * 1e3, 2)}
 
+    # ---- aggregate roofline fraction: every launch takes at least max(flops / P, bytes / B); their sum over the
+    # device time says how close the whole level sequence is to the chip's two roofs
+    def floor_ms(k, n, peak_tf, peak_gbs):
+        return max(n * flops_per[k] / (peak_tf * 1e9), (n * bytes_per[k] + weight_bytes[k]) / (peak_gbs * 1e6))
+    agg = {"datasheet": 0.0, "measured_ceilings": 0.0}
+    for k, lv, n, tile, ms, ks in per_launch:
+        if k in flops_per:
+            agg["datasheet"] += floor_ms(k, n, PEAK_FP32_MFMA_TFLOPS, PEAK_HBM_GBS)
+            agg["measured_ceilings"] += floor_ms(k, n, MEASURED_MFMA_TFLOPS, MEASURED_HBM_GBS)
+    agg = {key: round(v / t_device_ms, 4) for key, v in agg.items()}
+
     if args.verbose:
-        print(f"{'kind':>4} {'lvl':>4} {'n':>6} {'tile':>4} {'ks':>3} {'us':>9} {'TFLOP/s':>8} {'GB/s':>8}", file=sys.stderr)
+        print(f"{'kind':>4} {'lvl':>4} {'n':>6} {'tile':>4} {'ks':>3} {'us':>9} {'TFLOP/s':>8} {'%MFMA':>6} {'GB/s':>8} {'%HBM':>6} {'bound':>5}",
+              file=sys.stderr)
         for k, lv, n, tile, ms, ks in per_launch:
-            if k == K_REDUCE:
-                print(f"{'red':>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f}", file=sys.stderr)
+            if k == K_REDUCE or k not in flops_per:
+                print(f"{'red' if k == K_REDUCE else k:>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f}", file=sys.stderr)
                 continue
             fl = n * flops_per[k]
             by = n * bytes_per[k] + weight_bytes[k]
-            print(f"{k:>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f} {fl / ms / 1e9:>8.2f} {by / ms / 1e6:>8.1f}",
-                  file=sys.stderr)
+            tf, gbs = fl / ms / 1e9, by / ms / 1e6
+            which = "mfma" if fl / (PEAK_FP32_MFMA_TFLOPS * 1e9) >= by / (PEAK_HBM_GBS * 1e6) else "hbm"
+            print(f"{k:>4} {lv:>4} {n:>6} {tile:>4} {ks:>3} {ms * 1e3:>9.2f} {tf:>8.2f} {100 * tf / PEAK_FP32_MFMA_TFLOPS:>6.1f} "
+                  f"{gbs:>8.1f} {100 * gbs / PEAK_HBM_GBS:>6.1f} {which:>5}", file=sys.stderr)
         print(f"device sum {t_device_ms:.3f} ms, end-to-end {ms_per_step:.3f} ms/step, schedule {t_schedule_ms:.3f} ms",
               file=sys.stderr)
 
@@ -331,6 +349,17 @@ def main():
         cpu_baseline = {"value": round(n_nodes / (c1 - c0), 1), "unit": "nodes/s", "cores": nt, "kind": "oracle",
                         "sample": f"the whole {w['name']} batch ({n_nodes} nodes), evaluated once with whole "
                                   f"instances fanned out over {nt} host threads"}
+        # the oracle as written, one thread, on a bounded sample: the first instances of the same batch
+        if kind == "treelstm":
+            k1 = min(int(w["n_trees"]), 16)
+            n1 = int(w["tree_off"][k1])
+            w1 = dict(w, n_trees=k1, tree_off=w["tree_off"][: k1 + 1], left=w["left"][:n1], right=w["right"][:n1],
+                      token=w["token"][:n1])
+            s0 = time.perf_counter()
+            oracle.treelstm(w1, nthreads=1)
+            s1 = time.perf_counter()
+            cpu_baseline["single_thread"] = {"value": round(n1 / (s1 - s0), 1), "unit": "nodes/s", "cores": 1,
+                                             "sample": f"the first {k1} trees ({n1} nodes) of the batch"}
         torch.cuda.synchronize()
         got = [o.cpu().numpy().astype(np.float64) for o in out]
         mask = slice(None) if kind != "mvrnn" else (w["left"] >= 0)
@@ -345,6 +374,8 @@ def main():
         "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
                       "t_splitk_reduce_ms": round(t_reduce_ms, 4),
                       "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),
+                      "nodes_per_s_device": round(n_nodes / (t_device_ms * 1e-3), 1),
+                      "aggregate_roofline_frac": agg,
                       "device_tflops": round(total_flops / (t_device_ms * 1e-3) / 1e12, 3),
                       "max_abs_err_vs_oracle": err},
     }

@@ -722,6 +722,10 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //  * slightly more tiles than compute units: split in two for balance.
   //  * latency-bound levels (n x K up to about 256 000) run cell_tiny_kernel: one launch, no k split;
   if ((long)a.n * n_slabs * kBK <= 256000) return Shape{6, 0};
+  //  * levels whose 32-node tiles all fit the chip at once (one workgroup per compute unit) run them
+  //    unsplit: 29-30 us at 286 / 399 nodes against 32-33 us for 64-node tiles split in two;
+  const long tiles32 = (long)((a.n + 31) / 32) * n_jt;
+  if (tiles32 <= 256 && G >= 4) return Shape{32, 1};
   Shape best{a.n > 128 ? 64 : 32, 1};
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
   int s = 1;

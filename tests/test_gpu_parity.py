@@ -546,3 +546,35 @@ def test_generic_runtime_birnn_program_with_phases(ctx, P):
     P.assert_close(hb[:R].cpu().numpy(), ohb, "hb")
     P.assert_close(y.cpu().numpy(), oy, "y", ref_floor=0.1)
     g.close()
+
+
+# ---------------------------------------------------------------- large batches, sampled parity
+def test_treelstm_large_batch_sampled_against_the_oracle(ctx, P):
+    """4096 trees (about 290 000 nodes, leaf level of about 147 000): every kernel variant at grid sizes far
+    beyond the benchmark configurations.  Trees are independent, so the oracle evaluates a sample of them."""
+    w = gen.treelstm_workload(4096, 10, 60, 256, 20000, "zipf1.1", seed=501, bias_scale=0.1)
+    h, c = P.run_treelstm(ctx, w)
+    assert not np.isnan(h).any() and not np.isnan(c).any()
+    check_tree_schedule(ctx, w)
+    off = w["tree_off"]
+    for first in (0, 2048, 4096 - 48):
+        b, e = int(off[first]), int(off[first + 48])
+        sub = dict(w, n_trees=48, tree_off=(off[first:first + 49] - off[first]).astype(np.int32), left=w["left"][b:e],
+                   right=w["right"][b:e], token=w["token"][b:e])
+        oh, oc = oracle.treelstm(sub, nthreads=NT)
+        P.assert_close(h[b:e], oh, f"h of trees {first}..")
+        P.assert_close(c[b:e], oc, f"c of trees {first}..")
+
+
+def test_lstm_many_sequences_sampled_against_the_oracle(ctx, P):
+    w = gen.lstm_workload(3000, 0, 60, 256, 128, seed=502, bias_scale=0.1)
+    h, c = P.run_lstm(ctx, w)
+    assert not np.isnan(h).any()
+    check_seq_schedule(ctx, w["len"])
+    off = np.concatenate([[0], np.cumsum(w["len"])])
+    for first in (0, 1500, 3000 - 40):
+        b, e = int(off[first]), int(off[first + 40])
+        sub = dict(w, n_seq=40, len=w["len"][first:first + 40], x=w["x"][b:e])
+        oh, oc = oracle.varlen_lstm(sub, nthreads=NT)
+        P.assert_close(h[b:e], oh, f"h of sequences {first}..")
+        P.assert_close(c[b:e], oc, f"c of sequences {first}..")

@@ -193,15 +193,22 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   int node = blockIdx.x;
   if (node >= a.n) return;
   // The first node's indices head the longest dependent chain (indices -> operands -> matrix
-  // instructions), so they are requested before anything else; the shared weights, which depend on
-  // nothing, follow and arrive while the indices and then the operands are on their way.
+  // instructions), so they are requested before anything else.  The shared weights depend on
+  // nothing and follow as a few wide, coalesced loads: vector memory instructions issue in order,
+  // so anything slow to issue here (W_M fetched element by element in its operand layout was: 32
+  // loads per lane, each touching 32 lines) would hold back the operand loads behind it.
   RawIdx raw = load_idx(node);
   RawIdx raw_next = load_idx(min(node + (int)gridDim.x, a.n - 1));
+  // both weight matrices: coalesced 16-byte loads, 8 per thread each
+  constexpr int kWVec = kD * 2 * kD / 4 / 256;
+  floatx4 wmst[kWVec], wst[kWVec];
 #pragma unroll
-  for (int s = 0; s < 32; ++s) wm[s] = a.WM[(mb * 32 + lcol) * (2 * kD) + kh * kD + 2 * s + lhi];
-  floatx4 wst[kD * 2 * kD / 4 / 256];  // W on its way to LDS (rows padded to 132 floats)
+  for (int k = 0; k < kWVec; ++k) {
+    const int i = tid + 256 * k;
+    wmst[k] = *reinterpret_cast<const floatx4*>(a.WM + (i >> 5) * (2 * kD) + (i & 31) * 4);
+  }
 #pragma unroll
-  for (int k = 0; k < kD * 2 * kD / 4 / 256; ++k) {
+  for (int k = 0; k < kWVec; ++k) {
     const int i = tid + 256 * k;
     wst[k] = *reinterpret_cast<const floatx4*>(a.W + (i >> 5) * (2 * kD) + (i & 31) * 4);
   }
@@ -209,8 +216,19 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   raw = raw_next;
   floatx2 x0[32], x1[32], vv0, vv1;
   load_node(cur, x0, vv0);
+  // W_M goes through the LDS buffer of W first: every wavefront picks its operand registers
+  // (row 32 mb + lcol, columns 64 kh + 2 s + lhi) out of it, then W takes the buffer over
 #pragma unroll
-  for (int k = 0; k < kD * 2 * kD / 4 / 256; ++k) {
+  for (int k = 0; k < kWVec; ++k) {
+    const int i = tid + 256 * k;
+    *reinterpret_cast<floatx4*>(&s_W[(i >> 5) * kWld + (i & 31) * 4]) = wmst[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < 32; ++s) wm[s] = s_W[(mb * 32 + lcol) * kWld + kh * kD + 2 * s + lhi];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kWVec; ++k) {
     const int i = tid + 256 * k;
     *reinterpret_cast<floatx4*>(&s_W[(i >> 5) * kWld + (i & 31) * 4]) = wst[k];
   }

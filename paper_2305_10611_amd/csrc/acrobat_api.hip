@@ -37,7 +37,7 @@ struct acrobat_ctx {
   // split-k workspace of the cell kernels (allocated at the first forward call)
   SplitKWorkspace splitk;
   bool gather_fusion = true;  // false: explicit gather launches (ablation)
-  int mvrnn_variant = 0;  // d == 64: which level kernel (tuning override ACROBAT_MVRNN_VARIANT)
+  int mvrnn_variant = 0;  // which MV-RNN level kernel (tuning override ACROBAT_MVRNN_VARIANT): 1 = streaming
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;

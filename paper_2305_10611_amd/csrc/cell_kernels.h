@@ -88,7 +88,7 @@ hipError_t launch_cell_level(CellEpilogue epi, const CellLevelArgs& a, hipStream
 struct MvrnnLevelArgs {
   int32_t n;
   int32_t d;        // 64 or 128
-  int32_t variant;  // d == 64 only: 0 = register-resident kernel, 1 = streaming kernel
+  int32_t variant;  // 0 = default kernel (d = 64: register-resident, d = 128: four workgroups per node), 1 = streaming kernel
   const int32_t* out_rows;  // [n]
   const int32_t* lsrc;      // [n] encoded left child source
   const int32_t* rsrc;      // [n]

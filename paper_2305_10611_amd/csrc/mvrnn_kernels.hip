@@ -1,4 +1,5 @@
-// MV-RNN level kernels for gfx950 (d = 64: register-resident kernel; d = 64 or 128: streaming kernel).
+// MV-RNN level kernels for gfx950 (d = 64: register-resident kernel, one workgroup per node; d = 128:
+// four workgroups per node; d = 64 or 128: streaming kernel, kept as a tuning alternative).
 //
 // Per node with left child (a, A) and right child (b, B):
 //   p = tanh(W [B a ; A b]),   P = W_M [A ; B]          (W, W_M: [64,128])
@@ -427,6 +428,195 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mvrnn_stream_kernel(cons
   }
 }
 
+// d = 128, four workgroups per node: workgroup (node, r) computes rows 32 r .. 32 r + 31 of P and
+// of p.  It needs a quarter of W_M and of W (32 KB each instead of 128 KB: loaded once per launch,
+// W_M into 64 registers per lane, W into LDS) and streams both child matrices whole; B a and A b
+// fall out of the streamed registers, so each of the four workgroups forms them for itself and no
+// workgroup waits for another.  A node occupies four compute units for a quarter of the time,
+// which is what the narrow levels near the roots need: one node per compute unit costs 14 us of
+// matrix instructions however few nodes the level has.
+//  * wavefront (ch, kh): output columns 64 ch .. 64 ch + 63 (even / odd columns in two
+//    accumulator blocks, as in the d = 64 kernel), k half kh (kh = 0: W_M[:, :128] times A,
+//    kh = 1: W_M[:, 128:] times B): 64 two-row steps of two `v_mfma_f32_32x32x2_f32` each;
+//  * the child matrix streams through a ring of 32 eight-byte load slots per lane that runs
+//    across node boundaries;
+//  * the workgroups of one node are 8 ids apart, 8 consecutive ids being spread over the 8 XCDs:
+//    the four readers of a child matrix share one L2.
+__global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs a) {
+  constexpr int D = 128, DD = D * D;
+  constexpr int S = 64;            // two-row steps over one child matrix
+  constexpr int RING = 32;         // load slots in flight
+  constexpr int WLD = 2 * D + 4;   // LDS row stride of the weight rows
+  constexpr int RB = 32;           // output rows per workgroup
+  __shared__ float s_vp[2][2 * D];        // [column half of the writer][B a | A b], partial sums
+  __shared__ float s_red[2][2][16 * 64];  // [column half][k half of the writer][8 rows x even/odd x lane]
+  __shared__ __attribute__((aligned(16))) float s_W[RB * WLD];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: base addresses stay in scalar registers)
+  const int ch = wave & 1, kh = wave >> 1;
+  const int lcol = lane & 31, lhi = lane >> 5;
+  const int r = (blockIdx.x >> 3) & 3;
+  int slot = 8 * (blockIdx.x >> 5) + (blockIdx.x & 7);
+  const int nslots = 8 * (gridDim.x >> 5);  // the grid is a multiple of 32 workgroups
+  if (slot >= a.n) return;
+
+  struct RawIdx { int ls, rs, orow; };
+  const int32_t* __restrict__ lsrc = a.lsrc;
+  const int32_t* __restrict__ rsrc = a.rsrc;
+  const int32_t* __restrict__ orows = a.out_rows;
+  auto load_idx = [&](int node) {
+    const int u = __builtin_amdgcn_readfirstlane(node);
+    RawIdx i;
+    i.ls = lsrc[u];
+    i.rs = rsrc[u];
+    i.orow = orows[u];
+    return i;
+  };
+  auto resolve = [&](const RawIdx& i) {
+    const int ms = __builtin_amdgcn_readfirstlane(kh ? i.rs : i.ls), vs = __builtin_amdgcn_readfirstlane(kh ? i.ls : i.rs);
+    NodeRef n;
+    n.mat = ms >= 0 ? a.mat + (size_t)ms * DD : a.mat_tab + (size_t)(-(ms + 1)) * DD;
+    n.vec = vs >= 0 ? a.vec + (size_t)vs * D : a.vec_tab + (size_t)(-(vs + 1)) * D;
+    n.orow = (size_t)i.orow;
+    return n;
+  };
+  floatx2 ring[RING];
+  auto load_step = [&](const NodeRef& n, int s, int k) {  // s, k: compile-time at every call site
+    ring[k] = *reinterpret_cast<const floatx2*>(n.mat + (size_t)(2 * s + lhi) * D + 64 * ch + 2 * lcol);
+  };
+  auto load_vec = [&](const NodeRef& n) { return *reinterpret_cast<const floatx2*>(n.vec + 64 * ch + 2 * lcol); };
+
+  // indices first (they head the dependent chain), then the weight rows as coalesced 16-byte loads
+  RawIdx raw = load_idx(slot);
+  RawIdx raw_next = load_idx(min(slot + nslots, a.n - 1));
+  constexpr int kWVec = RB * 2 * D / 4 / 256;  // 8
+  floatx4 wmst[kWVec], wst[kWVec];
+#pragma unroll
+  for (int k = 0; k < kWVec; ++k) {
+    const int i = tid + 256 * k;
+    wmst[k] = *reinterpret_cast<const floatx4*>(a.WM + (size_t)(RB * r + (i >> 6)) * (2 * D) + (i & 63) * 4);
+  }
+#pragma unroll
+  for (int k = 0; k < kWVec; ++k) {
+    const int i = tid + 256 * k;
+    wst[k] = *reinterpret_cast<const floatx4*>(a.W + (size_t)(RB * r + (i >> 6)) * (2 * D) + (i & 63) * 4);
+  }
+  NodeRef cur = resolve(raw);
+  raw = raw_next;
+#pragma unroll
+  for (int s = 0; s < RING; ++s) load_step(cur, s, s);
+  floatx2 vv = load_vec(cur);
+
+  // W_M's rows pass through the LDS buffer of W: each wavefront picks its operand registers
+  // (row 32 r + lcol, columns 128 kh + 2 s + lhi), then W's rows take the buffer over
+  float wm[S];
+#pragma unroll
+  for (int k = 0; k < kWVec; ++k) {
+    const int i = tid + 256 * k;
+    *reinterpret_cast<floatx4*>(&s_W[(i >> 6) * WLD + (i & 63) * 4]) = wmst[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < S; ++s) wm[s] = s_W[lcol * WLD + D * kh + 2 * s + lhi];
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < kWVec; ++k) {
+    const int i = tid + 256 * k;
+    *reinterpret_cast<floatx4*>(&s_W[(i >> 6) * WLD + (i & 63) * 4]) = wst[k];
+  }
+
+  const int pr = tid >> 3, pq = tid & 7;  // p = tanh(W v): output row of this workgroup, eighth of the columns
+  while (true) {
+    // (opaque to the optimiser: nothing derived from these indices may be computed, and so waited
+    // for, before this point - they were requested a whole node ago)
+    asm volatile("" : "+v"(raw.ls), "+v"(raw.rs), "+v"(raw.orow));
+    const NodeRef nxt = resolve(raw);
+    // (past the end the last node is read again: harmless, and the loop body stays free of branches)
+    raw = load_idx(min(slot + 2 * nslots, a.n - 1));
+
+    floatx16 acc_e, acc_o;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc_e[q] = acc_o[q] = 0.0f;
+    float vp[16];
+    floatx2 vv_next;
+#pragma unroll
+    for (int s = 0; s < S; ++s) {
+      const floatx2 x = ring[s % RING];
+      acc_e = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], x[0], acc_e, 0, 0, 0);
+      acc_o = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], x[1], acc_o, 0, 0, 0);
+      vp[s % 16] = x[0] * vv[0] + x[1] * vv[1];  // rows 2 s + lhi of (child matrix) x (other child's vector)
+      if (s % 16 == 15) {
+        // sum over the 32 lanes of the half wavefront: a reduce-scatter butterfly over four lane
+        // bits, after which lanes 2 i and 2 i + 1 hold the two halves of step 16 (s / 16) + i
+#pragma unroll
+        for (int half = 8, bit = 16; half >= 1; half >>= 1, bit >>= 1) {
+          const bool up = (lcol & bit) != 0;
+#pragma unroll
+          for (int i = 0; i < half; ++i) {
+            float lo = vp[i], hi = vp[i + half];
+            // (keeps these two selects of values: folded into one select of the array index, the
+            // whole butterfly turns into compare chains over a register array indexed per lane)
+            asm("" : "+v"(lo), "+v"(hi));
+            const float send = up ? lo : hi;
+            const float keep = up ? hi : lo;
+            vp[i] = keep + __shfl_xor(send, bit);
+          }
+        }
+        vp[0] += __shfl_xor(vp[0], 1);
+        if ((lcol & 1) == 0) s_vp[ch][(kh ? 0 : D) + 2 * (16 * (s / 16) + (lcol >> 1)) + lhi] = vp[0];
+      }
+      // the slot just consumed takes the step 32 ahead (of the next node from the middle on)
+      if (s + RING < S) load_step(cur, s + RING, s % RING);
+      else load_step(nxt, s + RING - S, s % RING);
+      if (s == S - RING) vv_next = load_vec(nxt);
+    }
+    // the two k halves exchange half of their accumulator rows through LDS (kh = 0 hands over
+    // rows q >= 8, kh = 1 rows q < 8), so every wavefront finishes and stores 8 rows
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      s_red[ch][kh][(2 * q) * 64 + lane] = kh ? acc_e[q] : acc_e[q + 8];
+      s_red[ch][kh][(2 * q + 1) * 64 + lane] = kh ? acc_o[q] : acc_o[q + 8];
+    }
+    __syncthreads();  // s_vp and s_red complete (and, for the first node, W's rows in s_W)
+
+    // ---- p = tanh(W [B a ; A b]), rows 32 r .. 32 r + 31
+    {
+      float t = 0.0f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const floatx4 wk4 = *reinterpret_cast<const floatx4*>(&s_W[pr * WLD + pq * 32 + k * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t += wk4[e] * (s_vp[0][pq * 32 + k * 4 + e] + s_vp[1][pq * 32 + k * 4 + e]);
+      }
+      t += __shfl_xor(t, 1);
+      t += __shfl_xor(t, 2);
+      t += __shfl_xor(t, 4);
+      if (pq == 0) a.vec[cur.orow * D + RB * r + pr] = fast_tanh(t);
+    }
+    {
+      float* P = a.mat + cur.orow * DD + (size_t)(RB * r) * D + 64 * ch + 2 * lcol;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int qq = kh ? q + 8 : q;  // accumulator row finished by this wavefront
+        const int i = (qq >> 2) * 8 + lhi * 4 + (qq & 3);
+        const float mine_e = kh ? acc_e[q + 8] : acc_e[q], mine_o = kh ? acc_o[q + 8] : acc_o[q];
+        const float other_e = s_red[ch][kh ^ 1][(2 * q) * 64 + lane];
+        const float other_o = s_red[ch][kh ^ 1][(2 * q + 1) * 64 + lane];
+        floatx2 o;  // always (k half 0) + (k half 1)
+        o[0] = kh ? other_e + mine_e : mine_e + other_e;
+        o[1] = kh ? other_o + mine_o : mine_o + other_o;
+        *reinterpret_cast<floatx2*>(P + i * D) = o;
+      }
+    }
+    slot += nslots;
+    if (slot >= a.n) break;
+    __syncthreads();  // s_vp / s_red are reused by the next node
+    cur = nxt;
+    vv = vv_next;
+  }
+}
+
 __global__ __launch_bounds__(256) void mvrnn_leaf_copy_kernel(int n, int d, const int32_t* out_rows,
                                                               const int32_t* token, const float* vec_tab,
                                                               const float* mat_tab, float* vec, float* mat) {
@@ -447,8 +637,12 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
   if (tile) *tile = 1;
   if (a.n <= 0) return hipSuccess;
   const int grid = a.n < 512 ? a.n : 512;  // two resident workgroups per compute unit, each strides over the level
-  if (a.d == 128) {
+  if (a.d == 128 && a.variant == 1) {
     launch_with_events(mvrnn_stream_kernel<128>, dim3(a.n < 256 ? a.n : 256), dim3(256), 0, stream, ev.start, ev.stop, a);
+  } else if (a.d == 128) {
+    // four workgroups per node slot, slots in groups of 8; 512 resident workgroups = 128 slots
+    const int slots = a.n < 128 ? (a.n + 7) / 8 * 8 : 128;
+    launch_with_events(mvrnn_rows_kernel, dim3(4 * slots), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else if (a.variant == 1) {
     launch_with_events(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else {

@@ -210,13 +210,14 @@ def test_mvrnn_d128_paper_batch(ctx, P):
     assert np.isnan(vec[~internal]).all()
 
 
-def test_mvrnn_d64_streaming_variant(P, monkeypatch):
-    """d = 64 has two level kernels; the tuning override selects the streaming one."""
+@pytest.mark.parametrize("d,trees", [(64, 40), (128, 24)])
+def test_mvrnn_streaming_variant(P, monkeypatch, d, trees):
+    """Both sizes have two level kernels; the tuning override selects the streaming one."""
     import paper_2305_10611_amd as A
     monkeypatch.setenv("ACROBAT_MVRNN_VARIANT", "1")
     c = A.Context(0)
     try:
-        w = gen.mvrnn_workload(40, 1, 30, 64, seed=43)
+        w = gen.mvrnn_workload(trees, 1, 30, d, seed=43)
         vec, mat = P.run_mvrnn(c, w)
         ov, om = oracle.mvrnn(w, nthreads=NT)
         P.assert_close(vec, ov, "vec")

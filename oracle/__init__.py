@@ -167,3 +167,55 @@ def phase_schedule(prod_lists, phase):
     batch_off = np.zeros(n + 1, np.int32)
     nb = lib.oracle_phase_schedule(C.c_int(n), _p(prod_off), _p(prod), _p(phase), _p(depth), _p(order), _p(batch_off))
     return depth, order, batch_off[: nb + 1].copy()
+
+
+def mix64(z: int) -> int:
+    lib = _load()
+    lib.oracle_mix64.restype = C.c_uint64
+    return int(lib.oracle_mix64(C.c_uint64(z & (2**64 - 1))))
+
+
+def drnn_decide(key: int, depth: int, k: int, is_root: bool, w: dict):
+    """(has_child, has_sibling, label) of the node at position key `key`."""
+    lib = _load()
+    out = np.zeros(3, np.int32)
+    lib.oracle_drnn_decide(C.c_uint64(key), C.c_int(depth), C.c_int(k), C.c_int(int(is_root)), C.c_int(int(w["max_depth"])),
+                           C.c_int(int(w["max_children"])), C.c_double(float(w["p_child"])), C.c_double(float(w["p_sibling"])),
+                           C.c_int(int(w["n_labels"])), _p(out))
+    return int(out[0]), int(out[1]), int(out[2])
+
+
+def drnn_keys(seed: int, inst: int, path=()):
+    """Position key of the node reached from the root of instance `inst` by the child indices in `path`."""
+    lib = _load()
+    lib.oracle_drnn_root_key.restype = C.c_uint64
+    lib.oracle_drnn_child_key.restype = C.c_uint64
+    key = lib.oracle_drnn_root_key(C.c_uint64(seed), C.c_int(inst))
+    for k in path:
+        key = lib.oracle_drnn_child_key(C.c_uint64(key), C.c_int(int(k)))
+    return int(key)
+
+
+def drnn(w: dict, cap: int | None = None):
+    """Generate the trees of a doubly-recurrent-network batch (fields as made by
+    workloads.drnn_workload).  Returns a dict: structure arrays inst, parent, prev, sib_index,
+    depth, label (int32, pre-order per instance) and states a, f, g [N,H], y [N,n_out] (f64)."""
+    lib = _load()
+    H, n_out, n_inst = int(w["H"]), int(w["n_out"]), int(w["n_inst"])
+    cap = int(cap if cap is not None else w["cap"])
+    names = ("x0", "emb", "Wa", "ba", "Wf", "bf", "Wp", "bp", "Wo", "bo")
+    arrs = [_f32(w[k]) for k in names]
+    ints = {k: np.full(cap, -7, np.int32) for k in ("inst", "parent", "prev", "sib_index", "depth", "label")}
+    st = {k: np.full((cap, H), np.nan) for k in ("a", "f", "g")}
+    y = np.full((cap, n_out), np.nan)
+    n = lib.oracle_drnn(C.c_int(n_inst), C.c_int(H), C.c_int(int(w["n_labels"])), C.c_int(n_out),
+                        *[_p(a) for a in arrs], C.c_uint64(int(w["seed_decisions"])), C.c_int(int(w["max_depth"])),
+                        C.c_int(int(w["max_children"])), C.c_double(float(w["p_child"])), C.c_double(float(w["p_sibling"])),
+                        C.c_int(cap), *[_p(ints[k]) for k in ("inst", "parent", "prev", "sib_index", "depth", "label")],
+                        _p(st["a"]), _p(st["f"]), _p(st["g"]), _p(y))
+    if n < 0:
+        raise ValueError("drnn: more than cap nodes")
+    out = {k: v[:n].copy() for k, v in ints.items()}
+    out.update({k: v[:n].copy() for k, v in st.items()})
+    out["y"] = y[:n].copy()
+    return out

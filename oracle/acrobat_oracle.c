@@ -49,6 +49,22 @@
  *     executed before any operator of the next phase, so depth is counted inside a phase: a
  *     node's depth is 0 if it has no producer in its own phase.
  *
+ *   doubly recurrent network generating a tree top-down (table 3 names the model and cites its
+ *   source; the recurrent unit is listing 1's cell, as for the other recurrent models).  Node i
+ *   of an instance, with parent p and previous sibling q:
+ *     a_i = s(W_a [a_p ; E[l_p]] + b_a)     ancestral state; the root takes a_p = the instance's
+ *                                           input vector and l_p = 0
+ *     f_i = s(W_f [f_q ; E[l_q]] + b_f)     fraternal state; a first child (and the root) takes
+ *                                           f_q = 0 and l_q = 0
+ *     g_i = s(W_p [a_i ; f_i] + b_p)        predictive state
+ *     y_i = W_o g_i + b_o                   scores: has children, has a next sibling, labels
+ *   Whether i gets children, whether a sibling follows it, and its label l_i are decisions taken
+ *   once y_i exists (tensor-dependent control flow, section 4.2).  As in the paper's evaluation
+ *   (section 7.2) they are emulated pseudo-randomly: a counter-based generator keyed by the
+ *   node's position (instance, path of child indices from the root), so the tree an instance
+ *   grows does not depend on the order in which nodes are evaluated.  The program is the plain
+ *   recursion: a node, then its children left to right, each with its whole subtree.
+ *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand
  * computed 1- and 3-node trees, closed forms, library LSTM cells, brute force).
  */
@@ -550,4 +566,113 @@ int oracle_phase_schedule(int n_nodes, const int32_t* prod_off, const int32_t* p
       if (pos > before) batch_off[++nb] = pos;
     }
   return nb;
+}
+
+/* ------------------------------------------------------------------------- */
+/* doubly recurrent network: top-down tree generation                         */
+/* ------------------------------------------------------------------------- */
+/* One step of the splitmix64 sequence from state z (its published first outputs for state 0
+ * are e220a8397b1dcdaf, 6e789e6aa1b965f4, 06c45d188009454f). */
+uint64_t oracle_mix64(uint64_t z) {
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+/* Position keys: root of instance s, k-th child of the node with key `parent`. */
+uint64_t oracle_drnn_root_key(uint64_t seed, int inst) { return oracle_mix64(seed ^ oracle_mix64((uint64_t)inst)); }
+uint64_t oracle_drnn_child_key(uint64_t parent, int k) { return oracle_mix64(parent + (uint64_t)k + 1u); }
+
+static double unit_interval(uint64_t bits) { return (double)(bits >> 11) * (1.0 / 9007199254740992.0); }
+
+/* The emulated decisions of the node at `key`: depth counts from 0 at the root, k is its index
+ * among its siblings.  out = {has_child, has_sibling, label}. */
+void oracle_drnn_decide(uint64_t key, int depth, int k, int is_root, int max_depth, int max_children,
+                        double p_child, double p_sibling, int n_labels, int32_t* out) {
+  out[0] = depth + 1 < max_depth && unit_interval(oracle_mix64(key ^ 1u)) < p_child;
+  out[1] = !is_root && k + 1 < max_children && unit_interval(oracle_mix64(key ^ 2u)) < p_sibling;
+  out[2] = (int32_t)(oracle_mix64(key ^ 3u) % (uint64_t)n_labels);
+}
+
+typedef struct {
+  int H, n_labels, n_out, max_depth, max_children, cap;
+  double p_child, p_sibling;
+  const float *emb, *Wa, *ba, *Wf, *bf, *Wp, *bp, *Wo, *bo;
+  int32_t *inst, *parent, *prev, *sib_index, *depth, *label;
+  double *a, *f, *g, *y;
+  int n; /* nodes so far */
+  double *in, *z;
+} dr_model;
+
+/* evaluates one node (parent / prev: node ids or -1) and returns its id, or -1 when out of room */
+static int drnn_node(dr_model* m, int inst, int parent, int prev, int k, int depth, const float* x0) {
+  if (m->n >= m->cap) return -1;
+  const int H = m->H, i = m->n++;
+  m->inst[i] = inst; m->parent[i] = parent; m->prev[i] = prev; m->sib_index[i] = k; m->depth[i] = depth;
+  double* in = m->in;
+  double* z = m->z;
+  /* ancestral */
+  for (int q = 0; q < H; ++q) in[q] = parent >= 0 ? m->a[(size_t)parent * H + q] : (double)x0[q];
+  const float* e = m->emb + (size_t)(parent >= 0 ? m->label[parent] : 0) * H;
+  for (int q = 0; q < H; ++q) in[H + q] = (double)e[q];
+  matvec(m->Wa, H, 2 * H, 2 * H, in, m->ba, z);
+  for (int q = 0; q < H; ++q) m->a[(size_t)i * H + q] = sigm(z[q]);
+  /* fraternal */
+  for (int q = 0; q < H; ++q) in[q] = prev >= 0 ? m->f[(size_t)prev * H + q] : 0.0;
+  e = m->emb + (size_t)(prev >= 0 ? m->label[prev] : 0) * H;
+  for (int q = 0; q < H; ++q) in[H + q] = (double)e[q];
+  matvec(m->Wf, H, 2 * H, 2 * H, in, m->bf, z);
+  for (int q = 0; q < H; ++q) m->f[(size_t)i * H + q] = sigm(z[q]);
+  /* predictive state and scores */
+  for (int q = 0; q < H; ++q) in[q] = m->a[(size_t)i * H + q];
+  for (int q = 0; q < H; ++q) in[H + q] = m->f[(size_t)i * H + q];
+  matvec(m->Wp, H, 2 * H, 2 * H, in, m->bp, z);
+  for (int q = 0; q < H; ++q) m->g[(size_t)i * H + q] = sigm(z[q]);
+  for (int q = 0; q < H; ++q) in[q] = m->g[(size_t)i * H + q];
+  matvec(m->Wo, m->n_out, H, H, in, m->bo, m->y + (size_t)i * m->n_out);
+  return i;
+}
+
+/* the children of `parent` (key pkey, depth pdepth), left to right, each followed by its subtree */
+static int drnn_children(dr_model* m, int inst, int parent, uint64_t pkey, int pdepth) {
+  int prev = -1;
+  for (int k = 0;; ++k) {
+    const uint64_t key = oracle_drnn_child_key(pkey, k);
+    const int i = drnn_node(m, inst, parent, prev, k, pdepth + 1, NULL);
+    if (i < 0) return -1;
+    int32_t d[3];
+    oracle_drnn_decide(key, pdepth + 1, k, 0, m->max_depth, m->max_children, m->p_child, m->p_sibling, m->n_labels, d);
+    m->label[i] = d[2];
+    if (d[0] && drnn_children(m, inst, i, key, pdepth + 1) < 0) return -1;
+    if (!d[1]) return 0;
+    prev = i;
+  }
+}
+
+/* Generates one tree per instance from x0 [n_inst, H].  Nodes are numbered in the order the
+ * recursion visits them (instance by instance, pre-order).  Arrays hold `cap` nodes; returns the
+ * number of nodes, or -1 if they do not fit. */
+int oracle_drnn(int n_inst, int H, int n_labels, int n_out, const float* x0, const float* emb,
+                const float* Wa, const float* ba, const float* Wf, const float* bf, const float* Wp,
+                const float* bp, const float* Wo, const float* bo, uint64_t seed, int max_depth,
+                int max_children, double p_child, double p_sibling, int cap, int32_t* inst,
+                int32_t* parent, int32_t* prev, int32_t* sib_index, int32_t* depth, int32_t* label,
+                double* a, double* f, double* g, double* y) {
+  dr_model m = {H, n_labels, n_out, max_depth, max_children, cap, p_child, p_sibling, emb, Wa, ba, Wf, bf, Wp, bp,
+                Wo, bo, inst, parent, prev, sib_index, depth, label, a, f, g, y, 0, NULL, NULL};
+  m.in = (double*)malloc(sizeof(double) * 2 * (size_t)H);
+  m.z = (double*)malloc(sizeof(double) * (size_t)(H > n_out ? H : n_out));
+  int rc = 0;
+  for (int s = 0; s < n_inst && rc == 0; ++s) {
+    const uint64_t key = oracle_drnn_root_key(seed, s);
+    const int i = drnn_node(&m, s, -1, -1, 0, 0, x0 + (size_t)s * H);
+    if (i < 0) { rc = -1; break; }
+    int32_t d[3];
+    oracle_drnn_decide(key, 0, 0, 1, max_depth, max_children, p_child, p_sibling, n_labels, d);
+    label[i] = d[2];
+    if (d[0]) rc = drnn_children(&m, s, i, key, 0);
+  }
+  free(m.in); free(m.z);
+  return rc < 0 ? -1 : m.n;
 }

@@ -259,6 +259,32 @@ def birnn_workload(n_seq, len_lo, len_hi, H, D, n_out, seed, bias_scale=0.1):
     return out
 
 
+def drnn_workload(n_inst, H, n_labels, n_out, seed, max_depth=6, max_children=4, p_child=0.7, p_sibling=0.6,
+                  bias_scale=0.1, cap=None):
+    """Doubly-recurrent-network batch: one input vector per instance, from which a tree is
+    generated top-down.  Parameters: label embeddings emb [n_labels, H]; ancestral, fraternal and
+    predictive cells Wa, Wf, Wp [H, 2H] with biases [H]; score layer Wo [n_out, H], bo [n_out].
+    The decisions (children, next sibling, label) are emulated pseudo-randomly from
+    seed_decisions; max_depth levels at most, max_children children per node at most.  `cap`
+    bounds the number of nodes the outputs can hold."""
+    rng = make_rng(seed)
+    bound = 1.0 / np.sqrt(2 * H)
+    out = dict(kind="drnn", n_inst=n_inst, H=H, n_labels=n_labels, n_out=n_out, seed=seed,
+               seed_decisions=(int(seed) * 0x9E3779B1 + 12345) % (1 << 63), max_depth=max_depth, max_children=max_children,
+               p_child=p_child, p_sibling=p_sibling, x0=uniform_f32((n_inst, H), 1.0, rng) * np.float32(0.5) + np.float32(0.5),
+               emb=normal_f32((n_labels, H), rng))
+    for p in ("a", "f", "p"):
+        out["W" + p] = uniform_f32((H, 2 * H), bound, rng)
+        out["b" + p] = uniform_f32((H,), bias_scale, rng)
+    out["Wo"] = uniform_f32((n_out, H), 1.0 / np.sqrt(H), rng)
+    out["bo"] = uniform_f32((n_out,), bias_scale, rng)
+    if cap is None:  # every instance at its largest: a full tree of max_children-ary branching
+        per = sum(max_children ** d for d in range(max_depth))
+        cap = min(n_inst * per, n_inst * 4096)
+    out["cap"] = int(cap)
+    return out
+
+
 def paper_grid_workload(model: str, size: str, batch: int, seed: int | None = None):
     """Mini-batches shaped like the paper's evaluation grid (section 7.1): model size small /
     large (hidden 256 / 512; MV-RNN 64 / 128) and batch size 8 / 64.  The treebank and the

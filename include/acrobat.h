@@ -182,7 +182,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
  *   LSTM_STEP      (c, h)[out_row] from gates (i, f, o, u) + zadd[out_row, 4H] and row arg0 of cprev_src
  *                  (cprev_src NULL: zero previous state)
  *   STORE_Z / STORE_Z1   zout[out_row, 4H] / zout[out_row, H] = z + bias   (four gates / one)
- *   RNN_STEP       h[out_row] = sigmoid(z + zadd[out_row, H])
+ *   RNN_STEP       h[out_row] = sigmoid(z + bias + zadd[out_row, H])   (zadd NULL: no such term)
  *   RELU_OUT       y[out_row*ldo + j] = relu(z + bias[j]) for j < n_cols (W has n_cols rows; H = n_cols
  *                  rounded up to a multiple of 32)
  * All pointers are device pointers and must stay valid until the run has finished on its stream. */
@@ -238,12 +238,98 @@ int acrobat_dfg_invoke(acrobat_dfg* g, int32_t op, int32_t phase, int32_t depth,
  * row tree_off[t] + j.  Same structure checks and error codes as acrobat_schedule_trees. */
 int acrobat_dfg_build_treelstm(acrobat_dfg* g, const acrobat_trees* trees, int32_t vocab,
                                int32_t op_leaf, int32_t op_internal);
-/* Executes all nodes on the stream (asynchronously unless profiling is on). */
+/* Adds a ghost operation (section 4.1, appendix B.4): a node that occupies `depth` and is never
+ * executed.  A program whose branches reach the same operator after different numbers of steps
+ * invokes ghosts on the shorter branch and names the ghost as the operator's producer, so the
+ * operator lands at one depth - in one batch - for every instance.  Checked against `prod` (a
+ * node id or -1) like any node; *node (may be NULL) receives its id.  Results never change. */
+int acrobat_dfg_ghost(acrobat_dfg* g, int32_t phase, int32_t depth, int32_t prod, int32_t* node);
+/* Executes all nodes on the stream (asynchronously unless profiling is on).  Buckets of one
+ * (phase, depth) are independent of each other (concurrent operators, section 4.1): two of them
+ * with the same shapes share a launch. */
 int acrobat_dfg_run(acrobat_dfg* g, void* hip_stream);
 /* Buckets of the last run or of acrobat_dfg_schedule (host arrays owned by the graph, valid until
  * its next call): bucket_off[n_buckets + 1] into order[], bucket_op[n_buckets]. */
 int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** bucket_off,
                          const int32_t** order, const int32_t** bucket_op);
+
+/* ---- tensor-dependent control flow: tree generation with a doubly recurrent network ------
+ * Section 4.2: a program whose control flow depends on tensor values cannot be run to its end
+ * before anything is evaluated.  Every instance therefore runs on a fiber (a cooperatively
+ * scheduled stack), and so does every part of an instance that can proceed on its own; all fibers
+ * advance until each waits for a value, then everything invoked so far is executed in batches
+ * through the generic runtime above, the values are copied to the host, and the fibers go on.
+ *
+ * The program shipped here is the doubly recurrent network of table 3 (top-down generation of a
+ * tree from one input vector per instance; the paper prints no equations, this is the cited
+ * model with listing 1's cell as the recurrent unit).  Node i with parent p, previous sibling q:
+ *   a_i = s(Wa [a_p ; emb[l_p]] + ba)   (root: a_p = the instance's row of d_x0, l_p = 0)
+ *   f_i = s(Wf [f_q ; emb[l_q]] + bf)   (first child and root: f_q = 0, l_q = 0)
+ *   g_i = s(Wp [a_i ; f_i] + bp)        y_i = Wo g_i + bo        s(t) = 1 / (1 + exp(-t))
+ * Whether i has children, whether a sibling follows, and its label l_i are decided once y_i is
+ * on the host.  As in the paper's evaluation (section 7.2, untrained parameters) the decisions
+ * are emulated: a counter-based generator (splitmix64 steps) keyed by the node's position -
+ * key(root of instance s) = mix(seed ^ mix(s)), key(child k) = mix(key(parent) + k + 1);
+ * children iff depth + 1 < max_depth and u(mix(key ^ 1)) < p_child; sibling iff not the root,
+ * k + 1 < max_children and u(mix(key ^ 2)) < p_sibling; label = mix(key ^ 3) mod n_labels;
+ * u(b) = (b >> 11) / 2^53 - so an instance grows the same tree in every mode.
+ *
+ * mode: ACROBAT_TDC_SEQUENTIAL - no fibers, instance after instance, one evaluation per node;
+ * ACROBAT_TDC_INSTANCE_FIBERS - one fiber per instance (batch parallelism only, each instance
+ * generated depth first); ACROBAT_TDC_FORK_JOIN - also one fiber per list of children (subtrees
+ * grow concurrently).  use_ghosts: a later sibling's ancestral cell is held back by a ghost
+ * operation to the depth of its fraternal cell, so each evaluation has one batch per operator.
+ *
+ * Nodes are numbered in the order of creation; node i's states are row i of d_a, d_f, d_g
+ * [max_nodes, H] and d_y [max_nodes, n_out] (device, written).  acrobat_drnn_trees: host arrays
+ * of max_nodes int32 each, caller-owned, any may be NULL: instance, parent and previous sibling
+ * (node ids, -1: none), index among the siblings, depth (root 0), label, and the evaluation
+ * (0, 1, ...) that computed the node.  ACROBAT_ENOMEM if more than max_nodes nodes would be
+ * generated (device rows written so far stay written).  The call synchronises the stream at every
+ * evaluation and returns when the last one has finished.  Requires H and n_out multiples of 32. */
+#define ACROBAT_TDC_SEQUENTIAL 0
+#define ACROBAT_TDC_INSTANCE_FIBERS 1
+#define ACROBAT_TDC_FORK_JOIN 2
+
+typedef struct {
+  uint64_t seed;
+  int32_t max_depth;    /* levels per tree, >= 1 */
+  int32_t max_children; /* children per node, >= 1 */
+  float p_child, p_sibling;
+} acrobat_drnn_decisions;
+
+typedef struct { /* device pointers */
+  int32_t H, n_labels, n_out;
+  const float* emb;                  /* [n_labels, H] */
+  const float* Wa; const float* ba;  /* [H, 2H], [H] or NULL */
+  const float* Wf; const float* bf;
+  const float* Wp; const float* bp;
+  const float* Wo; const float* bo;  /* [n_out, H], [n_out] or NULL */
+} acrobat_drnn_params;
+
+typedef struct {
+  int32_t* inst; int32_t* parent; int32_t* prev; int32_t* sib_index; int32_t* depth; int32_t* label;
+  int32_t* round;
+} acrobat_drnn_trees;
+
+typedef struct {
+  int32_t n_nodes;
+  int32_t n_rounds;  /* evaluations */
+  int32_t n_buckets; /* batches (one per (depth, operator) and evaluation) */
+  int32_t n_fibers;  /* fibers started */
+  int32_t n_ghosts;  /* ghost operations invoked */
+} acrobat_drnn_stats;
+
+int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0,
+                         const acrobat_drnn_params* params, const acrobat_drnn_decisions* decisions,
+                         int32_t mode, int32_t use_ghosts, int32_t max_nodes, acrobat_drnn_trees* trees,
+                         float* d_a, float* d_f, float* d_g, float* d_y, acrobat_drnn_stats* stats,
+                         void* hip_stream);
+/* The same program, fibers and batching without any tensor work (host only, no context): the
+ * structure of the generated trees and the evaluation each node would belong to. */
+int acrobat_drnn_schedule(int32_t n_inst, int32_t n_labels, const acrobat_drnn_decisions* decisions,
+                          int32_t mode, int32_t use_ghosts, int32_t max_nodes,
+                          acrobat_drnn_trees* trees, acrobat_drnn_stats* stats);
 
 /* ---- introspection --------------------------------------------------------------------
  * Schedule built by the last forward call on this context (host arrays owned by the context,

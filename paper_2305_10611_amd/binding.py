@@ -46,6 +46,30 @@ class acrobat_op_desc(C.Structure):
 
 
 EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z, EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1 = range(7)
+TDC_SEQUENTIAL, TDC_INSTANCE_FIBERS, TDC_FORK_JOIN = 0, 1, 2
+
+
+class acrobat_drnn_decisions(C.Structure):
+    _fields_ = [("seed", C.c_uint64), ("max_depth", C.c_int32), ("max_children", C.c_int32),
+                ("p_child", C.c_float), ("p_sibling", C.c_float)]
+
+
+class acrobat_drnn_params(C.Structure):
+    _fields_ = [("H", C.c_int32), ("n_labels", C.c_int32), ("n_out", C.c_int32), ("emb", C.c_void_p),
+                ("Wa", C.c_void_p), ("ba", C.c_void_p), ("Wf", C.c_void_p), ("bf", C.c_void_p),
+                ("Wp", C.c_void_p), ("bp", C.c_void_p), ("Wo", C.c_void_p), ("bo", C.c_void_p)]
+
+
+DRNN_TREE_FIELDS = ("inst", "parent", "prev", "sib_index", "depth", "label", "round")
+
+
+class acrobat_drnn_trees(C.Structure):
+    _fields_ = [(k, C.c_void_p) for k in DRNN_TREE_FIELDS]
+
+
+class acrobat_drnn_stats(C.Structure):
+    _fields_ = [("n_nodes", C.c_int32), ("n_rounds", C.c_int32), ("n_buckets", C.c_int32), ("n_fibers", C.c_int32),
+                ("n_ghosts", C.c_int32)]
 
 EXPORTS = (
     "acrobat_create", "acrobat_destroy", "acrobat_last_error", "acrobat_strerror",
@@ -54,7 +78,8 @@ EXPORTS = (
     "acrobat_set_profiling", "acrobat_last_profile", "acrobat_schedule_birnn", "acrobat_birnn_forward",
     "acrobat_set_gather_fusion",
     "acrobat_dfg_create", "acrobat_dfg_destroy", "acrobat_dfg_last_error", "acrobat_dfg_register_op", "acrobat_dfg_clear", "acrobat_dfg_invoke",
-    "acrobat_dfg_build_treelstm", "acrobat_dfg_run", "acrobat_dfg_schedule",
+    "acrobat_dfg_build_treelstm", "acrobat_dfg_run", "acrobat_dfg_schedule", "acrobat_dfg_ghost",
+    "acrobat_drnn_forward", "acrobat_drnn_schedule",
 )
 
 
@@ -87,6 +112,12 @@ def _load():
     lib.acrobat_dfg_clear.argtypes = [vp]
     lib.acrobat_dfg_invoke.argtypes = [vp] + [i32] * 8 + [C.POINTER(i32)]
     lib.acrobat_dfg_build_treelstm.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32, i32]
+    lib.acrobat_dfg_ghost.argtypes = [vp, i32, i32, i32, C.POINTER(i32)]
+    lib.acrobat_drnn_forward.argtypes = ([vp, i32, vp, C.POINTER(acrobat_drnn_params), C.POINTER(acrobat_drnn_decisions),
+                                          i32, i32, i32, C.POINTER(acrobat_drnn_trees)] + [vp] * 4 +
+                                         [C.POINTER(acrobat_drnn_stats), vp])
+    lib.acrobat_drnn_schedule.argtypes = [i32, i32, C.POINTER(acrobat_drnn_decisions), i32, i32, i32,
+                                          C.POINTER(acrobat_drnn_trees), C.POINTER(acrobat_drnn_stats)]
     lib.acrobat_dfg_run.argtypes = [vp, vp]
     lib.acrobat_dfg_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
     lib.acrobat_last_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
@@ -167,6 +198,32 @@ def acrobat_schedule_birnn(lens):
     return rc, level_off[: n_levels.value + 1].copy(), level_codes
 
 
+def _drnn_decisions(w: dict):
+    return acrobat_drnn_decisions(int(w["seed_decisions"]), int(w["max_depth"]), int(w["max_children"]),
+                                  float(w["p_child"]), float(w["p_sibling"]))
+
+
+def _drnn_outputs(max_nodes: int):
+    arrs = {k: np.full(max(max_nodes, 1), -7, np.int32) for k in DRNN_TREE_FIELDS}
+    return arrs, acrobat_drnn_trees(*(_hp(arrs[k]) for k in DRNN_TREE_FIELDS))
+
+
+def _drnn_result(arrs, stats):
+    n = stats.n_nodes
+    trees = {k: v[:n].copy() for k, v in arrs.items()}
+    return trees, {k: getattr(stats, k) for k, _ in acrobat_drnn_stats._fields_}
+
+
+def acrobat_drnn_schedule(w: dict, mode=TDC_FORK_JOIN, use_ghosts=True, max_nodes=None):
+    """Host only. -> (rc, trees dict of int32 arrays, stats dict)"""
+    max_nodes = int(w["cap"] if max_nodes is None else max_nodes)
+    arrs, out = _drnn_outputs(max_nodes)
+    dec, stats = _drnn_decisions(w), acrobat_drnn_stats()
+    rc = lib.acrobat_drnn_schedule(int(w["n_inst"]), int(w["n_labels"]), C.byref(dec), mode, int(bool(use_ghosts)),
+                                   max_nodes, C.byref(out), C.byref(stats))
+    return (rc,) + _drnn_result(arrs, stats)
+
+
 class Dfg:
     """Owns one acrobat_dfg of a Context.  Methods mirror the C entry points and return the C return code."""
 
@@ -213,6 +270,12 @@ class Dfg:
         """-> (rc, node id)"""
         node = C.c_int32(-1)
         rc = lib.acrobat_dfg_invoke(self._g, op, phase, depth, out_row, arg0, arg1, prod0, prod1, C.byref(node))
+        return rc, node.value
+
+    def acrobat_dfg_ghost(self, phase, depth, prod=-1):
+        """-> (rc, node id)"""
+        node = C.c_int32(-1)
+        rc = lib.acrobat_dfg_ghost(self._g, phase, depth, prod, C.byref(node))
         return rc, node.value
 
     def acrobat_dfg_build_treelstm(self, trees: dict, vocab, op_leaf, op_internal) -> int:
@@ -285,6 +348,20 @@ class Context:
         b = acrobat_rnn_dir(*(_dp(t) for t in bwd))
         return lib.acrobat_birnn_forward(self._h, int(lens.size), _hp(lens), H, D, n_out, _dp(x), C.byref(f),
                                          C.byref(b), _dp(Cw), _dp(cb), _dp(hf), _dp(hb), _dp(y), stream)
+
+    def acrobat_drnn_forward(self, w: dict, x0, params: dict, a, f, g, y, mode=TDC_FORK_JOIN, use_ghosts=True,
+                             max_nodes=None, stream=0):
+        """params: device tensors emb, Wa, ba, Wf, bf, Wp, bp, Wo, bo (biases may be None); a, f, g
+        [max_nodes, H] and y [max_nodes, n_out] are written.  -> (rc, trees dict, stats dict)"""
+        max_nodes = int(w["cap"] if max_nodes is None else max_nodes)
+        arrs, out = _drnn_outputs(max_nodes)
+        dec, stats = _drnn_decisions(w), acrobat_drnn_stats()
+        p = acrobat_drnn_params(int(w["H"]), int(w["n_labels"]), int(w["n_out"]),
+                                *(_dp(params.get(k)) for k in ("emb", "Wa", "ba", "Wf", "bf", "Wp", "bp", "Wo", "bo")))
+        rc = lib.acrobat_drnn_forward(self._h, int(w["n_inst"]), _dp(x0), C.byref(p), C.byref(dec), mode,
+                                      int(bool(use_ghosts)), max_nodes, C.byref(out), _dp(a), _dp(f), _dp(g), _dp(y),
+                                      C.byref(stats), stream)
+        return (rc,) + _drnn_result(arrs, stats)
 
     def acrobat_last_schedule(self):
         n_levels, po, pn = C.c_int32(0), C.c_void_p(), C.c_void_p()

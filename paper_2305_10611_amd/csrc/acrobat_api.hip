@@ -16,6 +16,7 @@
 #include "cell_kernels.h"
 #include "dfg_runtime.h"
 #include "scheduler.h"
+#include "tdc_runtime.h"
 
 using namespace acrobat;
 
@@ -38,6 +39,11 @@ struct acrobat_ctx {
   SplitKWorkspace splitk;
   bool gather_fusion = true;  // false: explicit gather launches (ablation)
   int mvrnn_variant = 0;  // which MV-RNN level kernel (tuning override ACROBAT_MVRNN_VARIANT): 1 = streaming
+  // tree generation: a zero row (previous-sibling state of a first child) and the scores on the host
+  float* d_zero_row = nullptr;
+  size_t zero_row_cap = 0;  // in floats
+  float* h_scores = nullptr;
+  size_t scores_cap = 0;  // in floats
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
@@ -191,12 +197,77 @@ struct LaunchTimer {
     if (rc_ != ACROBAT_OK) return rc_;   \
   } while (0)
 
+// Executes the graph nodes `first`, `first + 1`, ... bucket by bucket on the stream.  Buckets of one
+// (phase, depth) do not depend on each other; two neighbours with the same shapes share a launch.
+int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream);
+
 int begin_call(acrobat_ctx* ctx) {
   if (!ctx) return ACROBAT_EINVAL;
   ctx->err.clear();
   ctx->records.clear();
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   return ACROBAT_OK;
+}
+
+int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream) {
+  acrobat_ctx* ctx = g->ctx;
+  g->graph.bucket(g->buckets, first);
+  const std::vector<DfgNode>& nodes = g->graph.nodes();
+  const size_t n = g->buckets.order.size();
+  if (n == 0) return ACROBAT_OK;
+  TRY(reserve_splitk(ctx, stream));
+  // by bucket position: row written | first operand row | second operand row
+  TRY(reserve_indices(ctx, 3 * n, stream));
+  int32_t* st = ctx->h_stage;
+  for (size_t p = 0; p < n; ++p) {
+    const DfgNode& x = nodes[g->buckets.order[p]];
+    st[p] = x.out_row;
+    st[n + p] = x.arg0;
+    st[2 * n + p] = x.arg1;
+  }
+  TRY(upload_indices(ctx, 3 * n, stream));
+  static const CellEpilogue kEpi[] = {EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z,
+                                      EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1};
+  auto level_args = [&](size_t b) {
+    const int32_t off = g->buckets.off[b], cnt = g->buckets.off[b + 1] - off;
+    const acrobat_op_desc& d = g->graph.ops()[g->buckets.op[b]];
+    CellLevelArgs a{};
+    a.n = cnt; a.H = d.H; a.nseg = d.nseg; a.kseg = d.kseg;
+    a.src0 = d.src0; a.ld0 = d.ld0; a.idx0 = ctx->d_idx + n + off;
+    a.src1 = d.src1; a.ld1 = d.ld1; a.idx1 = ctx->d_idx + 2 * n + off;
+    a.W = d.W; a.ldw = d.ldw; a.bias = d.bias;
+    a.out_rows = ctx->d_idx + off;
+    a.h = d.h; a.c = d.c; a.cprev_src = d.cprev_src; a.zadd = d.zadd; a.zout = d.zout;
+    a.n_cols = d.n_cols; a.y = d.y; a.ldo = d.ldo;
+    return a;
+  };
+  auto same_batch_shape = [&](size_t b0, size_t b1) {
+    const DfgNode& x = nodes[g->buckets.order[g->buckets.off[b0]]];
+    const DfgNode& y = nodes[g->buckets.order[g->buckets.off[b1]]];
+    if (x.phase != y.phase || x.depth != y.depth) return false;
+    const acrobat_op_desc& d0 = g->graph.ops()[g->buckets.op[b0]];
+    const acrobat_op_desc& d1 = g->graph.ops()[g->buckets.op[b1]];
+    return d0.epilogue == d1.epilogue && d0.H == d1.H && d0.nseg == d1.nseg && d0.kseg == d1.kseg &&
+           d0.epilogue != ACROBAT_EPI_RELU_OUT;
+  };
+  LaunchTimer timer{ctx, stream};
+  const size_t n_buckets = g->buckets.op.size();
+  for (size_t b = 0; b < n_buckets; ++b) {
+    const CellLevelArgs a = level_args(b);
+    const acrobat_op_desc& d = g->graph.ops()[g->buckets.op[b]];
+    if (b + 1 < n_buckets && same_batch_shape(b, b + 1)) {
+      const CellLevelArgs a1 = level_args(b + 1);
+      TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, a.n + a1.n));
+      HIP_TRY(ctx, launch_cell_level_pair(kEpi[d.epilogue], a, a1, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
+      TRY(timer.end());
+      ++b;
+      continue;
+    }
+    TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, a.n));
+    HIP_TRY(ctx, launch_cell_level(kEpi[d.epilogue], a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
+    TRY(timer.end());
+  }
+  return timer.finish();
 }
 
 }  // namespace
@@ -240,6 +311,8 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+  if (ctx->d_zero_row) (void)hipFree(ctx->d_zero_row);
+  if (ctx->h_scores) (void)hipHostFree(ctx->h_scores);
   if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   delete ctx;
@@ -727,6 +800,16 @@ int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** buc
   return ACROBAT_OK;
 }
 
+int acrobat_dfg_ghost(acrobat_dfg* g, int32_t phase, int32_t depth, int32_t prod, int32_t* node) {
+  if (!g) return ACROBAT_EINVAL;
+  try {
+    return g->graph.ghost(phase, depth, prod, node, g->err);
+  } catch (...) {
+    g->err = "host allocation failed";
+    return ACROBAT_ENOMEM;
+  }
+}
+
 int acrobat_dfg_run(acrobat_dfg* g, void* hip_stream) {
   if (!g) return ACROBAT_EINVAL;
   acrobat_ctx* ctx = g->ctx;
@@ -736,41 +819,151 @@ int acrobat_dfg_run(acrobat_dfg* g, void* hip_stream) {
   }
   try {
     TRY(begin_call(ctx));
-    g->graph.bucket(g->buckets);
-    const std::vector<DfgNode>& nodes = g->graph.nodes();
-    const size_t n = nodes.size();
-    if (n == 0) return ACROBAT_OK;
+    return run_graph(g, 0, static_cast<hipStream_t>(hip_stream));
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
+}
+
+namespace {
+
+const float kNoTensor[1] = {0.0f};  // stands in for tensors that a schedule-only run never touches
+
+// registers the six operators of the tree-generation program
+int drnn_register_ops(Dfg& graph, const acrobat_drnn_params& p, int32_t n_inst, int32_t max_nodes, const float* d_x0,
+                      const float* d_zero, float* d_a, float* d_f, float* d_g, float* d_y, DrnnOps& ops, std::string& err) {
+  const int32_t rows = max_nodes > 0 ? max_nodes : 1;
+  acrobat_op_desc cell{};
+  cell.epilogue = ACROBAT_EPI_RNN_STEP;
+  cell.H = p.H; cell.nseg = 2; cell.kseg = p.H;
+  cell.ld0 = p.H; cell.ld1 = p.H; cell.ldw = 2 * p.H;
+  cell.out_rows = rows;
+  auto reg = [&](const float* src0, int32_t rows0, const float* src1, int32_t rows1, const float* W, const float* b,
+                 float* h, int32_t* id) {
+    acrobat_op_desc d = cell;
+    d.src0 = src0; d.src0_rows = rows0; d.src1 = src1; d.src1_rows = rows1; d.W = W; d.bias = b; d.h = h;
+    return graph.register_op(d, id, err);
+  };
+  TRY(reg(d_x0, n_inst > 0 ? n_inst : 1, p.emb, p.n_labels, p.Wa, p.ba, d_a, &ops.a_root));
+  TRY(reg(d_a, rows, p.emb, p.n_labels, p.Wa, p.ba, d_a, &ops.a));
+  TRY(reg(d_zero, 1, p.emb, p.n_labels, p.Wf, p.bf, d_f, &ops.f_first));
+  TRY(reg(d_f, rows, p.emb, p.n_labels, p.Wf, p.bf, d_f, &ops.f));
+  TRY(reg(d_a, rows, d_f, rows, p.Wp, p.bp, d_g, &ops.p));
+  acrobat_op_desc o{};
+  o.epilogue = ACROBAT_EPI_STORE_Z1;
+  o.H = p.n_out; o.nseg = 1; o.kseg = p.H;
+  o.src0 = d_g; o.ld0 = p.H; o.src0_rows = rows;
+  o.W = p.Wo; o.ldw = p.H; o.bias = p.bo; o.zout = d_y; o.out_rows = rows;
+  return graph.register_op(o, &ops.o, err);
+}
+
+void drnn_copy_out(const DrnnTrees& t, const DrnnStats& st, acrobat_drnn_trees* out, acrobat_drnn_stats* stats) {
+  const size_t n = t.inst.size();
+  if (out) {
+    auto cp = [n](int32_t* dst, const std::vector<int32_t>& src) {
+      if (dst && n) std::memcpy(dst, src.data(), n * sizeof(int32_t));
+    };
+    cp(out->inst, t.inst); cp(out->parent, t.parent); cp(out->prev, t.prev); cp(out->sib_index, t.sib_index);
+    cp(out->depth, t.depth); cp(out->label, t.label); cp(out->round, t.round);
+  }
+  if (stats) *stats = {(int32_t)n, st.n_rounds, st.n_buckets, st.n_fibers, st.n_ghosts};
+}
+
+}  // namespace
+
+int acrobat_drnn_schedule(int32_t n_inst, int32_t n_labels, const acrobat_drnn_decisions* decisions, int32_t mode,
+                          int32_t use_ghosts, int32_t max_nodes, acrobat_drnn_trees* trees, acrobat_drnn_stats* stats) {
+  if (!decisions || n_inst < 0 || max_nodes < 0 || n_labels < 1) return ACROBAT_EINVAL;
+  try {
+    Dfg graph;
+    DfgBuckets buckets;
+    std::string err;
+    acrobat_drnn_params p{};
+    p.H = 32; p.n_labels = n_labels; p.n_out = 32;
+    p.emb = p.Wa = p.Wf = p.Wp = p.Wo = kNoTensor;
+    float* none = const_cast<float*>(kNoTensor);
+    DrnnOps ops;
+    TRY(drnn_register_ops(graph, p, n_inst, max_nodes, kNoTensor, kNoTensor, none, none, none, none, ops, err));
+    DrnnTrees t;
+    DrnnStats st;
+    const DrnnEvaluate evaluate = [&](size_t first, int32_t, int32_t, int32_t* n_buckets) {
+      graph.bucket(buckets, first);
+      *n_buckets = (int32_t)buckets.op.size();
+      return ACROBAT_OK;
+    };
+    const DrnnScores scores = [](int32_t) { return (const float*)nullptr; };
+    const int rc = drnn_generate(graph, ops, n_inst, n_labels, *decisions, mode, use_ghosts != 0, max_nodes, evaluate, scores,
+                                 t, st, err);
+    drnn_copy_out(t, st, trees, stats);
+    return rc;
+  } catch (...) {
+    return ACROBAT_ENOMEM;
+  }
+}
+
+int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, const acrobat_drnn_params* params,
+                         const acrobat_drnn_decisions* decisions, int32_t mode, int32_t use_ghosts, int32_t max_nodes,
+                         acrobat_drnn_trees* trees, float* d_a, float* d_f, float* d_g, float* d_y,
+                         acrobat_drnn_stats* stats, void* hip_stream) {
+  if (!ctx) return ACROBAT_EINVAL;
+  try {
+    TRY(begin_call(ctx));
+    if (stats) *stats = acrobat_drnn_stats{};
+    if (!params || !decisions || n_inst < 0 || max_nodes < 0) return fail(ctx, ACROBAT_EINVAL, "null argument or negative size");
+    const acrobat_drnn_params& p = *params;
+    if (p.H <= 0 || p.H % 32 || p.n_out <= 0 || p.n_out % 32 || p.n_labels < 1)
+      return fail(ctx, ACROBAT_EINVAL, "H and n_out must be positive multiples of 32, n_labels >= 1");
+    if (!p.emb || !p.Wa || !p.Wf || !p.Wp || !p.Wo) return fail(ctx, ACROBAT_EINVAL, "null parameter pointer");
+    if (n_inst == 0) return ACROBAT_OK;
+    if (!d_x0 || !d_a || !d_f || !d_g || !d_y) return fail(ctx, ACROBAT_EINVAL, "null tensor pointer");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    TRY(reserve_splitk(ctx, stream));
-    // by bucket position: row written | first operand row | second operand row
-    TRY(reserve_indices(ctx, 3 * n, stream));
-    int32_t* st = ctx->h_stage;
-    for (size_t p = 0; p < n; ++p) {
-      const DfgNode& x = nodes[g->buckets.order[p]];
-      st[p] = x.out_row;
-      st[n + p] = x.arg0;
-      st[2 * n + p] = x.arg1;
+    if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "a call that waits for tensor values cannot be captured");
+    if ((size_t)p.H > ctx->zero_row_cap) {
+      if (ctx->d_zero_row) HIP_TRY(ctx, hipFree(ctx->d_zero_row));
+      ctx->d_zero_row = nullptr;
+      ctx->zero_row_cap = 0;
+      HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_zero_row), (size_t)p.H * sizeof(float)));
+      ctx->zero_row_cap = (size_t)p.H;
+      HIP_TRY(ctx, hipMemset(ctx->d_zero_row, 0, (size_t)p.H * sizeof(float)));
     }
-    TRY(upload_indices(ctx, 3 * n, stream));
-    LaunchTimer timer{ctx, stream};
-    for (size_t b = 0; b < g->buckets.op.size(); ++b) {
-      const int32_t off = g->buckets.off[b], cnt = g->buckets.off[b + 1] - off;
-      const acrobat_op_desc& d = g->graph.ops()[g->buckets.op[b]];
-      CellLevelArgs a{};
-      a.n = cnt; a.H = d.H; a.nseg = d.nseg; a.kseg = d.kseg;
-      a.src0 = d.src0; a.ld0 = d.ld0; a.idx0 = ctx->d_idx + n + off;
-      a.src1 = d.src1; a.ld1 = d.ld1; a.idx1 = ctx->d_idx + 2 * n + off;
-      a.W = d.W; a.ldw = d.ldw; a.bias = d.bias;
-      a.out_rows = ctx->d_idx + off;
-      a.h = d.h; a.c = d.c; a.cprev_src = d.cprev_src; a.zadd = d.zadd; a.zout = d.zout;
-      a.n_cols = d.n_cols; a.y = d.y; a.ldo = d.ldo;
-      static const CellEpilogue kEpi[] = {EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z,
-                                          EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1};
-      TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, cnt));
-      HIP_TRY(ctx, launch_cell_level(kEpi[d.epilogue], a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
-      TRY(timer.end());
+    const size_t need = (size_t)max_nodes * (size_t)p.n_out;
+    if (need > ctx->scores_cap) {
+      if (ctx->h_scores) HIP_TRY(ctx, hipHostFree(ctx->h_scores));
+      ctx->h_scores = nullptr;
+      ctx->scores_cap = 0;
+      HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_scores), need * sizeof(float), hipHostMallocDefault));
+      ctx->scores_cap = need;
     }
-    return timer.finish();
+    acrobat_dfg g;
+    g.ctx = ctx;
+    DrnnOps ops;
+    {
+      const int rc = drnn_register_ops(g.graph, p, n_inst, max_nodes, d_x0, ctx->d_zero_row, d_a, d_f, d_g, d_y, ops, g.err);
+      if (rc != ACROBAT_OK) return fail(ctx, rc, g.err);
+    }
+    // one evaluation: the batches of everything invoked since the last one, then the new nodes'
+    // scores to the host - the values the program is waiting for
+    const size_t n_out = (size_t)p.n_out;
+    const DrnnEvaluate evaluate = [&](size_t first, int32_t first_node, int32_t n_nodes, int32_t* n_buckets) {
+      TRY(run_graph(&g, first, stream));
+      *n_buckets = (int32_t)g.buckets.op.size();
+      if (n_nodes > 0)
+        HIP_TRY(ctx, hipMemcpyAsync(ctx->h_scores + (size_t)first_node * n_out, d_y + (size_t)first_node * n_out,
+                                    (size_t)n_nodes * n_out * sizeof(float), hipMemcpyDeviceToHost, stream));
+      HIP_TRY(ctx, hipStreamSynchronize(stream));
+      return ACROBAT_OK;
+    };
+    const DrnnScores scores = [&](int32_t node) { return (const float*)(ctx->h_scores + (size_t)node * n_out); };
+    DrnnTrees t;
+    DrnnStats st;
+    std::string err;
+    const int rc = drnn_generate(g.graph, ops, n_inst, p.n_labels, *decisions, mode, use_ghosts != 0, max_nodes, evaluate,
+                                 scores, t, st, err);
+    drnn_copy_out(t, st, trees, stats);
+    if (rc != ACROBAT_OK) return ctx->err.empty() ? fail(ctx, rc, err) : rc;
+    return ACROBAT_OK;
   } catch (const std::bad_alloc&) {
     return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
   } catch (...) {

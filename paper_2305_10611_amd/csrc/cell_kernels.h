@@ -34,7 +34,7 @@ struct CellLevelArgs {
   const int32_t* out_rows;      // [n] arena row written by each node, null = node index
   float* h; float* c;           // arena [rows, H]
   const float* cprev_src;       // tree/LSTM: c rows gathered with idx0 (and idx1); null = zero state
-  const float* zadd;            // LSTM / RNN step: [rows, G*H] pre-activations added to z (row = out row)
+  const float* zadd;            // LSTM / RNN step: [rows, G*H] pre-activations added to z (row = out row); RNN step: may be null
   float* zout;                  // STORE_Z: [rows, G*H]
   // RELU_OUT only: the weight matrix has n_cols <= H rows (H = n_cols rounded up to 32 sizes the
   // grid), y[row * ldo + j] is written for j < n_cols.  0 elsewhere (= H).

@@ -140,7 +140,7 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
   } else if constexpr (EPI == EPI_RNN_STEP) {
     float zx[NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) zx[v] = a.zadd[orow[v] * (size_t)H + j];
+    for (int v = 0; v < NV; ++v) zx[v] = a.zadd ? a.zadd[orow[v] * (size_t)H + j] : 0.0f;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
       if (!live[v]) continue;

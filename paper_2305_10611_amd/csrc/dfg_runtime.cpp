@@ -1,6 +1,7 @@
 #include "dfg_runtime.h"
 
 #include <algorithm>
+#include <initializer_list>
 #include <limits>
 
 namespace acrobat {
@@ -17,7 +18,7 @@ int Dfg::register_op(const acrobat_op_desc& d, int32_t* id, std::string& err) {
   if ((e == ACROBAT_EPI_TREE_LEAF || e == ACROBAT_EPI_TREE_INTERNAL || e == ACROBAT_EPI_LSTM_STEP) && (!d.h || !d.c)) { err = "h or c arena is null"; return ACROBAT_EINVAL; }
   if (e == ACROBAT_EPI_TREE_INTERNAL && (!d.cprev_src || d.nseg != 2)) { err = "internal tree cell: two segments and cprev_src"; return ACROBAT_EINVAL; }
   if (e == ACROBAT_EPI_LSTM_STEP && (!d.zadd || (d.cprev_src && d.src0_rows <= 0))) { err = "LSTM step: zadd is null"; return ACROBAT_EINVAL; }
-  if (e == ACROBAT_EPI_RNN_STEP && (!d.h || !d.zadd)) { err = "RNN step: h or zadd is null"; return ACROBAT_EINVAL; }
+  if (e == ACROBAT_EPI_RNN_STEP && !d.h) { err = "RNN step: h is null"; return ACROBAT_EINVAL; }
   if ((e == ACROBAT_EPI_STORE_Z || e == ACROBAT_EPI_STORE_Z1) && !d.zout) { err = "zout is null"; return ACROBAT_EINVAL; }
   const int gates = d.epilogue == ACROBAT_EPI_TREE_LEAF || d.epilogue == ACROBAT_EPI_TREE_INTERNAL ? 5
                     : d.epilogue == ACROBAT_EPI_LSTM_STEP || d.epilogue == ACROBAT_EPI_STORE_Z ? 4 : 1;
@@ -27,18 +28,10 @@ int Dfg::register_op(const acrobat_op_desc& d, int32_t* id, std::string& err) {
   return ACROBAT_OK;
 }
 
-int Dfg::invoke(int32_t op, int32_t phase, int32_t depth, int32_t out_row, int32_t arg0, int32_t arg1, int32_t prod0,
-                int32_t prod1, int32_t* node, std::string& err) {
-  if (op < 0 || op >= (int32_t)ops_.size()) { err = "unknown op id"; return ACROBAT_EINVAL; }
+int Dfg::check_depth(int32_t phase, int32_t depth, std::initializer_list<int32_t> producers, std::string& err) const {
   if (phase < 0 || depth < 0 || phase > 4096 || depth > (1 << 24)) { err = "phase or depth out of range"; return ACROBAT_EINVAL; }
-  if (out_row < 0 || arg0 < 0 || arg1 < 0) { err = "negative row"; return ACROBAT_EINVAL; }
-  {
-    const acrobat_op_desc& d = ops_[op];
-    const bool uses0 = d.nseg > 0 || d.cprev_src, uses1 = d.nseg > 1;
-    if (out_row >= d.out_rows || (uses0 && arg0 >= d.src0_rows) || (uses1 && arg1 >= d.src1_rows)) { err = "row out of range"; return ACROBAT_EINVAL; }
-  }
   if (nodes_.size() >= (size_t)std::numeric_limits<int32_t>::max()) { err = "too many nodes"; return ACROBAT_EINVAL; }
-  for (int32_t p : {prod0, prod1}) {
+  for (int32_t p : producers) {
     if (p < 0) continue;
     if (p >= (int32_t)nodes_.size()) { err = "producer is not an earlier node"; return ACROBAT_ESTRUCT; }
     const DfgNode& q = nodes_[p];
@@ -48,23 +41,50 @@ int Dfg::invoke(int32_t op, int32_t phase, int32_t depth, int32_t out_row, int32
       return ACROBAT_ESTRUCT;
     }
   }
-  if (nodes_.empty()) max_phase_ = max_depth_ = 0;
-  max_phase_ = std::max(max_phase_, phase);
-  max_depth_ = std::max(max_depth_, depth);
-  nodes_.push_back({op, phase, depth, out_row, arg0, arg1});
-  if (node) *node = (int32_t)nodes_.size() - 1;
   return ACROBAT_OK;
 }
 
-void Dfg::bucket(DfgBuckets& out) const {
+void Dfg::push(const DfgNode& n, int32_t* node) {
+  if (nodes_.empty()) max_phase_ = max_depth_ = 0;
+  max_phase_ = std::max(max_phase_, n.phase);
+  max_depth_ = std::max(max_depth_, n.depth);
+  nodes_.push_back(n);
+  if (node) *node = (int32_t)nodes_.size() - 1;
+}
+
+int Dfg::invoke(int32_t op, int32_t phase, int32_t depth, int32_t out_row, int32_t arg0, int32_t arg1, int32_t prod0,
+                int32_t prod1, int32_t* node, std::string& err) {
+  if (op < 0 || op >= (int32_t)ops_.size()) { err = "unknown op id"; return ACROBAT_EINVAL; }
+  if (out_row < 0 || arg0 < 0 || arg1 < 0) { err = "negative row"; return ACROBAT_EINVAL; }
+  {
+    const acrobat_op_desc& d = ops_[op];
+    const bool uses0 = d.nseg > 0 || d.cprev_src, uses1 = d.nseg > 1;
+    if (out_row >= d.out_rows || (uses0 && arg0 >= d.src0_rows) || (uses1 && arg1 >= d.src1_rows)) { err = "row out of range"; return ACROBAT_EINVAL; }
+  }
+  const int rc = check_depth(phase, depth, {prod0, prod1}, err);
+  if (rc != ACROBAT_OK) return rc;
+  push({op, phase, depth, out_row, arg0, arg1}, node);
+  return ACROBAT_OK;
+}
+
+int Dfg::ghost(int32_t phase, int32_t depth, int32_t prod, int32_t* node, std::string& err) {
+  const int rc = check_depth(phase, depth, {prod}, err);
+  if (rc != ACROBAT_OK) return rc;
+  push({-1, phase, depth, 0, 0, 0}, node);
+  return ACROBAT_OK;
+}
+
+void Dfg::bucket(DfgBuckets& out, size_t first) const {
   out.off.assign(1, 0);
   out.order.clear();
   out.op.clear();
-  const size_t n = nodes_.size();
+  std::vector<int32_t> a, b;
+  for (size_t i = first; i < nodes_.size(); ++i)
+    if (nodes_[i].op >= 0) a.push_back((int32_t)i);
+  const size_t n = a.size();
   if (n == 0) return;
+  b.resize(n);
   // three stable counting passes, least significant key first: op, depth, phase
-  std::vector<int32_t> a(n), b(n);
-  for (size_t i = 0; i < n; ++i) a[i] = (int32_t)i;
   auto pass = [&](int32_t n_keys, auto key) {
     std::vector<int32_t> cnt((size_t)n_keys + 1, 0);
     for (size_t i = 0; i < n; ++i) ++cnt[(size_t)key(nodes_[a[i]]) + 1];
@@ -72,8 +92,11 @@ void Dfg::bucket(DfgBuckets& out) const {
     for (size_t i = 0; i < n; ++i) b[(size_t)cnt[key(nodes_[a[i]])]++] = a[i];
     a.swap(b);
   };
+  // (depths are counted from the smallest one present: late evaluations of a growing graph hold few, deep nodes)
+  int32_t dmin = max_depth_;
+  for (size_t i = 0; i < n; ++i) dmin = std::min(dmin, nodes_[a[i]].depth);
   pass((int32_t)ops_.size(), [](const DfgNode& x) { return x.op; });
-  pass(max_depth_ + 1, [](const DfgNode& x) { return x.depth; });
+  pass(max_depth_ - dmin + 1, [dmin](const DfgNode& x) { return x.depth - dmin; });
   pass(max_phase_ + 1, [](const DfgNode& x) { return x.phase; });
   out.order = a;
   for (size_t i = 0; i < n; ++i) {

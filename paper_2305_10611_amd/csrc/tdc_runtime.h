@@ -1,0 +1,59 @@
+// Programs with tensor-dependent control flow on the batched dataflow-graph runtime (section 4.2),
+// and the one such program this library ships: top-down tree generation with a doubly recurrent
+// network (table 3; evaluated in section 7.2 with emulated decisions).
+//
+// The unbatched program is ordinary recursive code that calls invoke() for every operator, with
+// the depth it computes inline, and await() wherever it needs a tensor's value to decide how to
+// go on.  Each instance runs on a fiber, and (mode FORK_JOIN) so does every list of children,
+// since the subtrees of a node can be generated independently of each other.  When every fiber
+// waits, the operators invoked since the last evaluation are executed in batches and the fibers
+// go on.  Host code only: the evaluation itself is a callback.
+#pragma once
+#include <cstdint>
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "acrobat.h"
+#include "dfg_runtime.h"
+
+namespace acrobat {
+
+struct DrnnOps {  // ids of the ops registered in the graph
+  int32_t a_root, a, f_first, f, p, o;
+};
+
+struct DrnnTrees {  // one entry per generated node, in the order of creation
+  std::vector<int32_t> inst, parent, prev, sib_index, depth, label, round;
+};
+
+struct DrnnStats {
+  int32_t n_rounds = 0;    // evaluations
+  int32_t n_buckets = 0;   // batches over all evaluations
+  int32_t n_fibers = 0;    // fibers started
+  int32_t n_ghosts = 0;    // ghost operations invoked
+};
+
+// The decisions of one node, emulated from its position (the paper's evaluation replaces the
+// tensor-dependent decisions by pseudo-random ones since its models are untrained, section 7.2);
+// `y` are the node's scores on the host - the value the program had to wait for.
+struct DrnnDecision { bool has_child, has_sibling; int32_t label; };
+uint64_t drnn_root_key(uint64_t seed, int32_t inst);
+uint64_t drnn_child_key(uint64_t parent_key, int32_t k);
+DrnnDecision drnn_decide(const acrobat_drnn_decisions& d, int32_t n_labels, uint64_t key, int32_t depth, int32_t k,
+                         bool is_root, const float* y);
+
+// evaluate(first_dfg_node, first_tree_node, n_tree_nodes, &n_buckets): executes the graph nodes from
+// first_dfg_node on and makes the scores of the tree nodes [first_tree_node, + n_tree_nodes)
+// readable through scores(node) (may return null when nothing is computed at all).
+using DrnnEvaluate = std::function<int(size_t, int32_t, int32_t, int32_t*)>;
+using DrnnScores = std::function<const float*(int32_t)>;
+
+// Runs the generation program for n_inst instances.  mode: ACROBAT_TDC_*.  use_ghosts: align the
+// ancestral cell of a later sibling with its fraternal cell by a ghost operation.  Fails with
+// ACROBAT_ENOMEM when more than max_nodes nodes would be generated.
+int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, const acrobat_drnn_decisions& dec,
+                  int32_t mode, bool use_ghosts, int32_t max_nodes, const DrnnEvaluate& evaluate,
+                  const DrnnScores& scores, DrnnTrees& out, DrnnStats& stats, std::string& err);
+
+}  // namespace acrobat

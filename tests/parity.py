@@ -67,6 +67,50 @@ def run_birnn(ctx, w, use_bias=True):
     return hf[:R].cpu().numpy(), hb[:R].cpu().numpy(), y[:R].cpu().numpy()
 
 
+def run_drnn(ctx, w, mode=2, use_ghosts=True, use_bias=True, max_nodes=None, check=True):
+    """-> (rc, trees, stats, (a, f, g, y) as numpy arrays of the generated nodes)"""
+    H, n_out = int(w["H"]), int(w["n_out"])
+    cap = int(w["cap"] if max_nodes is None else max_nodes)
+    t = {k: dev(np.asarray(w[k], np.float32)) for k in ("x0", "emb", "Wa", "ba", "Wf", "bf", "Wp", "bp", "Wo", "bo")}
+    params = {k: (t[k] if use_bias or not k.startswith("b") else None) for k in t if k != "x0"}
+    a, f, g = (nan_filled(max(cap, 1), H) for _ in range(3))
+    y = nan_filled(max(cap, 1), n_out)
+    rc, trees, stats = ctx.acrobat_drnn_forward(w, t["x0"], params, a, f, g, y, mode, use_ghosts, cap, stream_handle())
+    if check:
+        ctx.check(rc)
+    torch.cuda.synchronize()
+    n = stats["n_nodes"]
+    return rc, trees, stats, tuple(v[:n].cpu().numpy() for v in (a, f, g, y))
+
+
+def tree_paths(t):
+    """(instance, child indices from the root) of every node of a generated forest."""
+    out = []
+    for i in range(len(t["inst"])):
+        p, j = [], i
+        while t["parent"][j] >= 0:
+            p.append(int(t["sib_index"][j]))
+            j = int(t["parent"][j])
+        out.append((int(t["inst"][i]), tuple(reversed(p))))
+    return out
+
+
+def match_trees(got, want):
+    """Checks that two forests hold the same positions with the same label, depth and relatives;
+    returns, for every node of `got`, the index of the node of `want` at the same position."""
+    pg, pw = tree_paths(got), tree_paths(want)
+    assert len(set(pg)) == len(pg) == len(pw) and set(pg) == set(pw), "different sets of tree positions"
+    at = {p: i for i, p in enumerate(pw)}
+    for i, p in enumerate(pg):
+        j = at[p]
+        assert got["label"][i] == want["label"][j] and got["depth"][i] == want["depth"][j]
+        assert got["sib_index"][i] == want["sib_index"][j]
+        for rel in ("parent", "prev"):
+            a, b = int(got[rel][i]), int(want[rel][j])
+            assert (a < 0) == (b < 0) and (a < 0 or pg[a] == pw[b])
+    return np.array([at[p] for p in pg], np.int64)
+
+
 def errors(got, want, ref_floor=1e-30):
     """(max abs error, max over rows of max-norm relative error).  ref_floor bounds a row's
     reference norm from below: rows a ReLU clamps to exactly zero have no relative error."""

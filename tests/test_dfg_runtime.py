@@ -125,7 +125,13 @@ def test_malformed_ops_and_trees_are_rejected():
     assert g.acrobat_dfg_register_op_desc(bad)[0] == A.EINVAL
     bad = fake_op(B.EPI_TREE_INTERNAL, nseg=1)
     assert g.acrobat_dfg_register_op_desc(bad)[0] == A.EINVAL
+    ok = fake_op(B.EPI_RNN_STEP)
+    ok.zadd = None  # an RNN step without a hoisted input term
+    assert g.acrobat_dfg_register_op_desc(ok)[0] == A.OK
     bad = fake_op(B.EPI_RNN_STEP)
+    bad.h = None
+    assert g.acrobat_dfg_register_op_desc(bad)[0] == A.EINVAL
+    bad = fake_op(B.EPI_LSTM_STEP)
     bad.zadd = None
     assert g.acrobat_dfg_register_op_desc(bad)[0] == A.EINVAL
     _, leaf = g.acrobat_dfg_register_op_desc(fake_op(B.EPI_TREE_LEAF))

@@ -579,3 +579,130 @@ def test_lstm_many_sequences_sampled_against_the_oracle(ctx, P):
         oh, oc = oracle.varlen_lstm(sub, nthreads=NT)
         P.assert_close(h[b:e], oh, f"h of sequences {first}..")
         P.assert_close(c[b:e], oc, f"c of sequences {first}..")
+
+
+DRNN_KINDS = {4: "cell", 6: "scores"}
+
+
+def check_drnn(P, w, trees, states, want):
+    at = P.match_trees(trees, want)
+    for name, got in zip(("a", "f", "g", "y"), states):
+        assert got.shape[0] == len(at)
+        P.assert_close(got, want[name][at], "drnn " + name)
+
+
+@pytest.mark.parametrize("mode", (0, 1, 2))
+@pytest.mark.parametrize("ghosts", (False, True))
+def test_drnn_matches_the_oracle_in_every_mode(ctx, P, mode, ghosts):
+    """Tensor-dependent control flow (section 4.2): the same trees and states whether nodes are
+    evaluated one by one, one per instance at a time, or with every subtree on its own fiber."""
+    w = gen.drnn_workload(11, 64, 9, 32, seed=91, max_depth=5, max_children=4, bias_scale=0.3)
+    want = oracle.drnn(w)
+    rc, trees, st, states = P.run_drnn(ctx, w, mode, ghosts)
+    assert st["n_nodes"] == len(want["inst"]) and st["n_ghosts"] == (int((trees["sib_index"] > 0).sum()) if ghosts else 0)
+    check_drnn(P, w, trees, states, want)
+    # the host-only run of the program takes the same decisions, in the same evaluations
+    import paper_2305_10611_amd as A
+    rc2, trees2, st2 = A.acrobat_drnn_schedule(w, mode, ghosts)
+    assert rc2 == A.OK and st2 == st
+    for k in trees:
+        assert np.array_equal(trees[k], trees2[k])
+
+
+def test_drnn_paper_batch_without_bias_and_profile(ctx, P):
+    from workloads.generators import paper_grid_workload
+    w = paper_grid_workload("drnn", "small", 64)
+    want = oracle.drnn(w)
+    n = len(want["inst"])
+    ctx.acrobat_set_profiling(True)
+    try:
+        rc, trees, st, states = P.run_drnn(ctx, w)
+        recs = ctx.acrobat_last_profile()
+    finally:
+        ctx.acrobat_set_profiling(False)
+    check_drnn(P, w, trees, states, want)
+    assert st["n_rounds"] == trees["round"].max() + 1
+    assert all(r[0] == 12 and r[3] > 0 for r in recs)  # generic-runtime batches, each with a measured time
+    # rows: every node passes through the ancestral, fraternal and predictive cell and the score layer
+    assert sum(r[2] for r in recs) == 4 * n
+    # the ancestral and the later-sibling fraternal batch of an evaluation share one launch
+    assert len(recs) < st["n_buckets"]
+    w0 = dict(w, ba=np.zeros_like(w["ba"]), bf=np.zeros_like(w["bf"]), bp=np.zeros_like(w["bp"]), bo=np.zeros_like(w["bo"]))
+    rc, trees0, st0, states0 = P.run_drnn(ctx, w, use_bias=False)
+    check_drnn(P, w0, trees0, states0, oracle.drnn(w0))
+
+
+def test_drnn_large_hidden_size_and_wide_levels(ctx, P):
+    w = gen.drnn_workload(48, 512, 16, 32, seed=92, max_depth=5, max_children=4)
+    want = oracle.drnn(w)
+    rc, trees, st, states = P.run_drnn(ctx, w)
+    check_drnn(P, w, trees, states, want)
+
+
+def test_drnn_degenerate_and_error_cases(ctx, P):
+    import paper_2305_10611_amd as A
+    w = gen.drnn_workload(6, 64, 3, 32, seed=93)
+    want = oracle.drnn(w)
+    n = len(want["inst"])
+    rc, trees, st, states = P.run_drnn(ctx, w, max_nodes=n)  # exactly enough room
+    check_drnn(P, w, trees, states, want)
+    rc, trees, st, _ = P.run_drnn(ctx, w, max_nodes=n - 1, check=False)
+    assert rc == A.ENOMEM and "max_nodes" in ctx.acrobat_last_error() and st["n_nodes"] == n - 1
+    rc, trees, st, states = P.run_drnn(ctx, dict(w, n_inst=0, x0=w["x0"][:0]), check=False)
+    assert rc == A.OK and st["n_nodes"] == 0
+    w1 = dict(w, max_depth=1)  # roots only: one evaluation
+    rc, trees, st, states = P.run_drnn(ctx, w1)
+    assert st["n_nodes"] == 6 and st["n_rounds"] == 1
+    check_drnn(P, w1, trees, states, oracle.drnn(w1))
+    for bad in (dict(w, max_children=0), dict(w, p_sibling=-0.5), dict(w, max_depth=0)):
+        assert P.run_drnn(ctx, bad, check=False)[0] == A.EINVAL
+    # sizes the kernels do not take are refused before anything is touched
+    t = {k: P.dev(np.asarray(w[k], np.float32)) for k in ("x0", "emb", "Wa", "Wf", "Wp", "Wo")}
+    buf = P.nan_filled(n, 64)
+    for bad in (dict(w, H=48), dict(w, n_out=20), dict(w, n_labels=0)):
+        rc, _, _ = ctx.acrobat_drnn_forward(bad, t["x0"], t, buf, buf, buf, buf, max_nodes=n)
+        assert rc == A.EINVAL
+    rc, _, _ = ctx.acrobat_drnn_forward(w, t["x0"], dict(t, Wp=None), buf, buf, buf, buf, max_nodes=n)
+    assert rc == A.EINVAL and "null" in ctx.acrobat_last_error()
+
+
+def test_ghost_operations_do_not_change_results(ctx, P):
+    """Two ops in a row for half of the rows, the second op alone for the rest (a conditional): with a
+    ghost on the short branch the second op runs as one batch; the values are those without it."""
+    import torch
+    import paper_2305_10611_amd as A
+    from paper_2305_10611_amd import binding as B
+    H, n = 64, 40
+    rng = gen.make_rng(94)
+    x = P.dev(gen.uniform_f32((n, H), 1.0, rng))
+    W1, W2 = (P.dev(gen.uniform_f32((H, H), 0.125, rng)) for _ in range(2))
+    outs = []
+    for use_ghost in (False, True):
+        h1, h2 = P.nan_filled(n, H), P.nan_filled(n, H)
+        g = A.Dfg(ctx)
+        rc, op1 = g.acrobat_dfg_register_op(B.EPI_RNN_STEP, H, nseg=1, kseg=H, src0=x, ld0=H, W=W1, ldw=H, h=h1, src0_rows=n, out_rows=n)
+        assert rc == A.OK
+        # rows that skipped op1 read x, the others read h1: two ops with the same weights
+        rc, op2a = g.acrobat_dfg_register_op(B.EPI_RNN_STEP, H, nseg=1, kseg=H, src0=h1, ld0=H, W=W2, ldw=H, h=h2, src0_rows=n, out_rows=n)
+        rc, op2b = g.acrobat_dfg_register_op(B.EPI_RNN_STEP, H, nseg=1, kseg=H, src0=x, ld0=H, W=W2, ldw=H, h=h2, src0_rows=n, out_rows=n)
+        for i in range(n):
+            if i % 2 == 0:
+                rc, a = g.acrobat_dfg_invoke(op1, 0, 0, i, i)
+                assert g.acrobat_dfg_invoke(op2a, 0, 1, i, i, 0, a)[0] == A.OK
+            elif use_ghost:
+                rc, gh = g.acrobat_dfg_ghost(0, 0)
+                assert g.acrobat_dfg_invoke(op2b, 0, 1, i, i, 0, gh)[0] == A.OK
+            else:
+                assert g.acrobat_dfg_invoke(op2b, 0, 0, i, i)[0] == A.OK
+        off, order, bops = g.acrobat_dfg_schedule()
+        assert len(bops) == 3 and len(order) == n + n // 2
+        ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+        torch.cuda.synchronize()
+        outs.append(h2.cpu().numpy())
+        g.close()
+    assert not np.isnan(outs[0]).any() and np.array_equal(outs[0], outs[1])
+    sig = lambda z: 1.0 / (1.0 + np.exp(-z))
+    xd = x.cpu().numpy().astype(np.float64)
+    h1d = sig(xd @ W1.cpu().numpy().astype(np.float64).T)
+    src = np.where((np.arange(n) % 2 == 0)[:, None], h1d, xd)
+    P.assert_close(outs[1], sig(src @ W2.cpu().numpy().astype(np.float64).T), "h2")

@@ -290,15 +290,19 @@ def paper_grid_workload(model: str, size: str, batch: int, seed: int | None = No
     large (hidden 256 / 512; MV-RNN 64 / 128) and batch size 8 / 64.  The treebank and the
     sentence-pair corpus themselves are not available: sentence lengths are drawn uniformly from
     [5, 35] (mean 20), trees are random binary splits; parameters are random, as in the paper.
-    The BiRNN's output layer has 16 units."""
-    assert size in ("small", "large") and model in ("treelstm", "mvrnn", "birnn")
-    s = (SEED_BASE + 100 + {"treelstm": 0, "mvrnn": 10, "birnn": 20}[model] + (0 if size == "small" else 5) + batch
+    The BiRNN's output layer has 16 units.  The tree generator (no dataset in the paper either: random
+    input vectors) has 30 labels, 2 + 30 scores per node, and grows trees of at most 6 levels and 4
+    children per node (about 25 nodes on average, a few above 100)."""
+    assert size in ("small", "large") and model in ("treelstm", "mvrnn", "birnn", "drnn")
+    s = (SEED_BASE + 100 + {"treelstm": 0, "mvrnn": 10, "birnn": 20, "drnn": 30}[model] + (0 if size == "small" else 5) + batch
          if seed is None else seed)
     if model == "treelstm":
         w = treelstm_workload(batch, 5, 35, 256 if size == "small" else 512, 20000, "zipf1.1", s)
     elif model == "birnn":
         H = 256 if size == "small" else 512
         w = birnn_workload(batch, 5, 35, H, H, 16, s)
+    elif model == "drnn":
+        w = drnn_workload(batch, 256 if size == "small" else 512, 30, 32, s)
     else:
         w = mvrnn_workload(batch, 5, 35, 64 if size == "small" else 128, s)
     w["name"] = f"paper_{model}_{size}_bs{batch}"

@@ -40,6 +40,78 @@ MEASURED_TRAFFIC = {
 }
 
 
+def bench_drnn(args, w, ctx, dev, stream):
+    """Tree generation with tensor-dependent control flow (paper grid only): one step = the whole
+    mini-batch, every evaluation with its launches, score copy and synchronisation.  The number
+    of nodes is an outcome of the run; nothing about the trees is known beforehand."""
+    import torch
+    import paper_2305_10611_amd as A
+    H, n_out, cap = int(w["H"]), int(w["n_out"]), int(w["cap"])
+    t = {k: dev(np.asarray(w[k], np.float32)) for k in ("x0", "emb", "Wa", "ba", "Wf", "bf", "Wp", "bp", "Wo", "bo")}
+    a, f, g = (torch.empty(cap, H, device="cuda") for _ in range(3))
+    y = torch.empty(cap, n_out, device="cuda")
+
+    def run(mode, ghosts):
+        rc, trees, st = ctx.acrobat_drnn_forward(w, t["x0"], t, a, f, g, y, mode, ghosts, cap, stream)
+        ctx.check(rc)
+        return trees, st
+
+    def timed(mode, ghosts, steps, warmup):
+        for _ in range(warmup):
+            run(mode, ghosts)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            trees, st = run(mode, ghosts)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, trees, st
+
+    ms, trees, st = timed(A.TDC_FORK_JOIN, True, args.steps, args.warmup)
+    n = st["n_nodes"]
+    few = max(3, args.steps // 10)
+    modes = {"fork_join_fibers_with_ghosts": {"ms_per_step": round(ms, 4), **st}}
+    for name, mode, ghosts in (("fork_join_fibers_without_ghosts", A.TDC_FORK_JOIN, False),
+                               ("one_fiber_per_instance", A.TDC_INSTANCE_FIBERS, True),
+                               ("no_fibers", A.TDC_SEQUENTIAL, True)):
+        m, _, s2 = timed(mode, ghosts, few if mode != A.TDC_SEQUENTIAL else 2, 1)
+        modes[name] = {"ms_per_step": round(m, 4), **s2}
+    th = []
+    for _ in range(10):
+        h0 = time.perf_counter()
+        A.acrobat_drnn_schedule(w, A.TDC_FORK_JOIN, True, cap)
+        th.append(time.perf_counter() - h0)
+    ctx.acrobat_set_profiling(True)
+    run(A.TDC_FORK_JOIN, True)
+    recs = ctx.acrobat_last_profile()
+    ctx.acrobat_set_profiling(False)
+    t_device_ms = sum(r[3] for r in recs)
+    flops = n * (3 * 2.0 * 2 * H * H + 2.0 * H * n_out)
+    if args.verbose:
+        for r in recs:
+            print(f"batch {r[1]:>3} n {r[2]:>5} tile {r[4]:>3} {r[3] * 1e3:>8.2f} us", file=sys.stderr)
+    cpu_baseline, err = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        from tests.parity import match_trees
+        c0 = time.perf_counter()
+        ref = oracle.drnn(w)
+        c1 = time.perf_counter()
+        cpu_baseline = {"value": round(n / (c1 - c0), 1), "unit": "nodes/s", "cores": 1, "kind": "oracle",
+                        "sample": f"the whole {w['name']} batch ({n} nodes), one thread"}
+        at = match_trees(trees, ref)
+        err = max(float(np.abs(v[:n].cpu().numpy().astype(np.float64) - ref[k][at]).max())
+                  for k, v in (("a", a), ("f", f), ("g", g), ("y", y)))
+    line = {"metric": "node evals/sec", "value": round(n / (ms * 1e-3), 1), "unit": "nodes/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": w["name"], "index": -1, "nodes": n, "seed": int(w["seed"])},
+            "roofline": None, "cpu_baseline": cpu_baseline, "tensor_dependent_control_flow": modes,
+            "breakdown": {"t_host_program_ms": round(float(np.median(th)) * 1e3, 4), "t_device_ms": round(t_device_ms, 4),
+                          "launches": len(recs), "evaluations": st["n_rounds"], "algorithmic_gflop": round(flops / 1e9, 3),
+                          "max_abs_err_vs_oracle": err}}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,6 +168,10 @@ def main():
     ctx = A.Context(0)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     stream = torch.cuda.current_stream().cuda_stream
+    if kind == "drnn":
+        bench_drnn(args, w, ctx, dev, stream)
+        ctx.close()
+        return
     n_nodes = int(w["n_nodes"])
 
     if kind == "treelstm":

@@ -204,7 +204,7 @@ def _drnn_decisions(w: dict):
 
 
 def _drnn_outputs(max_nodes: int):
-    arrs = {k: np.full(max(max_nodes, 1), -7, np.int32) for k in DRNN_TREE_FIELDS}
+    arrs = {k: np.empty(max(max_nodes, 1), np.int32) for k in DRNN_TREE_FIELDS}
     return arrs, acrobat_drnn_trees(*(_hp(arrs[k]) for k in DRNN_TREE_FIELDS))
 
 

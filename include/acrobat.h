@@ -280,6 +280,11 @@ int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** buc
  * grow concurrently).  use_ghosts: a later sibling's ancestral cell is held back by a ghost
  * operation to the depth of its fraternal cell, so each evaluation has one batch per operator.
  *
+ * The fraternal state of a first child depends on the parameters only (no previous sibling: zero
+ * state, label 0).  Like other constant tensors (section 7.2) it is computed once, with the roots,
+ * and reused by its consumers; the first children's own rows of d_f are written by one more batch
+ * after the last evaluation.
+ *
  * Nodes are numbered in the order of creation; node i's states are row i of d_a, d_f, d_g
  * [max_nodes, H] and d_y [max_nodes, n_out] (device, written).  acrobat_drnn_trees: host arrays
  * of max_nodes int32 each, caller-owned, any may be NULL: instance, parent and previous sibling

@@ -199,7 +199,10 @@ struct LaunchTimer {
 
 // Executes the graph nodes `first`, `first + 1`, ... bucket by bucket on the stream.  Buckets of one
 // (phase, depth) do not depend on each other; two neighbours with the same shapes share a launch.
-int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream);
+// indices_in_place: the kernels read the index lists straight out of the pinned staging buffer
+// instead of a device copy - one command less in the chain of a short evaluation; only for callers
+// that synchronise the stream before the staging buffer is written again.
+int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_place = false);
 
 int begin_call(acrobat_ctx* ctx) {
   if (!ctx) return ACROBAT_EINVAL;
@@ -209,7 +212,7 @@ int begin_call(acrobat_ctx* ctx) {
   return ACROBAT_OK;
 }
 
-int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream) {
+int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_place) {
   acrobat_ctx* ctx = g->ctx;
   g->graph.bucket(g->buckets, first);
   const std::vector<DfgNode>& nodes = g->graph.nodes();
@@ -225,7 +228,14 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream) {
     st[n + p] = x.arg0;
     st[2 * n + p] = x.arg1;
   }
-  TRY(upload_indices(ctx, 3 * n, stream));
+  const int32_t* idx = ctx->d_idx;
+  if (indices_in_place) {
+    int32_t* mapped = nullptr;
+    HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&mapped), ctx->h_stage, 0));
+    idx = mapped;
+  } else {
+    TRY(upload_indices(ctx, 3 * n, stream));
+  }
   static const CellEpilogue kEpi[] = {EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z,
                                       EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1};
   auto level_args = [&](size_t b) {
@@ -233,10 +243,10 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream) {
     const acrobat_op_desc& d = g->graph.ops()[g->buckets.op[b]];
     CellLevelArgs a{};
     a.n = cnt; a.H = d.H; a.nseg = d.nseg; a.kseg = d.kseg;
-    a.src0 = d.src0; a.ld0 = d.ld0; a.idx0 = ctx->d_idx + n + off;
-    a.src1 = d.src1; a.ld1 = d.ld1; a.idx1 = ctx->d_idx + 2 * n + off;
+    a.src0 = d.src0; a.ld0 = d.ld0; a.idx0 = idx + n + off;
+    a.src1 = d.src1; a.ld1 = d.ld1; a.idx1 = idx + 2 * n + off;
     a.W = d.W; a.ldw = d.ldw; a.bias = d.bias;
-    a.out_rows = ctx->d_idx + off;
+    a.out_rows = idx + off;
     a.h = d.h; a.c = d.c; a.cprev_src = d.cprev_src; a.zadd = d.zadd; a.zout = d.zout;
     a.n_cols = d.n_cols; a.y = d.y; a.ldo = d.ldo;
     return a;
@@ -936,22 +946,24 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
       HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_scores), need * sizeof(float), hipHostMallocDefault));
       ctx->scores_cap = need;
     }
+    // The score layer writes straight into pinned host memory: the program waits for these values
+    // at every evaluation, and a store over the bus is cheaper than a copy command in the chain of
+    // dependent launches.  d_y receives them all in one copy at the end.
+    float* scores_dev = nullptr;  // device-side address of the pinned buffer
+    HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&scores_dev), ctx->h_scores, 0));
     acrobat_dfg g;
     g.ctx = ctx;
     DrnnOps ops;
     {
-      const int rc = drnn_register_ops(g.graph, p, n_inst, max_nodes, d_x0, ctx->d_zero_row, d_a, d_f, d_g, d_y, ops, g.err);
+      const int rc = drnn_register_ops(g.graph, p, n_inst, max_nodes, d_x0, ctx->d_zero_row, d_a, d_f, d_g, scores_dev, ops, g.err);
       if (rc != ACROBAT_OK) return fail(ctx, rc, g.err);
     }
-    // one evaluation: the batches of everything invoked since the last one, then the new nodes'
-    // scores to the host - the values the program is waiting for
+    // one evaluation: the batches of everything invoked since the last one, then wait - the scores
+    // of the new nodes are what the program needs to go on
     const size_t n_out = (size_t)p.n_out;
-    const DrnnEvaluate evaluate = [&](size_t first, int32_t first_node, int32_t n_nodes, int32_t* n_buckets) {
-      TRY(run_graph(&g, first, stream));
+    const DrnnEvaluate evaluate = [&](size_t first, int32_t, int32_t, int32_t* n_buckets) {
+      TRY(run_graph(&g, first, stream, /*indices_in_place=*/true));  // (synchronised below, before the next staging)
       *n_buckets = (int32_t)g.buckets.op.size();
-      if (n_nodes > 0)
-        HIP_TRY(ctx, hipMemcpyAsync(ctx->h_scores + (size_t)first_node * n_out, d_y + (size_t)first_node * n_out,
-                                    (size_t)n_nodes * n_out * sizeof(float), hipMemcpyDeviceToHost, stream));
       HIP_TRY(ctx, hipStreamSynchronize(stream));
       return ACROBAT_OK;
     };
@@ -962,6 +974,10 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
     const int rc = drnn_generate(g.graph, ops, n_inst, p.n_labels, *decisions, mode, use_ghosts != 0, max_nodes, evaluate,
                                  scores, t, st, err);
     drnn_copy_out(t, st, trees, stats);
+    if (!t.inst.empty()) {
+      HIP_TRY(ctx, hipMemcpyAsync(d_y, ctx->h_scores, t.inst.size() * n_out * sizeof(float), hipMemcpyHostToDevice, stream));
+      HIP_TRY(ctx, hipStreamSynchronize(stream));
+    }
     if (rc != ACROBAT_OK) return ctx->err.empty() ? fail(ctx, rc, err) : rc;
     return ACROBAT_OK;
   } catch (const std::bad_alloc&) {

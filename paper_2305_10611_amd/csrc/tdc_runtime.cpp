@@ -34,6 +34,9 @@ struct Generator {
   FiberScheduler* fibers;  // null: no fibers, every await evaluates at once
 
   std::vector<int32_t> o_node, o_depth;  // per tree node: graph node and depth of its score operator
+  std::vector<int32_t> f_rows;           // per tree node: row holding its fraternal state (0 for first children)
+  std::vector<int32_t> deferred;         // first children whose own fraternal row is still to be written
+  int32_t first_f_node = -1;             // graph node that computes the shared first-child fraternal state
   size_t executed = 0;                   // graph nodes [0, executed) have been evaluated
   int32_t scored = 0;                    // tree nodes [0, scored) have their scores
   int rc = ACROBAT_OK;
@@ -43,8 +46,9 @@ struct Generator {
     if (rc == ACROBAT_OK) { rc = code; err = msg; }
   }
 
-  // executes everything invoked since the last evaluation
-  void evaluate_pending() {
+  // executes everything invoked since the last evaluation (counts_as_round false: the deferred
+  // batch at the end, which no decision waits for)
+  void evaluate_pending(bool counts_as_round = true) {
     if (failed() || executed == g.size()) return;
     const int32_t n_new = (int32_t)out.inst.size() - scored;
     int32_t buckets = 0;
@@ -54,7 +58,7 @@ struct Generator {
     executed = g.size();
     scored += n_new;
     stats.n_buckets += buckets;
-    ++stats.n_rounds;
+    if (counts_as_round) ++stats.n_rounds;
   }
 
   // returns once the scores of tree node i exist
@@ -66,6 +70,13 @@ struct Generator {
 
   // One node: the three cells and the score layer, each invoked with its depth computed inline.
   // parent / prev: tree nodes or -1.  Returns the tree node, -1 after a failure.
+  //
+  // The fraternal state of a first child depends on nothing but the parameters (no previous
+  // sibling: zero state, label 0): it is the same vector for every first child and for every root.
+  // As the paper does for constant tensors (section 7.2), it is computed once - with the roots, in
+  // the first evaluation - and reused: consumers of a first child's fraternal state read the row of
+  // tree node 0 instead.  The first children's own rows of the output are filled by one batch at the
+  // very end (deferred), off the chain of dependent evaluations.
   int32_t node(int32_t inst, int32_t parent, int32_t prev, int32_t k, int32_t depth) {
     if (failed()) return -1;
     const int32_t i = (int32_t)out.inst.size();
@@ -81,15 +92,24 @@ struct Generator {
       d_a = d_f;
     }
     int32_t n_a = -1, n_f = -1, n_p = -1, n_o = -1;
+    int32_t f_row = i;  // row of the fraternal arena that holds this node's fraternal state
     int e;
     if (parent >= 0) e = g.invoke(ops.a, 0, d_a, i, parent, out.label[parent], prod_a, -1, &n_a, err);
     else e = g.invoke(ops.a_root, 0, d_a, i, inst, 0, -1, -1, &n_a, err);
     if (e == ACROBAT_OK) {
-      if (prev >= 0) e = g.invoke(ops.f, 0, d_f, i, prev, out.label[prev], o_node[prev], -1, &n_f, err);
-      else e = g.invoke(ops.f_first, 0, d_f, i, 0, 0, -1, -1, &n_f, err);
+      if (prev >= 0) {
+        e = g.invoke(ops.f, 0, d_f, i, f_rows[prev], out.label[prev], o_node[prev], -1, &n_f, err);
+      } else if (parent < 0) {
+        e = g.invoke(ops.f_first, 0, d_f, i, 0, 0, -1, -1, &n_f, err);
+        if (i == 0) first_f_node = n_f;
+      } else {
+        f_row = 0;
+        n_f = first_f_node;
+        deferred.push_back(i);
+      }
     }
     const int32_t d_p = std::max(d_a, d_f) + 1;
-    if (e == ACROBAT_OK) e = g.invoke(ops.p, 0, d_p, i, i, i, n_a, n_f, &n_p, err);
+    if (e == ACROBAT_OK) e = g.invoke(ops.p, 0, d_p, i, i, f_row, n_a, n_f, &n_p, err);
     if (e == ACROBAT_OK) e = g.invoke(ops.o, 0, d_p + 1, i, i, 0, n_p, -1, &n_o, err);
     if (e != ACROBAT_OK) { fail(e, err); return -1; }
     out.inst.push_back(inst);
@@ -101,7 +121,16 @@ struct Generator {
     out.round.push_back(-1);
     o_node.push_back(n_o);
     o_depth.push_back(d_p + 1);
+    f_rows.push_back(f_row);
     return i;
+  }
+
+  // the deferred batch: the first children's own fraternal rows
+  void finish() {
+    if (failed() || deferred.empty()) return;
+    for (int32_t i : deferred)
+      if (g.invoke(ops.f_first, 0, 0, i, 0, 0, -1, -1, nullptr, err) != ACROBAT_OK) { fail(ACROBAT_EINVAL, err); return; }
+    evaluate_pending(false);
   }
 
   // the children of `parent`, left to right; each child's own children are generated by a fiber of
@@ -177,6 +206,7 @@ int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, 
                 mode == ACROBAT_TDC_SEQUENTIAL ? nullptr : &fibers};
   if (mode == ACROBAT_TDC_SEQUENTIAL) {
     for (int32_t s = 0; s < n_inst && !gen.failed(); ++s) gen.instance(s);
+    gen.finish();
     return gen.rc;
   }
   for (int32_t s = 0; s < n_inst; ++s) {
@@ -191,6 +221,7 @@ int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, 
     fibers.release();
   }
   if (!gen.failed() && !fibers.error().empty()) gen.fail(ACROBAT_EINVAL, "exception in a fiber: " + fibers.error());
+  gen.finish();
   return gen.rc;
 }
 

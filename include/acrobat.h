@@ -298,7 +298,7 @@ int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** buc
 
 typedef struct {
   uint64_t seed;
-  int32_t max_depth;    /* levels per tree, >= 1 */
+  int32_t max_depth;    /* levels per tree, 1 .. 4096 */
   int32_t max_children; /* children per node, >= 1 */
   float p_child, p_sibling;
 } acrobat_drnn_decisions;

@@ -201,7 +201,12 @@ int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, 
     err = "unknown mode";
     return ACROBAT_EINVAL;
   }
-  FiberScheduler fibers;
+  // the recursion over a tree's levels runs on a fiber's stack (or, without fibers, on the caller's)
+  if (dec.max_depth > 4096) {
+    err = "max_depth above 4096";
+    return ACROBAT_EINVAL;
+  }
+  FiberScheduler fibers(((size_t)64 << 10) + ((size_t)1 << 10) * (size_t)dec.max_depth);
   Generator gen{g, ops, n_labels, dec, mode == ACROBAT_TDC_FORK_JOIN, use_ghosts, max_nodes, evaluate, scores, out, stats, err,
                 mode == ACROBAT_TDC_SEQUENTIAL ? nullptr : &fibers};
   if (mode == ACROBAT_TDC_SEQUENTIAL) {

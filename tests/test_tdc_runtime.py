@@ -72,6 +72,7 @@ def test_capacity_parameters_and_repeated_runs():
         assert rc == A.ENOMEM and st2["n_nodes"] == n - 1
     assert A.acrobat_drnn_schedule(dict(w, max_depth=0))[0] == A.EINVAL
     assert A.acrobat_drnn_schedule(dict(w, max_children=0))[0] == A.EINVAL
+    assert A.acrobat_drnn_schedule(dict(w, max_depth=5000))[0] == A.EINVAL
     assert A.acrobat_drnn_schedule(dict(w, p_child=1.5))[0] == A.EINVAL
     assert A.acrobat_drnn_schedule(w, mode=7)[0] == A.EINVAL
     rc, t0, st0 = A.acrobat_drnn_schedule(dict(w, n_inst=0))
@@ -142,3 +143,12 @@ def test_ghost_depth_is_checked_like_any_node():
     assert g.acrobat_dfg_invoke(X, 0, 4, 1, 1, 0, gh)[0] == A.OK
     assert g.acrobat_dfg_ghost(0, 1, 99)[0] == A.ESTRUCT
     g.close()
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_a_chain_as_deep_as_allowed(mode):
+    """One child per node down to the deepest level: the recursion nests 4096 calls on one stack."""
+    w = gen.drnn_workload(2, 32, 3, 32, seed=85, max_depth=4096, max_children=1, p_child=1.0, p_sibling=1.0, cap=8192)
+    rc, t, st = A.acrobat_drnn_schedule(w, mode, True)
+    assert rc == A.OK and st["n_nodes"] == 8192 and t["depth"].max() == 4095
+    assert st["n_rounds"] == (8192 if mode == A.TDC_SEQUENTIAL else 4096)

@@ -211,7 +211,7 @@ def drnn(w: dict, cap: int | None = None):
     n = lib.oracle_drnn(C.c_int(n_inst), C.c_int(H), C.c_int(int(w["n_labels"])), C.c_int(n_out),
                         *[_p(a) for a in arrs], C.c_uint64(int(w["seed_decisions"])), C.c_int(int(w["max_depth"])),
                         C.c_int(int(w["max_children"])), C.c_double(float(w["p_child"])), C.c_double(float(w["p_sibling"])),
-                        C.c_int(cap), *[_p(ints[k]) for k in ("inst", "parent", "prev", "sib_index", "depth", "label")],
+                        C.c_int(int(bool(w.get("from_scores", False)))), C.c_int(cap), *[_p(ints[k]) for k in ("inst", "parent", "prev", "sib_index", "depth", "label")],
                         _p(st["a"]), _p(st["f"]), _p(st["g"]), _p(y))
     if n < 0:
         raise ValueError("drnn: more than cap nodes")

@@ -62,8 +62,11 @@
  *   once y_i exists (tensor-dependent control flow, section 4.2).  As in the paper's evaluation
  *   (section 7.2) they are emulated pseudo-randomly: a counter-based generator keyed by the
  *   node's position (instance, path of child indices from the root), so the tree an instance
- *   grows does not depend on the order in which nodes are evaluated.  The program is the plain
- *   recursion: a node, then its children left to right, each with its whole subtree.
+ *   grows does not depend on the order in which nodes are evaluated.  Alternatively they are read
+ *   off the scores: children iff y[0] > 0 (and the depth limit allows), a sibling follows iff
+ *   y[1] > 0 (and the limit on children allows), label = first index of the largest label score.
+ *   The program is the plain recursion: a node, then its children left to right, each with its
+ *   whole subtree.
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (hand
  * computed 1- and 3-node trees, closed forms, library LSTM cells, brute force).
@@ -595,8 +598,20 @@ void oracle_drnn_decide(uint64_t key, int depth, int k, int is_root, int max_dep
   out[2] = (int32_t)(oracle_mix64(key ^ 3u) % (uint64_t)n_labels);
 }
 
+/* The same decisions read off a node's scores y[0 .. n_out). */
+void oracle_drnn_decide_from_scores(const double* y, int depth, int k, int is_root, int max_depth, int max_children,
+                                    int n_labels, int n_out, int32_t* out) {
+  out[0] = depth + 1 < max_depth && y[0] > 0.0;
+  out[1] = !is_root && k + 1 < max_children && y[1] > 0.0;
+  const int n = n_labels < n_out - 2 ? n_labels : n_out - 2;
+  int best = 0;
+  for (int l = 1; l < n; ++l)
+    if (y[2 + l] > y[2 + best]) best = l;
+  out[2] = best;
+}
+
 typedef struct {
-  int H, n_labels, n_out, max_depth, max_children, cap;
+  int H, n_labels, n_out, max_depth, max_children, cap, from_scores;
   double p_child, p_sibling;
   const float *emb, *Wa, *ba, *Wf, *bf, *Wp, *bp, *Wo, *bo;
   int32_t *inst, *parent, *prev, *sib_index, *depth, *label;
@@ -642,7 +657,10 @@ static int drnn_children(dr_model* m, int inst, int parent, uint64_t pkey, int p
     const int i = drnn_node(m, inst, parent, prev, k, pdepth + 1, NULL);
     if (i < 0) return -1;
     int32_t d[3];
-    oracle_drnn_decide(key, pdepth + 1, k, 0, m->max_depth, m->max_children, m->p_child, m->p_sibling, m->n_labels, d);
+    if (m->from_scores)
+      oracle_drnn_decide_from_scores(m->y + (size_t)i * m->n_out, pdepth + 1, k, 0, m->max_depth, m->max_children, m->n_labels, m->n_out, d);
+    else
+      oracle_drnn_decide(key, pdepth + 1, k, 0, m->max_depth, m->max_children, m->p_child, m->p_sibling, m->n_labels, d);
     m->label[i] = d[2];
     if (d[0] && drnn_children(m, inst, i, key, pdepth + 1) < 0) return -1;
     if (!d[1]) return 0;
@@ -656,10 +674,10 @@ static int drnn_children(dr_model* m, int inst, int parent, uint64_t pkey, int p
 int oracle_drnn(int n_inst, int H, int n_labels, int n_out, const float* x0, const float* emb,
                 const float* Wa, const float* ba, const float* Wf, const float* bf, const float* Wp,
                 const float* bp, const float* Wo, const float* bo, uint64_t seed, int max_depth,
-                int max_children, double p_child, double p_sibling, int cap, int32_t* inst,
+                int max_children, double p_child, double p_sibling, int from_scores, int cap, int32_t* inst,
                 int32_t* parent, int32_t* prev, int32_t* sib_index, int32_t* depth, int32_t* label,
                 double* a, double* f, double* g, double* y) {
-  dr_model m = {H, n_labels, n_out, max_depth, max_children, cap, p_child, p_sibling, emb, Wa, ba, Wf, bf, Wp, bp,
+  dr_model m = {H, n_labels, n_out, max_depth, max_children, cap, from_scores, p_child, p_sibling, emb, Wa, ba, Wf, bf, Wp, bp,
                 Wo, bo, inst, parent, prev, sib_index, depth, label, a, f, g, y, 0, NULL, NULL};
   m.in = (double*)malloc(sizeof(double) * 2 * (size_t)H);
   m.z = (double*)malloc(sizeof(double) * (size_t)(H > n_out ? H : n_out));
@@ -669,7 +687,8 @@ int oracle_drnn(int n_inst, int H, int n_labels, int n_out, const float* x0, con
     const int i = drnn_node(&m, s, -1, -1, 0, 0, x0 + (size_t)s * H);
     if (i < 0) { rc = -1; break; }
     int32_t d[3];
-    oracle_drnn_decide(key, 0, 0, 1, max_depth, max_children, p_child, p_sibling, n_labels, d);
+    if (from_scores) oracle_drnn_decide_from_scores(y + (size_t)i * n_out, 0, 0, 1, max_depth, max_children, n_labels, n_out, d);
+    else oracle_drnn_decide(key, 0, 0, 1, max_depth, max_children, p_child, p_sibling, n_labels, d);
     label[i] = d[2];
     if (d[0]) rc = drnn_children(&m, s, i, key, 0);
   }

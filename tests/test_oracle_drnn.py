@@ -172,3 +172,59 @@ def test_instances_are_independent_and_capacity_is_checked():
     with pytest.raises(ValueError):
         oracle.drnn(w, cap=len(r["inst"]) - 1)
     assert len(oracle.drnn(w, cap=len(r["inst"]))["inst"]) == len(r["inst"])
+
+
+def test_hand_values_with_decisions_read_off_the_scores(golden):
+    g = golden("hand_cases.txt")
+    w = tiny(2, 3, n_labels=2, n_out=4, emb=[[2.0], [-1.0]], Wo=[[1.0], [1.0], [1.0], [-1.0]], bo=[0.0, -0.4375, 0.0, 1.25],
+             from_scores=True, p_child=0.0, p_sibling=0.0)
+    r = oracle.drnn(w)
+    assert r["parent"].tolist() == [-1, 0, 0, 0] and r["prev"].tolist() == [-1, -1, 1, 2]
+    assert r["label"].tolist() == [int(v) for v in g["drnn_scores_label"]]
+    tight = dict(rtol=0, atol=2e-16)
+    for k in "afg":
+        np.testing.assert_allclose(r[k][:, 0], g["drnn_scores_" + k], **tight)
+    # one level only: the root's y0 > 0 no longer gives it children
+    assert len(oracle.drnn(dict(w, max_depth=1))["inst"]) == 1
+    # a higher threshold on the sibling score: child 0 (g - 0.4688 < 0) stays alone
+    assert oracle.drnn(dict(w, bo=[0.0, -0.46875, 0.0, 1.25]))["parent"].tolist() == [-1, 0]
+
+
+def score_decisions(y, depth, k, is_root, w):
+    n = min(int(w["n_labels"]), int(w["n_out"]) - 2)
+    return (depth + 1 < w["max_depth"] and y[0] > 0, (not is_root) and k + 1 < w["max_children"] and y[1] > 0,
+            int(np.argmax(y[2:2 + n])))
+
+
+def test_score_driven_structure_follows_the_scores():
+    w = gen.drnn_workload(24, 64, 30, 32, seed=128, from_scores=True)
+    r = oracle.drnn(w)
+    n = len(r["inst"])
+    sizes = np.bincount(r["inst"], minlength=24)
+    # this seed grows trees of several sizes with several labels (checked, not assumed)
+    assert n > 300 and len(set(sizes.tolist())) >= 4 and sizes.max() > 20 and len(set(r["label"].tolist())) >= 3
+    pth = paths(r)
+    index = {p: i for i, p in enumerate(pth)}
+    n_child = np.bincount(r["parent"][r["parent"] >= 0], minlength=n)
+    for i, (inst, p) in enumerate(pth):
+        has_child, has_sib, label = score_decisions(r["y"][i], len(p), p[-1] if p else 0, not p, w)
+        assert label == r["label"][i]
+        assert has_child == (n_child[i] > 0)
+        assert has_sib == ((inst, p[:-1] + (p[-1] + 1,)) in index if p else False)
+
+
+def test_scores_that_always_say_yes_grow_the_full_tree_of_the_emulation():
+    """Topology scores forced positive = emulated decisions with probability one (one label, so labels agree)."""
+    w = gen.drnn_workload(3, 8, 1, 3, seed=76, max_depth=4, max_children=3, p_child=1.0, p_sibling=1.0)
+    full = oracle.drnn(w)
+    assert len(full["inst"]) == 3 * (1 + 3 + 9 + 27)
+    ws = dict(w, from_scores=True, Wo=w["Wo"].copy(), bo=w["bo"].copy())
+    ws["Wo"][:2] = 0.0
+    ws["bo"][:2] = 1.0
+    got = oracle.drnn(ws)
+    for k in ("inst", "parent", "prev", "sib_index", "depth", "label"):
+        assert np.array_equal(got[k], full[k])
+    for k in "afg":
+        assert np.array_equal(got[k], full[k])
+    ws["bo"][0] = -1.0  # ... and with the first score forced negative nobody has children
+    assert len(oracle.drnn(ws)["inst"]) == 3

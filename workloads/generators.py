@@ -260,13 +260,18 @@ def birnn_workload(n_seq, len_lo, len_hi, H, D, n_out, seed, bias_scale=0.1):
 
 
 def drnn_workload(n_inst, H, n_labels, n_out, seed, max_depth=6, max_children=4, p_child=0.7, p_sibling=0.6,
-                  bias_scale=0.1, cap=None):
+                  bias_scale=0.1, cap=None, from_scores=False, topology_bias=(0.0, 0.0), weight_gain=8.0, score_gain=4.0):
     """Doubly-recurrent-network batch: one input vector per instance, from which a tree is
     generated top-down.  Parameters: label embeddings emb [n_labels, H]; ancestral, fraternal and
     predictive cells Wa, Wf, Wp [H, 2H] with biases [H]; score layer Wo [n_out, H], bo [n_out].
     The decisions (children, next sibling, label) are emulated pseudo-randomly from
     seed_decisions; max_depth levels at most, max_children children per node at most.  `cap`
-    bounds the number of nodes the outputs can hold."""
+    bounds the number of nodes the outputs can hold.  from_scores: the decisions are read off the
+    scores instead (children iff y[0] > 0, sibling iff y[1] > 0, label = argmax of the rest); the
+    two topology scores then get the biases topology_bias, which set how bushy the trees are, and the
+    cell weights and the score layer are scaled up (weight_gain, score_gain): with the small weights of
+    the other workloads an untrained network's scores hardly differ from node to node and every node
+    would decide alike.  Whether a seed grows interesting trees is luck; users check the result."""
     rng = make_rng(seed)
     bound = 1.0 / np.sqrt(2 * H)
     out = dict(kind="drnn", n_inst=n_inst, H=H, n_labels=n_labels, n_out=n_out, seed=seed,
@@ -278,6 +283,14 @@ def drnn_workload(n_inst, H, n_labels, n_out, seed, max_depth=6, max_children=4,
         out["b" + p] = uniform_f32((H,), bias_scale, rng)
     out["Wo"] = uniform_f32((n_out, H), 1.0 / np.sqrt(H), rng)
     out["bo"] = uniform_f32((n_out,), bias_scale, rng)
+    out["from_scores"] = bool(from_scores)
+    if from_scores:
+        for p in ("a", "f", "p"):
+            out["W" + p] = (out["W" + p] * np.float32(weight_gain)).astype(np.float32)
+        out["Wo"] = (out["Wo"] * np.float32(score_gain)).astype(np.float32)
+        # centre the topology scores (states are sigmoids, mean about 0.5) and shift them by the biases
+        for r in (0, 1):
+            out["bo"][r] = np.float32(topology_bias[r]) - np.float32(0.5) * out["Wo"][r].sum(dtype=np.float32)
     if cap is None:  # every instance at its largest: a full tree of max_children-ary branching
         per = sum(max_children ** d for d in range(max_depth))
         cap = min(n_inst * per, n_inst * 4096)

@@ -301,6 +301,12 @@ typedef struct {
   int32_t max_depth;    /* levels per tree, 1 .. 4096 */
   int32_t max_children; /* children per node, >= 1 */
   float p_child, p_sibling;
+  /* 0: emulated decisions as described above.  1: the decisions are read off the scores - children
+   * iff depth + 1 < max_depth and y[0] > 0; a sibling follows iff the node is not a root,
+   * k + 1 < max_children and y[1] > 0; label = the first l with the largest y[2 + l],
+   * l < min(n_labels, n_out - 2) - seed, p_child and p_sibling are then unused, and
+   * acrobat_drnn_schedule (which has no scores) refuses the mode. */
+  int32_t from_scores;
 } acrobat_drnn_decisions;
 
 typedef struct { /* device pointers */

@@ -51,7 +51,7 @@ TDC_SEQUENTIAL, TDC_INSTANCE_FIBERS, TDC_FORK_JOIN = 0, 1, 2
 
 class acrobat_drnn_decisions(C.Structure):
     _fields_ = [("seed", C.c_uint64), ("max_depth", C.c_int32), ("max_children", C.c_int32),
-                ("p_child", C.c_float), ("p_sibling", C.c_float)]
+                ("p_child", C.c_float), ("p_sibling", C.c_float), ("from_scores", C.c_int32)]
 
 
 class acrobat_drnn_params(C.Structure):
@@ -200,7 +200,7 @@ def acrobat_schedule_birnn(lens):
 
 def _drnn_decisions(w: dict):
     return acrobat_drnn_decisions(int(w["seed_decisions"]), int(w["max_depth"]), int(w["max_children"]),
-                                  float(w["p_child"]), float(w["p_sibling"]))
+                                  float(w["p_child"]), float(w["p_sibling"]), int(bool(w.get("from_scores", False))))
 
 
 def _drnn_outputs(max_nodes: int):

@@ -904,7 +904,8 @@ int acrobat_drnn_schedule(int32_t n_inst, int32_t n_labels, const acrobat_drnn_d
       return ACROBAT_OK;
     };
     const DrnnScores scores = [](int32_t) { return (const float*)nullptr; };
-    const int rc = drnn_generate(graph, ops, n_inst, n_labels, *decisions, mode, use_ghosts != 0, max_nodes, evaluate, scores,
+    if (decisions->from_scores) return ACROBAT_EINVAL;  // nothing is computed here: there are no scores to decide from
+    const int rc = drnn_generate(graph, ops, n_inst, n_labels, 32, *decisions, mode, use_ghosts != 0, max_nodes, evaluate, scores,
                                  t, st, err);
     drnn_copy_out(t, st, trees, stats);
     return rc;
@@ -971,7 +972,7 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
     DrnnTrees t;
     DrnnStats st;
     std::string err;
-    const int rc = drnn_generate(g.graph, ops, n_inst, p.n_labels, *decisions, mode, use_ghosts != 0, max_nodes, evaluate,
+    const int rc = drnn_generate(g.graph, ops, n_inst, p.n_labels, p.n_out, *decisions, mode, use_ghosts != 0, max_nodes, evaluate,
                                  scores, t, st, err);
     drnn_copy_out(t, st, trees, stats);
     if (!t.inst.empty()) {

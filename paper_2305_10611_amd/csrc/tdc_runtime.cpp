@@ -22,7 +22,7 @@ double unit_interval(uint64_t bits) { return (double)(bits >> 11) * (1.0 / 90071
 struct Generator {
   Dfg& g;
   const DrnnOps& ops;
-  const int32_t n_labels;
+  const int32_t n_labels, n_out;
   const acrobat_drnn_decisions& dec;
   const bool fork, use_ghosts;
   const int32_t max_nodes;
@@ -143,7 +143,7 @@ struct Generator {
       if (i < 0) return;
       await(i);
       if (failed()) return;
-      const DrnnDecision d = drnn_decide(dec, n_labels, key, pdepth + 1, k, false, scores(i));
+      const DrnnDecision d = drnn_decide(dec, n_labels, n_out, key, pdepth + 1, k, false, scores(i));
       out.label[i] = d.label;
       if (d.has_child) descend(inst, i, key, pdepth + 1);
       if (failed() || !d.has_sibling) return;
@@ -166,7 +166,7 @@ struct Generator {
     if (i < 0) return;
     await(i);
     if (failed()) return;
-    const DrnnDecision d = drnn_decide(dec, n_labels, key, 0, 0, true, scores(i));
+    const DrnnDecision d = drnn_decide(dec, n_labels, n_out, key, 0, 0, true, scores(i));
     out.label[i] = d.label;
     if (d.has_child) descend(inst, i, key, 0);
   }
@@ -177,23 +177,33 @@ struct Generator {
 uint64_t drnn_root_key(uint64_t seed, int32_t inst) { return mix64(seed ^ mix64((uint64_t)inst)); }
 uint64_t drnn_child_key(uint64_t parent_key, int32_t k) { return mix64(parent_key + (uint64_t)k + 1u); }
 
-DrnnDecision drnn_decide(const acrobat_drnn_decisions& d, int32_t n_labels, uint64_t key, int32_t depth, int32_t k,
-                         bool is_root, const float* y) {
-  (void)y;  // the emulation does not look at the scores it waited for
+DrnnDecision drnn_decide(const acrobat_drnn_decisions& d, int32_t n_labels, int32_t n_out, uint64_t key, int32_t depth,
+                         int32_t k, bool is_root, const float* y) {
   DrnnDecision r;
+  if (d.from_scores) {
+    r.has_child = depth + 1 < d.max_depth && y[0] > 0.0f;
+    r.has_sibling = !is_root && k + 1 < d.max_children && y[1] > 0.0f;
+    const int32_t n = n_labels < n_out - 2 ? n_labels : n_out - 2;
+    r.label = 0;
+    for (int32_t l = 1; l < n; ++l)
+      if (y[2 + l] > y[2 + r.label]) r.label = l;
+    return r;
+  }
+  // the emulation does not look at the scores it waited for
   r.has_child = depth + 1 < d.max_depth && unit_interval(mix64(key ^ 1u)) < (double)d.p_child;
   r.has_sibling = !is_root && k + 1 < d.max_children && unit_interval(mix64(key ^ 2u)) < (double)d.p_sibling;
   r.label = (int32_t)(mix64(key ^ 3u) % (uint64_t)n_labels);
   return r;
 }
 
-int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, const acrobat_drnn_decisions& dec,
+int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, int32_t n_out, const acrobat_drnn_decisions& dec,
                   int32_t mode, bool use_ghosts, int32_t max_nodes, const DrnnEvaluate& evaluate,
                   const DrnnScores& scores, DrnnTrees& out, DrnnStats& stats, std::string& err) {
   out = DrnnTrees();
   stats = DrnnStats();
   if (n_inst < 0 || n_labels < 1 || max_nodes < 0 || dec.max_depth < 1 || dec.max_children < 1 ||
-      !(dec.p_child >= 0.0f && dec.p_child <= 1.0f) || !(dec.p_sibling >= 0.0f && dec.p_sibling <= 1.0f)) {
+      (!dec.from_scores && (!(dec.p_child >= 0.0f && dec.p_child <= 1.0f) || !(dec.p_sibling >= 0.0f && dec.p_sibling <= 1.0f))) ||
+      (dec.from_scores && n_out < 3)) {
     err = "bad generation parameters";
     return ACROBAT_EINVAL;
   }
@@ -207,7 +217,7 @@ int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, 
     return ACROBAT_EINVAL;
   }
   FiberScheduler fibers(((size_t)64 << 10) + ((size_t)1 << 10) * (size_t)dec.max_depth);
-  Generator gen{g, ops, n_labels, dec, mode == ACROBAT_TDC_FORK_JOIN, use_ghosts, max_nodes, evaluate, scores, out, stats, err,
+  Generator gen{g, ops, n_labels, n_out, dec, mode == ACROBAT_TDC_FORK_JOIN, use_ghosts, max_nodes, evaluate, scores, out, stats, err,
                 mode == ACROBAT_TDC_SEQUENTIAL ? nullptr : &fibers};
   if (mode == ACROBAT_TDC_SEQUENTIAL) {
     for (int32_t s = 0; s < n_inst && !gen.failed(); ++s) gen.instance(s);

@@ -34,14 +34,15 @@ struct DrnnStats {
   int32_t n_ghosts = 0;    // ghost operations invoked
 };
 
-// The decisions of one node, emulated from its position (the paper's evaluation replaces the
-// tensor-dependent decisions by pseudo-random ones since its models are untrained, section 7.2);
-// `y` are the node's scores on the host - the value the program had to wait for.
+// The decisions of one node.  Emulated from its position (the paper's evaluation replaces the
+// tensor-dependent decisions by pseudo-random ones since its models are untrained, section 7.2) or,
+// with dec.from_scores, read off `y`, the node's n_out scores on the host - the value the program
+// had to wait for either way.
 struct DrnnDecision { bool has_child, has_sibling; int32_t label; };
 uint64_t drnn_root_key(uint64_t seed, int32_t inst);
 uint64_t drnn_child_key(uint64_t parent_key, int32_t k);
-DrnnDecision drnn_decide(const acrobat_drnn_decisions& d, int32_t n_labels, uint64_t key, int32_t depth, int32_t k,
-                         bool is_root, const float* y);
+DrnnDecision drnn_decide(const acrobat_drnn_decisions& d, int32_t n_labels, int32_t n_out, uint64_t key, int32_t depth,
+                         int32_t k, bool is_root, const float* y);
 
 // evaluate(first_dfg_node, first_tree_node, n_tree_nodes, &n_buckets): executes the graph nodes from
 // first_dfg_node on and makes the scores of the tree nodes [first_tree_node, + n_tree_nodes)
@@ -52,7 +53,7 @@ using DrnnScores = std::function<const float*(int32_t)>;
 // Runs the generation program for n_inst instances.  mode: ACROBAT_TDC_*.  use_ghosts: align the
 // ancestral cell of a later sibling with its fraternal cell by a ghost operation.  Fails with
 // ACROBAT_ENOMEM when more than max_nodes nodes would be generated.
-int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, const acrobat_drnn_decisions& dec,
+int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, int32_t n_out, const acrobat_drnn_decisions& dec,
                   int32_t mode, bool use_ghosts, int32_t max_nodes, const DrnnEvaluate& evaluate,
                   const DrnnScores& scores, DrnnTrees& out, DrnnStats& stats, std::string& err);
 

@@ -706,3 +706,20 @@ def test_ghost_operations_do_not_change_results(ctx, P):
     h1d = sig(xd @ W1.cpu().numpy().astype(np.float64).T)
     src = np.where((np.arange(n) % 2 == 0)[:, None], h1d, xd)
     P.assert_close(outs[1], sig(src @ W2.cpu().numpy().astype(np.float64).T), "h2")
+
+
+@pytest.mark.parametrize("mode", (1, 2))
+def test_drnn_decisions_read_off_the_scores(ctx, P, mode):
+    """Truly tensor-dependent control flow: whether a node has children, whether a sibling follows and
+    its label are computed from the scores the score kernel stored for it.  Decisions taken from
+    fp32 scores equal those from the oracle's fp64 scores as long as no score is near its threshold:
+    the margins of this workload are checked first (they are thousands of times the fp32 error)."""
+    w = gen.drnn_workload(24, 64, 30, 32, seed=128, from_scores=True)
+    want = oracle.drnn(w)
+    y = want["y"]
+    top2 = np.sort(y[:, 2:], axis=1)[:, -2:]
+    assert min(np.abs(y[:, 0]).min(), np.abs(y[:, 1]).min(), (top2[:, 1] - top2[:, 0]).min()) > 1e-3
+    assert len(want["inst"]) > 300 and len(set(want["label"].tolist())) >= 3
+    rc, trees, st, states = P.run_drnn(ctx, w, mode, True)
+    assert st["n_nodes"] == len(want["inst"])
+    check_drnn(P, w, trees, states, want)

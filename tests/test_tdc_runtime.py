@@ -75,6 +75,7 @@ def test_capacity_parameters_and_repeated_runs():
     assert A.acrobat_drnn_schedule(dict(w, max_depth=5000))[0] == A.EINVAL
     assert A.acrobat_drnn_schedule(dict(w, p_child=1.5))[0] == A.EINVAL
     assert A.acrobat_drnn_schedule(w, mode=7)[0] == A.EINVAL
+    assert A.acrobat_drnn_schedule(dict(w, from_scores=True))[0] == A.EINVAL  # no scores without a GPU
     rc, t0, st0 = A.acrobat_drnn_schedule(dict(w, n_inst=0))
     assert rc == A.OK and st0["n_nodes"] == 0 and st0["n_rounds"] == 0
     # single nodes: roots that get no children

@@ -939,7 +939,7 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
       ctx->zero_row_cap = (size_t)p.H;
       HIP_TRY(ctx, hipMemset(ctx->d_zero_row, 0, (size_t)p.H * sizeof(float)));
     }
-    const size_t need = (size_t)max_nodes * (size_t)p.n_out;
+    const size_t need = (size_t)(max_nodes > 0 ? max_nodes : 1) * (size_t)p.n_out;
     if (need > ctx->scores_cap) {
       if (ctx->h_scores) HIP_TRY(ctx, hipHostFree(ctx->h_scores));
       ctx->h_scores = nullptr;

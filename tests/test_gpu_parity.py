@@ -650,6 +650,8 @@ def test_drnn_degenerate_and_error_cases(ctx, P):
     assert rc == A.ENOMEM and "max_nodes" in ctx.acrobat_last_error() and st["n_nodes"] == n - 1
     rc, trees, st, states = P.run_drnn(ctx, dict(w, n_inst=0, x0=w["x0"][:0]), check=False)
     assert rc == A.OK and st["n_nodes"] == 0
+    rc, trees, st, _ = P.run_drnn(ctx, w, max_nodes=0, check=False)  # no room at all
+    assert rc == A.ENOMEM and st["n_nodes"] == 0
     w1 = dict(w, max_depth=1)  # roots only: one evaluation
     rc, trees, st, states = P.run_drnn(ctx, w1)
     assert st["n_nodes"] == 6 and st["n_rounds"] == 1

@@ -185,6 +185,12 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
  *   RNN_STEP       h[out_row] = sigmoid(z + bias + zadd[out_row, H])   (zadd NULL: no such term)
  *   RELU_OUT       y[out_row*ldo + j] = relu(z + bias[j]) for j < n_cols (W has n_cols rows; H = n_cols
  *                  rounded up to a multiple of 32)
+ *   MVRNN          the matrix-vector cell (section 7.2), no contraction segments (nseg = 0): H = d, 64 or 128;
+ *                  arg0 / arg1 name the left / right child - a value >= 0 is a row of the arenas h = vec
+ *                  [out_rows, d] and c = mat [out_rows, d, d] (an internal child), a value -(t + 1) is row t of
+ *                  the tables src0 = vec_tab [src0_rows, d] and src1 = mat_tab [src0_rows, d, d] (a leaf child,
+ *                  read in place); W [d, 2d], W2 = W_M [d, 2d]; writes row out_row of h and c:
+ *                  vec = tanh(W [B a ; A b]), mat = W_M [A ; B] for children (a, A), (b, B)
  * All pointers are device pointers and must stay valid until the run has finished on its stream. */
 #define ACROBAT_EPI_TREE_LEAF 0
 #define ACROBAT_EPI_TREE_INTERNAL 1
@@ -193,6 +199,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
 #define ACROBAT_EPI_RNN_STEP 4
 #define ACROBAT_EPI_RELU_OUT 5
 #define ACROBAT_EPI_STORE_Z1 6
+#define ACROBAT_EPI_MVRNN 7
 
 typedef struct {
   int32_t epilogue; /* ACROBAT_EPI_* */
@@ -211,6 +218,7 @@ typedef struct {
   /* row counts for the range check of acrobat_dfg_invoke's arguments: arg0 < src0_rows (also the
    * rows of cprev_src), arg1 < src1_rows, out_row < out_rows (rows of h, c, zadd, zout, y) */
   int32_t src0_rows, src1_rows, out_rows;
+  const float* W2; /* MVRNN only: W_M */
 } acrobat_op_desc;
 
 typedef struct acrobat_dfg acrobat_dfg;
@@ -229,7 +237,8 @@ int acrobat_dfg_clear(acrobat_dfg* g);
  * the op has two segments).  prod0 / prod1: node ids of the instances that produce the operands,
  * -1 for graph inputs; they serve the check of the inline depth (section 4.1, goal G.1): a node
  * must be in the same or a later phase than its producers and deeper than those of its own phase,
- * else ACROBAT_ESTRUCT.  *node (may be NULL) receives the new node's id (0, 1, 2, ...). */
+ * else ACROBAT_ESTRUCT.  Rows are checked against the op's row counts (an MVRNN op also takes the
+ * negative leaf codes down to -src0_rows).  *node (may be NULL) receives the new node's id (0, 1, 2, ...). */
 int acrobat_dfg_invoke(acrobat_dfg* g, int32_t op, int32_t phase, int32_t depth, int32_t out_row,
                        int32_t arg0, int32_t arg1, int32_t prod0, int32_t prod1, int32_t* node);
 /* The unbatched TreeLSTM program (recursive evaluation of every tree, depth computed inline,

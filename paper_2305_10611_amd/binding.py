@@ -42,10 +42,10 @@ class acrobat_op_desc(C.Structure):
                 ("W", C.c_void_p), ("ldw", C.c_int32), ("bias", C.c_void_p), ("h", C.c_void_p), ("c", C.c_void_p),
                 ("cprev_src", C.c_void_p), ("zadd", C.c_void_p), ("zout", C.c_void_p),
                 ("n_cols", C.c_int32), ("y", C.c_void_p), ("ldo", C.c_int32),
-                ("src0_rows", C.c_int32), ("src1_rows", C.c_int32), ("out_rows", C.c_int32)]
+                ("src0_rows", C.c_int32), ("src1_rows", C.c_int32), ("out_rows", C.c_int32), ("W2", C.c_void_p)]
 
 
-EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z, EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1 = range(7)
+EPI_TREE_LEAF, EPI_TREE_INTERNAL, EPI_LSTM_STEP, EPI_STORE_Z, EPI_RNN_STEP, EPI_RELU_OUT, EPI_STORE_Z1, EPI_MVRNN = range(8)
 TDC_SEQUENTIAL, TDC_INSTANCE_FIBERS, TDC_FORK_JOIN = 0, 1, 2
 
 
@@ -252,13 +252,13 @@ class Dfg:
 
     def acrobat_dfg_register_op(self, epilogue, H, nseg=0, kseg=0, src0=None, ld0=0, src1=None, ld1=0, W=None, ldw=0,
                                 bias=None, h=None, c=None, cprev_src=None, zadd=None, zout=None, n_cols=0, y=None, ldo=0,
-                                src0_rows=0, src1_rows=0, out_rows=0):
+                                src0_rows=0, src1_rows=0, out_rows=0, W2=None):
         """-> (rc, op_id); tensors are device tensors (kept alive by this object)."""
-        t = (src0, src1, W, bias, h, c, cprev_src, zadd, zout, y)
+        t = (src0, src1, W, bias, h, c, cprev_src, zadd, zout, y, W2)
         self._keep.append(t)
         d = acrobat_op_desc(epilogue, H, nseg, kseg, _dp(src0), ld0, _dp(src1), ld1, _dp(W), ldw, _dp(bias), _dp(h),
                             _dp(c), _dp(cprev_src), _dp(zadd), _dp(zout), n_cols, _dp(y), ldo, src0_rows, src1_rows,
-                            out_rows)
+                            out_rows, _dp(W2))
         op = C.c_int32(-1)
         rc = lib.acrobat_dfg_register_op(self._g, C.byref(d), C.byref(op))
         return rc, op.value

@@ -258,13 +258,30 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_
     const acrobat_op_desc& d0 = g->graph.ops()[g->buckets.op[b0]];
     const acrobat_op_desc& d1 = g->graph.ops()[g->buckets.op[b1]];
     return d0.epilogue == d1.epilogue && d0.H == d1.H && d0.nseg == d1.nseg && d0.kseg == d1.kseg &&
-           d0.epilogue != ACROBAT_EPI_RELU_OUT;
+           d0.epilogue != ACROBAT_EPI_RELU_OUT && d0.epilogue != ACROBAT_EPI_MVRNN;
   };
   LaunchTimer timer{ctx, stream};
   const size_t n_buckets = g->buckets.op.size();
   for (size_t b = 0; b < n_buckets; ++b) {
-    const CellLevelArgs a = level_args(b);
     const acrobat_op_desc& d = g->graph.ops()[g->buckets.op[b]];
+    if (d.epilogue == ACROBAT_EPI_MVRNN) {
+      const int32_t off = g->buckets.off[b];
+      MvrnnLevelArgs m{};
+      m.n = g->buckets.off[b + 1] - off;
+      m.d = d.H;
+      m.variant = ctx->mvrnn_variant;
+      m.out_rows = idx + off;
+      m.lsrc = idx + n + off;
+      m.rsrc = idx + 2 * n + off;
+      m.vec_tab = d.src0; m.mat_tab = d.src1;
+      m.W = d.W; m.WM = d.W2;
+      m.vec = d.h; m.mat = d.c;
+      TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, m.n));
+      HIP_TRY(ctx, launch_mvrnn_level(m, stream, timer.tile(), timer.ev));
+      TRY(timer.end());
+      continue;
+    }
+    const CellLevelArgs a = level_args(b);
     if (b + 1 < n_buckets && same_batch_shape(b, b + 1)) {
       const CellLevelArgs a1 = level_args(b + 1);
       TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, a.n + a1.n));

@@ -7,7 +7,16 @@
 namespace acrobat {
 
 int Dfg::register_op(const acrobat_op_desc& d, int32_t* id, std::string& err) {
-  if (d.epilogue < ACROBAT_EPI_TREE_LEAF || d.epilogue > ACROBAT_EPI_STORE_Z1) { err = "unknown epilogue kind"; return ACROBAT_EINVAL; }
+  if (d.epilogue < ACROBAT_EPI_TREE_LEAF || d.epilogue > ACROBAT_EPI_MVRNN) { err = "unknown epilogue kind"; return ACROBAT_EINVAL; }
+  if (d.epilogue == ACROBAT_EPI_MVRNN) {
+    if (d.H != 64 && d.H != 128) { err = "matrix-vector cell: d must be 64 or 128"; return ACROBAT_EINVAL; }
+    if (d.nseg != 0) { err = "matrix-vector cell: nseg must be 0"; return ACROBAT_EINVAL; }
+    if (!d.src0 || !d.src1 || !d.W || !d.W2 || !d.h || !d.c) { err = "matrix-vector cell: a table, weight or arena pointer is null"; return ACROBAT_EINVAL; }
+    if (d.src0_rows <= 0 || d.out_rows <= 0) { err = "row counts must be positive"; return ACROBAT_EINVAL; }
+    ops_.push_back(d);
+    *id = (int32_t)ops_.size() - 1;
+    return ACROBAT_OK;
+  }
   if (d.H <= 0 || d.H % 32) { err = "H must be a positive multiple of 32"; return ACROBAT_EINVAL; }
   if (d.nseg < 0 || d.nseg > 2 || (d.nseg > 0 && (d.kseg <= 0 || d.kseg % 32))) { err = "nseg in 0..2, kseg a positive multiple of 32"; return ACROBAT_EINVAL; }
   if (d.nseg > 0 && (!d.src0 || !d.W)) { err = "operand or weight pointer is null"; return ACROBAT_EINVAL; }
@@ -55,8 +64,16 @@ void Dfg::push(const DfgNode& n, int32_t* node) {
 int Dfg::invoke(int32_t op, int32_t phase, int32_t depth, int32_t out_row, int32_t arg0, int32_t arg1, int32_t prod0,
                 int32_t prod1, int32_t* node, std::string& err) {
   if (op < 0 || op >= (int32_t)ops_.size()) { err = "unknown op id"; return ACROBAT_EINVAL; }
-  if (out_row < 0 || arg0 < 0 || arg1 < 0) { err = "negative row"; return ACROBAT_EINVAL; }
-  {
+  if (ops_[op].epilogue == ACROBAT_EPI_MVRNN) {
+    const acrobat_op_desc& d = ops_[op];  // children: arena rows, or -(table row + 1)
+    if (out_row < 0 || out_row >= d.out_rows || arg0 < -d.src0_rows || arg0 >= d.out_rows || arg1 < -d.src0_rows || arg1 >= d.out_rows) {
+      err = "row out of range";
+      return ACROBAT_EINVAL;
+    }
+  } else if (out_row < 0 || arg0 < 0 || arg1 < 0) {
+    err = "negative row";
+    return ACROBAT_EINVAL;
+  } else {
     const acrobat_op_desc& d = ops_[op];
     const bool uses0 = d.nseg > 0 || d.cprev_src, uses1 = d.nseg > 1;
     if (out_row >= d.out_rows || (uses0 && arg0 >= d.src0_rows) || (uses1 && arg1 >= d.src1_rows)) { err = "row out of range"; return ACROBAT_EINVAL; }

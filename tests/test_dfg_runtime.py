@@ -149,3 +149,29 @@ def test_malformed_ops_and_trees_are_rejected():
                right=np.array([-1], np.int32), token=np.array([5], np.int32))
     assert g.acrobat_dfg_build_treelstm(tok, 3, leaf, internal) == A.ESTRUCT
     g.close()
+
+
+def test_matrix_vector_cell_op_takes_leaf_codes():
+    g = A.Dfg(None)
+    p = 0x1000
+    mv = B.acrobat_op_desc(B.EPI_MVRNN, 64, 0, 0, p, 0, p, 0, p, 0, None, p, p, None, None, None, 0, None, 0, 10, 0, 25, p)
+    rc, op = g.acrobat_dfg_register_op_desc(mv)
+    assert rc == A.OK
+    for field, value in (("H", 96), ("nseg", 1), ("W2", None), ("src1", None), ("c", None), ("src0_rows", 0)):
+        bad = B.acrobat_op_desc.from_buffer_copy(mv)
+        setattr(bad, field, value)
+        assert g.acrobat_dfg_register_op_desc(bad)[0] == A.EINVAL, field
+    # children: arena rows 0 .. 24 or leaf codes -1 .. -10 (table rows 0 .. 9)
+    rc, n0 = g.acrobat_dfg_invoke(op, 0, 1, 0, -1, -10)
+    assert rc == A.OK
+    rc, n1 = g.acrobat_dfg_invoke(op, 0, 2, 1, 0, -3, n0)
+    assert rc == A.OK
+    assert g.acrobat_dfg_invoke(op, 0, 1, 2, -11, -1)[0] == A.EINVAL
+    assert g.acrobat_dfg_invoke(op, 0, 1, 2, 25, -1)[0] == A.EINVAL
+    assert g.acrobat_dfg_invoke(op, 0, 1, 25, -1, -1)[0] == A.EINVAL
+    assert g.acrobat_dfg_invoke(op, 0, 2, 2, 0, 0, n1)[0] == A.ESTRUCT  # not deeper than its producer
+    rc, other = g.acrobat_dfg_register_op_desc(fake_op(B.EPI_TREE_LEAF))
+    assert g.acrobat_dfg_invoke(other, 0, 0, 0, -1)[0] == A.EINVAL  # other ops take no negative rows
+    off, order, bops = g.acrobat_dfg_schedule()
+    assert list(order) == [n0, n1] and list(bops) == [op, op]
+    g.close()

@@ -725,3 +725,53 @@ def test_drnn_decisions_read_off_the_scores(ctx, P, mode):
     rc, trees, st, states = P.run_drnn(ctx, w, mode, True)
     assert st["n_nodes"] == len(want["inst"])
     check_drnn(P, w, trees, states, want)
+
+
+@pytest.mark.parametrize("d", (64, 128))
+def test_generic_runtime_mvrnn_program(ctx, P, d):
+    """The matrix-vector cell as an op of the generic runtime: the recursive program invokes it once per
+    internal node with the depth computed inline; leaves are read in place through their codes."""
+    import torch
+    import paper_2305_10611_amd as A
+    from paper_2305_10611_amd import binding as B
+    w = gen.mvrnn_workload(14, 1, 13, d, seed=97)
+    w, _ = gen.relabel_trees(w, gen.make_rng(98), extra={"token": w["token"]})
+    N, V = int(w["tree_off"][-1]), int(w["V"])
+    t = {k: P.dev(w[k]) for k in ("vec_tab", "mat_tab", "W", "WM")}
+    vec, mat = P.nan_filled(N, d), P.nan_filled(N, d, d)
+    g = A.Dfg(ctx)
+    rc, op = g.acrobat_dfg_register_op(B.EPI_MVRNN, d, src0=t["vec_tab"], src1=t["mat_tab"], W=t["W"], W2=t["WM"], h=vec, c=mat,
+                                       src0_rows=V, out_rows=N)
+    assert rc == A.OK, g.acrobat_dfg_last_error()
+    left, right, token, off = w["left"], w["right"], w["token"], w["tree_off"]
+
+    def evaluate(base, j):  # -> (child code, depth, producer node)
+        gnode = base + j
+        if left[gnode] < 0:
+            return -(int(token[gnode]) + 1), 0, -1
+        cl, dl, pl = evaluate(base, int(left[gnode]))
+        cr, dr, pr = evaluate(base, int(right[gnode]))
+        depth = 1 + max(dl, dr)
+        rc, node = g.acrobat_dfg_invoke(op, 0, depth, gnode, cl, cr, pl, pr)
+        assert rc == A.OK, g.acrobat_dfg_last_error()
+        return gnode, depth, node
+
+    for tr in range(w["n_trees"]):
+        b, e = int(off[tr]), int(off[tr + 1])
+        children = set(left[b:e][left[b:e] >= 0].tolist()) | set(right[b:e][right[b:e] >= 0].tolist())
+        root = [j for j in range(e - b) if j not in children][0]
+        evaluate(b, root)
+    ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+    torch.cuda.synchronize()
+    internal = left >= 0
+    ov, om = oracle.mvrnn(w, nthreads=NT)
+    P.assert_close(vec.cpu().numpy()[internal], ov[internal], "vec")
+    P.assert_close(mat.cpu().numpy()[internal], om[internal], "mat")
+    assert torch.isnan(vec[torch.from_numpy(~internal).cuda()]).all()  # leaves are read in place, never copied
+    # same kernels, same batches (one per height) as the specialised entry point: the same bits
+    sv, sm = P.run_mvrnn(ctx, w, copy_leaves=0)
+    assert np.array_equal(vec.cpu().numpy()[internal], sv[internal]) and np.array_equal(mat.cpu().numpy()[internal], sm[internal])
+    boff, order, bops = g.acrobat_dfg_schedule()
+    level_off, _ = ctx.acrobat_last_schedule()
+    assert np.array_equal(np.diff(boff), np.diff(level_off)[1:])
+    g.close()

@@ -775,3 +775,49 @@ def test_generic_runtime_mvrnn_program(ctx, P, d):
     level_off, _ = ctx.acrobat_last_schedule()
     assert np.array_equal(np.diff(boff), np.diff(level_off)[1:])
     g.close()
+
+
+def test_generic_runtime_lstm_program(ctx, P):
+    """Listing 2 through invoke(): the hoisted input transform of every step at depth 0 of phase 0, step t of a
+    sequence at depth t of phase 1 (the first step is an op of its own: it has no previous state)."""
+    import torch
+    import paper_2305_10611_amd as A
+    from paper_2305_10611_amd import binding as B
+    w = gen.lstm_workload(19, 0, 14, 64, 32, seed=99, bias_scale=0.2)
+    R, H, D = int(w["len"].sum()), 64, 32
+    t = {k: P.dev(w[k]) for k in ("x", "Wx", "Wh", "b")}
+    h, c, xp = P.nan_filled(R, H), P.nan_filled(R, H), P.nan_filled(R, 4 * H)
+    g = A.Dfg(ctx)
+
+    def reg(*a, **k):
+        rc, op = g.acrobat_dfg_register_op(*a, **k)
+        assert rc == A.OK, g.acrobat_dfg_last_error()
+        return op
+    proj = reg(B.EPI_STORE_Z, H, nseg=1, kseg=D, src0=t["x"], ld0=D, W=t["Wx"], ldw=D, bias=t["b"], zout=xp, src0_rows=R, out_rows=R)
+    first = reg(B.EPI_LSTM_STEP, H, zadd=xp, h=h, c=c, out_rows=R)
+    step = reg(B.EPI_LSTM_STEP, H, nseg=1, kseg=H, src0=h, ld0=H, W=t["Wh"], ldw=H, zadd=xp, h=h, c=c, cprev_src=c,
+               src0_rows=R, out_rows=R)
+    seq_off = np.concatenate([[0], np.cumsum(w["len"])])
+    for s_ in range(len(w["len"])):
+        b, T = int(seq_off[s_]), int(w["len"][s_])
+        prev = -1
+        for i in range(T):
+            rc, p = g.acrobat_dfg_invoke(proj, 0, 0, b + i, b + i)
+            assert rc == A.OK
+            if i == 0:
+                rc, prev = g.acrobat_dfg_invoke(first, 1, 0, b, 0, 0, p)
+            else:
+                rc, prev = g.acrobat_dfg_invoke(step, 1, i, b + i, b + i - 1, 0, p, prev)
+            assert rc == A.OK, g.acrobat_dfg_last_error()
+    boff, order, bops = g.acrobat_dfg_schedule()
+    T_max = int(w["len"].max())
+    assert list(bops) == [proj, first] + [step] * (T_max - 1)
+    assert list(np.diff(boff)[1:]) == [int((w["len"] > k).sum()) for k in range(T_max)]
+    ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+    torch.cuda.synchronize()
+    oh, oc = oracle.varlen_lstm(w)
+    P.assert_close(h.cpu().numpy(), oh, "h")
+    P.assert_close(c.cpu().numpy(), oc, "c")
+    sh, sc = P.run_lstm(ctx, w)
+    assert np.array_equal(h.cpu().numpy(), sh) and np.array_equal(c.cpu().numpy(), sc)
+    g.close()

@@ -134,6 +134,10 @@ def test_structure_follows_the_decisions_and_the_limits():
             assert r["parent"][i] == -1 and r["prev"][i] == -1
     assert sorted(set(r["inst"].tolist())) == list(range(40))  # every instance has a root
     assert (np.diff(r["inst"]) >= 0).all()
+    # every position has a key of its own (siblings, cousins, other instances): no two nodes share their decisions
+    keys = [oracle.drnn_keys(w["seed_decisions"], inst, p) for inst, p in pth]
+    assert len(set(keys)) == n
+    assert oracle.drnn_keys(w["seed_decisions"] + 1, 0) != oracle.drnn_keys(w["seed_decisions"], 0)
     for i in range(n):
         inst, p = pth[i]
         has_child, has_sib, label = oracle.drnn_decide(oracle.drnn_keys(w["seed_decisions"], inst, p), len(p),

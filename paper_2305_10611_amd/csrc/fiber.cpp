@@ -4,6 +4,7 @@
 #include <unistd.h>
 
 #include <cstdint>
+#include <cstring>
 #include <exception>
 #include <vector>
 
@@ -48,7 +49,7 @@ thread_local FiberScheduler* tl_scheduler = nullptr;  // the scheduler whose run
 
 // Stacks outlive their scheduler: mapping one costs two system calls and its first use a page
 // fault, more than everything else a short-lived fiber does.  Per thread, all of one size.
-constexpr size_t kPooledStacks = 4096;
+constexpr size_t kPooledStacks = 65536;  // (address space and the pages a fiber touched: a few KB each)
 struct StackPool {
   size_t bytes = 0;  // mapping size of the pooled stacks
   std::vector<char*> free;
@@ -106,7 +107,7 @@ FiberScheduler::Fiber* FiberScheduler::acquire() {
 }
 
 void FiberScheduler::retire(Fiber* f) {
-  f->fn = nullptr;
+  if (f->fn) f->fn = nullptr;
   idle_.push_back(f);
 }
 
@@ -115,7 +116,8 @@ void FiberScheduler::entry() {
   FiberScheduler* s = tl_scheduler;
   Fiber* f = s->current_;
   try {
-    f->fn();
+    if (f->plain) f->plain(f->arg);
+    else f->fn();
   } catch (const std::exception& e) {
     if (s->error_.empty()) s->error_ = e.what();
   } catch (...) {
@@ -126,10 +128,7 @@ void FiberScheduler::entry() {
   __builtin_trap();  // a finished fiber is never resumed
 }
 
-bool FiberScheduler::spawn(std::function<void()> fn) {
-  Fiber* f = acquire();
-  if (!f) return false;
-  f->fn = std::move(fn);
+void FiberScheduler::make_runnable(Fiber* f) {
   f->done = false;
   // initial frame: six zeroed callee-saved registers, then the address the first switch returns
   // to; the stack pointer is then 8 modulo 16, as right after a call instruction
@@ -142,6 +141,24 @@ bool FiberScheduler::spawn(std::function<void()> fn) {
   f->sp = sp;
   runnable_.push_back(f);
   ++n_spawned_;
+}
+
+bool FiberScheduler::spawn(std::function<void()> fn) {
+  Fiber* f = acquire();
+  if (!f) return false;
+  f->fn = std::move(fn);
+  f->plain = nullptr;
+  make_runnable(f);
+  return true;
+}
+
+bool FiberScheduler::spawn(void (*fn)(void*), const void* arg, size_t arg_bytes) {
+  if (arg_bytes > kInlineArg) return false;
+  Fiber* f = acquire();
+  if (!f) return false;
+  f->plain = fn;
+  std::memcpy(f->arg, arg, arg_bytes);
+  make_runnable(f);
   return true;
 }
 

@@ -28,6 +28,10 @@ class FiberScheduler {
 
   // A new runnable fiber that will call fn.  False if no stack could be allocated.
   bool spawn(std::function<void()> fn);
+  // The same for a plain function and up to kInlineArg bytes of argument, copied into the fiber (no
+  // allocation: forking is the most frequent operation of a recursive program).
+  static constexpr size_t kInlineArg = 48;
+  bool spawn(void (*fn)(void*), const void* arg, size_t arg_bytes);
   // Inside a fiber: suspend until the next release().
   void block();
   // Runs the runnable fibers, first come first served, including those spawned meanwhile, until
@@ -48,11 +52,14 @@ class FiberScheduler {
     void* sp = nullptr;      // saved stack pointer while suspended
     char* stack = nullptr;   // mapping: guard page + stack_bytes_
     std::function<void()> fn;
+    void (*plain)(void*) = nullptr;
+    alignas(16) unsigned char arg[kInlineArg];
     bool done = false;
   };
   static void entry();
   Fiber* acquire();
   void retire(Fiber* f);
+  void make_runnable(Fiber* f);
 
   size_t stack_bytes_;
   void* main_sp_ = nullptr;

@@ -133,31 +133,50 @@ struct Generator {
     evaluate_pending(false);
   }
 
-  // the children of `parent`, left to right; each child's own children are generated by a fiber of
-  // their own (fork) or at once, inside this call
+  // the children of `parent`, left to right.  The subtree under a child that has a next sibling is
+  // generated by a fiber of its own (fork) while this one goes on with the siblings; under the last
+  // child this fiber simply descends - nothing is left for it to do at this level.
   void children(int32_t inst, int32_t parent, uint64_t pkey, int32_t pdepth) {
-    int32_t prev = -1;
-    for (int32_t k = 0;; ++k) {
-      const uint64_t key = drnn_child_key(pkey, k);
-      const int32_t i = node(inst, parent, prev, k, pdepth + 1);
-      if (i < 0) return;
-      await(i);
-      if (failed()) return;
-      const DrnnDecision d = drnn_decide(dec, n_labels, n_out, key, pdepth + 1, k, false, scores(i));
-      out.label[i] = d.label;
-      if (d.has_child) descend(inst, i, key, pdepth + 1);
-      if (failed() || !d.has_sibling) return;
-      prev = i;
+    for (;;) {  // one level per turn
+      int32_t prev = -1, last = -1;
+      uint64_t last_key = 0;
+      for (int32_t k = 0;; ++k) {
+        const uint64_t key = drnn_child_key(pkey, k);
+        const int32_t i = node(inst, parent, prev, k, pdepth + 1);
+        if (i < 0) return;
+        await(i);
+        if (failed()) return;
+        const DrnnDecision d = drnn_decide(dec, n_labels, n_out, key, pdepth + 1, k, false, scores(i));
+        out.label[i] = d.label;
+        if (d.has_child) {
+          if (d.has_sibling && fork && fibers) {
+            spawn_children(inst, i, key, pdepth + 1);
+          } else if (d.has_sibling) {
+            children(inst, i, key, pdepth + 1);  // no fibers for subtrees: depth first
+          } else {
+            last = i;
+            last_key = key;
+          }
+        }
+        if (failed() || !d.has_sibling) break;
+        prev = i;
+      }
+      if (failed() || last < 0) return;
+      parent = last;
+      pkey = last_key;
+      ++pdepth;
     }
   }
 
-  void descend(int32_t inst, int32_t parent, uint64_t pkey, int32_t pdepth) {
-    if (fork && fibers) {
-      ++stats.n_fibers;
-      if (!fibers->spawn([=] { children(inst, parent, pkey, pdepth); })) fail(ACROBAT_ENOMEM, "no memory for a fiber stack");
-    } else {
-      children(inst, parent, pkey, pdepth);
-    }
+  struct ForkArgs { Generator* gen; int32_t inst, parent, pdepth; uint64_t pkey; };
+  static void fork_entry(void* p) {
+    const ForkArgs a = *static_cast<const ForkArgs*>(p);
+    a.gen->children(a.inst, a.parent, a.pkey, a.pdepth);
+  }
+  void spawn_children(int32_t inst, int32_t parent, uint64_t pkey, int32_t pdepth) {
+    ++stats.n_fibers;
+    const ForkArgs a{this, inst, parent, pdepth, pkey};
+    if (!fibers->spawn(&fork_entry, &a, sizeof(a))) fail(ACROBAT_ENOMEM, "no memory for a fiber stack");
   }
 
   void instance(int32_t inst) {
@@ -168,7 +187,7 @@ struct Generator {
     if (failed()) return;
     const DrnnDecision d = drnn_decide(dec, n_labels, n_out, key, 0, 0, true, scores(i));
     out.label[i] = d.label;
-    if (d.has_child) descend(inst, i, key, 0);
+    if (d.has_child) children(inst, i, key, 0);  // a root has no siblings: its fiber descends itself
   }
 };
 
@@ -226,7 +245,11 @@ int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, 
   }
   for (int32_t s = 0; s < n_inst; ++s) {
     ++stats.n_fibers;
-    if (!fibers.spawn([&gen, s] { gen.instance(s); })) { err = "no memory for a fiber stack"; return ACROBAT_ENOMEM; }
+    struct Args { Generator* gen; int32_t inst; } a{&gen, s};
+    if (!fibers.spawn([](void* p) { const Args x = *static_cast<const Args*>(p); x.gen->instance(x.inst); }, &a, sizeof(a))) {
+      err = "no memory for a fiber stack";
+      return ACROBAT_ENOMEM;
+    }
   }
   // all fibers advance until each has finished or waits for scores; then one evaluation for all
   for (;;) {

@@ -821,3 +821,14 @@ def test_generic_runtime_lstm_program(ctx, P):
     sh, sc = P.run_lstm(ctx, w)
     assert np.array_equal(h.cpu().numpy(), sh) and np.array_equal(c.cpu().numpy(), sc)
     g.close()
+
+
+def test_drnn_many_instances(ctx, P):
+    """512 instances at once: evaluations with about a thousand nodes per batch (several node tiles, the wide
+    kernels instead of the latency-bound ones), thousands of fibers alive."""
+    w = gen.drnn_workload(512, 128, 30, 32, seed=95)
+    want = oracle.drnn(w)
+    assert len(want["inst"]) > 10000
+    rc, trees, st, states = P.run_drnn(ctx, w)
+    assert st["n_fibers"] > 2000 and st["n_rounds"] < 30
+    check_drnn(P, w, trees, states, want)

@@ -40,9 +40,11 @@ def test_every_mode_generates_the_oracles_trees(mode, ghosts):
             p = int(got["parent"][i])
             assert got["round"][i] == (got["round"][p] + got["sib_index"][i] + 1 if p >= 0 else 0)
         assert st["n_rounds"] == got["round"].max() + 1
-        has_child = np.zeros(n, bool)
+        # one fiber per instance, one more per subtree that grows while its root's siblings are still generated
+        has_child, has_next = np.zeros(n, bool), np.zeros(n, bool)
         has_child[got["parent"][got["parent"] >= 0]] = True
-        assert st["n_fibers"] == w["n_inst"] + int(has_child.sum())
+        has_next[got["prev"][got["prev"] >= 0]] = True
+        assert st["n_fibers"] == w["n_inst"] + int((has_child & has_next).sum())
     assert st["n_ghosts"] == (int((got["sib_index"] > 0).sum()) if ghosts else 0)
 
 
@@ -90,7 +92,7 @@ def test_many_fibers_and_deep_recursion():
     for _ in range(2):
         rc, got, st = A.acrobat_drnn_schedule(w, A.TDC_FORK_JOIN, True)
         assert rc == A.OK and st["n_nodes"] == len(want["inst"]) > 3000
-        assert st["n_fibers"] > 1000
+        assert st["n_fibers"] > 800
     assert_same_trees(got, want)
     # depth-first generation of whole instances inside one fiber each: recursion max_depth deep
     rc, got, st = A.acrobat_drnn_schedule(w, A.TDC_INSTANCE_FIBERS, True)

@@ -92,7 +92,7 @@ def bench_drnn(args, w, ctx, dev, stream):
     cpu_baseline, err = None, None
     if not args.no_cpu_baseline:
         import oracle
-        from tests.parity import match_trees
+        from workloads.generators import match_trees
         c0 = time.perf_counter()
         ref = oracle.drnn(w)
         c1 = time.perf_counter()

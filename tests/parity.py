@@ -83,32 +83,7 @@ def run_drnn(ctx, w, mode=2, use_ghosts=True, use_bias=True, max_nodes=None, che
     return rc, trees, stats, tuple(v[:n].cpu().numpy() for v in (a, f, g, y))
 
 
-def tree_paths(t):
-    """(instance, child indices from the root) of every node of a generated forest."""
-    out = []
-    for i in range(len(t["inst"])):
-        p, j = [], i
-        while t["parent"][j] >= 0:
-            p.append(int(t["sib_index"][j]))
-            j = int(t["parent"][j])
-        out.append((int(t["inst"][i]), tuple(reversed(p))))
-    return out
-
-
-def match_trees(got, want):
-    """Checks that two forests hold the same positions with the same label, depth and relatives;
-    returns, for every node of `got`, the index of the node of `want` at the same position."""
-    pg, pw = tree_paths(got), tree_paths(want)
-    assert len(set(pg)) == len(pg) == len(pw) and set(pg) == set(pw), "different sets of tree positions"
-    at = {p: i for i, p in enumerate(pw)}
-    for i, p in enumerate(pg):
-        j = at[p]
-        assert got["label"][i] == want["label"][j] and got["depth"][i] == want["depth"][j]
-        assert got["sib_index"][i] == want["sib_index"][j]
-        for rel in ("parent", "prev"):
-            a, b = int(got[rel][i]), int(want[rel][j])
-            assert (a < 0) == (b < 0) and (a < 0 or pg[a] == pw[b])
-    return np.array([at[p] for p in pg], np.int64)
+from workloads.generators import match_trees, tree_paths  # noqa: E402,F401  (structure helpers, shared with bench.py)
 
 
 def errors(got, want, ref_floor=1e-30):

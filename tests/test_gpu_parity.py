@@ -832,3 +832,24 @@ def test_drnn_many_instances(ctx, P):
     rc, trees, st, states = P.run_drnn(ctx, w)
     assert st["n_fibers"] > 2000 and st["n_rounds"] < 30
     check_drnn(P, w, trees, states, want)
+
+
+def test_drnn_refuses_stream_capture(ctx, P):
+    """A call that must read tensor values on the host between its launches cannot be recorded into a graph."""
+    import torch
+    import paper_2305_10611_amd as A
+    w = gen.drnn_workload(4, 64, 5, 32, seed=96)
+    P.run_drnn(ctx, w)  # buffers exist already: the refusal below is not about allocation
+    t = {k: P.dev(np.asarray(w[k], np.float32)) for k in ("x0", "emb", "Wa", "ba", "Wf", "bf", "Wp", "bp", "Wo", "bo")}
+    cap = int(w["cap"])
+    a, f, g = (P.nan_filled(cap, 64) for _ in range(3))
+    y = P.nan_filled(cap, 32)
+    s = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s, capture_error_mode="relaxed"):
+        rc, trees, st = ctx.acrobat_drnn_forward(w, t["x0"], t, a, f, g, y, stream=s.cuda_stream)
+    assert rc == A.EINVAL and "captured" in ctx.acrobat_last_error() and st["n_nodes"] == 0
+    torch.cuda.synchronize()
+    assert torch.isnan(a).all()
+    rc, trees, st, states = P.run_drnn(ctx, w)  # and the context still works
+    check_drnn(P, w, trees, states, oracle.drnn(w))

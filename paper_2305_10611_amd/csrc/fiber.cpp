@@ -174,6 +174,16 @@ void FiberScheduler::run() {
   while (!runnable_.empty()) {
     Fiber* f = runnable_.front();
     runnable_.pop_front();
+    // with thousands of fibers each one's frames have left the cache by the time its turn comes:
+    // fetch those of a fiber a few turns ahead
+    constexpr size_t kAhead = 4;  // (a fiber's turn is shorter than a memory access)
+    if (runnable_.size() >= kAhead) {
+      const char* next = static_cast<const char*>(runnable_[kAhead - 1]->sp);
+      __builtin_prefetch(next);
+      __builtin_prefetch(next + 64);
+      __builtin_prefetch(next + 128);
+      __builtin_prefetch(next + 192);
+    }
     current_ = f;
     ++n_switches_;
     acrobat_fiber_switch(&main_sp_, f->sp);

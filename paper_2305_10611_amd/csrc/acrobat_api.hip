@@ -28,6 +28,7 @@ struct acrobat_ctx {
   std::vector<int32_t> level_off, level_nodes;
   // index staging: pinned host buffer -> device buffer, one copy per forward call
   int32_t* h_stage = nullptr;
+  int32_t* h_stage_dev = nullptr;  // the staging buffer's address on the device side (kernels may read it in place)
   int32_t* d_idx = nullptr;
   size_t stage_cap = 0, idx_cap = 0;  // in int32 elements
   hipEvent_t stage_done = nullptr;    // the last upload out of h_stage has finished
@@ -104,6 +105,7 @@ int reserve_indices(acrobat_ctx* ctx, size_t n, hipStream_t stream) {
     ctx->stage_cap = 0;
     HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_stage), cap * sizeof(int32_t), hipHostMallocDefault));
     ctx->stage_cap = cap;
+    HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->h_stage_dev), ctx->h_stage, 0));
   }
   if (n > ctx->idx_cap) {
     const size_t cap = n + n / 2 + 1024;
@@ -230,9 +232,7 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_
   }
   const int32_t* idx = ctx->d_idx;
   if (indices_in_place) {
-    int32_t* mapped = nullptr;
-    HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&mapped), ctx->h_stage, 0));
-    idx = mapped;
+    idx = ctx->h_stage_dev;
   } else {
     TRY(upload_indices(ctx, 3 * n, stream));
   }

@@ -45,6 +45,8 @@ struct acrobat_ctx {
   size_t zero_row_cap = 0;  // in floats
   float* h_scores = nullptr;
   size_t scores_cap = 0;  // in floats
+  hipStream_t tdc_stream = nullptr;             // second group of instances (the first uses the caller's stream)
+  hipEvent_t tdc_order = nullptr;               // orders the second stream behind the caller's at the start of a call
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
@@ -201,10 +203,13 @@ struct LaunchTimer {
 
 // Executes the graph nodes `first`, `first + 1`, ... bucket by bucket on the stream.  Buckets of one
 // (phase, depth) do not depend on each other; two neighbours with the same shapes share a launch.
-// indices_in_place: the kernels read the index lists straight out of the pinned staging buffer
-// instead of a device copy - one command less in the chain of a short evaluation; only for callers
-// that synchronise the stream before the staging buffer is written again.
-int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_place = false);
+int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream);
+// The launches of run_graph for nodes that g->buckets already holds.  The index lists are written to
+// `st` (pinned host memory, 3 ints per node).  in_place null: st is the context's staging buffer and is
+// uploaded to the device copy; else `in_place` is st's address on the device side and the kernels read
+// the lists straight out of it - one command less in the chain of a short evaluation, for callers that
+// wait for these launches before they write that memory again.
+int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_t* in_place);
 
 int begin_call(acrobat_ctx* ctx) {
   if (!ctx) return ACROBAT_EINVAL;
@@ -214,16 +219,23 @@ int begin_call(acrobat_ctx* ctx) {
   return ACROBAT_OK;
 }
 
-int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_place) {
+int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream) {
   acrobat_ctx* ctx = g->ctx;
   g->graph.bucket(g->buckets, first);
-  const std::vector<DfgNode>& nodes = g->graph.nodes();
   const size_t n = g->buckets.order.size();
   if (n == 0) return ACROBAT_OK;
   TRY(reserve_splitk(ctx, stream));
-  // by bucket position: row written | first operand row | second operand row
   TRY(reserve_indices(ctx, 3 * n, stream));
-  int32_t* st = ctx->h_stage;
+  TRY(launch_buckets(g, stream, ctx->h_stage, nullptr));
+  return ACROBAT_OK;
+}
+
+int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_t* in_place) {
+  acrobat_ctx* ctx = g->ctx;
+  const std::vector<DfgNode>& nodes = g->graph.nodes();
+  const size_t n = g->buckets.order.size();
+  if (n == 0) return ACROBAT_OK;
+  // by bucket position: row written | first operand row | second operand row
   for (size_t p = 0; p < n; ++p) {
     const DfgNode& x = nodes[g->buckets.order[p]];
     st[p] = x.out_row;
@@ -231,8 +243,8 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream, bool indices_in_
     st[2 * n + p] = x.arg1;
   }
   const int32_t* idx = ctx->d_idx;
-  if (indices_in_place) {
-    idx = ctx->h_stage_dev;
+  if (in_place) {
+    idx = in_place;
   } else {
     TRY(upload_indices(ctx, 3 * n, stream));
   }
@@ -340,6 +352,8 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->d_zero_row) (void)hipFree(ctx->d_zero_row);
   if (ctx->h_scores) (void)hipHostFree(ctx->h_scores);
+  if (ctx->tdc_stream) (void)hipStreamDestroy(ctx->tdc_stream);
+  if (ctx->tdc_order) (void)hipEventDestroy(ctx->tdc_order);
   if (ctx->stage_done) (void)hipEventDestroy(ctx->stage_done);
   for (hipEvent_t e : ctx->events) (void)hipEventDestroy(e);
   delete ctx;
@@ -904,7 +918,8 @@ int acrobat_drnn_schedule(int32_t n_inst, int32_t n_labels, const acrobat_drnn_d
                           int32_t use_ghosts, int32_t max_nodes, acrobat_drnn_trees* trees, acrobat_drnn_stats* stats) {
   if (!decisions || n_inst < 0 || max_nodes < 0 || n_labels < 1) return ACROBAT_EINVAL;
   try {
-    Dfg graph;
+    Dfg graph[kMaxTdcGroups];
+    Dfg* graphs[kMaxTdcGroups] = {&graph[0], &graph[1]};
     DfgBuckets buckets;
     std::string err;
     acrobat_drnn_params p{};
@@ -912,18 +927,19 @@ int acrobat_drnn_schedule(int32_t n_inst, int32_t n_labels, const acrobat_drnn_d
     p.emb = p.Wa = p.Wf = p.Wp = p.Wo = kNoTensor;
     float* none = const_cast<float*>(kNoTensor);
     DrnnOps ops;
-    TRY(drnn_register_ops(graph, p, n_inst, max_nodes, kNoTensor, kNoTensor, none, none, none, none, ops, err));
+    for (Dfg& g : graph) TRY(drnn_register_ops(g, p, n_inst, max_nodes, kNoTensor, kNoTensor, none, none, none, none, ops, err));
     DrnnTrees t;
     DrnnStats st;
-    const DrnnEvaluate evaluate = [&](size_t first, int32_t, int32_t, int32_t* n_buckets) {
-      graph.bucket(buckets, first);
+    const DrnnEvaluate evaluate = [&](int32_t group, size_t first, int32_t* n_buckets) {
+      graph[group].bucket(buckets, first);
       *n_buckets = (int32_t)buckets.op.size();
       return ACROBAT_OK;
     };
+    const DrnnWait wait = [](int32_t) { return ACROBAT_OK; };
     const DrnnScores scores = [](int32_t) { return (const float*)nullptr; };
     if (decisions->from_scores) return ACROBAT_EINVAL;  // nothing is computed here: there are no scores to decide from
-    const int rc = drnn_generate(graph, ops, n_inst, n_labels, 32, *decisions, mode, use_ghosts != 0, max_nodes, evaluate, scores,
-                                 t, st, err);
+    const int rc = drnn_generate(graphs, drnn_default_groups(n_inst, mode), ops, n_inst, n_labels, 32, *decisions, mode, use_ghosts != 0, max_nodes,
+                                 evaluate, wait, scores, t, st, err);
     drnn_copy_out(t, st, trees, stats);
     return rc;
   } catch (...) {
@@ -969,29 +985,58 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
     // dependent launches.  d_y receives them all in one copy at the end.
     float* scores_dev = nullptr;  // device-side address of the pinned buffer
     HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&scores_dev), ctx->h_scores, 0));
-    acrobat_dfg g;
-    g.ctx = ctx;
-    DrnnOps ops;
-    {
-      const int rc = drnn_register_ops(g.graph, p, n_inst, max_nodes, d_x0, ctx->d_zero_row, d_a, d_f, d_g, scores_dev, ops, g.err);
-      if (rc != ACROBAT_OK) return fail(ctx, rc, g.err);
+    // Two groups of instances, each with a graph and a stream of its own (the
+    // second stream is the library's, default priority): the host runs one group's program while the
+    // other group's kernels execute.  With per-launch timing on there is one group: its records are
+    // read after every evaluation.
+    const int32_t n_groups = ctx->profiling ? 1 : drnn_default_groups(n_inst, mode);
+    if (!ctx->tdc_stream) HIP_TRY(ctx, hipStreamCreateWithFlags(&ctx->tdc_stream, hipStreamNonBlocking));
+    if (!ctx->tdc_order) HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->tdc_order, hipEventDisableTiming));
+    hipStream_t streams[kMaxTdcGroups] = {stream, ctx->tdc_stream};
+    if (n_groups > 1) {  // what the caller has enqueued so far comes first on the second stream too
+      HIP_TRY(ctx, hipEventRecord(ctx->tdc_order, stream));
+      HIP_TRY(ctx, hipStreamWaitEvent(ctx->tdc_stream, ctx->tdc_order, 0));
     }
-    // one evaluation: the batches of everything invoked since the last one, then wait - the scores
-    // of the new nodes are what the program needs to go on
+    acrobat_dfg g[kMaxTdcGroups];
+    Dfg* graphs[kMaxTdcGroups] = {&g[0].graph, &g[1].graph};
+    DrnnOps ops;
+    for (acrobat_dfg& x : g) {
+      x.ctx = ctx;
+      const int rc = drnn_register_ops(x.graph, p, n_inst, max_nodes, d_x0, ctx->d_zero_row, d_a, d_f, d_g, scores_dev, ops, x.err);
+      if (rc != ACROBAT_OK) return fail(ctx, rc, x.err);
+    }
+    TRY(reserve_splitk(ctx, stream));
+    // Index lists: every group stages its lists in a region of its own of the pinned buffer and its
+    // kernels read them there.  A region is rewritten only after the group's previous evaluation has
+    // been waited for; it grows (both streams idle first) when an evaluation needs more.
+    size_t region = 4096 + 16 * (size_t)n_inst;  // int32 per group
+    TRY(reserve_indices(ctx, (size_t)n_groups * region, stream));
     const size_t n_out = (size_t)p.n_out;
-    const DrnnEvaluate evaluate = [&](size_t first, int32_t, int32_t, int32_t* n_buckets) {
-      TRY(run_graph(&g, first, stream, /*indices_in_place=*/true));  // (synchronised below, before the next staging)
-      *n_buckets = (int32_t)g.buckets.op.size();
-      HIP_TRY(ctx, hipStreamSynchronize(stream));
+    const DrnnEvaluate evaluate = [&](int32_t k, size_t first, int32_t* n_buckets) {
+      g[k].graph.bucket(g[k].buckets, first);
+      *n_buckets = (int32_t)g[k].buckets.op.size();
+      const size_t need = 3 * g[k].buckets.order.size();
+      if (need > region) {
+        for (int32_t q = 0; q < n_groups; ++q) HIP_TRY(ctx, hipStreamSynchronize(streams[q]));
+        region = 2 * need;
+        TRY(reserve_indices(ctx, (size_t)n_groups * region, stream));
+      }
+      TRY(launch_buckets(&g[k], streams[k], ctx->h_stage + (size_t)k * region, ctx->h_stage_dev + (size_t)k * region));
+      return ACROBAT_OK;
+    };
+    // (each group has a stream to itself; waiting for the stream measured faster than waiting for an event on it)
+    const DrnnWait wait = [&](int32_t k) {
+      HIP_TRY(ctx, hipStreamSynchronize(streams[k]));
       return ACROBAT_OK;
     };
     const DrnnScores scores = [&](int32_t node) { return (const float*)(ctx->h_scores + (size_t)node * n_out); };
     DrnnTrees t;
     DrnnStats st;
     std::string err;
-    const int rc = drnn_generate(g.graph, ops, n_inst, p.n_labels, p.n_out, *decisions, mode, use_ghosts != 0, max_nodes, evaluate,
-                                 scores, t, st, err);
+    const int rc = drnn_generate(graphs, n_groups, ops, n_inst, p.n_labels, p.n_out, *decisions, mode, use_ghosts != 0, max_nodes,
+                                 evaluate, wait, scores, t, st, err);
     drnn_copy_out(t, st, trees, stats);
+    for (int32_t q = 0; q < n_groups; ++q) HIP_TRY(ctx, hipStreamSynchronize(streams[q]));
     if (!t.inst.empty()) {
       HIP_TRY(ctx, hipMemcpyAsync(d_y, ctx->h_scores, t.inst.size() * n_out * sizeof(float), hipMemcpyHostToDevice, stream));
       HIP_TRY(ctx, hipStreamSynchronize(stream));

@@ -28,7 +28,7 @@ struct DrnnTrees {  // one entry per generated node, in the order of creation
 };
 
 struct DrnnStats {
-  int32_t n_rounds = 0;    // evaluations
+  int32_t n_rounds = 0;    // evaluations (of the group that needed most)
   int32_t n_buckets = 0;   // batches over all evaluations
   int32_t n_fibers = 0;    // fibers started
   int32_t n_ghosts = 0;    // ghost operations invoked
@@ -44,17 +44,33 @@ uint64_t drnn_child_key(uint64_t parent_key, int32_t k);
 DrnnDecision drnn_decide(const acrobat_drnn_decisions& d, int32_t n_labels, int32_t n_out, uint64_t key, int32_t depth,
                          int32_t k, bool is_root, const float* y);
 
-// evaluate(first_dfg_node, first_tree_node, n_tree_nodes, &n_buckets): executes the graph nodes from
-// first_dfg_node on and makes the scores of the tree nodes [first_tree_node, + n_tree_nodes)
-// readable through scores(node) (may return null when nothing is computed at all).
-using DrnnEvaluate = std::function<int(size_t, int32_t, int32_t, int32_t*)>;
+// The instances are dealt out to n_groups groups (instance s to group s % n_groups), each with a
+// graph and a set of fibers of its own.  While one group's operators execute, the host runs the
+// program of the other: the two never wait at the same time (with one group the host and the device
+// simply alternate).
+//   evaluate(group, first_graph_node, &n_buckets)  starts the execution of that group's graph nodes
+//     from first_graph_node on and returns without waiting;
+//   wait(group)  returns when everything started for the group has finished; the scores of its nodes
+//     are then readable through scores(node) (which may return null when nothing is computed at all).
+using DrnnEvaluate = std::function<int(int32_t, size_t, int32_t*)>;
+using DrnnWait = std::function<int(int32_t)>;
 using DrnnScores = std::function<const float*(int32_t)>;
 
-// Runs the generation program for n_inst instances.  mode: ACROBAT_TDC_*.  use_ghosts: align the
-// ancestral cell of a later sibling with its fraternal cell by a ghost operation.  Fails with
-// ACROBAT_ENOMEM when more than max_nodes nodes would be generated.
-int drnn_generate(Dfg& g, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, int32_t n_out, const acrobat_drnn_decisions& dec,
-                  int32_t mode, bool use_ghosts, int32_t max_nodes, const DrnnEvaluate& evaluate,
-                  const DrnnScores& scores, DrnnTrees& out, DrnnStats& stats, std::string& err);
+constexpr int32_t kMaxTdcGroups = 2;
+// Two groups pay once the host program of an evaluation takes longer than issuing its launches a
+// second time (measured: from about 200 instances on, 4 % at 256, 18 % at 1024; below, the host is
+// busier with two groups than it was idle with one).
+inline int32_t drnn_default_groups(int32_t n_inst, int32_t mode) {
+  return mode != ACROBAT_TDC_SEQUENTIAL && n_inst >= 192 ? kMaxTdcGroups : 1;
+}
+
+// Runs the generation program for n_inst instances.  graphs[0 .. n_groups): one graph per group, the
+// operators registered alike in each.  mode: ACROBAT_TDC_* (without fibers there is one group).
+// use_ghosts: align the ancestral cell of a later sibling with its fraternal cell by a ghost
+// operation.  Fails with ACROBAT_ENOMEM when more than max_nodes nodes would be generated.
+int drnn_generate(Dfg* const* graphs, int32_t n_groups, const DrnnOps& ops, int32_t n_inst, int32_t n_labels, int32_t n_out,
+                  const acrobat_drnn_decisions& dec, int32_t mode, bool use_ghosts, int32_t max_nodes,
+                  const DrnnEvaluate& evaluate, const DrnnWait& wait, const DrnnScores& scores, DrnnTrees& out,
+                  DrnnStats& stats, std::string& err);
 
 }  // namespace acrobat

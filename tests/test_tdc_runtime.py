@@ -49,17 +49,24 @@ def test_every_mode_generates_the_oracles_trees(mode, ghosts):
 
 
 def test_ghosts_give_one_batch_per_operator_and_evaluation():
-    w = gen.drnn_workload(40, 32, 5, 32, seed=82, max_depth=6, max_children=4)
+    w = gen.drnn_workload(200, 32, 5, 32, seed=82, max_depth=5, max_children=4)
     rc, t, with_ghosts = A.acrobat_drnn_schedule(w, A.TDC_FORK_JOIN, True)
     rc2, _, without = A.acrobat_drnn_schedule(w, A.TDC_FORK_JOIN, False)
     assert rc == rc2 == A.OK and with_ghosts["n_rounds"] == without["n_rounds"]
-    # operators present in an evaluation: ancestral cell (root variant in evaluation 0), fraternal cell
-    # of later siblings, predictive cell, scores; the constant fraternal state of first children is
-    # computed with the roots and their own rows are written by one batch at the very end
-    want = 1 + int((t["parent"] >= 0).any())
-    for r in range(with_ghosts["n_rounds"]):
-        sel = t["round"] == r
-        want += 3 + int((t["sib_index"][sel] > 0).any())
+    # From 192 instances on they are dealt out to two groups (even / odd), each evaluated on its own.  Operators present in
+    # an evaluation of a group: ancestral cell (root variant in evaluation 0), fraternal cell of later siblings,
+    # predictive cell, scores; the constant fraternal state of first children is computed with the group's
+    # roots, and the first children's own rows are written by one batch at the very end.
+    want = int((t["parent"] >= 0).any())
+    for grp in (0, 1):
+        mine = t["inst"] % 2 == grp
+        want += 1
+        for r in range(int(t["round"][mine].max()) + 1):
+            sel = mine & (t["round"] == r)
+            assert sel.any()
+            want += 3 + int((t["sib_index"][sel] > 0).any())
+    assert with_ghosts["n_buckets"] == want
+    assert with_ghosts["n_rounds"] == t["round"].max() + 1
     assert without["n_buckets"] > want  # later siblings' ancestral cells sit at their parent's depth: extra batches
 
 

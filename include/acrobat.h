@@ -300,7 +300,12 @@ int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** buc
  * (node ids, -1: none), index among the siblings, depth (root 0), label, and the evaluation
  * (0, 1, ...) that computed the node.  ACROBAT_ENOMEM if more than max_nodes nodes would be
  * generated (device rows written so far stay written).  The call synchronises the stream at every
- * evaluation and returns when the last one has finished.  Requires H and n_out multiples of 32. */
+ * evaluation and returns when the last one has finished.  From 192 instances on (fiber modes,
+ * profiling off) the instances are dealt out to two groups - instance s to group s mod 2 - that are
+ * evaluated independently, the second on a stream of the library's own (default priority, ordered
+ * behind what the given stream holds at the call): the host runs one group's program while the
+ * other's kernels execute; `round` then counts each group's evaluations.  Requires H and n_out
+ * multiples of 32. */
 #define ACROBAT_TDC_SEQUENTIAL 0
 #define ACROBAT_TDC_INSTANCE_FIBERS 1
 #define ACROBAT_TDC_FORK_JOIN 2

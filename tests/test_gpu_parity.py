@@ -853,3 +853,42 @@ def test_drnn_refuses_stream_capture(ctx, P):
     assert torch.isnan(a).all()
     rc, trees, st, states = P.run_drnn(ctx, w)  # and the context still works
     check_drnn(P, w, trees, states, oracle.drnn(w))
+
+
+def test_saturated_gates_stay_finite(ctx, P):
+    """Pre-activations of several hundred in both directions: the fast sigmoid / tanh forms must saturate to
+    0, 1 and -1 without producing inf or NaN.  (With weights this large an fp32 pre-activation is only good to
+    about 1e-3, so the few gates that happen to land near their transition differ from the oracle by that much:
+    the comparison here is loose; the tolerances proper are tested at ordinary scales.)"""
+    def loosely_close(got, want, what):
+        assert np.isfinite(got).all(), what
+        diff = np.abs(got.astype(np.float64) - want)
+        assert diff.max() < 0.05 and (diff > 1e-3).mean() < 0.01, f"{what}: max {diff.max():.2e}, {(diff > 1e-3).mean():.2%} above 1e-3"
+
+    w = gen.treelstm_workload(12, 1, 24, 64, 50, "uniform", seed=88, bias_scale=0.0)
+    rng = gen.make_rng(89)
+    for k in ("W_leaf", "U"):
+        w[k] = (w[k] * np.float32(400.0)).astype(np.float32)
+    w["b_leaf"] = gen.uniform_f32(w["b_leaf"].shape, 300.0, rng)
+    w["b"] = gen.uniform_f32(w["b"].shape, 300.0, rng)
+    h, c = P.run_treelstm(ctx, w)
+    oh, oc = oracle.treelstm(w, nthreads=NT)
+    assert np.abs(oc).max() > 3.0 and (np.abs(oh) > 0.999).any() and (np.abs(oh) < 1e-6).any()  # saturated both ways
+    assert np.abs(h).max() <= 1.0
+    loosely_close(h, oh, "h")
+    loosely_close(c, oc, "c")
+    s_ = gen.lstm_workload(20, 1, 12, 64, 32, seed=90, bias_scale=0.0)
+    for k in ("Wx", "Wh"):
+        s_[k] = (s_[k] * np.float32(400.0)).astype(np.float32)
+    s_["b"] = gen.uniform_f32(s_["b"].shape, 300.0, rng)
+    h, c = P.run_lstm(ctx, s_)
+    oh, oc = oracle.varlen_lstm(s_, nthreads=NT)
+    loosely_close(h, oh, "lstm h")
+    loosely_close(c, oc, "lstm c")
+    m = gen.mvrnn_workload(6, 2, 9, 64, seed=91)
+    m["W"] = (m["W"] * np.float32(300.0)).astype(np.float32)  # tanh(W v) saturates
+    vec, mat = P.run_mvrnn(ctx, m)
+    ov, om = oracle.mvrnn(m, nthreads=NT)
+    internal = m["left"] >= 0
+    assert (np.abs(ov[internal]) > 0.999).any() and np.abs(vec[internal]).max() <= 1.0
+    loosely_close(vec[internal], ov[internal], "vec")

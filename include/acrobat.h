@@ -37,6 +37,10 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+/* The library is built with hidden symbol visibility; what this header declares is its whole ABI. */
+#if defined(__GNUC__)
+#pragma GCC visibility push(default)
+#endif
 
 #define ACROBAT_OK 0
 #define ACROBAT_EINVAL (-1)  /* null pointer, negative size, unsupported shape            */
@@ -71,8 +75,8 @@ typedef struct {
 /* ---- host level scheduler (no GPU needed) --------------------------------------------
  * Depth schedule of section 4.1 (footnote: depth = 0 for a node that consumes nothing
  * produced in the graph, else 1 + the largest producer depth; batches run by increasing
- * depth).  One schedule node is one whole cell (grain-size coarsening, appendix B.2), all
- * leaves sit in level 0 (hoisted input transforms, appendix B.1) and the two children of a
+ * depth).  One schedule node is one whole cell (grain-size coarsening, appendix "Grain Size Coarsening"), all
+ * leaves sit in level 0 (hoisted input transforms, appendix "Operator Hoisting") and the two children of a
  * node are concurrent.  Inside a level nodes are listed by ascending global id.
  *
  * Outputs are caller-allocated host arrays: level_off[N + 1] (only n_levels + 1 entries are
@@ -88,7 +92,7 @@ int acrobat_schedule_trees(const acrobat_trees* trees, int32_t vocab, int32_t* n
 int acrobat_schedule_seqs(int32_t n_seq, const int32_t* len, int32_t* n_levels,
                           int32_t* level_off, int32_t* level_rows);
 
-/* Bidirectional-RNN schedule with program phases (section 4.1, appendix B.4): operators of a phase
+/* Bidirectional-RNN schedule with program phases (section 4.1, appendix "Combating Eagerness of Depth Scheduling"): operators of a phase
  * are scheduled and executed before any operator of the next phase, so depth counts inside a
  * phase.  Phase 0 holds the two recurrences (listing 2: step k of a direction has depth k), phase 1
  * every per-token output operator - all of them in ONE batch although the sequences differ in
@@ -106,7 +110,7 @@ int acrobat_schedule_birnn(int32_t n_seq, const int32_t* len, int32_t* n_levels,
  * Level 0 is one batched kernel over all leaves that gathers embedding rows by token id
  * (hoisting + gather fusion, section 5.2); each later level is one kernel that gathers the
  * children's h and c rows by index, contracts [n_level x 2H] with U^T (all five gates in one
- * pass: horizontal fusion, appendix B.3) and applies the gates (vertical fusion).
+ * pass: horizontal fusion, appendix "Exploiting Data Reuse") and applies the gates (vertical fusion).
  * Requires H, D multiples of 32.  d_h and d_c receive one row per node, row = global node id.
  * Device pointers: d_emb [V,D], d_Wleaf [5H,D], d_bleaf [5H] or NULL (= 0), d_U [5H,2H],
  * d_b [5H] or NULL, d_h / d_c [N,H] (written). */
@@ -127,12 +131,12 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
                           const float* d_WM, float* d_vec, float* d_mat, int32_t copy_leaves,
                           void* hip_stream);
 
-/* Variable-length LSTM (recurrence of listing 1 with the four-gate cell of appendix B.3).
+/* Variable-length LSTM (recurrence of listing 1 with the four-gate cell of appendix "Exploiting Data Reuse").
  * Gate order of the 4H rows: (i, f, o, u);  z = W_x x_t + W_h h_{t-1} + b ;
  * c_t = s(z_f) c_{t-1} + s(z_i) tanh(z_u) ; h_t = s(z_o) tanh(c_t) ; h_{-1} = c_{-1} = 0.
  * len[n_seq] (host, each >= 0).  Rows are packed sequence-major: row(s,t) = seq_off[s] + t.
  * The input transform of all steps of all sequences runs first as one dense batch (hoisted,
- * appendix B.1); then one kernel per time step over the still-active sequences.
+ * appendix "Operator Hoisting"); then one kernel per time step over the still-active sequences.
  * Requires H, D multiples of 32.  d_x [sum len, D], d_Wx [4H,D], d_Wh [4H,H], d_b [4H] or
  * NULL, d_h / d_c [sum len, H] (written). */
 int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, int32_t H,
@@ -141,8 +145,8 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
                                 void* hip_stream);
 
 /* Bidirectional RNN with a per-token output layer (the BiRNN of table 3; cell of listing 1 used
- * in both directions with separate parameters, appendix C.1; output operators batched by program
- * phases, section 7.5).  With p = forward or backward:
+ * in both directions with separate parameters, appendix "Exploiting Data Reuse" (code duplication); output operators batched by program
+ * phases, Evaluation, "Benefits of Optimizations").  With p = forward or backward:
  *   hf_t = s(Wf_x x_t + bf + Wf_h hf_{t-1}), hf_{-1} = f.h_init     (steps t = 0 .. len-1)
  *   hb_t = s(Wb_x x_t + bb + Wb_h hb_{t+1}), hb_{len} = b.h_init    (steps t = len-1 .. 0)
  *   y_t  = relu(cb + C [hf_t ; hb_t])                               (C: [n_out, 2H])
@@ -165,7 +169,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
                           float* d_hf, float* d_hb, float* d_y, void* hip_stream);
 
 /* ---- generic runtime: batched execution of an explicit dataflow graph ---------------------
- * The step before the specialised entry points above (section 4.1, listing 2; appendix C): the
+ * The step before the specialised entry points above (section 4.1, listing 2; appendix "Other Details"): the
  * unbatched program of a mini-batch calls acrobat_dfg_invoke once per operator instance, passing
  * the depth it computed inline, and acrobat_dfg_run executes the graph bucket by bucket - a
  * bucket being all nodes of one (phase, depth, op), in ascending node id - with one batched
@@ -185,7 +189,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
  *   RNN_STEP       h[out_row] = sigmoid(z + bias + zadd[out_row, H])   (zadd NULL: no such term)
  *   RELU_OUT       y[out_row*ldo + j] = relu(z + bias[j]) for j < n_cols (W has n_cols rows; H = n_cols
  *                  rounded up to a multiple of 32)
- *   MVRNN          the matrix-vector cell (section 7.2), no contraction segments (nseg = 0): H = d, 64 or 128;
+ *   MVRNN          the matrix-vector cell (Evaluation, "Overall Performance"), no contraction segments (nseg = 0): H = d, 64 or 128;
  *                  arg0 / arg1 name the left / right child - a value >= 0 is a row of the arenas h = vec
  *                  [out_rows, d] and c = mat [out_rows, d, d] (an internal child), a value -(t + 1) is row t of
  *                  the tables src0 = vec_tab [src0_rows, d] and src1 = mat_tab [src0_rows, d, d] (a leaf child,
@@ -247,7 +251,7 @@ int acrobat_dfg_invoke(acrobat_dfg* g, int32_t op, int32_t phase, int32_t depth,
  * row tree_off[t] + j.  Same structure checks and error codes as acrobat_schedule_trees. */
 int acrobat_dfg_build_treelstm(acrobat_dfg* g, const acrobat_trees* trees, int32_t vocab,
                                int32_t op_leaf, int32_t op_internal);
-/* Adds a ghost operation (section 4.1, appendix B.4): a node that occupies `depth` and is never
+/* Adds a ghost operation (section 4.1, appendix "Combating Eagerness of Depth Scheduling"): a node that occupies `depth` and is never
  * executed.  A program whose branches reach the same operator after different numbers of steps
  * invokes ghosts on the shorter branch and names the ghost as the operator's producer, so the
  * operator lands at one depth - in one batch - for every instance.  Checked against `prod` (a
@@ -276,7 +280,7 @@ int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** buc
  *   f_i = s(Wf [f_q ; emb[l_q]] + bf)   (first child and root: f_q = 0, l_q = 0)
  *   g_i = s(Wp [a_i ; f_i] + bp)        y_i = Wo g_i + bo        s(t) = 1 / (1 + exp(-t))
  * Whether i has children, whether a sibling follows, and its label l_i are decided once y_i is
- * on the host.  As in the paper's evaluation (section 7.2, untrained parameters) the decisions
+ * on the host.  As in the paper's evaluation (Evaluation, "Overall Performance", untrained parameters) the decisions
  * are emulated: a counter-based generator (splitmix64 steps) keyed by the node's position -
  * key(root of instance s) = mix(seed ^ mix(s)), key(child k) = mix(key(parent) + k + 1);
  * children iff depth + 1 < max_depth and u(mix(key ^ 1)) < p_child; sibling iff not the root,
@@ -290,7 +294,7 @@ int acrobat_dfg_schedule(acrobat_dfg* g, int32_t* n_buckets, const int32_t** buc
  * operation to the depth of its fraternal cell, so each evaluation has one batch per operator.
  *
  * The fraternal state of a first child depends on the parameters only (no previous sibling: zero
- * state, label 0).  Like other constant tensors (section 7.2) it is computed once, with the roots,
+ * state, label 0).  Like other constant tensors (Evaluation, "Overall Performance") it is computed once, with the roots,
  * and reused by its consumers; the first children's own rows of d_f are written by one more batch
  * after the last evaluation.
  *
@@ -319,7 +323,10 @@ typedef struct {
    * iff depth + 1 < max_depth and y[0] > 0; a sibling follows iff the node is not a root,
    * k + 1 < max_children and y[1] > 0; label = the first l with the largest y[2 + l],
    * l < min(n_labels, n_out - 2) - seed, p_child and p_sibling are then unused, and
-   * acrobat_drnn_schedule (which has no scores) refuses the mode. */
+   * acrobat_drnn_schedule (which has no scores) refuses the mode.  The scores are fp32 results: a
+   * score within rounding error of its threshold (or two label scores that close to each other) may
+   * legitimately decide differently than a higher-precision evaluation would, and the tree then grows
+   * differently from there on. */
   int32_t from_scores;
 } acrobat_drnn_decisions;
 
@@ -391,16 +398,30 @@ typedef struct {
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 
-/* Ablation of gather fusion (section 5.2; measured in the paper's section 7.5).  Enabled (the
+/* Ablation of gather fusion (section 5.2; measured in the paper's Evaluation, "Benefits of Optimizations").  Enabled (the
  * default), the level kernels read their operand rows in place through the index lists.  Disabled,
  * acrobat_treelstm_forward first copies every level's operand rows (embedding rows; child h and c
  * rows) into contiguous scratch with an explicit gather launch and the level kernel reads the
  * copies - the scheme of frameworks without gather fusion.  Results are bit-identical. */
 int acrobat_set_gather_fusion(acrobat_ctx* ctx, int32_t enabled);
+
+/* Tuning and test hook; no result ever depends on it beyond the summation order of the contraction.
+ * The launcher normally picks a kernel variant per level from the level's size.  force_tile != 0 makes
+ * every cell level of this context use one variant instead: 64 or 32 = nodes per workgroup tile of the
+ * tiled kernel, 6 = the kernel for latency-bound levels; force_ksplit (a power of two up to 32, 0 =
+ * automatic) is then the number of workgroups sharing a tile's contraction range (tile 6: slabs moved
+ * per step, 4 or 8).  A forced shape that does not apply to a level (k range not divisible, workspace
+ * too small) falls back to the automatic choice for that level.  mvrnn_variant: 0 = default MV-RNN
+ * level kernels, 1 = the streaming kernel.  All zero restores the defaults.  The library reads no
+ * environment variables. */
+int acrobat_set_tuning(acrobat_ctx* ctx, int32_t force_tile, int32_t force_ksplit, int32_t mvrnn_variant);
 /* Records of the last forward call (context-owned, valid until the next forward call). */
 int acrobat_last_profile(const acrobat_ctx* ctx, int32_t* n_records,
                          const acrobat_launch_record** records);
 
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
 #ifdef __cplusplus
 }
 #endif

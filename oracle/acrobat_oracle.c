@@ -18,23 +18,23 @@
  *
  *   binary TreeLSTM, gates (i, f_l, f_r, o, u), each with its own weight block:
  *     leaf:      z = W_leaf x + b_leaf,  x = E[token],  children's h and c are the
- *                shared constant zero state (section 7.2: the leaf state is a
+ *                shared constant zero state (Evaluation, "Overall Performance": the leaf state is a
  *                constant tensor created once)
  *     internal:  z = U [h_l ; h_r] + b   (the input transform only exists at
- *                leaves: it is the hoisted, depth-0 part; appendix B.1)
+ *                leaves: it is the hoisted, depth-0 part; appendix "Operator Hoisting")
  *     i=s(z[0:H]) f_l=s(z[H:2H]) f_r=s(z[2H:3H]) o=s(z[3H:4H]) u=tanh(z[4H:5H])
  *     c = i*u + f_l*c_l + f_r*c_r        h = o*tanh(c)       s(t)=1/(1+exp(-t))
  *
  *   MV-RNN (each node carries a vector and a matrix; left child (a,A), right (b,B)):
- *     p = tanh(W [B a ; A b])     P = W_M [A ; B]     (section 7.2: the model
+ *     p = tanh(W [B a ; A b])     P = W_M [A ; B]     (Evaluation, "Overall Performance": the model
  *     multiplies two intermediate activations); a leaf's (a,A) are table rows.
  *
- *   LSTM along a sequence (listing 1/2 structure, appendix B.3 "four gates"):
+ *   LSTM along a sequence (listing 1/2 structure, appendix "Exploiting Data Reuse" "four gates"):
  *     z = W_x x_t + W_h h_{t-1} + b, gates (i, f, o, u),
  *     c_t = f*c_{t-1} + i*u,  h_t = o*tanh(c_t),  h_{-1} = c_{-1} = 0.
  *
  *   bidirectional RNN with a per-token output layer (listing 1's cell in both directions,
- *   appendix C.1; output operators as in token classification, section 7.5):
+ *   appendix "Exploiting Data Reuse" (code duplication); output operators as in token classification, Evaluation, "Benefits of Optimizations"):
  *     forward:   hf_t = s(Wf_x x_t + bf + Wf_h hf_{t-1}),  hf_{-1} = f_init (a parameter)
  *     backward:  hb_t = s(Wb_x x_t + bb + Wb_h hb_{t+1}),  hb_{len} = b_init (same cell on the
  *                reversed sequence, own parameters)
@@ -45,7 +45,7 @@
  *     nodes run by increasing depth.  Order inside one depth is a convention
  *     (ascending global node id): members of a batch are independent.
  *
- *   program phases (section 4.1, appendix B.4): operators of a phase are scheduled and
+ *   program phases (section 4.1, appendix "Combating Eagerness of Depth Scheduling"): operators of a phase are scheduled and
  *     executed before any operator of the next phase, so depth is counted inside a phase: a
  *     node's depth is 0 if it has no producer in its own phase.
  *
@@ -60,7 +60,7 @@
  *     y_i = W_o g_i + b_o                   scores: has children, has a next sibling, labels
  *   Whether i gets children, whether a sibling follows it, and its label l_i are decisions taken
  *   once y_i exists (tensor-dependent control flow, section 4.2).  As in the paper's evaluation
- *   (section 7.2) they are emulated pseudo-randomly: a counter-based generator keyed by the
+ *   (Evaluation, "Overall Performance") they are emulated pseudo-randomly: a counter-based generator keyed by the
  *   node's position (instance, path of child indices from the root), so the tree an instance
  *   grows does not depend on the order in which nodes are evaluated.  Alternatively they are read
  *   off the scores: children iff y[0] > 0 (and the depth limit allows), a sibling follows iff

@@ -123,6 +123,7 @@ def _load():
     lib.acrobat_last_schedule.argtypes = [vp, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
     lib.acrobat_set_profiling.argtypes = [vp, i32]
     lib.acrobat_set_gather_fusion.argtypes = [vp, i32]
+    lib.acrobat_set_tuning.argtypes = [vp, i32, i32, i32]
     lib.acrobat_last_profile.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(acrobat_launch_record))]
     return lib
 
@@ -378,6 +379,9 @@ class Context:
 
     def acrobat_set_gather_fusion(self, enabled: bool) -> int:
         return lib.acrobat_set_gather_fusion(self._h, int(bool(enabled)))
+
+    def acrobat_set_tuning(self, force_tile=0, force_ksplit=0, mvrnn_variant=0) -> int:
+        return lib.acrobat_set_tuning(self._h, force_tile, force_ksplit, mvrnn_variant)
 
     def acrobat_last_profile(self):
         n, p = C.c_int32(0), C.POINTER(acrobat_launch_record)()

@@ -14,6 +14,8 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed fp32 instructions are switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # only the C ABI declared in include/acrobat.h is exported
+    "-fvisibility=hidden", "-fvisibility-inlines-hidden",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 
@@ -26,12 +28,14 @@ def needs_build() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    deps = (sources() + glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.map")) +
+            glob.glob(os.path.join(ROOT, "include", "*.h")))
     return any(os.path.getmtime(p) > t for p in deps)
 
 
 def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
+    cmd = ["hipcc", *HIPCC_FLAGS, "-Wl,--version-script=" + os.path.join(CSRC, "acrobat.map"),
+           "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", LIB, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

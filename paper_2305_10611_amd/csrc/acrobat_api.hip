@@ -148,9 +148,6 @@ int reserve_splitk(acrobat_ctx* ctx, hipStream_t stream) {
   HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
   ctx->splitk.partial = p;
   ctx->splitk.partial_floats = kPartialFloats;
-  // tuning override for experiments: ACROBAT_FORCE_TILE=128|64|32|16, ACROBAT_FORCE_KSPLIT=1..32
-  if (const char* v = std::getenv("ACROBAT_FORCE_TILE")) ctx->splitk.force_bm = std::atoi(v);
-  if (const char* v = std::getenv("ACROBAT_FORCE_KSPLIT")) ctx->splitk.force_ksplit = std::atoi(v);
   return ACROBAT_OK;
 }
 
@@ -209,7 +206,9 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream);
 // uploaded to the device copy; else `in_place` is st's address on the device side and the kernels read
 // the lists straight out of it - one command less in the chain of a short evaluation, for callers that
 // wait for these launches before they write that memory again.
-int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_t* in_place);
+// `ws`: the k-split workspace these launches may use.  Callers that keep several groups of launches in
+// flight on different streams hand every group a region of its own.
+int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_t* in_place, const SplitKWorkspace& ws);
 
 int begin_call(acrobat_ctx* ctx) {
   if (!ctx) return ACROBAT_EINVAL;
@@ -226,11 +225,11 @@ int run_graph(acrobat_dfg* g, size_t first, hipStream_t stream) {
   if (n == 0) return ACROBAT_OK;
   TRY(reserve_splitk(ctx, stream));
   TRY(reserve_indices(ctx, 3 * n, stream));
-  TRY(launch_buckets(g, stream, ctx->h_stage, nullptr));
+  TRY(launch_buckets(g, stream, ctx->h_stage, nullptr, ctx->splitk));
   return ACROBAT_OK;
 }
 
-int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_t* in_place) {
+int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_t* in_place, const SplitKWorkspace& ws) {
   acrobat_ctx* ctx = g->ctx;
   const std::vector<DfgNode>& nodes = g->graph.nodes();
   const size_t n = g->buckets.order.size();
@@ -297,13 +296,13 @@ int launch_buckets(acrobat_dfg* g, hipStream_t stream, int32_t* st, const int32_
     if (b + 1 < n_buckets && same_batch_shape(b, b + 1)) {
       const CellLevelArgs a1 = level_args(b + 1);
       TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, a.n + a1.n));
-      HIP_TRY(ctx, launch_cell_level_pair(kEpi[d.epilogue], a, a1, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
+      HIP_TRY(ctx, launch_cell_level_pair(kEpi[d.epilogue], a, a1, stream, ws, timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
       ++b;
       continue;
     }
     TRY(timer.begin(ACROBAT_K_DFG_BUCKET, (int32_t)b, a.n));
-    HIP_TRY(ctx, launch_cell_level(kEpi[d.epilogue], a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
+    HIP_TRY(ctx, launch_cell_level(kEpi[d.epilogue], a, stream, ws, timer.tile(), timer.ksplit(), timer.ev));
     TRY(timer.end());
   }
   return timer.finish();
@@ -1006,6 +1005,14 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
       if (rc != ACROBAT_OK) return fail(ctx, rc, x.err);
     }
     TRY(reserve_splitk(ctx, stream));
+    // The groups' launches overlap on their streams, and a k-split level parks its partial tiles in the
+    // workspace between its two launches: every group gets a region of its own.
+    SplitKWorkspace group_ws[kMaxTdcGroups];
+    for (int32_t q = 0; q < n_groups; ++q) {
+      group_ws[q] = ctx->splitk;
+      group_ws[q].partial_floats = ctx->splitk.partial_floats / (size_t)n_groups;
+      group_ws[q].partial = ctx->splitk.partial + (size_t)q * group_ws[q].partial_floats;
+    }
     // Index lists: every group stages its lists in a region of its own of the pinned buffer and its
     // kernels read them there.  A region is rewritten only after the group's previous evaluation has
     // been waited for; it grows (both streams idle first) when an evaluation needs more.
@@ -1021,7 +1028,8 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
         region = 2 * need;
         TRY(reserve_indices(ctx, (size_t)n_groups * region, stream));
       }
-      TRY(launch_buckets(&g[k], streams[k], ctx->h_stage + (size_t)k * region, ctx->h_stage_dev + (size_t)k * region));
+      TRY(launch_buckets(&g[k], streams[k], ctx->h_stage + (size_t)k * region, ctx->h_stage_dev + (size_t)k * region,
+                         group_ws[k]));
       return ACROBAT_OK;
     };
     // (each group has a stream to itself; waiting for the stream measured faster than waiting for an event on it)
@@ -1062,6 +1070,19 @@ int acrobat_last_schedule(const acrobat_ctx* ctx, int32_t* n_levels, const int32
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled) {
   if (!ctx) return ACROBAT_EINVAL;
   ctx->profiling = enabled != 0;
+  return ACROBAT_OK;
+}
+
+int acrobat_set_tuning(acrobat_ctx* ctx, int32_t force_tile, int32_t force_ksplit, int32_t mvrnn_variant) {
+  if (!ctx) return ACROBAT_EINVAL;
+  if (force_tile != 0 && force_tile != 6 && force_tile != 32 && force_tile != 64)
+    return fail(ctx, ACROBAT_EINVAL, "force_tile must be 0, 6, 32 or 64");
+  if (force_ksplit < 0 || force_ksplit > 32 || (force_ksplit & (force_ksplit - 1)))
+    return fail(ctx, ACROBAT_EINVAL, "force_ksplit must be 0 or a power of two up to 32");
+  if (mvrnn_variant != 0 && mvrnn_variant != 1) return fail(ctx, ACROBAT_EINVAL, "mvrnn_variant must be 0 or 1");
+  ctx->splitk.force_bm = force_tile;
+  ctx->splitk.force_ksplit = force_ksplit;
+  ctx->mvrnn_variant = mvrnn_variant;
   return ACROBAT_OK;
 }
 

@@ -5,8 +5,8 @@
 // level's operand rows straight from the arena through index lists instead of from a
 // gathered contiguous copy (gather fusion, section 5.2), contracts them with the shared
 // weight matrix once for all gates (parameter reuse, section 5.1; horizontal fusion,
-// appendix B.3) on the fp32 matrix cores and applies the gate non-linearities and the state
-// update before anything is written back (vertical fusion, section 7.5).
+// appendix "Exploiting Data Reuse") on the fp32 matrix cores and applies the gate non-linearities and the state
+// update before anything is written back (vertical fusion, Evaluation, "Benefits of Optimizations").
 //
 // Tiling.  A workgroup of four wavefronts owns BM = 32*WM nodes and 32 hidden units j, and
 // for those it computes ALL G gates: the weight tile is made of G row blocks of the weight
@@ -35,6 +35,7 @@
 // weight rows of one or two j tiles and keeps them in its own L2 for the whole level.
 #include "cell_kernels.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace acrobat {
@@ -679,12 +680,17 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
 template <int G, int EPI, int U>
 hipError_t launch_tiny(const CellLevelPair& pr, unsigned grid, hipStream_t stream, const LaunchEvents& ev) {
   constexpr size_t bytes = (size_t)(2 * U * 64 * kBK + 96) * sizeof(float);
-  static bool configured = false;  // more than 64 KB of dynamic LDS has to be asked for once
-  if (!configured) {
+  // More than 64 KB of dynamic LDS has to be asked for once per device.  One bit per device id; two
+  // threads that both find the bit clear both set the attribute, which is harmless.
+  static std::atomic<uint64_t> configured{0};
+  int dev = 0;
+  if (const hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev >= 64 || !(configured.load(std::memory_order_acquire) & bit)) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&cell_tiny_kernel<G, EPI, U>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
-    configured = true;
+    if (dev < 64) configured.fetch_or(bit, std::memory_order_release);
   }
   launch_with_events((cell_tiny_kernel<G, EPI, U>), dim3(grid), dim3(kThreads), bytes, stream, ev.start, ev.stop, 
                         pr);
@@ -708,13 +714,14 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
     return (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
   };
   if (ws.force_bm == 6) return Shape{6, ws.force_ksplit == 4 || ws.force_ksplit == 8 ? ws.force_ksplit : 0};
-  if (ws.force_bm == 128 || ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
+  if (ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
     Shape f{ws.force_bm, ws.force_ksplit > 0 ? ws.force_ksplit : 1};
     if (fits(f.bm, f.ksplit)) return f;
   }
   // Rules fitted to sweeps on MI355X (TreeLSTM H = 512 and 256, LSTM H = 512):
-  //  * 64-node tiles for all but the smallest levels (128-node tiles leave too few workgroups
-  //    at these level sizes, 32-node tiles re-read the weights too often);
+  //  * 64-node tiles for all but the smallest levels (32-node tiles re-read the weights too often;
+  //    a 128-node tile was measured and dropped: at the level sizes of these workloads it leaves
+  //    too few workgroups and turns 2.1 rounds into 3);
   //  * one compute unit streams its operand slabs at only ~40 GB/s, so a level with fewer
   //    tiles than compute units is latency bound: split k until about 256 workgroups exist
   //    (at least 2 slabs each, at most 8 ways - the reduction kernel costs a launch, ~3 us,
@@ -783,10 +790,7 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
   const unsigned g1 = b ? (unsigned)((long)((b->n + sh.bm - 1) / sh.bm) * (b->H / 32)) : 0;
   pr.split = (int32_t)g0;
   const unsigned grid = g0 + g1;
-  if (sh.bm == 128) {
-    launch_with_events((cell_level_kernel<G, EPI, 4, 1>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, pr, sh.ksplit, ws.partial);
-  } else if (sh.bm == 64) {
+  if (sh.bm == 64) {
     launch_with_events((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
                           ev.stop, pr, sh.ksplit, ws.partial);
   } else {

@@ -33,7 +33,7 @@ class Dfg {
   // and must not be in an earlier phase than a producer.
   int invoke(int32_t op, int32_t phase, int32_t depth, int32_t out_row, int32_t arg0, int32_t arg1, int32_t prod0,
              int32_t prod1, int32_t* node, std::string& err);
-  // A ghost operation (section 4.1, appendix B.4): a node that only occupies a depth.  A program
+  // A ghost operation (section 4.1, appendix "Combating Eagerness of Depth Scheduling"): a node that only occupies a depth.  A program
   // whose branches reach the same operator after different numbers of steps invokes ghosts on the
   // shorter branch, so that the operator lands at one depth - one batch - for every instance.  It is
   // checked against its producer like any node and can be named as a producer; it is never executed.

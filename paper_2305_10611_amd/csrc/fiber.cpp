@@ -20,6 +20,7 @@
 asm(R"(
 .text
 .globl acrobat_fiber_switch
+.hidden acrobat_fiber_switch
 .type acrobat_fiber_switch,@function
 acrobat_fiber_switch:
     pushq %rbp

@@ -4,10 +4,10 @@
 // Per node with left child (a, A) and right child (b, B):
 //   p = tanh(W [B a ; A b]),   P = W_M [A ; B]          (W, W_M: [64,128])
 // The two child matrices (16 KB each) are per-instance operands - this is the cell that
-// multiplies two activations (section 7.2) - while W and W_M are shared by every node of
+// multiplies two activations (Evaluation, "Overall Performance") - while W and W_M are shared by every node of
 // every level (parameter reuse, section 5.1).  Children are read where they live: an
 // internal child from the arena, a leaf child straight from the embedding tables (gather
-// fusion, section 5.2; no copies of leaf embeddings, section 7.4).
+// fusion, section 5.2; no copies of leaf embeddings, Evaluation, "Overall Performance").
 //
 // One workgroup (4 wavefronts) handles one node at a time and strides over the level, so
 // the shared weights are loaded into registers once per workgroup:

@@ -3,8 +3,8 @@
 // Depth schedule of section 4.1: a node that consumes nothing produced inside the graph
 // has depth 0, any other node 1 + the largest depth among its producers; batches run by
 // increasing depth and the members of one depth are independent.  One schedule node is a
-// whole cell (appendix B.2), every leaf cell only consumes its embedding row so all leaves
-// land in depth 0 (the hoisted input transform of appendix B.1), and sibling subtrees are
+// whole cell (appendix "Grain Size Coarsening"), every leaf cell only consumes its embedding row so all leaves
+// land in depth 0 (the hoisted input transform of appendix "Operator Hoisting"), and sibling subtrees are
 // concurrent (section 4.1, "instance parallelism").
 //
 // The paper computes depths inline while the unbatched program runs, relying on program

@@ -102,7 +102,7 @@ struct Generator {
   //
   // The fraternal state of a first child depends on nothing but the parameters (no previous
   // sibling: zero state, label 0): it is the same vector for every first child and for every root.
-  // As the paper does for constant tensors (section 7.2), it is computed once per group - with the
+  // As the paper does for constant tensors (Evaluation, "Overall Performance"), it is computed once per group - with the
   // roots, in the first evaluation - and reused: consumers of a first child's fraternal state read
   // the row of the group's first root instead.  The first children's own rows of the output are
   // filled by one batch at the very end (deferred), off the chain of dependent evaluations.

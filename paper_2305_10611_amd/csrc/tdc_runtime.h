@@ -1,6 +1,6 @@
 // Programs with tensor-dependent control flow on the batched dataflow-graph runtime (section 4.2),
 // and the one such program this library ships: top-down tree generation with a doubly recurrent
-// network (table 3; evaluated in section 7.2 with emulated decisions).
+// network (table 3; evaluated in Evaluation, "Overall Performance" with emulated decisions).
 //
 // The unbatched program is ordinary recursive code that calls invoke() for every operator, with
 // the depth it computes inline, and await() wherever it needs a tensor's value to decide how to
@@ -35,7 +35,7 @@ struct DrnnStats {
 };
 
 // The decisions of one node.  Emulated from its position (the paper's evaluation replaces the
-// tensor-dependent decisions by pseudo-random ones since its models are untrained, section 7.2) or,
+// tensor-dependent decisions by pseudo-random ones since its models are untrained, Evaluation, "Overall Performance") or,
 // with dec.from_scores, read off `y`, the node's n_out scores on the host - the value the program
 // had to wait for either way.
 struct DrnnDecision { bool has_child, has_sibling; int32_t label; };

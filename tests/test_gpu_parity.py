@@ -188,7 +188,7 @@ def test_mvrnn_small_ragged_and_relabelled(ctx, P):
 
 
 def test_mvrnn_d128_ragged_and_relabelled(ctx, P):
-    """The paper's large MV-RNN size (section 7.1): 128-d vectors, 128 x 128 matrices."""
+    """The paper's large MV-RNN size (Evaluation, "Experimental Setup"): 128-d vectors, 128 x 128 matrices."""
     w = gen.mvrnn_workload(13, 1, 12, 128, seed=41)
     w2, perm = gen.relabel_trees(w, gen.make_rng(42), extra={"token": w["token"]})
     for ww in (w, w2):
@@ -211,12 +211,12 @@ def test_mvrnn_d128_paper_batch(ctx, P):
 
 
 @pytest.mark.parametrize("d,trees", [(64, 40), (128, 24)])
-def test_mvrnn_streaming_variant(P, monkeypatch, d, trees):
-    """Both sizes have two level kernels; the tuning override selects the streaming one."""
+def test_mvrnn_streaming_variant(P, d, trees):
+    """Both sizes have two level kernels; the tuning hook selects the streaming one."""
     import paper_2305_10611_amd as A
-    monkeypatch.setenv("ACROBAT_MVRNN_VARIANT", "1")
     c = A.Context(0)
     try:
+        assert c.acrobat_set_tuning(0, 0, 1) == A.OK
         w = gen.mvrnn_workload(trees, 1, 30, d, seed=43)
         vec, mat = P.run_mvrnn(c, w)
         ov, om = oracle.mvrnn(w, nthreads=NT)
@@ -321,7 +321,7 @@ def test_birnn_ragged_with_bias_and_empty_sequences(ctx, P, H, D, n_out, n_seq, 
     got = P.run_birnn(ctx, w)
     check_birnn_schedule(ctx, w["len"])
     check_birnn(P, got, oracle.birnn(w, nthreads=NT))
-    # a second call right behind the first reuses the second stream and both workspace halves
+    # a second call right behind the first reuses the context's index and scratch buffers
     got2 = P.run_birnn(ctx, w)
     assert all(np.array_equal(a, b) for a, b in zip(got, got2))
 
@@ -386,16 +386,15 @@ def test_profiling_records_every_launch(ctx, P):
 
 
 # ---------------------------------------------------------------- every kernel variant
-@pytest.mark.parametrize("tile,ksplit", [(128, 1), (64, 1), (32, 1), (128, 2), (64, 4), (32, 8), (32, 2), (6, 4), (6, 8)])
-def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit, monkeypatch):
+@pytest.mark.parametrize("tile,ksplit", [(64, 1), (32, 1), (64, 2), (64, 4), (32, 8), (32, 2), (6, 4), (6, 8)])
+def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit):
     """The launcher normally picks the node-tile height and k split from the level size; the
-    tuning override forces one variant for every level (leaf, internal, LSTM input and steps).
+    tuning hook forces one variant for every level (leaf, internal, LSTM input and steps).
     Tile 6 is the kernel for latency-bound levels (its second number is the slabs moved per step)."""
     import paper_2305_10611_amd as A
-    monkeypatch.setenv("ACROBAT_FORCE_TILE", str(tile))
-    monkeypatch.setenv("ACROBAT_FORCE_KSPLIT", str(ksplit))
-    c = A.Context(0)  # the override is read when the context allocates its workspace
+    c = A.Context(0)
     try:
+        assert c.acrobat_set_tuning(tile, ksplit, 0) == A.OK
         w = gen.treelstm_workload(23, 1, 40, 256, 300, "zipf1.1", seed=tile + ksplit, bias_scale=0.2)
         h, cc = P.run_treelstm(c, w)
         oh, oc = oracle.treelstm(w, nthreads=NT)
@@ -831,6 +830,33 @@ def test_drnn_many_instances(ctx, P):
     assert len(want["inst"]) > 10000
     rc, trees, st, states = P.run_drnn(ctx, w)
     assert st["n_fibers"] > 2000 and st["n_rounds"] < 30
+    check_drnn(P, w, trees, states, want)
+
+
+@pytest.mark.parametrize("H,n_inst", [(256, 256), (512, 192)])
+def test_drnn_two_groups_with_every_level_split_along_k(P, H, n_inst):
+    """From 192 instances on two groups of instances are in flight on two streams.  With every level forced
+    to split its contraction range, both groups park partial tiles in the workspace between the two launches
+    of a level at the same time: each group must have a region of its own."""
+    import paper_2305_10611_amd as A
+    c = A.Context(0)
+    try:
+        assert c.acrobat_set_tuning(64, 4, 0) == A.OK
+        w = gen.drnn_workload(n_inst, H, 12, 32, seed=97 + H, max_depth=4, max_children=3, bias_scale=0.2)
+        want = oracle.drnn(w)
+        rc, trees, st, states = P.run_drnn(c, w, mode=A.TDC_FORK_JOIN)
+        assert set(trees["inst"][trees["round"] == 0] % 2) == {0, 1}  # both groups ran
+        check_drnn(P, w, trees, states, want)
+    finally:
+        c.close()
+
+
+def test_drnn_two_groups_with_wide_batches_that_split_on_their_own(ctx, P):
+    """H = 512 and 1 300 roots per group: the launcher itself splits these batches along k (no tuning hook),
+    in both groups at once."""
+    w = gen.drnn_workload(2600, 512, 8, 32, seed=98, max_depth=2, max_children=2, bias_scale=0.2)
+    want = oracle.drnn(w)
+    rc, trees, st, states = P.run_drnn(ctx, w)
     check_drnn(P, w, trees, states, want)
 
 

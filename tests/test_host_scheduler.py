@@ -23,6 +23,14 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(A.lib, name), name
 
 
+def test_library_exports_nothing_but_the_declared_c_abi():
+    """Hidden visibility + the linker's version script: no C++ internals leak out of the shared library."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", A.binding._build.LIB], capture_output=True, text=True, check=True).stdout
+    names = {line.split()[-1] for line in out.splitlines() if line.strip()}
+    assert names == set(A.EXPORTS), sorted(names ^ set(A.EXPORTS))
+
+
 @pytest.mark.parametrize("cfg", [0, 1, 2, 3])
 def test_tree_schedule_is_bit_exact_on_benchmark_configs(cfg):
     w = make_config(cfg)

@@ -8,7 +8,7 @@ path's tests can consume exactly the same arrays without sharing any logic.
 The paper evaluates TreeLSTM and MV-RNN on parse trees of a sentiment
 treebank and its recurrent models on a cross-lingual inference corpus, with
 hidden sizes 256/512 (64/128 for MV-RNN), batch sizes 8/64 and untrained
-parameters (paper section 7.1 and table 3).  Neither corpus is available
+parameters (paper Evaluation, "Experimental Setup" and table 3).  Neither corpus is available
 here, so the generators below produce stand-ins with the same structure:
 binary trees with sentence-length leaf counts, Zipf-distributed token ids,
 variable-length sequences, random weights.
@@ -327,7 +327,7 @@ def match_trees(got, want):
 
 
 def paper_grid_workload(model: str, size: str, batch: int, seed: int | None = None):
-    """Mini-batches shaped like the paper's evaluation grid (section 7.1): model size small /
+    """Mini-batches shaped like the paper's evaluation grid (Evaluation, "Experimental Setup"): model size small /
     large (hidden 256 / 512; MV-RNN 64 / 128) and batch size 8 / 64.  The treebank and the
     sentence-pair corpus themselves are not available: sentence lengths are drawn uniformly from
     [5, 35] (mean 20), trees are random binary splits; parameters are random, as in the paper.

@@ -119,11 +119,33 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
                              const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
                              float* d_c, void* hip_stream);
 
-/* MV-RNN (model of table 3; section 7.2: the cell multiplies two activations).  Every node
+/* acrobat_treelstm_forward for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same results (same kernels, same schedule,
+ * same choice of kernel variant per level as long as a level's partial tiles fit the fixed workspace; a
+ * level whose partial tiles do not fit runs unsplit, which only changes the summation order), but the
+ * call allocates and frees nothing on the device or in pinned memory: the index lists are staged in a
+ * pinned buffer of fixed size that acrobat_create made, and their device copy and the partial tiles of
+ * k-split levels live in one array of ACROBAT_NOALLOC_SCRATCH_MIB MiB that is part of the library's
+ * device image.  Each GPU the library is used on holds that array until the process ends.
+ *  - At most ACROBAT_NOALLOC_MAX_NODES nodes per call, else ACROBAT_EINVAL (nothing is launched).
+ *  - Every call on a GPU, from any context, shares that GPU's array: calls that overlap on one GPU
+ *    (two streams, two contexts, two threads) race.  Calls on one stream are safe back to back.
+ *    Nothing in the array has to start at zero and nothing is carried from call to call: the index
+ *    lists are uploaded whole and every partial tile is written before it is read.
+ *  - Per-launch profiling and the unfused-gather ablation are not available here (the settings are
+ *    ignored); acrobat_last_schedule works as usual.  The host-side schedule still uses the C++ heap. */
+#define ACROBAT_NOALLOC_MAX_NODES 65536
+#define ACROBAT_NOALLOC_SCRATCH_MIB 32
+int acrobat_treelstm_forward_noalloc(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D,
+                                     int32_t V, const float* d_emb, const float* d_Wleaf,
+                                     const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
+                                     float* d_c, void* hip_stream);
+
+/* MV-RNN (model of table 3; Evaluation, "Overall Performance": the cell multiplies two activations).  Every node
  * carries a vector and a d x d matrix; with left child (a, A) and right child (b, B):
  *   p = tanh(W [B a ; A b])      P = W_M [A ; B]      W, W_M: [d, 2d]
  * A leaf's (a, A) are rows `token` of the tables and are read in place by the parent's kernel
- * (no copy of leaf embeddings, section 7.4).  d_vec [N,d] / d_mat [N,d,d] receive the states of
+ * (no copy of leaf embeddings, Evaluation, "Overall Performance").  d_vec [N,d] / d_mat [N,d,d] receive the states of
  * internal nodes at row = global node id; leaf rows are written (copied from the tables) only
  * if copy_leaves != 0.  Requires d == 64 or d == 128.  Tables: d_vec_tab [V,d], d_mat_tab [V,d,d]. */
 int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t d, int32_t V,

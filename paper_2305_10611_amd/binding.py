@@ -76,7 +76,7 @@ EXPORTS = (
     "acrobat_schedule_trees", "acrobat_schedule_seqs", "acrobat_treelstm_forward",
     "acrobat_mvrnn_forward", "acrobat_varlen_lstm_forward", "acrobat_last_schedule",
     "acrobat_set_profiling", "acrobat_last_profile", "acrobat_schedule_birnn", "acrobat_birnn_forward",
-    "acrobat_set_gather_fusion",
+    "acrobat_set_gather_fusion", "acrobat_set_tuning", "acrobat_treelstm_forward_noalloc",
     "acrobat_dfg_create", "acrobat_dfg_destroy", "acrobat_dfg_last_error", "acrobat_dfg_register_op", "acrobat_dfg_clear", "acrobat_dfg_invoke",
     "acrobat_dfg_build_treelstm", "acrobat_dfg_run", "acrobat_dfg_schedule", "acrobat_dfg_ghost",
     "acrobat_drnn_forward", "acrobat_drnn_schedule",
@@ -98,6 +98,7 @@ def _load():
     lib.acrobat_schedule_trees.argtypes = [C.POINTER(acrobat_trees), i32, C.POINTER(i32), vp, vp, vp, vp]
     lib.acrobat_schedule_seqs.argtypes = [i32, vp, C.POINTER(i32), vp, vp]
     lib.acrobat_treelstm_forward.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32, i32] + [vp] * 8
+    lib.acrobat_treelstm_forward_noalloc.argtypes = lib.acrobat_treelstm_forward.argtypes
     lib.acrobat_mvrnn_forward.argtypes = [vp, C.POINTER(acrobat_trees), i32, i32] + [vp] * 6 + [i32, vp]
     lib.acrobat_varlen_lstm_forward.argtypes = [vp, i32, vp, i32, i32] + [vp] * 7
     lib.acrobat_schedule_birnn.argtypes = [i32, vp, C.POINTER(i32), vp, vp]
@@ -330,6 +331,11 @@ class Context:
         st, keep = _trees_struct(trees)
         return lib.acrobat_treelstm_forward(self._h, C.byref(st), H, D, V, _dp(emb), _dp(W_leaf), _dp(b_leaf),
                                             _dp(U), _dp(b), _dp(h), _dp(c), stream)
+
+    def acrobat_treelstm_forward_noalloc(self, trees: dict, H, D, V, emb, W_leaf, b_leaf, U, b, h, c, stream=0) -> int:
+        st, keep = _trees_struct(trees)
+        return lib.acrobat_treelstm_forward_noalloc(self._h, C.byref(st), H, D, V, _dp(emb), _dp(W_leaf), _dp(b_leaf),
+                                                    _dp(U), _dp(b), _dp(h), _dp(c), stream)
 
     def acrobat_mvrnn_forward(self, trees: dict, d, V, vec_tab, mat_tab, W, WM, vec, mat, copy_leaves=0,
                               stream=0) -> int:

@@ -1,13 +1,13 @@
 // C ABI of the batched dataflow-graph executor: context, index upload, level launch loop.
 //
-// Runtime pieces of the paper that live here (appendix C "Other Details"): arena-style reuse
+// Runtime pieces of the paper that live here (appendix "Other Details"): arena-style reuse
 // of the index/scratch buffers across calls, asynchronous execution on the caller's stream,
 // and one batched host-to-device transfer per forward call for all index lists.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -19,6 +19,35 @@
 #include "tdc_runtime.h"
 
 using namespace acrobat;
+
+// Scratch of the entry point that allocates nothing (acrobat_treelstm_forward_noalloc): the device copy
+// of the index lists, then the partial tiles of k-split levels.  One array per GPU, held until the
+// process ends; every call on a GPU shares it.  In host code the array's name is only a handle: the
+// device address comes from hipGetSymbolAddress, once per device (static_scratch_for).
+constexpr size_t kStaticScratchBytes = (size_t)ACROBAT_NOALLOC_SCRATCH_MIB << 20;
+constexpr size_t kStaticIndexBytes = (size_t)1 << 20;  // 3 int32 per node for ACROBAT_NOALLOC_MAX_NODES nodes
+static_assert(3 * sizeof(int32_t) * (size_t)ACROBAT_NOALLOC_MAX_NODES <= kStaticIndexBytes, "index region too small");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on `device`, which must be the current device.  Looked up once per device.
+hipError_t static_scratch_for(int device, void** out) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
+}  // namespace
 
 struct acrobat_ctx {
   int device = 0;
@@ -33,13 +62,19 @@ struct acrobat_ctx {
   size_t stage_cap = 0, idx_cap = 0;  // in int32 elements
   hipEvent_t stage_done = nullptr;    // the last upload out of h_stage has finished
   bool stage_pending = false;
+  // the entry point that allocates nothing: a staging buffer of fixed size (made by acrobat_create) and
+  // this device's address of the library's static scratch array
+  int32_t* h_fixed_stage = nullptr;   // kStaticIndexBytes of pinned host memory
+  hipEvent_t fixed_done = nullptr;    // the last upload out of h_fixed_stage has finished
+  bool fixed_pending = false;
+  unsigned char* static_scratch = nullptr;
   // scratch for the hoisted LSTM input transform
   float* d_scratch = nullptr;
   size_t scratch_cap = 0;  // in floats
   // split-k workspace of the cell kernels (allocated at the first forward call)
   SplitKWorkspace splitk;
   bool gather_fusion = true;  // false: explicit gather launches (ablation)
-  int mvrnn_variant = 0;  // which MV-RNN level kernel (tuning override ACROBAT_MVRNN_VARIANT): 1 = streaming
+  int mvrnn_variant = 0;  // which MV-RNN level kernel (acrobat_set_tuning): 1 = streaming
   // tree generation: a zero row (previous-sibling state of a first child) and the scores on the host
   float* d_zero_row = nullptr;
   size_t zero_row_cap = 0;  // in floats
@@ -157,10 +192,12 @@ int reserve_splitk(acrobat_ctx* ctx, hipStream_t stream) {
 struct LaunchTimer {
   acrobat_ctx* ctx;
   hipStream_t stream;
+  bool allowed = true;  // false: this call never times its launches, whatever the context's setting
   LaunchEvents ev;  // events of the launch that begin() announced (all null when profiling is off)
+  bool on() const { return allowed && ctx->profiling; }
   int begin(int32_t kind, int32_t level, int32_t n) {
     ev = LaunchEvents();
-    if (!ctx->profiling) return ACROBAT_OK;
+    if (!on()) return ACROBAT_OK;
     if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "profiling cannot be combined with stream capture");
     const size_t first = 2 * ctx->records.size();
     while (ctx->events.size() < first + 4) {
@@ -175,16 +212,16 @@ struct LaunchTimer {
     ev.reduce_stop = ctx->events[first + 3];
     return ACROBAT_OK;
   }
-  int32_t* tile() { return ctx->profiling ? &ctx->records.back().tile : nullptr; }
-  int32_t* ksplit() { return ctx->profiling ? &ctx->records.back().ksplit : nullptr; }
+  int32_t* tile() { return on() ? &ctx->records.back().tile : nullptr; }
+  int32_t* ksplit() { return on() ? &ctx->records.back().ksplit : nullptr; }
   int end() {
-    if (!ctx->profiling) return ACROBAT_OK;
+    if (!on()) return ACROBAT_OK;
     const acrobat_launch_record r = ctx->records.back();
     if (r.ksplit > 1) ctx->records.push_back({ACROBAT_K_SPLITK_REDUCE, r.level, r.n, r.tile, r.ksplit, 0.0f});
     return ACROBAT_OK;
   }
   int finish() {
-    if (!ctx->profiling) return ACROBAT_OK;
+    if (!on()) return ACROBAT_OK;
     HIP_TRY(ctx, hipStreamSynchronize(stream));
     for (size_t i = 0; i < ctx->records.size(); ++i)
       HIP_TRY(ctx, hipEventElapsedTime(&ctx->records[i].ms, ctx->events[2 * i], ctx->events[2 * i + 1]));
@@ -332,11 +369,16 @@ int acrobat_create(acrobat_ctx** out, int device) {
   acrobat_ctx* ctx = new (std::nothrow) acrobat_ctx();
   if (!ctx) return ACROBAT_ENOMEM;
   ctx->device = device;
-  if (const char* v = std::getenv("ACROBAT_MVRNN_VARIANT")) ctx->mvrnn_variant = std::atoi(v);
-  if (hipEventCreateWithFlags(&ctx->stage_done, hipEventDisableTiming) != hipSuccess) {
-    delete ctx;
+  void* scratch_ptr = nullptr;
+  if (hipEventCreateWithFlags(&ctx->stage_done, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->fixed_done, hipEventDisableTiming) != hipSuccess ||
+      hipHostMalloc(reinterpret_cast<void**>(&ctx->h_fixed_stage), kStaticIndexBytes, hipHostMallocDefault) != hipSuccess ||
+      static_scratch_for(device, &scratch_ptr) != hipSuccess) {
+    (void)hipGetLastError();
+    acrobat_destroy(ctx);
     return ACROBAT_EHIP;
   }
+  ctx->static_scratch = static_cast<unsigned char*>(scratch_ptr);
   *out = ctx;
   return ACROBAT_OK;
 }
@@ -345,6 +387,9 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (!ctx) return;
   (void)hipSetDevice(ctx->device);
   if (ctx->stage_pending) (void)hipEventSynchronize(ctx->stage_done);
+  if (ctx->fixed_pending) (void)hipEventSynchronize(ctx->fixed_done);
+  if (ctx->h_fixed_stage) (void)hipHostFree(ctx->h_fixed_stage);
+  if (ctx->fixed_done) (void)hipEventDestroy(ctx->fixed_done);
   if (ctx->d_idx) (void)hipFree(ctx->d_idx);
   if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
@@ -405,10 +450,17 @@ int acrobat_schedule_seqs(int32_t n_seq, const int32_t* len, int32_t* n_levels, 
   }
 }
 
-int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D,
-                             int32_t V, const float* d_emb, const float* d_Wleaf,
-                             const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
-                             float* d_c, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// acrobat_treelstm_forward and its variant that allocates nothing.  `noalloc`: the index lists are staged in
+// the context's fixed pinned buffer and uploaded into the library's static device array, which also holds the
+// partial tiles of k-split levels; nothing is allocated or freed, no per-launch events are made (profiling is
+// ignored) and the unfused-gather ablation, which needs scratch, is not available.
+int treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D, int32_t V, const float* d_emb,
+                     const float* d_Wleaf, const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
+                     float* d_c, void* hip_stream, const bool noalloc) {
   try {
     TRY(begin_call(ctx));
     if (!trees) return fail(ctx, ACROBAT_EINVAL, "trees is null");
@@ -429,29 +481,57 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
 
     if ((double)5 * H * 2 * H >= 2147483648.0 || (double)5 * H * D >= 2147483648.0)
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
-    TRY(reserve_splitk(ctx, stream));
+    if (noalloc && N > ACROBAT_NOALLOC_MAX_NODES)
+      return fail(ctx, ACROBAT_EINVAL, "acrobat_treelstm_forward_noalloc: more than ACROBAT_NOALLOC_MAX_NODES (" +
+                                           std::to_string(ACROBAT_NOALLOC_MAX_NODES) + ") nodes");
     // index lists by schedule position: out row | first operand row | second operand row
     // (+ 0, 1, 2, ... for the unfused-gather ablation, whose level kernels read gathered copies)
     const int32_t n_leaf = s.level_off[1];
     int32_t n_wide = 0;  // widest internal level
     for (int32_t lv = 1; lv < s.n_levels; ++lv) n_wide = std::max(n_wide, s.level_off[lv + 1] - s.level_off[lv]);
-    const bool unfused = !ctx->gather_fusion;
+    const bool unfused = !ctx->gather_fusion && !noalloc;
     const size_t n_iota = unfused ? (size_t)std::max(n_leaf, 2 * n_wide) : 0;
-    TRY(reserve_indices(ctx, 3 * (size_t)N + n_iota, stream));
-    int32_t* st = ctx->h_stage;
+    int32_t* st = nullptr;     // pinned staging
+    int32_t* d_idx = nullptr;  // its device copy
+    SplitKWorkspace ws;
+    if (noalloc) {
+      if (ctx->fixed_pending) {  // the previous upload out of the fixed staging buffer must be through
+        HIP_TRY(ctx, hipEventSynchronize(ctx->fixed_done));
+        ctx->fixed_pending = false;
+      }
+      st = ctx->h_fixed_stage;
+      d_idx = reinterpret_cast<int32_t*>(ctx->static_scratch);
+      ws = ctx->splitk;  // tuning hook settings
+      ws.partial = reinterpret_cast<float*>(ctx->static_scratch + kStaticIndexBytes);
+      ws.partial_floats = (kStaticScratchBytes - kStaticIndexBytes) / sizeof(float);
+    } else {
+      TRY(reserve_splitk(ctx, stream));
+      TRY(reserve_indices(ctx, 3 * (size_t)N + n_iota, stream));
+      st = ctx->h_stage;
+      d_idx = ctx->d_idx;
+      ws = ctx->splitk;
+    }
     std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
     for (int32_t p = 0; p < n_leaf; ++p) st[N + p] = trees->token[s.level_nodes[p]];  // leaves gather by token
     std::memcpy(st + N + n_leaf, s.lrow.data() + n_leaf, (size_t)(N - n_leaf) * sizeof(int32_t));
     std::memcpy(st + 2 * (size_t)N, s.rrow.data(), (size_t)N * sizeof(int32_t));
     for (size_t i = 0; i < n_iota; ++i) st[3 * (size_t)N + i] = (int32_t)i;
     if (unfused) TRY(reserve_scratch(ctx, std::max((size_t)n_leaf * D, 4 * (size_t)n_wide * H), stream));
-    TRY(upload_indices(ctx, 3 * (size_t)N + n_iota, stream));
-    const int32_t* d_out = ctx->d_idx;
-    const int32_t* d_ia = ctx->d_idx + N;
-    const int32_t* d_ib = ctx->d_idx + 2 * (size_t)N;
-    const int32_t* d_iota = ctx->d_idx + 3 * (size_t)N;
+    if (noalloc) {
+      HIP_TRY(ctx, hipMemcpyAsync(d_idx, st, 3 * (size_t)N * sizeof(int32_t), hipMemcpyHostToDevice, stream));
+      if (!stream_is_capturing(stream)) {
+        HIP_TRY(ctx, hipEventRecord(ctx->fixed_done, stream));
+        ctx->fixed_pending = true;
+      }
+    } else {
+      TRY(upload_indices(ctx, 3 * (size_t)N + n_iota, stream));
+    }
+    const int32_t* d_out = d_idx;
+    const int32_t* d_ia = d_idx + N;
+    const int32_t* d_ib = d_idx + 2 * (size_t)N;
+    const int32_t* d_iota = d_idx + 3 * (size_t)N;
 
-    LaunchTimer timer{ctx, stream};
+    LaunchTimer timer{ctx, stream, !noalloc};
     for (int32_t lv = 0; lv < s.n_levels; ++lv) {
       const int32_t off = s.level_off[lv], n = s.level_off[lv + 1] - off;
       CellLevelArgs a{};
@@ -494,7 +574,7 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
         TRY(timer.end());
       }
       TRY(timer.begin(lv == 0 ? ACROBAT_K_TREE_LEAF : ACROBAT_K_TREE_INTERNAL, lv, n));
-      HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream, ctx->splitk,
+      HIP_TRY(ctx, launch_cell_level(lv == 0 ? EPI_TREE_LEAF : EPI_TREE_INTERNAL, a, stream, ws,
                                      timer.tile(), timer.ksplit(), timer.ev));
       TRY(timer.end());
     }
@@ -504,6 +584,24 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
   } catch (...) {
     return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
   }
+}
+
+}  // namespace
+
+extern "C" {
+
+int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D,
+                             int32_t V, const float* d_emb, const float* d_Wleaf,
+                             const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
+                             float* d_c, void* hip_stream) {
+  return treelstm_forward(ctx, trees, H, D, V, d_emb, d_Wleaf, d_bleaf, d_U, d_b, d_h, d_c, hip_stream, false);
+}
+
+int acrobat_treelstm_forward_noalloc(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, int32_t D,
+                                     int32_t V, const float* d_emb, const float* d_Wleaf,
+                                     const float* d_bleaf, const float* d_U, const float* d_b, float* d_h,
+                                     float* d_c, void* hip_stream) {
+  return treelstm_forward(ctx, trees, H, D, V, d_emb, d_Wleaf, d_bleaf, d_U, d_b, d_h, d_c, hip_stream, true);
 }
 
 int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t d, int32_t V,

@@ -133,6 +133,14 @@ def main():
                     help="TreeLSTM only: also time the same batch through the generic dataflow-graph runtime (the "
                          "unbatched program calls invoke() per node with inline depths), reported under "
                          "\"generic_runtime\"")
+    ap.add_argument("--graph-replay", action="store_true",
+                    help="also time the forward call replayed from a captured HIP graph (index upload + every launch), "
+                         "and what capturing and instantiating it costs; reported under \"graph_replay\"")
+    ap.add_argument("--persistent", choices=("auto", "off"), default="auto",
+                    help="LSTM only: off = one launch per time step instead of one persistent launch for the recurrence")
+    ap.add_argument("--sync-probe", action="store_true",
+                    help="only run the library's probe of barriers among workgroups inside one kernel (three styles, "
+                         "groups on one XCD or spread) and print one JSON line per case")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="only run one plain device-to-device copy of this many MiB (a kernel of known traffic "
                          "for scaling hardware-counter readings) and exit")
@@ -157,6 +165,25 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration_mib": args.copy_calibration_mib, "launches": 3}))
         return
+    if args.sync_probe:
+        ctx = A.Context(0)
+        names = ("store+wg_barrier", "announce", "wait", "acquire+wg_barrier", "load")
+        for groups, gsize in ((8, 32), (8, 8), (1, 256), (1, 32)):
+            for same_xcd in (1, 0):
+                for style in (0, 1, 2):
+                    if style == 2 and gsize > 32:
+                        continue
+                    for store, load in ((0, 0), (512, 16384)):
+                        load = min(load, gsize * store // 1024 * 1024)
+                        rc, us, ph = ctx.acrobat_sync_probe(groups, gsize, 2000, same_xcd, style, 1, store, load)
+                        ctx.check(rc)
+                        print(json.dumps({"sync_probe": {"groups": groups, "group_size": gsize, "same_xcd": same_xcd,
+                                                         "style": ("counter+fences", "counter", "flag lines")[style],
+                                                         "store_bytes": 4 * store, "load_bytes": 4 * load,
+                                                         "us_per_round": round(us, 2),
+                                                         "phase_us": {k: round(v, 2) for k, v in zip(names, ph)}}}), flush=True)
+        ctx.close()
+        return
     if args.paper_grid:
         from workloads.generators import paper_grid_workload
         model, size, batch = args.paper_grid.split(":")
@@ -166,6 +193,8 @@ def main():
         w = make_config(args.config)
     kind = w["kind"]
     ctx = A.Context(0)
+    if args.persistent == "off":
+        ctx.acrobat_set_persistent(False)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     stream = torch.cuda.current_stream().cuda_stream
     if kind == "drnn":
@@ -229,9 +258,15 @@ def main():
         make_step = lambda c, o, st: (lambda: c.check(c.acrobat_varlen_lstm_forward(
             w["len"], H, D, t["x"], t["Wx"], t["Wh"], t["b"], o[0], o[1], st)))
         sched = lambda: A.acrobat_schedule_seqs(w["len"])
-        flops_per = {A.binding.K_LSTM_INPUT: 2.0 * D * 4 * H, A.binding.K_LSTM_STEP: 2.0 * H * 4 * H}
-        bytes_per = {A.binding.K_LSTM_INPUT: 4.0 * D + 16.0 * H, A.binding.K_LSTM_STEP: 16.0 * H + 8.0 * H + 8.0 * H + 8}
-        weight_bytes = {A.binding.K_LSTM_INPUT: 16.0 * H * D, A.binding.K_LSTM_STEP: 16.0 * H * H}
+        # the recurrence is either one launch per step (K_LSTM_STEP) or one launch for all steps (K_LSTM_PERSISTENT):
+        # same work per (sequence, step); the persistent launch reads the weights once
+        step_flops, step_bytes = 2.0 * H * 4 * H, 16.0 * H + 8.0 * H + 8.0 * H + 8
+        flops_per = {A.binding.K_LSTM_INPUT: 2.0 * D * 4 * H, A.binding.K_LSTM_STEP: step_flops,
+                     A.binding.K_LSTM_PERSISTENT: step_flops}
+        bytes_per = {A.binding.K_LSTM_INPUT: 4.0 * D + 16.0 * H, A.binding.K_LSTM_STEP: step_bytes,
+                     A.binding.K_LSTM_PERSISTENT: step_bytes}
+        weight_bytes = {A.binding.K_LSTM_INPUT: 16.0 * H * D, A.binding.K_LSTM_STEP: 16.0 * H * H,
+                        A.binding.K_LSTM_PERSISTENT: 16.0 * H * H}
         dominant = A.binding.K_LSTM_STEP
         total_flops = n_nodes * (flops_per[A.binding.K_LSTM_INPUT] + flops_per[A.binding.K_LSTM_STEP])
         dtype, bound = "f32", "mfma"
@@ -271,6 +306,31 @@ def main():
         oms = (o1 - o0) * 1e3 / args.steps
         overlap = {"streams": 2, "ms_per_step": round(oms, 4), "value": round(n_nodes / (oms * 1e-3), 1)}
         ctx2.close()
+
+    # ---- information only: the same forward call replayed from a captured graph
+    graph_replay = None
+    if args.graph_replay:
+        gs = torch.cuda.Stream()
+        gstep = make_step(ctx, out, gs.cuda_stream)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=gs, capture_error_mode="relaxed"):
+            gstep()
+        torch.cuda.synchronize()
+        c1 = time.perf_counter()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        r1 = time.perf_counter()
+        graph_replay = {"replay_ms_per_step": round((r1 - r0) * 1e3 / args.steps, 4), "eager_ms_per_step": round(ms_per_step, 4),
+                        "capture_and_instantiate_ms": round((c1 - c0) * 1e3, 3)}
+        del graph
+        step()  # the outputs checked further down come from the eager path
 
     # ---- information only: gather fusion off (explicit gather launch before every level)
     ablation = None
@@ -352,6 +412,8 @@ def main():
     for i, r in enumerate(recs[0]):
         per_launch.append((r[0], r[1], r[2], r[4], float(np.mean([rr[i][3] for rr in recs])), r[5]))
     t_device_ms = sum(p[4] for p in per_launch)
+    if any(p[0] == A.binding.K_LSTM_PERSISTENT for p in per_launch):
+        dominant = A.binding.K_LSTM_PERSISTENT
     K_REDUCE = A.binding.K_SPLITK_REDUCE
     t_reduce_ms = sum(p[4] for p in per_launch if p[0] == K_REDUCE)
     # dominant kernel = the variant of the dominant kind that accounts for most device time
@@ -447,6 +509,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": w["name"], "index": args.config, "nodes": n_nodes, "seed": int(w["seed"])},
         "roofline": roofline, "cpu_baseline": cpu_baseline, "two_stream_throughput": overlap, "ablation": ablation, "generic_runtime": generic,
+        "graph_replay": graph_replay,
         "breakdown": {"t_schedule_ms": round(t_schedule_ms, 4), "t_device_ms": round(t_device_ms, 4),
                       "t_splitk_reduce_ms": round(t_reduce_ms, 4),
                       "launches": len(per_launch), "algorithmic_gflop": round(total_flops / 1e9, 3),

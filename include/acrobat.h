@@ -48,6 +48,7 @@ extern "C" {
                              /* parents, cycle, not exactly one root, token out of range   */
 #define ACROBAT_ENOMEM (-3)  /* host or device allocation failed                           */
 #define ACROBAT_EHIP (-4)    /* a HIP runtime call failed                                  */
+#define ACROBAT_ETIMEOUT (-5) /* a bounded wait inside a persistent kernel ran out (acrobat_device_status) */
 
 typedef struct acrobat_ctx acrobat_ctx;
 
@@ -165,6 +166,42 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
                                 int32_t D, const float* d_x, const float* d_Wx,
                                 const float* d_Wh, const float* d_b, float* d_h, float* d_c,
                                 void* hip_stream);
+
+/* Level-launch strategy of the recurrence (the paper's activity breakdown, table 6, and its remark on
+ * persistence in Evaluation, "Overall Performance": launch overhead is of the order of the kernel time).
+ * Enabled (the default), acrobat_varlen_lstm_forward runs all time steps in ONE launch whenever H is 128,
+ * 256 or 512, at most 256 sequences have a step to run, and every workgroup of that launch is resident on
+ * the GPU at once (an occupancy query; otherwise, or when disabled, one launch per step as described
+ * above).  The batches are the same - step t over the sequences with len > t - and so is the schedule
+ * that acrobat_last_schedule reports; the workgroups keep W_h on chip for all steps and synchronise
+ * among themselves through arrival counters in device memory.  Every wait inside that kernel is bounded
+ * by max_polls polls of a counter (max_polls < 0: the default, about a quarter of a million): a
+ * workgroup whose wait runs out raises a status word, all workgroups then leave at their next poll and
+ * the kernel ends normally with incomplete outputs.  acrobat_device_status reports that: call it once the
+ * stream has been synchronised; it returns ACROBAT_OK or ACROBAT_ETIMEOUT and clears the condition.
+ * Nothing else may occupy the GPU's compute units for long while such a launch runs (another stream's
+ * kernels delay the workgroups that are not yet resident; the bound turns a too long delay into
+ * ACROBAT_ETIMEOUT instead of a hang). */
+int acrobat_set_persistent(acrobat_ctx* ctx, int32_t enabled, int32_t max_polls);
+int acrobat_device_status(acrobat_ctx* ctx);
+
+/* Diagnostic: what a barrier among workgroups inside one kernel costs on this GPU.  groups x group_size
+ * workgroups (groups <= 8, at most 256 workgroups and never more than the GPU has compute units) run
+ * `rounds` rounds of: store store_floats floats each, announce that, wait for the whole group (bounded as
+ * above), read load_floats floats of what the group stored.  same_xcd != 0: workgroup b belongs to group
+ * b % groups, so with groups == 8 a group's members share an XCD and its L2; else to group b / group_size,
+ * members spread over all XCDs.  style 0: one arrival counter per group, agent-scope release before the
+ * arrival and acquire after the wait (the fences write back / invalidate the XCD's L2), plain loads;
+ * write_through != 0 then stores the payload with agent-scope atomic stores.  style 1: the same counter
+ * without fences - write-through stores completed before the arrival, agent-scope loads.  style 2: style 1
+ * with a flag line per consumer instead of the counter (group_size <= 32).  The persistent recurrence
+ * kernel uses style 1.  Outputs (host): *us_per_round = kernel time / rounds; phase_us[5] = mean over
+ * workgroups and rounds of the time spent in payload stores + workgroup barrier, announcing, waiting,
+ * acquire + workgroup barrier, payload loads (including the completion of the acquire's invalidate).
+ * Allocates its buffers per call and synchronises the stream. */
+int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int32_t rounds, int32_t same_xcd,
+                       int32_t style, int32_t write_through, int32_t store_floats, int32_t load_floats,
+                       double* us_per_round, double* phase_us, void* hip_stream);
 
 /* Bidirectional RNN with a per-token output layer (the BiRNN of table 3; cell of listing 1 used
  * in both directions with separate parameters, appendix "Exploiting Data Reuse" (code duplication); output operators batched by program
@@ -417,6 +454,7 @@ typedef struct {
 #define ACROBAT_K_SPLITK_REDUCE 10
 #define ACROBAT_K_GATHER 11
 #define ACROBAT_K_DFG_BUCKET 12 /* level = bucket index */
+#define ACROBAT_K_LSTM_PERSISTENT 13 /* all time steps of the recurrence in one launch; n = all rows */
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 

@@ -11,10 +11,10 @@ import torch  # noqa: F401  (first: the library must bind to the HIP runtime PyT
 
 from . import build as _build
 
-OK, EINVAL, ESTRUCT, ENOMEM, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, ESTRUCT, ENOMEM, EHIP, ETIMEOUT = 0, -1, -2, -3, -4, -5
 K_TREE_LEAF, K_TREE_INTERNAL, K_MVRNN_LEVEL, K_MVRNN_LEAFCOPY, K_LSTM_INPUT, K_LSTM_STEP = 1, 2, 3, 4, 5, 6
 K_RNN_INPUT, K_RNN_STEP, K_RNN_OUTPUT, K_SPLITK_REDUCE = 7, 8, 9, 10
-K_GATHER = 11
+K_GATHER, K_DFG_BUCKET, K_LSTM_PERSISTENT = 11, 12, 13
 
 
 class AcrobatError(RuntimeError):
@@ -77,6 +77,7 @@ EXPORTS = (
     "acrobat_mvrnn_forward", "acrobat_varlen_lstm_forward", "acrobat_last_schedule",
     "acrobat_set_profiling", "acrobat_last_profile", "acrobat_schedule_birnn", "acrobat_birnn_forward",
     "acrobat_set_gather_fusion", "acrobat_set_tuning", "acrobat_treelstm_forward_noalloc",
+    "acrobat_set_persistent", "acrobat_device_status", "acrobat_sync_probe",
     "acrobat_dfg_create", "acrobat_dfg_destroy", "acrobat_dfg_last_error", "acrobat_dfg_register_op", "acrobat_dfg_clear", "acrobat_dfg_invoke",
     "acrobat_dfg_build_treelstm", "acrobat_dfg_run", "acrobat_dfg_schedule", "acrobat_dfg_ghost",
     "acrobat_drnn_forward", "acrobat_drnn_schedule",
@@ -125,6 +126,9 @@ def _load():
     lib.acrobat_set_profiling.argtypes = [vp, i32]
     lib.acrobat_set_gather_fusion.argtypes = [vp, i32]
     lib.acrobat_set_tuning.argtypes = [vp, i32, i32, i32]
+    lib.acrobat_set_persistent.argtypes = [vp, i32, i32]
+    lib.acrobat_device_status.argtypes = [vp]
+    lib.acrobat_sync_probe.argtypes = [vp] + [i32] * 8 + [C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     lib.acrobat_last_profile.argtypes = [vp, C.POINTER(i32), C.POINTER(C.POINTER(acrobat_launch_record))]
     return lib
 
@@ -388,6 +392,20 @@ class Context:
 
     def acrobat_set_tuning(self, force_tile=0, force_ksplit=0, mvrnn_variant=0) -> int:
         return lib.acrobat_set_tuning(self._h, force_tile, force_ksplit, mvrnn_variant)
+
+    def acrobat_set_persistent(self, enabled=True, max_polls=-1) -> int:
+        return lib.acrobat_set_persistent(self._h, int(bool(enabled)), max_polls)
+
+    def acrobat_device_status(self) -> int:
+        return lib.acrobat_device_status(self._h)
+
+    def acrobat_sync_probe(self, groups, group_size, rounds, same_xcd, style, write_through, store_floats, load_floats,
+                           stream=0):
+        """-> (rc, microseconds per round, [5 phase times in microseconds])"""
+        us, phases = C.c_double(0.0), (C.c_double * 5)()
+        rc = lib.acrobat_sync_probe(self._h, groups, group_size, rounds, int(bool(same_xcd)), style, int(bool(write_through)),
+                                    store_floats, load_floats, C.byref(us), phases, stream)
+        return rc, us.value, list(phases)
 
     def acrobat_last_profile(self):
         n, p = C.c_int32(0), C.POINTER(acrobat_launch_record)()

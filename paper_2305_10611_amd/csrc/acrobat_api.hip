@@ -15,6 +15,7 @@
 #include "acrobat.h"
 #include "cell_kernels.h"
 #include "dfg_runtime.h"
+#include "persistent_kernels.h"
 #include "scheduler.h"
 #include "tdc_runtime.h"
 
@@ -82,6 +83,11 @@ struct acrobat_ctx {
   size_t scores_cap = 0;  // in floats
   hipStream_t tdc_stream = nullptr;             // second group of instances (the first uses the caller's stream)
   hipEvent_t tdc_order = nullptr;               // orders the second stream behind the caller's at the start of a call
+  // persistent kernels: arrival counters + status word on the device, the status word's copy on the host
+  bool persistent = true;           // acrobat_set_persistent
+  int32_t max_polls = 1 << 18;      // bound of every wait inside a persistent kernel
+  unsigned* d_sync = nullptr;       // [kPersistSyncWords]: the probe's flag lines | arrival counters | status
+  unsigned* h_status = nullptr;     // pinned; written by a copy behind every persistent launch
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
@@ -183,6 +189,17 @@ int reserve_splitk(acrobat_ctx* ctx, hipStream_t stream) {
   HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
   ctx->splitk.partial = p;
   ctx->splitk.partial_floats = kPartialFloats;
+  return ACROBAT_OK;
+}
+
+constexpr int kSyncWords = kPersistSyncWords;  // the probe's flag lines, arrival counters, then the status word
+
+int reserve_sync(acrobat_ctx* ctx, hipStream_t stream) {
+  if (ctx->d_sync) return ACROBAT_OK;
+  if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "stream capture: counters not allocated, run once without capture first");
+  HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_sync), kSyncWords * sizeof(unsigned)));
+  HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), sizeof(unsigned), hipHostMallocDefault));
+  *ctx->h_status = 0;
   return ACROBAT_OK;
 }
 
@@ -356,6 +373,7 @@ const char* acrobat_strerror(int code) {
     case ACROBAT_ESTRUCT: return "malformed input structure";
     case ACROBAT_ENOMEM: return "out of memory";
     case ACROBAT_EHIP: return "HIP runtime error";
+    case ACROBAT_ETIMEOUT: return "a wait inside a persistent kernel ran out";
     default: return "unknown error code";
   }
 }
@@ -394,6 +412,8 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
+  if (ctx->d_sync) (void)hipFree(ctx->d_sync);
+  if (ctx->h_status) (void)hipHostFree(ctx->h_status);
   if (ctx->d_zero_row) (void)hipFree(ctx->d_zero_row);
   if (ctx->h_scores) (void)hipHostFree(ctx->h_scores);
   if (ctx->tdc_stream) (void)hipStreamDestroy(ctx->tdc_stream);
@@ -699,19 +719,8 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
     if ((double)4 * H * H >= 2147483648.0 || (double)4 * H * D >= 2147483648.0)
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
     TRY(reserve_splitk(ctx, stream));
-    // by schedule position: row written | row of the previous step (unused at t = 0)
-    TRY(reserve_indices(ctx, 2 * (size_t)R, stream));
-    int32_t* st = ctx->h_stage;
-    std::memcpy(st, s.level_rows.data(), (size_t)R * sizeof(int32_t));
-    for (int32_t p = 0; p < R; ++p) st[R + p] = s.level_rows[p] - 1;
-    for (int32_t p = 0; p < s.level_off[1]; ++p) st[R + p] = s.level_rows[p];  // keep in range
     TRY(reserve_scratch(ctx, (size_t)R * 4 * (size_t)H, stream));
-    TRY(upload_indices(ctx, 2 * (size_t)R, stream));
-    const int32_t* d_out = ctx->d_idx;
-    const int32_t* d_prev = ctx->d_idx + R;
-
-    LaunchTimer timer{ctx, stream};
-    {  // hoisted input transform of every step of every sequence: one dense batch
+    auto input_transform = [&](LaunchTimer& timer) {  // hoisted: every step of every sequence in one dense batch
       CellLevelArgs a{};
       a.n = R; a.H = H; a.nseg = 1; a.kseg = D;
       a.src0 = d_x; a.ld0 = D;
@@ -719,8 +728,71 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       a.zout = ctx->d_scratch;
       TRY(timer.begin(ACROBAT_K_LSTM_INPUT, 0, R));
       HIP_TRY(ctx, launch_cell_level(EPI_STORE_Z, a, stream, ctx->splitk, timer.tile(), timer.ksplit(), timer.ev));
+      return timer.end();
+    };
+
+    // One launch for the whole recurrence where the shape allows it: the steps are the same batches in the
+    // same order, executed by workgroups that keep W_h on chip and synchronise among themselves.
+    const int32_t n_live = s.level_off[1];  // sequences with at least one step
+    const int32_t n_blocks = (n_live + kPersistSlots - 1) / kPersistSlots;
+    if (ctx->persistent && s.n_levels >= 2 && (double)R * H * sizeof(float) < 4294967296.0 &&
+        lstm_persistent_eligible(H, n_blocks, nullptr)) {
+      TRY(reserve_sync(ctx, stream));
+      const size_t n_slots = (size_t)n_blocks * kPersistSlots;
+      TRY(reserve_indices(ctx, 2 * n_slots, stream));
+      int32_t* st = ctx->h_stage;
+      // sequences by non-increasing length (ties by id): a counting sort over the lengths; rank r goes to block
+      // r % n_blocks, slot r / n_blocks, so every block gets the same mix of lengths and its live slots are a prefix
+      std::vector<int32_t> first(s.n_levels + 2, 0);  // first[l]: count, then rank of the first sequence of length l
+      for (int32_t q = 0; q < n_seq; ++q)
+        if (len[q] > 0) ++first[len[q]];
+      for (int32_t l = s.n_levels, run = 0; l >= 1; --l) {
+        const int32_t cnt = first[l];
+        first[l] = run;
+        run += cnt;
+      }
+      std::fill(st, st + 2 * n_slots, 0);
+      int32_t row0 = 0;
+      for (int32_t q = 0; q < n_seq; ++q) {
+        if (len[q] > 0) {
+          const int32_t r = first[len[q]]++;
+          const size_t slot = (size_t)(r % n_blocks) * kPersistSlots + r / n_blocks;
+          st[slot] = row0;
+          st[n_slots + slot] = len[q];
+        }
+        row0 += len[q];
+      }
+      TRY(upload_indices(ctx, 2 * n_slots, stream));
+      LaunchTimer timer{ctx, stream};
+      HIP_TRY(ctx, launch_fill_u32(ctx->d_sync + kPersistFlagWords, 0u, kSyncWords - kPersistFlagWords, stream));
+      TRY(input_transform(timer));
+      LstmPersistentArgs pa{};
+      pa.n_blocks = n_blocks; pa.H = H;
+      pa.slot_row0 = ctx->d_idx; pa.slot_len = ctx->d_idx + n_slots;
+      pa.Wh = d_Wh; pa.xp = ctx->d_scratch; pa.h = d_h; pa.c = d_c;
+      pa.h_bytes = (uint32_t)((size_t)R * H * sizeof(float));
+      pa.counters = ctx->d_sync + kPersistFlagWords; pa.status = ctx->d_sync + kSyncWords - 1;
+      pa.max_polls = ctx->max_polls;
+      TRY(timer.begin(ACROBAT_K_LSTM_PERSISTENT, 0, R));
+      if (timer.tile()) *timer.tile() = 16;
+      HIP_TRY(ctx, launch_lstm_persistent(pa, stream, timer.ev));
       TRY(timer.end());
+      HIP_TRY(ctx, hipMemcpyAsync(ctx->h_status, pa.status, sizeof(unsigned), hipMemcpyDeviceToHost, stream));
+      return timer.finish();
     }
+
+    // by schedule position: row written | row of the previous step (unused at t = 0)
+    TRY(reserve_indices(ctx, 2 * (size_t)R, stream));
+    int32_t* st = ctx->h_stage;
+    std::memcpy(st, s.level_rows.data(), (size_t)R * sizeof(int32_t));
+    for (int32_t p = 0; p < R; ++p) st[R + p] = s.level_rows[p] - 1;
+    for (int32_t p = 0; p < s.level_off[1]; ++p) st[R + p] = s.level_rows[p];  // keep in range
+    TRY(upload_indices(ctx, 2 * (size_t)R, stream));
+    const int32_t* d_out = ctx->d_idx;
+    const int32_t* d_prev = ctx->d_idx + R;
+
+    LaunchTimer timer{ctx, stream};
+    TRY(input_transform(timer));
     for (int32_t t = 0; t < s.n_levels; ++t) {
       const int32_t off = s.level_off[t], n = s.level_off[t + 1] - off;
       CellLevelArgs a{};
@@ -1169,6 +1241,93 @@ int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled) {
   if (!ctx) return ACROBAT_EINVAL;
   ctx->profiling = enabled != 0;
   return ACROBAT_OK;
+}
+
+int acrobat_set_persistent(acrobat_ctx* ctx, int32_t enabled, int32_t max_polls) {
+  if (!ctx) return ACROBAT_EINVAL;
+  ctx->persistent = enabled != 0;
+  ctx->max_polls = max_polls < 0 ? (1 << 18) : max_polls;
+  return ACROBAT_OK;
+}
+
+int acrobat_device_status(acrobat_ctx* ctx) {
+  if (!ctx) return ACROBAT_EINVAL;
+  if (!ctx->h_status || *ctx->h_status == 0) return ACROBAT_OK;
+  *ctx->h_status = 0;
+  return fail(ctx, ACROBAT_ETIMEOUT, "a workgroup of a persistent launch gave up waiting; the launch's outputs are incomplete");
+}
+
+int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int32_t rounds, int32_t same_xcd,
+                       int32_t style, int32_t write_through, int32_t store_floats, int32_t load_floats,
+                       double* us_per_round, double* phase_us, void* hip_stream) {
+  try {
+    TRY(begin_call(ctx));
+    if (!us_per_round || !phase_us) return fail(ctx, ACROBAT_EINVAL, "null output pointer");
+    if (groups < 1 || groups > kPersistMaxBlocks || group_size < 1 || groups * group_size > 256 || rounds < 1 || rounds > 100000)
+      return fail(ctx, ACROBAT_EINVAL, "groups in 1..8, at most 256 workgroups, rounds in 1..100000");
+    if (style < 0 || style > 2 || (style == 2 && group_size > kPersistMaxColBlocks))
+      return fail(ctx, ACROBAT_EINVAL, "style in 0..2; flag lines (style 2) hold at most 32 members");
+    if (store_floats < 0 || store_floats > 16384 || store_floats % 256 || load_floats < 0 || load_floats % 1024 ||
+        load_floats > group_size * store_floats)
+      return fail(ctx, ACROBAT_EINVAL, "payload sizes: store multiple of 256 up to 16384, load multiple of 1024 within the group's stores");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "the probe synchronises: it cannot be captured");
+    int cus = 0;
+    HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device));
+    if (groups * group_size > cus) return fail(ctx, ACROBAT_EINVAL, "more workgroups than compute units: they would not all be resident");
+    TRY(reserve_sync(ctx, stream));
+    const int n_wg = groups * group_size;
+    const size_t payload_floats = 2 * (size_t)n_wg * (size_t)std::max(store_floats, 1);
+    float* payload = nullptr;
+    unsigned long long* ticks = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = ACROBAT_OK;
+    auto cleanup = [&]() {
+      if (payload) (void)hipFree(payload);
+      if (ticks) (void)hipFree(ticks);
+      if (e0) (void)hipEventDestroy(e0);
+      if (e1) (void)hipEventDestroy(e1);
+    };
+#define PROBE_TRY(expr)                                     \
+  do {                                                      \
+    hipError_t e_ = (expr);                                 \
+    if (e_ != hipSuccess) { rc = fail_hip(ctx, e_, #expr); cleanup(); return rc; } \
+  } while (0)
+    PROBE_TRY(hipMalloc(reinterpret_cast<void**>(&payload), payload_floats * sizeof(float)));
+    PROBE_TRY(hipMalloc(reinterpret_cast<void**>(&ticks), (size_t)n_wg * 5 * sizeof(unsigned long long)));
+    PROBE_TRY(hipEventCreate(&e0));
+    PROBE_TRY(hipEventCreate(&e1));
+    SyncProbeArgs a{};
+    a.groups = groups; a.group_size = group_size; a.rounds = rounds; a.same_xcd = same_xcd != 0; a.style = style;
+    a.write_through = write_through != 0;
+    a.store_floats = store_floats; a.load_floats = load_floats;
+    a.payload = payload; a.flags = ctx->d_sync; a.counters = ctx->d_sync + kPersistFlagWords;
+    a.status = ctx->d_sync + kSyncWords - 1; a.max_polls = ctx->max_polls;
+    a.ticks = ticks;
+    LaunchEvents ev;
+    ev.start = e0; ev.stop = e1;
+    PROBE_TRY(launch_fill_u32(ctx->d_sync, 0u, kSyncWords, stream));
+    PROBE_TRY(launch_sync_probe(a, stream, ev));
+    PROBE_TRY(hipMemcpyAsync(ctx->h_status, a.status, sizeof(unsigned), hipMemcpyDeviceToHost, stream));
+    PROBE_TRY(hipStreamSynchronize(stream));
+    float ms = 0.0f;
+    PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
+    std::vector<unsigned long long> host((size_t)n_wg * 5);
+    PROBE_TRY(hipMemcpy(host.data(), ticks, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+#undef PROBE_TRY
+    cleanup();
+    *us_per_round = (double)ms * 1e3 / rounds;
+    for (int i = 0; i < 5; ++i) {  // mean over the workgroups; the clock runs at 100 MHz
+      double sum = 0.0;
+      for (int w = 0; w < n_wg; ++w) sum += (double)host[(size_t)w * 5 + i];
+      phase_us[i] = sum / n_wg / rounds * 0.01;
+    }
+    return acrobat_device_status(ctx);
+  } catch (const std::bad_alloc&) {
+    return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");
+  } catch (...) {
+    return fail(ctx, ACROBAT_EINVAL, "unexpected exception");
+  }
 }
 
 int acrobat_set_tuning(acrobat_ctx* ctx, int32_t force_tile, int32_t force_ksplit, int32_t mvrnn_variant) {

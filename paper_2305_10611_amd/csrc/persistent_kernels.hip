@@ -1,0 +1,379 @@
+// Persistent kernels for gfx950: a whole sequence of dependent depth levels in ONE launch.
+//
+// A depth level normally is one kernel launch (cell_kernels.hip): the kernel boundary is the dependency
+// between consecutive levels.  For a recurrence of 100 short steps that boundary - launch gap, index
+// loads, re-streaming the same 4 MB of weights - is most of the run time (the paper's activity breakdown,
+// table 6, shows the same for its GPU: API time as large as kernel time; its comparison with Cortex in
+// Evaluation, "Overall Performance", credits that system's persistence of model parameters on chip).
+// Here the recurrence weights stay in registers for all steps and the workgroups synchronise among
+// themselves:
+//  * workgroups that exchange data are placed on one XCD (workgroup ids go round-robin to the 8 XCDs, so
+//    ids that agree modulo 8 share an L2); placement is only a matter of speed, never of correctness:
+//    every exchange uses agent-scope accesses;
+//  * a workgroup waits only for the producers of the rows it reads (the workgroups of its own node
+//    block), never for the whole grid: one arrival counter per block.  (A flag line per consumer, into
+//    which every producer stores the step number, was measured too: 0.3 us per step slower than the
+//    counter once the counter is no longer fenced.)
+//  * no fences.  An agent-scope release writes back and an acquire invalidates the whole L2 of the XCD,
+//    6 us per step with 256 workgroups doing so (measured).  Instead the exchanged rows are stored
+//    write-through (agent-scope atomic stores) and every wavefront waits for its stores to complete
+//    before the workgroup publishes its flags, and the consumers read the rows with agent-scope loads
+//    (buffer loads with the sc1 cache policy), which do not hit stale lines.  That is the instruction
+//    sequence of a release / acquire pair at agent scope without the cache-wide write-back and
+//    invalidate, which only serve plain stores and loads around it - there are none here;
+//  * every wait is bounded: when it runs out the workgroup raises the status word, every workgroup sees
+//    it at its next poll, and the grid drains and ends normally.  The host refuses the launch unless an
+//    occupancy query shows that all workgroups are resident at once.
+#include "persistent_kernels.h"
+
+namespace acrobat {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+// s_waitcnt with vmcnt = 0 and the other counters at their maximum (gfx9 encoding): all vector memory
+// operations of this wavefront, stores included, have completed
+constexpr int kWaitVmcnt0 = 0x0F70;
+
+__device__ __forceinline__ float fast_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
+__device__ __forceinline__ float fast_tanh(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * x) + 1.0f); }
+
+__device__ __forceinline__ unsigned load_agent(const unsigned* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+constexpr int kRsrcFlags = 0x00020000;  // raw buffer resource, 32-bit data format (gfx9)
+constexpr int kAuxAgentScope = 16;      // cache policy of a buffer load: sc1 = coherent at agent scope
+
+// 16-byte load that is coherent at agent scope without an acquire fence: the line is fetched past the
+// caches that other workgroups' write-through stores do not reach.  `byte_off` < 2^32 (host-checked).
+__device__ __forceinline__ floatx4 load_agent_f4(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off) {
+  return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, kAuxAgentScope));
+}
+
+// Wavefront 0 of a workgroup waits until every one of the `n` (<= 32) flag words of its line is >= target:
+// lane i < n watches word i.  All 64 lanes take part (uniform control flow); returns false as wait_for does.
+__device__ __forceinline__ bool wait_for_flags(const unsigned* line, int n, unsigned target, unsigned* status, int max_polls) {
+  const int lane = threadIdx.x & 63;
+  int polls = 0;
+  while (true) {
+    const unsigned v = lane < n ? load_agent(line + lane) : target;
+    if (__ballot(v < target) == 0) return true;
+    if (++polls > max_polls) {
+      if (lane == 0) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return false;
+    }
+    if ((polls & 15) == 0 && load_agent(status) != 0) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
+// Thread 0 of a workgroup waits until *counter >= target.  Returns false when the wait ran out or another
+// workgroup has raised the status word; the caller then leaves its loop.
+__device__ __forceinline__ bool wait_for(const unsigned* counter, unsigned target, unsigned* status, int max_polls) {
+  int polls = 0;
+  while (load_agent(counter) < target) {
+    if (++polls > max_polls) {
+      __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return false;
+    }
+    if ((polls & 15) == 0 && load_agent(status) != 0) return false;
+    __builtin_amdgcn_s_sleep(1);
+  }
+  return true;
+}
+
+__global__ void fill_u32_kernel(unsigned* p, unsigned value, int n) {
+  for (int i = threadIdx.x + blockIdx.x * blockDim.x; i < n; i += blockDim.x * gridDim.x) p[i] = value;
+}
+
+// ---- LSTM recurrence ---------------------------------------------------------------------------------
+// Workgroup (nb, cb) = (blockIdx % 8, blockIdx / 8): node block nb lives on XCD nb.  Wavefront g computes
+// gate g for the workgroup's 16 hidden units: its 16 weight rows are the B operand of
+// v_mfma_f32_16x16x4_f32 and stay in H/4 registers per lane; the A operand is the block's h_{t-1} rows,
+// staged in LDS once per step.  Lane l supplies A[slot l%16][k] and B[k][unit l%16] for the four k
+// = 16 it + 4 (l/16) + e, e = 0..3, of 16-k group `it` (one 16-byte LDS read feeds four instructions), and
+// holds z[slot 4 (l/16) + v][unit l%16] in result register v.  The slots of a block are sorted by
+// non-increasing length, so the live sequences of a step are a prefix and a step multiplies 16 or 32 rows.
+template <int H>
+__global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const LstmPersistentArgs a) {
+  constexpr int CB = H / 16;   // column blocks = workgroups per node block
+  constexpr int LD = H + 4;    // padded LDS row: 16-byte reads of 8 consecutive rows hit distinct banks
+  constexpr int NIT = H / 16;  // 16-k groups
+  constexpr int CW = 128;      // columns per staging chunk: 32 rows x 128 columns = 4 passes of the 256 threads
+  constexpr int CH = H / CW;
+  static_assert(H % CW == 0 && kPersistSlots == 32 && kThreads == 256, "staging layout");
+  __shared__ __attribute__((aligned(16))) float hs[kPersistSlots * LD];
+  __shared__ float zs[4][kPersistSlots][17];
+  __shared__ int s_row0[kPersistSlots], s_len[kPersistSlots];
+  __shared__ int s_go;
+
+  const int nb = blockIdx.x % kPersistMaxBlocks, cb = blockIdx.x / kPersistMaxBlocks;
+  if (nb >= a.n_blocks) return;
+  const int tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
+  const int col = lane & 15, kq = lane >> 4;
+
+  if (tid < kPersistSlots) {
+    s_row0[tid] = a.slot_row0[nb * kPersistSlots + tid];
+    s_len[tid] = a.slot_len[nb * kPersistSlots + tid];
+  }
+  for (int i = tid; i < kPersistSlots * LD; i += kThreads) hs[i] = 0.0f;  // rows of dead slots stay finite
+  // this wavefront's weight rows: gate g, units 16 cb + col
+  floatx4 wreg[NIT];
+  {
+    const float* wrow = a.Wh + ((size_t)g * H + 16 * cb + col) * H + 4 * kq;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) wreg[it] = *reinterpret_cast<const floatx4*>(wrow + 16 * it);
+  }
+  __syncthreads();
+
+  const int T = s_len[0];  // the block's longest sequence
+  // epilogue ownership: slot tid / 8, units 16 cb + 2 (tid % 8) and the next one
+  const int my_slot = tid >> 3, u0 = (tid & 7) * 2;
+  const int my_len = s_len[my_slot];
+  const size_t my_row0 = (size_t)s_row0[my_slot];
+  float c0 = 0.0f, c1 = 0.0f;
+  unsigned* const counter = a.counters + nb * kPersistCounterStride;  // arrivals of this block's workgroups
+  const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.h, 0, (int)a.h_bytes, kRsrcFlags);
+
+  for (int t = 0; t < T; ++t) {
+    // input transform of this step: does not depend on h, requested before the wait
+    floatx2 xv[4];
+    if (my_len > t) {
+      const float* xrow = a.xp + (my_row0 + t) * (size_t)(4 * H) + 16 * cb + u0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) xv[q] = *reinterpret_cast<const floatx2*>(xrow + q * H);
+    }
+    float z[4][2];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) z[q][0] = z[q][1] = 0.0f;
+
+    if (t > 0) {
+      const int live = __popcll(__ballot(lane < kPersistSlots && s_len[lane & 31] > t));
+      // h_{t-1} of the block is complete once all CB workgroups have arrived t times
+      if (tid == 0) s_go = wait_for(counter, (unsigned)(CB * t), a.status, a.max_polls) ? 1 : 0;
+      __syncthreads();
+      if (!s_go) break;
+      // The live rows (all of them were live at t - 1) go to LDS in chunks of 128 columns: every load is
+      // requested up front, and the matrix instructions of a chunk run while the later chunks are in flight.
+      floatx4 stage[CH][4];
+#pragma unroll
+      for (int c = 0; c < CH; ++c)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int row = (p * kThreads + tid) >> 5;
+          if (row < live)
+            stage[c][p] = load_agent_f4(h_rsrc, (unsigned)((((size_t)s_row0[row] + t - 1) * H + CW * c + 4 * (tid & 31)) * sizeof(float)));
+        }
+      // contraction: 16 or 32 rows x 16 units x H for this wavefront's gate, two accumulators per row group
+      const float* arow = &hs[col * LD + 4 * kq];
+      floatx4 acc00 = {0, 0, 0, 0}, acc01 = {0, 0, 0, 0}, acc10 = {0, 0, 0, 0}, acc11 = {0, 0, 0, 0};
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int row = (p * kThreads + tid) >> 5;
+          if (row < live) *reinterpret_cast<floatx4*>(&hs[row * LD + CW * c + 4 * (tid & 31)]) = stage[c][p];
+        }
+        __syncthreads();
+        if (live > 16) {
+#pragma unroll
+          for (int it = c * (CW / 16); it < (c + 1) * (CW / 16); ++it) {
+            const floatx4 f0 = *reinterpret_cast<const floatx4*>(arow + 16 * it);
+            const floatx4 f1 = *reinterpret_cast<const floatx4*>(arow + 16 * LD + 16 * it);
+            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[0], wreg[it][0], acc00, 0, 0, 0);
+            acc10 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[0], wreg[it][0], acc10, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[1], wreg[it][1], acc01, 0, 0, 0);
+            acc11 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[1], wreg[it][1], acc11, 0, 0, 0);
+            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[2], wreg[it][2], acc00, 0, 0, 0);
+            acc10 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[2], wreg[it][2], acc10, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[3], wreg[it][3], acc01, 0, 0, 0);
+            acc11 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[3], wreg[it][3], acc11, 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int it = c * (CW / 16); it < (c + 1) * (CW / 16); ++it) {
+            const floatx4 f0 = *reinterpret_cast<const floatx4*>(arow + 16 * it);
+            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[0], wreg[it][0], acc00, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[1], wreg[it][1], acc01, 0, 0, 0);
+            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[2], wreg[it][2], acc00, 0, 0, 0);
+            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[3], wreg[it][3], acc01, 0, 0, 0);
+          }
+        }
+      }
+      // gate g of (slot 4 kq + v [+ 16], unit col) -> LDS, so that a thread finds all four gates of its elements
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        zs[g][4 * kq + v][col] = acc00[v] + acc01[v];
+        zs[g][16 + 4 * kq + v][col] = acc10[v] + acc11[v];
+      }
+      __syncthreads();
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        z[q][0] = zs[q][my_slot][u0];
+        z[q][1] = zs[q][my_slot][u0 + 1];
+      }
+    }
+
+    if (my_len > t) {
+      float hv[2];
+      float* cc[2] = {&c0, &c1};
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const float zi = z[0][e] + xv[0][e], zf = z[1][e] + xv[1][e], zo = z[2][e] + xv[2][e], zu = z[3][e] + xv[3][e];
+        const float cn = fast_sigmoid(zf) * *cc[e] + fast_sigmoid(zi) * fast_tanh(zu);
+        *cc[e] = cn;
+        hv[e] = fast_sigmoid(zo) * fast_tanh(cn);
+      }
+      const size_t o = (my_row0 + t) * (size_t)H + 16 * cb + u0;
+      // h is read by the other workgroups of the block at the next step: write-through stores
+      __hip_atomic_store(a.h + o, hv[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(a.h + o + 1, hv[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      floatx2 cv = {c0, c1};
+      *reinterpret_cast<floatx2*>(a.c + o) = cv;
+    }
+    if (t + 1 < T) {
+      __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // this wavefront's stores have completed
+      __syncthreads();                          // ... and so have the other wavefronts'
+      if (tid == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
+// ---- probe ---------------------------------------------------------------------------------------------
+// style 0: arrival counter; release (fence + atomic add), acquire fence, plain payload loads - the textbook
+//          barrier; write_through only changes how the payload is stored.
+// style 1: arrival counter, but no fences: write-through payload stores completed before the workgroup
+//          barrier, relaxed atomic add, agent-scope payload loads.
+// style 2: style 1 with a flag line per consumer instead of the counter (group_size <= 32).
+__global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArgs a) {
+  __shared__ int s_go;
+  const int wg = blockIdx.x;
+  const int group = a.same_xcd ? wg % a.groups : wg / a.group_size;
+  const int member = a.same_xcd ? wg / a.groups : wg % a.group_size;
+  const int tid = threadIdx.x;
+  unsigned* const counter = a.counters + group * kPersistCounterStride;
+  const unsigned* const my_line = a.flags + ((size_t)group * kPersistMaxColBlocks + member) * kPersistMaxColBlocks;
+  unsigned* const my_word = a.flags + ((size_t)group * kPersistMaxColBlocks + (tid & 31)) * kPersistMaxColBlocks + member;
+  const size_t gen_floats = (size_t)a.groups * a.group_size * a.store_floats;
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(a.payload, 0, (int)(2 * gen_floats * sizeof(float)), kRsrcFlags);
+  const bool fenced = a.style == 0;
+  unsigned long long ticks[5] = {0, 0, 0, 0, 0};
+  float sink = 0.0f;
+  for (int r = 0; r < a.rounds; ++r) {
+    float* mine = a.payload + (size_t)(r & 1) * gen_floats + ((size_t)group * a.group_size + member) * a.store_floats;
+    const unsigned long long t0 = wall_clock64();
+    for (int i = tid; i < a.store_floats; i += kThreads) {
+      const float v = (float)(r + i);
+      if (a.write_through || !fenced) __hip_atomic_store(mine + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else mine[i] = v;
+    }
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    __syncthreads();
+    const unsigned long long t1 = wall_clock64();
+    unsigned long long t2 = t1, t3 = t1;
+    if (a.style == 2) {
+      if (tid < a.group_size) __hip_atomic_store(my_word, (unsigned)(r + 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid < 64) {
+        t2 = wall_clock64();
+        const bool ok = wait_for_flags(my_line, a.group_size, (unsigned)(r + 1), a.status, a.max_polls);
+        if (tid == 0) s_go = ok ? 1 : 0;
+        t3 = wall_clock64();
+      }
+    } else if (tid == 0) {
+      if (fenced) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      else __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (fenced) __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // so that the cost of the release is seen apart from the wait
+      t2 = wall_clock64();
+      s_go = wait_for(counter, (unsigned)(a.group_size * (r + 1)), a.status, a.max_polls) ? 1 : 0;
+      t3 = wall_clock64();
+    }
+    __syncthreads();
+    if (!s_go) break;
+    if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    const unsigned long long t4 = wall_clock64();
+    // read what the group stored this round (its first load_floats floats), all loads in flight together
+    const size_t base = (size_t)(r & 1) * gen_floats + (size_t)group * a.group_size * a.store_floats;
+    for (int i0 = 0; i0 < a.load_floats; i0 += kThreads * 4 * 16) {
+      floatx4 v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int i = i0 + (u * kThreads + tid) * 4;
+        const bool in = i < a.load_floats;
+        v[u] = floatx4{0, 0, 0, 0};
+        if (in && fenced) v[u] = *reinterpret_cast<const floatx4*>(a.payload + base + i);
+        if (in && !fenced) v[u] = load_agent_f4(rsrc, (unsigned)((base + i) * sizeof(float)));
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) sink += v[u][0] + v[u][1] + v[u][2] + v[u][3];
+    }
+    if (sink == 12345.678f) a.payload[0] = sink;  // keeps the loads
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);       // the acquire's invalidate, if any, has completed too
+    const unsigned long long t5 = wall_clock64();
+    if (tid == 0) {
+      ticks[0] += t1 - t0; ticks[1] += t2 - t1; ticks[2] += t3 - t2; ticks[3] += t4 - t3; ticks[4] += t5 - t4;
+    }
+  }
+  if (tid == 0)
+    for (int i = 0; i < 5; ++i) a.ticks[(size_t)wg * 5 + i] = ticks[i];
+}
+
+template <int H>
+hipError_t launch_lstm_h(const LstmPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev) {
+  const unsigned grid = (unsigned)(kPersistMaxBlocks * (H / 16));
+  launch_with_events((lstm_persistent_kernel<H>), dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, a);
+  return hipGetLastError();
+}
+
+template <int H>
+bool resident_at_once(int n_workgroups) {
+  int dev = 0, per_cu = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, lstm_persistent_kernel<H>, kThreads, 0) != hipSuccess) return false;
+  return (long)per_cu * cus >= n_workgroups;
+}
+
+}  // namespace
+
+bool lstm_persistent_eligible(int32_t H, int32_t n_blocks, const char** why) {
+  const char* dummy;
+  if (!why) why = &dummy;
+  if (n_blocks < 1 || n_blocks > kPersistMaxBlocks) { *why = "more node blocks than one launch holds"; return false; }
+  bool ok = false;
+  switch (H) {
+    case 128: ok = resident_at_once<128>(kPersistMaxBlocks * 8); break;
+    case 256: ok = resident_at_once<256>(kPersistMaxBlocks * 16); break;
+    case 512: ok = resident_at_once<512>(kPersistMaxBlocks * 32); break;
+    default: *why = "hidden size not instantiated"; return false;
+  }
+  if (!ok) *why = "the workgroups would not all be resident at once";
+  return ok;
+}
+
+hipError_t launch_lstm_persistent(const LstmPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev) {
+  switch (a.H) {
+    case 128: return launch_lstm_h<128>(a, stream, ev);
+    case 256: return launch_lstm_h<256>(a, stream, ev);
+    case 512: return launch_lstm_h<512>(a, stream, ev);
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_fill_u32(unsigned* p, unsigned value, int n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 4 * kThreads - 1) / (4 * kThreads))), dim3(kThreads), 0, stream, p, value, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_sync_probe(const SyncProbeArgs& a, hipStream_t stream, const LaunchEvents& ev) {
+  launch_with_events(sync_probe_kernel, dim3((unsigned)(a.groups * a.group_size)), dim3(kThreads), 0, stream, ev.start,
+                     ev.stop, a);
+  return hipGetLastError();
+}
+
+}  // namespace acrobat

@@ -263,6 +263,91 @@ def test_lstm_ragged_with_bias_and_empty_sequences(ctx, P, H, D, n_seq, lo, hi):
     P.assert_close(c, oc, "c")
 
 
+@pytest.mark.parametrize("H,D,n_seq,lo,hi", [(128, 32, 5, 1, 9), (128, 64, 33, 0, 40), (256, 128, 256, 1, 30), (256, 64, 100, 2, 2),
+                                             (512, 64, 70, 0, 25), (512, 512, 256, 1, 100), (512, 32, 17, 60, 60)])
+def test_lstm_whole_recurrence_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
+    """Shapes the persistent kernel takes (H in {128, 256, 512}, at most 256 live sequences): one launch for all
+    time steps, same schedule, same tolerances; and against the one-launch-per-step path of the same library."""
+    import paper_2305_10611_amd as A
+    w = gen.lstm_workload(n_seq, lo, hi, H, D, seed=3 * H + D + n_seq, bias_scale=0.3)
+    ctx.acrobat_set_profiling(True)
+    try:
+        h, c = P.run_lstm(ctx, w)
+        kinds = [r[0] for r in ctx.acrobat_last_profile()]
+    finally:
+        ctx.acrobat_set_profiling(False)
+    assert kinds == [A.binding.K_LSTM_INPUT, A.binding.K_LSTM_PERSISTENT]
+    assert ctx.acrobat_device_status() == A.OK
+    check_seq_schedule(ctx, w["len"])
+    oh, oc = oracle.varlen_lstm(w, nthreads=NT)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+    h2, c2 = P.run_lstm(ctx, w)  # again, without per-launch events: the counters are cleared by every call
+    assert np.array_equal(h, h2) and np.array_equal(c, c2)
+    ctx.acrobat_set_persistent(False)
+    try:
+        ctx.acrobat_set_profiling(True)
+        h1, c1 = P.run_lstm(ctx, w)
+        kinds = [r[0] for r in ctx.acrobat_last_profile()]
+    finally:
+        ctx.acrobat_set_profiling(False)
+        ctx.acrobat_set_persistent(True)
+    assert kinds.count(A.binding.K_LSTM_STEP) == int(w["len"].max()) and A.binding.K_LSTM_PERSISTENT not in kinds
+    P.assert_close(h1, oh, "h, one launch per step")
+    P.assert_close(c1, oc, "c, one launch per step")
+    P.assert_close(h, h1.astype(np.float64), "h, one launch vs one launch per step")
+
+
+def test_lstm_more_sequences_than_one_persistent_launch_holds(ctx, P):
+    """257 live sequences need nine node blocks: the call falls back to one launch per step."""
+    import paper_2305_10611_amd as A
+    w = gen.lstm_workload(257, 1, 6, 128, 32, seed=71, bias_scale=0.2)
+    ctx.acrobat_set_profiling(True)
+    try:
+        h, c = P.run_lstm(ctx, w)
+        kinds = [r[0] for r in ctx.acrobat_last_profile()]
+    finally:
+        ctx.acrobat_set_profiling(False)
+    assert A.binding.K_LSTM_PERSISTENT not in kinds and A.binding.K_LSTM_STEP in kinds
+    oh, oc = oracle.varlen_lstm(w, nthreads=NT)
+    P.assert_close(h, oh, "h")
+    P.assert_close(c, oc, "c")
+
+
+def test_lstm_persistent_wait_that_runs_out_ends_the_kernel_and_is_reported(P):
+    """The bound of the waits inside the persistent kernel, forced from the host: with no polls allowed the
+    first workgroup that finds its block's previous step incomplete gives up, every workgroup leaves at its
+    next poll, the kernel ends normally and acrobat_device_status reports ACROBAT_ETIMEOUT once.  The context
+    then works as before."""
+    import torch
+    import paper_2305_10611_amd as A
+    w = gen.lstm_workload(200, 30, 40, 256, 64, seed=72, bias_scale=0.2)
+    c = A.Context(0)
+    try:
+        assert c.acrobat_set_persistent(True, 0) == A.OK
+        P.run_lstm(c, w)  # synchronises
+        assert c.acrobat_device_status() == A.ETIMEOUT and "gave up waiting" in c.acrobat_last_error()
+        assert c.acrobat_device_status() == A.OK  # reported once
+        assert c.acrobat_set_persistent(True, -1) == A.OK
+        h, cc = P.run_lstm(c, w)
+        assert c.acrobat_device_status() == A.OK
+        oh, oc = oracle.varlen_lstm(w, nthreads=NT)
+        P.assert_close(h, oh, "h")
+        P.assert_close(cc, oc, "c")
+    finally:
+        c.close()
+
+
+def test_sync_probe_reports_sane_times(ctx):
+    import paper_2305_10611_amd as A
+    for same_xcd, style, wt in ((1, 0, 1), (0, 0, 0), (1, 1, 0), (1, 2, 0), (0, 2, 0)):
+        rc, us, phases = ctx.acrobat_sync_probe(8, 8, 200, same_xcd, style, wt, 512, 4096)
+        assert rc == A.OK, ctx.acrobat_last_error()
+        assert 0.2 < us < 500.0 and all(0.0 <= p < 500.0 for p in phases) and sum(phases) <= us * 1.5
+    assert ctx.acrobat_sync_probe(9, 8, 10, 1, 0, 1, 512, 1024)[0] == A.EINVAL
+    assert ctx.acrobat_sync_probe(1, 64, 10, 1, 2, 1, 512, 1024)[0] == A.EINVAL  # a flag line holds 32 members
+
+
 def test_lstm_degenerate(ctx, P):
     w = gen.lstm_workload(4, 1, 3, 32, 32, seed=5)
     w0 = dict(w, len=np.zeros(4, np.int32))

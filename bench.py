@@ -138,6 +138,8 @@ def main():
                          "and what capturing and instantiating it costs; reported under \"graph_replay\"")
     ap.add_argument("--persistent", choices=("auto", "off"), default="auto",
                     help="LSTM only: off = one launch per time step instead of one persistent launch for the recurrence")
+    ap.add_argument("--tuning", default=None, metavar="TILE,KSPLIT",
+                    help="force one kernel variant for every cell level (acrobat_set_tuning), e.g. 64,1 or 65,1")
     ap.add_argument("--sync-probe", action="store_true",
                     help="only run the library's probe of barriers among workgroups inside one kernel (three styles, "
                          "groups on one XCD or spread) and print one JSON line per case")
@@ -195,6 +197,9 @@ def main():
     ctx = A.Context(0)
     if args.persistent == "off":
         ctx.acrobat_set_persistent(False)
+    if args.tuning:
+        tile, ks = (int(v) for v in args.tuning.split(","))
+        ctx.check(ctx.acrobat_set_tuning(tile, ks, 0))
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     stream = torch.cuda.current_stream().cuda_stream
     if kind == "drnn":

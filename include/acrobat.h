@@ -131,8 +131,9 @@ int acrobat_treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32
  *  - At most ACROBAT_NOALLOC_MAX_NODES nodes per call, else ACROBAT_EINVAL (nothing is launched).
  *  - Every call on a GPU, from any context, shares that GPU's array: calls that overlap on one GPU
  *    (two streams, two contexts, two threads) race.  Calls on one stream are safe back to back.
- *    Nothing in the array has to start at zero and nothing is carried from call to call: the index
- *    lists are uploaded whole and every partial tile is written before it is read.
+ *    The index lists are uploaded whole and every partial tile is written before it is read; the only
+ *    words that must be zero when a call starts are the tile counters of evenly split levels at the end
+ *    of the array, which are zero when the library is loaded and which every launch leaves at zero.
  *  - Per-launch profiling and the unfused-gather ablation are not available here (the settings are
  *    ignored); acrobat_last_schedule works as usual.  The host-side schedule still uses the C++ heap. */
 #define ACROBAT_NOALLOC_MAX_NODES 65536
@@ -438,7 +439,8 @@ typedef struct {
   int32_t level; /* depth of the batch */
   int32_t n;     /* nodes (rows) in the batch */
   int32_t tile;  /* nodes per workgroup tile of the kernel variant that was launched */
-  int32_t ksplit; /* workgroups sharing the contraction range of one tile */
+  int32_t ksplit; /* workgroups sharing the contraction range of one tile; 0: the level was cut into equal
+                     shares, one per compute unit, whatever tile boundaries they cross */
   float ms;      /* execution time of the kernel */
 } acrobat_launch_record;
 
@@ -468,9 +470,10 @@ int acrobat_set_gather_fusion(acrobat_ctx* ctx, int32_t enabled);
 /* Tuning and test hook; no result ever depends on it beyond the summation order of the contraction.
  * The launcher normally picks a kernel variant per level from the level's size.  force_tile != 0 makes
  * every cell level of this context use one variant instead: 64 or 32 = nodes per workgroup tile of the
- * tiled kernel, 6 = the kernel for latency-bound levels; force_ksplit (a power of two up to 32, 0 =
- * automatic) is then the number of workgroups sharing a tile's contraction range (tile 6: slabs moved
- * per step, 4 or 8).  A forced shape that does not apply to a level (k range not divisible, workspace
+ * tiled kernel, 6 = the kernel for latency-bound levels, 65 or 33 = 64- or 32-node tiles with the level
+ * cut into equal shares, one per compute unit, inside one launch; force_ksplit (a power of two up to 32,
+ * 0 = automatic) is then the number of workgroups sharing a tile's contraction range (tile 6: slabs moved
+ * per step, 4 or 8; ignored for 65 and 33).  A forced shape that does not apply to a level (k range not divisible, workspace
  * too small) falls back to the automatic choice for that level.  mvrnn_variant: 0 = default MV-RNN
  * level kernels, 1 = the streaming kernel.  All zero restores the defaults.  The library reads no
  * environment variables. */

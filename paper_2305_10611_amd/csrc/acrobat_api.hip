@@ -27,6 +27,7 @@ using namespace acrobat;
 // device address comes from hipGetSymbolAddress, once per device (static_scratch_for).
 constexpr size_t kStaticScratchBytes = (size_t)ACROBAT_NOALLOC_SCRATCH_MIB << 20;
 constexpr size_t kStaticIndexBytes = (size_t)1 << 20;  // 3 int32 per node for ACROBAT_NOALLOC_MAX_NODES nodes
+constexpr size_t kStaticCounterBytes = (size_t)32 << 10;  // tile counters of evenly split levels, at the end
 static_assert(3 * sizeof(int32_t) * (size_t)ACROBAT_NOALLOC_MAX_NODES <= kStaticIndexBytes, "index region too small");
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
@@ -69,6 +70,7 @@ struct acrobat_ctx {
   hipEvent_t fixed_done = nullptr;    // the last upload out of h_fixed_stage has finished
   bool fixed_pending = false;
   unsigned char* static_scratch = nullptr;
+  int32_t n_cu = 0;  // compute units of the device
   // scratch for the hoisted LSTM input transform
   float* d_scratch = nullptr;
   size_t scratch_cap = 0;  // in floats
@@ -189,6 +191,16 @@ int reserve_splitk(acrobat_ctx* ctx, hipStream_t stream) {
   HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&p), kPartialFloats * sizeof(float)));
   ctx->splitk.partial = p;
   ctx->splitk.partial_floats = kPartialFloats;
+  // tile counters of the levels that are split evenly inside one launch: zero between launches
+  constexpr int kCounters = 8192;
+  unsigned* c = nullptr;
+  HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&c), kCounters * sizeof(unsigned)));
+  HIP_TRY(ctx, hipMemset(c, 0, kCounters * sizeof(unsigned)));
+  ctx->splitk.counters = c;
+  ctx->splitk.n_counters = kCounters;
+  int cus = 0;
+  HIP_TRY(ctx, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->device));
+  ctx->splitk.n_cu = cus;
   return ACROBAT_OK;
 }
 
@@ -397,6 +409,10 @@ int acrobat_create(acrobat_ctx** out, int device) {
     return ACROBAT_EHIP;
   }
   ctx->static_scratch = static_cast<unsigned char*>(scratch_ptr);
+  if (hipDeviceGetAttribute(&ctx->n_cu, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) {
+    acrobat_destroy(ctx);
+    return ACROBAT_EHIP;
+  }
   *out = ctx;
   return ACROBAT_OK;
 }
@@ -411,6 +427,7 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->d_idx) (void)hipFree(ctx->d_idx);
   if (ctx->d_scratch) (void)hipFree(ctx->d_scratch);
   if (ctx->splitk.partial) (void)hipFree(ctx->splitk.partial);
+  if (ctx->splitk.counters) (void)hipFree(ctx->splitk.counters);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->d_sync) (void)hipFree(ctx->d_sync);
   if (ctx->h_status) (void)hipHostFree(ctx->h_status);
@@ -523,7 +540,12 @@ int treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, in
       d_idx = reinterpret_cast<int32_t*>(ctx->static_scratch);
       ws = ctx->splitk;  // tuning hook settings
       ws.partial = reinterpret_cast<float*>(ctx->static_scratch + kStaticIndexBytes);
-      ws.partial_floats = (kStaticScratchBytes - kStaticIndexBytes) / sizeof(float);
+      ws.partial_floats = (kStaticScratchBytes - kStaticIndexBytes - kStaticCounterBytes) / sizeof(float);
+      // the tile counters: a region nothing else ever writes, zero when the library is loaded and whenever no
+      // launch is in flight
+      ws.counters = reinterpret_cast<unsigned*>(ctx->static_scratch + kStaticScratchBytes - kStaticCounterBytes);
+      ws.n_counters = (int32_t)(kStaticCounterBytes / sizeof(unsigned));
+      ws.n_cu = ctx->n_cu;
     } else {
       TRY(reserve_splitk(ctx, stream));
       TRY(reserve_indices(ctx, 3 * (size_t)N + n_iota, stream));
@@ -1182,6 +1204,8 @@ int acrobat_drnn_forward(acrobat_ctx* ctx, int32_t n_inst, const float* d_x0, co
       group_ws[q] = ctx->splitk;
       group_ws[q].partial_floats = ctx->splitk.partial_floats / (size_t)n_groups;
       group_ws[q].partial = ctx->splitk.partial + (size_t)q * group_ws[q].partial_floats;
+      group_ws[q].n_counters = ctx->splitk.n_counters / n_groups;
+      group_ws[q].counters = ctx->splitk.counters + (size_t)q * group_ws[q].n_counters;
     }
     // Index lists: every group stages its lists in a region of its own of the pinned buffer and its
     // kernels read them there.  A region is rewritten only after the group's previous evaluation has
@@ -1332,8 +1356,8 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
 
 int acrobat_set_tuning(acrobat_ctx* ctx, int32_t force_tile, int32_t force_ksplit, int32_t mvrnn_variant) {
   if (!ctx) return ACROBAT_EINVAL;
-  if (force_tile != 0 && force_tile != 6 && force_tile != 32 && force_tile != 64)
-    return fail(ctx, ACROBAT_EINVAL, "force_tile must be 0, 6, 32 or 64");
+  if (force_tile != 0 && force_tile != 6 && force_tile != 32 && force_tile != 64 && force_tile != 33 && force_tile != 65)
+    return fail(ctx, ACROBAT_EINVAL, "force_tile must be 0, 6, 32, 64, 33 or 65");
   if (force_ksplit < 0 || force_ksplit > 32 || (force_ksplit & (force_ksplit - 1)))
     return fail(ctx, ACROBAT_EINVAL, "force_ksplit must be 0 or a power of two up to 32");
   if (mvrnn_variant != 0 && mvrnn_variant != 1) return fail(ctx, ACROBAT_EINVAL, "mvrnn_variant must be 0 or 1");

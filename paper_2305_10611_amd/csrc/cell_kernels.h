@@ -48,6 +48,11 @@ struct CellLevelArgs {
 struct SplitKWorkspace {
   float* partial = nullptr;
   size_t partial_floats = 0;
+  // tile counters of the levels that are split evenly over the chip inside one launch (zero whenever no such
+  // launch is in flight), and the number of compute units the split is made for
+  unsigned* counters = nullptr;
+  int32_t n_counters = 0;
+  int32_t n_cu = 0;
   int32_t force_bm = 0, force_ksplit = 0;  // tuning override, 0 = automatic
 };
 

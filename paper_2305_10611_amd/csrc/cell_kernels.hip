@@ -35,6 +35,9 @@
 // weight rows of one or two j tiles and keeps them in its own L2 for the whole level.
 #include "cell_kernels.h"
 
+#include "agent_access.h"
+
+#include <algorithm>
 #include <atomic>
 #include <type_traits>
 
@@ -174,31 +177,37 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
   }
 }
 
+// LDS of one workgroup of the tiled kernels: slab buffers (reused by the reduction over the k-split
+// wavefronts) and the tile's index table [3][BM] behind them.
+template <int G, int WM, int WK>
+struct TileLds {
+  static constexpr int BM = 32 * WM;
+  static constexpr int Q = 4 / WK;  // 8-k groups of a slab handled by one wavefront
+  static constexpr int TILE_FLOATS = (BM + 32 * G) * kBK;
+  static constexpr int RED_FLOATS = WM * (WK - 1) * G * kBlockFloats;
+  static constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers (see the pipeline in contract_tile)
+  static constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
+  static constexpr int TOTAL_FLOATS = SMEM_FLOATS + 3 * BM;
+  static constexpr int NV = 4 * (4 / WK);  // accumulator rows a lane owns after the reduction over wk
+};
+
+// Contraction of one tile (BM nodes from m0, hidden units j0 .. j0 + 31, all G gates) over the slabs
+// [slab0, slab0 + my_slabs) of the k range.  On return own[g][v] holds this wavefront's share of the
+// result (accumulator row acc_row(v), see tile_acc_row) and sidx the tile's index table.
 template <int G, int EPI, int WM, int WK>
-__global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelPair pr, const int ksplit,
-                                                                 float* __restrict__ partial) {
-  const bool second = blockIdx.x >= (unsigned)pr.split;  // which of the two batches (uniform)
-  const CellLevelArgs& a = pr.a[second];
-  const int bid = (int)blockIdx.x - (second ? pr.split : 0);
+__device__ __forceinline__ void contract_tile(const CellLevelArgs& a, const int m0, const int j0, const int slab0,
+                                              const int my_slabs, float* const smem, int* const sidx,
+                                              float (&own)[G][TileLds<G, WM, WK>::NV]) {
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
-  constexpr int BM = 32 * WM;
-  constexpr int BROWS = 32 * G;
-  constexpr int Q = 4 / WK;  // 8-k groups of a slab handled by one wavefront
-  constexpr int TILE_FLOATS = (BM + BROWS) * kBK;
-  constexpr int RED_FLOATS = WM * (WK - 1) * G * kBlockFloats;
-  constexpr int NBUF = Q == 1 ? 3 : 2;  // slab buffers in LDS (see the pipeline below)
-  constexpr int SMEM_FLOATS = NBUF * TILE_FLOATS > RED_FLOATS ? NBUF * TILE_FLOATS : RED_FLOATS;
-  __shared__ __attribute__((aligned(16))) float smem[SMEM_FLOATS + 3 * BM];
-  int* const sidx = reinterpret_cast<int*>(smem + SMEM_FLOATS);  // the tile's index table, see cell_epilogue
+  using L = TileLds<G, WM, WK>;
+  constexpr int BM = L::BM;
+  constexpr int Q = L::Q;
+  constexpr int TILE_FLOATS = L::TILE_FLOATS;
+  constexpr int NBUF = L::NBUF;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave % WM, wk = wave / WM;
   const int H = a.H, n = a.n;
-  const int n_jt = H >> 5;
-  const int jt = bid % n_jt;
-  const int rest = bid / n_jt;
-  const int ks = rest % ksplit, mt = rest / ksplit;
-  const int j0 = jt * 32, m0 = mt * BM;
 
   // ---- global -> LDS staging assignment: 16-byte chunk `tid & 7` of tile row `tid >> 3` (+32 i)
   const int lrow = tid >> 3, lpart = (tid & 7) * 4;
@@ -226,8 +235,6 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
     for (int v = 0; v < 16; ++v) acc[g][v] = 0.0f;
 
   const int slabs_per_seg = a.kseg / kBK;
-  const int my_slabs = (a.nseg * slabs_per_seg) / ksplit;  // host guarantees divisibility
-  const int slab0 = ks * my_slabs;
 
   // Software pipeline, written so that one wavefront per SIMD can keep the matrix pipe busy
   // and two workgroups fit a compute unit (<= 80 KB LDS, <= 256 registers):
@@ -395,8 +402,6 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   // epilogue for the rows it owns, so the gate arithmetic is spread over all four SIMDs.  Each
   // quad is summed in ascending wk order, whoever owns it.
   constexpr int QPW = 4 / WK;  // quads owned per wavefront
-  constexpr int NV = 4 * QPW;  // accumulator rows owned per lane
-  float own[G][NV];
   if constexpr (WK == 1) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
@@ -448,29 +453,176 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
         for (int e = 0; e < 4; ++e) own[g][qi * 4 + e] = sum[e];
       }
   }
-  // accumulator row of owned row v: quad wk*QPW + v/4, element v%4
-  auto acc_row = [&](int v) { return (wk * QPW + (v >> 2)) * 4 + (v & 3); };
+}
+
+// accumulator row of a lane's owned row v: quad wk * QPW + v / 4, element v % 4
+template <int WK>
+__device__ __forceinline__ int tile_acc_row(int wk, int v) { return (wk * (4 / WK) + (v >> 2)) * 4 + (v & 3); }
+
+// fused epilogue of a contracted tile (accumulator row r of a lane: node = m0 + 32 wm + 8 (r / 4) + 4 (lane / 32) + r % 4)
+template <int G, int EPI, int WM, int WK>
+__device__ __forceinline__ void tile_epilogue(const CellLevelArgs& a, const int m0, const int j0, const int* sidx,
+                                              const float (&own)[G][TileLds<G, WM, WK>::NV]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave % WM, wk = wave / WM;
+  cell_epilogue<G, EPI, TileLds<G, WM, WK>::NV>(
+      a, j0 + (lane & 31), [&](int g, int v) { return own[g][v]; },
+      [&](int v) {
+        const int r = tile_acc_row<WK>(wk, v);
+        return m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+      },
+      sidx, 32 * WM, m0);
+}
+
+template <int G, int EPI, int WM, int WK>
+__global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevelPair pr, const int ksplit,
+                                                                 float* __restrict__ partial) {
+  const bool second = blockIdx.x >= (unsigned)pr.split;  // which of the two batches (uniform)
+  const CellLevelArgs& a = pr.a[second];
+  const int bid = (int)blockIdx.x - (second ? pr.split : 0);
+  using L = TileLds<G, WM, WK>;
+  __shared__ __attribute__((aligned(16))) float smem[L::TOTAL_FLOATS];
+  int* const sidx = reinterpret_cast<int*>(smem + L::SMEM_FLOATS);  // the tile's index table, see cell_epilogue
+
+  const int n_jt = a.H >> 5;
+  const int jt = bid % n_jt;
+  const int rest = bid / n_jt;
+  const int ks = rest % ksplit, mt = rest / ksplit;
+  const int j0 = jt * 32, m0 = mt * L::BM;
+  const int my_slabs = (a.nseg * (a.kseg / kBK)) / ksplit;  // host guarantees divisibility
+  float own[G][L::NV];
+  contract_tile<G, EPI, WM, WK>(a, m0, j0, ks * my_slabs, my_slabs, smem, sidx, own);
 
   // ---- k split over workgroups: store the partial tile in register layout and stop; the
   // reduction kernel that follows on the stream adds the partial tiles and runs the epilogue
   if (ksplit > 1) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave % WM, wk = wave / WM;
     const int tile = mt * n_jt + jt;
     float* mine = partial + ((size_t)(tile * ksplit + ks) * WM + wm) * (G * kBlockFloats);
 #pragma unroll
     for (int g = 0; g < G; ++g)
 #pragma unroll
-      for (int v = 0; v < NV; ++v) mine[(g * 16 + acc_row(v)) * 64 + lane] = own[g][v];
+      for (int v = 0; v < L::NV; ++v) mine[(g * 16 + tile_acc_row<WK>(wk, v)) * 64 + lane] = own[g][v];
     return;
   }
+  tile_epilogue<G, EPI, WM, WK>(a, m0, j0, sidx, own);
+}
 
-  // ---- fused epilogue (accumulator row r of a lane: node = m0 + 32 wm + 8 (r / 4) + 4 (lane / 32) + r % 4)
-  cell_epilogue<G, EPI, NV>(
-      a, j0 + (lane & 31), [&](int g, int v) { return own[g][v]; },
-      [&](int v) {
-        const int r = acc_row(v);
-        return m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-      },
-      sidx, BM, m0);
+// ---- even split of a level over the chip ("stream-k") ---------------------------------------------------
+// A level of T tiles is T * n_slabs units of work (one unit = one 32-k slab of one tile) in the order
+// (tile, slab).  With fewer tiles than the chip has room for, whole tiles leave compute units idle for a
+// good part of the level (208 tiles on 256 units: the level takes as long as 256 tiles would).  Here the
+// unit range is cut into P equal contiguous shares, one per workgroup, so a share is the tail of one tile,
+// some whole tiles and the head of another.  A workgroup finishes the whole tiles itself.  For a piece of a
+// tile it stores its partial sums to the workspace (write-through), completes those stores and counts
+// itself in at the tile's counter; whoever counts in last adds the pieces - all of them read back from the
+// workspace, in ascending order of k, so the sum does not depend on who came last - and runs the epilogue.
+// Nobody waits for anybody, so nothing here can hang and no workgroup needs another to be resident.  No
+// fence is involved (a release / acquire pair at agent scope costs several microseconds on this part, see
+// persistent_kernels.hip): the pieces are stored with agent-scope atomic stores and read with agent-scope
+// atomic loads.  A workgroup's share touches at most two tiles partially (its first and its last), hence
+// two workspace slots per workgroup.  The last arriver resets the counter for the next launch.
+struct StreamKArgs {
+  CellLevelArgs a;
+  int32_t n_wg;        // P, at most the number of units
+  float* partial;      // [P][2][WM][G][4 quads][64 lanes][4 rows]
+  uint32_t partial_bytes;
+  unsigned* counters;  // [tiles], zero at launch and again at exit
+};
+
+template <int G, int EPI, int WM, int WK>
+__global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamKArgs sk) {
+  const CellLevelArgs& a = sk.a;
+  using L = TileLds<G, WM, WK>;
+  __shared__ __attribute__((aligned(16))) float smem[L::TOTAL_FLOATS];
+  __shared__ int s_last;
+  int* const sidx = reinterpret_cast<int*>(smem + L::SMEM_FLOATS);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave % WM, wk = wave / WM;
+  const int n_jt = a.H >> 5;
+  // all of this fits 32 bits: the host admits at most 8192 tiles and 512 workgroups, and a k range of 2^16 slabs
+  // would be a contraction over two million columns
+  const int n_slabs = a.nseg * (a.kseg / kBK);
+  const int tiles = ((a.n + L::BM - 1) / L::BM) * n_jt;
+  const unsigned U = (unsigned)tiles * (unsigned)n_slabs, P = (unsigned)sk.n_wg;
+  auto start_of = [&](unsigned p) { return (unsigned)((unsigned long long)p * U / P); };               // first unit of workgroup p
+  auto owner_of = [&](unsigned x) { return (unsigned)(((unsigned long long)(x + 1) * P - 1) / U); };  // whose share holds unit x
+  constexpr int QPW = 4 / WK;  // accumulator quads (4 rows each) a wavefront owns per gate
+  // byte offset in the workspace of the slot where workgroup p parks its piece of `tile` (this wavefront's node block)
+  auto slot_of = [&](unsigned p, int tile) {
+    return (unsigned)(((2 * p + ((int)(start_of(p) / n_slabs) == tile ? 0 : 1)) * WM + wm) * (G * kBlockFloats) * sizeof(float));
+  };
+  auto quad_off = [&](int g, int qi) { return (unsigned)((((g * 4 + wk * QPW + qi) * 64) + lane) * 4 * sizeof(float)); };
+  const __amdgpu_buffer_rsrc_t ws_rsrc = agent_buffer(sk.partial, sk.partial_bytes);
+  const unsigned p = blockIdx.x;
+  const unsigned u1 = start_of(p + 1);
+  bool first = true;
+  for (unsigned u = start_of(p); u < u1; first = false) {
+    const int tile = (int)(u / n_slabs);
+    const int s0 = (int)(u - (unsigned)tile * n_slabs);
+    const int cnt = (n_slabs - s0 < (int)(u1 - u)) ? n_slabs - s0 : (int)(u1 - u);
+    u += cnt;
+    const int jt = tile % n_jt, mt = tile / n_jt;
+    const int j0 = jt * 32, m0 = mt * L::BM;
+    if (!first) __syncthreads();  // the previous tile's epilogue is through with the index table and the slabs
+    float own[G][L::NV];
+    contract_tile<G, EPI, WM, WK>(a, m0, j0, s0, cnt, smem, sidx, own);
+    if (cnt < n_slabs) {  // a piece: park it, count in, and leave unless last
+      // 16 bytes per lane and access: the four rows of accumulator quad (wk * QPW + qi) of gate g
+      const unsigned mine = slot_of(p, tile);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int qi = 0; qi < QPW; ++qi) {
+          const agent_f4 v = {own[g][4 * qi], own[g][4 * qi + 1], own[g][4 * qi + 2], own[g][4 * qi + 3]};
+          store_agent_f4(ws_rsrc, mine + quad_off(g, qi), v);
+        }
+      wait_stores_done();  // this wavefront's stores have completed
+      __syncthreads();     // ... and so have the other wavefronts'
+      const unsigned first_wg = owner_of((unsigned)tile * n_slabs), last_wg = owner_of((unsigned)tile * n_slabs + n_slabs - 1);
+      if (threadIdx.x == 0) {
+        const unsigned arrived = __hip_atomic_fetch_add(sk.counters + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = arrived == last_wg - first_wg;
+        if (last) __hip_atomic_store(sk.counters + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = last ? 1 : 0;
+      }
+      __syncthreads();
+      if (!s_last) continue;
+      // the pieces in ascending order of k, this workgroup's own from its registers (the same bits it parked)
+      float sum[G][L::NV];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int v = 0; v < L::NV; ++v) sum[g][v] = 0.0f;
+      for (unsigned q = first_wg; q <= last_wg; ++q) {
+        if (q == p) {
+#pragma unroll
+          for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int v = 0; v < L::NV; ++v) sum[g][v] += own[g][v];
+          continue;
+        }
+        const unsigned theirs = slot_of(q, tile);
+        agent_f4 piece[G][QPW];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int qi = 0; qi < QPW; ++qi) piece[g][qi] = load_agent_f4(ws_rsrc, theirs + quad_off(g, qi));
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int qi = 0; qi < QPW; ++qi)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sum[g][4 * qi + e] += piece[g][qi][e];
+      }
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int v = 0; v < L::NV; ++v) own[g][v] = sum[g][v];
+    }
+    tile_epilogue<G, EPI, WM, WK>(a, m0, j0, sidx, own);
+  }
 }
 
 // Second half of a level whose k range was split over `ksplit` workgroups: one wavefront per
@@ -699,7 +851,21 @@ hipError_t launch_tiny(const CellLevelPair& pr, unsigned grid, hipStream_t strea
 
 struct Shape {
   int bm, ksplit;  // bm == 6 stands for cell_tiny_kernel (ksplit then carries its slabs per step, 0 = automatic)
+  int streamk_wgs = 0;  // > 0: the level is split evenly over this many workgroups in one launch (ksplit is 1)
 };
+
+// Workgroups for the even split of a level, 0 if the level cannot be split that way.
+template <int G>
+int streamk_workgroups(const CellLevelArgs& a, const SplitKWorkspace& ws, int bm) {
+  const long n_slabs = (long)a.nseg * (a.kseg / kBK);
+  const long tiles = (long)((a.n + bm - 1) / bm) * (a.H / 32);
+  if (n_slabs < 4 || ws.n_cu <= 0 || !ws.counters || tiles > ws.n_counters) return 0;
+  // a share is at least a quarter of a tile's k range: at most five pieces per tile, at least one unit per workgroup
+  const long wgs = std::min<long>(ws.n_cu, 4 * tiles);  // two per compute unit measured slower (65 vs 61 us at 288 tiles)
+  const size_t floats = (size_t)wgs * 2 * (bm / 32) * G * kBlockFloats;
+  if (floats > ws.partial_floats || floats * sizeof(float) >= ((size_t)1 << 32)) return 0;
+  return (int)wgs;
+}
 
 // Picks the node-tile height and the k split for a level from a small cost model.
 template <int G>
@@ -714,6 +880,11 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
     return (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
   };
   if (ws.force_bm == 6) return Shape{6, ws.force_ksplit == 4 || ws.force_ksplit == 8 ? ws.force_ksplit : 0};
+  if (ws.force_bm == 65 || ws.force_bm == 33) {  // tuning override: even split with 64- or 32-node tiles
+    const int bm = ws.force_bm - 1;
+    const int wgs = streamk_workgroups<G>(a, ws, bm);
+    if (wgs > 0) return Shape{bm, 1, wgs};
+  }
   if (ws.force_bm == 64 || ws.force_bm == 32) {  // tuning override
     Shape f{ws.force_bm, ws.force_ksplit > 0 ? ws.force_ksplit : 1};
     if (fits(f.bm, f.ksplit)) return f;
@@ -735,6 +906,21 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   if (tiles32 <= 256 && G >= 4) return Shape{32, 1};
   Shape best{a.n > 128 ? 64 : 32, 1};
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
+  //  * up to two rounds of 64-node tiles: whole tiles leave compute units idle for part of the level (144 or
+  //    208 tiles take as long as 256, 288 nearly as long as 512).  Cutting the level into equal shares, one
+  //    per compute unit, inside one launch (cell_streamk_kernel) evens that out but costs about 12 us of its
+  //    own (a second prologue, parking and adding the pieces).  Fitted on H = 512: a slab of a five-gate
+  //    tile takes 1.4 us on a compute unit, two co-resident tiles 1.87 times one; measured 61 instead of
+  //    74 us at 288 tiles, 39 instead of 44 at 144, but 49 instead of 45 at 208 and 90 instead of 85 at 448.
+  if (best.bm == 64 && tiles <= 2L * ws.n_cu && ws.n_cu > 0) {
+    const double full = 0.28 * G * n_slabs;  // one whole tile on a compute unit of its own, us
+    const double plain = tiles <= ws.n_cu ? full : 1.87 * full;
+    const double even = (double)tiles / ws.n_cu * full + 12.0;
+    if (even < 0.95 * plain) {
+      const int wgs = streamk_workgroups<G>(a, ws, 64);
+      if (wgs > 0) return Shape{64, 1, wgs};
+    }
+  }
   int s = 1;
   while (s * 2 <= 8 && tiles * s * 2 <= 256 && n_slabs % (s * 2) == 0 && n_slabs / (s * 2) >= 2) s *= 2;
   //  * the reduction kernel adds about 4.4 us to the level's dependent chain while one workgroup
@@ -760,11 +946,12 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
   const Shape sh = pick_shape<G>(a, ws);
   if (b) {
     const Shape sh2 = pick_shape<G>(*b, ws);
-    const bool shareable = sh.bm == sh2.bm && (sh.bm == 6 ? sh.ksplit == sh2.ksplit : (sh.ksplit == 1 && sh2.ksplit == 1));
+    const bool shareable = sh.bm == sh2.bm && sh.streamk_wgs == 0 && sh2.streamk_wgs == 0 &&
+                           (sh.bm == 6 ? sh.ksplit == sh2.ksplit : (sh.ksplit == 1 && sh2.ksplit == 1));
     if (!shareable) {  // two launches in a row, bracketed as one: first kernel's begin .. last kernel's end
       LaunchEvents e0, e1;
       e0.start = ev.start;
-      if (sh2.bm != 6 && sh2.ksplit > 1) e1.reduce_stop = ev.stop;
+      if (sh2.bm != 6 && sh2.ksplit > 1 && sh2.streamk_wgs == 0) e1.reduce_stop = ev.stop;
       else e1.stop = ev.stop;
       const hipError_t err = launch_shape<G, EPI>(a, nullptr, stream, ws, tile, nullptr, e0);
       if (err != hipSuccess) return err;
@@ -784,6 +971,19 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
     const int u = sh.ksplit ? sh.ksplit : (g0 + g1 <= 256 ? 8 : 4);
     if (ksplit) *ksplit = 1;
     return u == 8 ? launch_tiny<G, EPI, 8>(pr, g0 + g1, stream, ev) : launch_tiny<G, EPI, 4>(pr, g0 + g1, stream, ev);
+  }
+  if (sh.streamk_wgs > 0) {
+    StreamKArgs sk{a, sh.streamk_wgs, ws.partial,
+                   (uint32_t)((size_t)sh.streamk_wgs * 2 * (sh.bm / 32) * G * kBlockFloats * sizeof(float)), ws.counters};
+    if (ksplit) *ksplit = 0;  // reported as 0: cut into equal shares, not into a fixed number of k ranges per tile
+    if (sh.bm == 64) {
+      launch_with_events((cell_streamk_kernel<G, EPI, 2, 2>), dim3((unsigned)sh.streamk_wgs), dim3(kThreads), 0, stream,
+                         ev.start, ev.stop, sk);
+    } else {
+      launch_with_events((cell_streamk_kernel<G, EPI, 1, 4>), dim3((unsigned)sh.streamk_wgs), dim3(kThreads), 0, stream,
+                         ev.start, ev.stop, sk);
+    }
+    return hipGetLastError();
   }
   const int n_jt = a.H / 32;
   const unsigned g0 = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);

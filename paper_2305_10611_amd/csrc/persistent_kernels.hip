@@ -26,6 +26,8 @@
 //    occupancy query shows that all workgroups are resident at once.
 #include "persistent_kernels.h"
 
+#include "agent_access.h"
+
 namespace acrobat {
 namespace {
 
@@ -33,26 +35,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
-// s_waitcnt with vmcnt = 0 and the other counters at their maximum (gfx9 encoding): all vector memory
-// operations of this wavefront, stores included, have completed
-constexpr int kWaitVmcnt0 = 0x0F70;
 
 __device__ __forceinline__ float fast_sigmoid(float x) { return __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 __device__ __forceinline__ float fast_tanh(float x) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(__expf(2.0f * x) + 1.0f); }
-
-__device__ __forceinline__ unsigned load_agent(const unsigned* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
-constexpr int kRsrcFlags = 0x00020000;  // raw buffer resource, 32-bit data format (gfx9)
-constexpr int kAuxAgentScope = 16;      // cache policy of a buffer load: sc1 = coherent at agent scope
-
-// 16-byte load that is coherent at agent scope without an acquire fence: the line is fetched past the
-// caches that other workgroups' write-through stores do not reach.  `byte_off` < 2^32 (host-checked).
-__device__ __forceinline__ floatx4 load_agent_f4(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off) {
-  return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)byte_off, 0, kAuxAgentScope));
-}
 
 // Wavefront 0 of a workgroup waits until every one of the `n` (<= 32) flag words of its line is >= target:
 // lane i < n watches word i.  All 64 lanes take part (uniform control flow); returns false as wait_for does.
@@ -137,7 +122,7 @@ __global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const Lstm
   const size_t my_row0 = (size_t)s_row0[my_slot];
   float c0 = 0.0f, c1 = 0.0f;
   unsigned* const counter = a.counters + nb * kPersistCounterStride;  // arrivals of this block's workgroups
-  const __amdgpu_buffer_rsrc_t h_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.h, 0, (int)a.h_bytes, kRsrcFlags);
+  const __amdgpu_buffer_rsrc_t h_rsrc = agent_buffer(a.h, a.h_bytes);
 
   for (int t = 0; t < T; ++t) {
     // input transform of this step: does not depend on h, requested before the wait
@@ -236,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const Lstm
       *reinterpret_cast<floatx2*>(a.c + o) = cv;
     }
     if (t + 1 < T) {
-      __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // this wavefront's stores have completed
+      wait_stores_done();  // this wavefront's stores have completed
       __syncthreads();                          // ... and so have the other wavefronts'
       if (tid == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -260,7 +245,7 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
   unsigned* const my_word = a.flags + ((size_t)group * kPersistMaxColBlocks + (tid & 31)) * kPersistMaxColBlocks + member;
   const size_t gen_floats = (size_t)a.groups * a.group_size * a.store_floats;
   const __amdgpu_buffer_rsrc_t rsrc =
-      __builtin_amdgcn_make_buffer_rsrc(a.payload, 0, (int)(2 * gen_floats * sizeof(float)), kRsrcFlags);
+      agent_buffer(a.payload, (unsigned)(2 * gen_floats * sizeof(float)));
   const bool fenced = a.style == 0;
   unsigned long long ticks[5] = {0, 0, 0, 0, 0};
   float sink = 0.0f;
@@ -272,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
       if (a.write_through || !fenced) __hip_atomic_store(mine + i, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       else mine[i] = v;
     }
-    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    wait_stores_done();
     __syncthreads();
     const unsigned long long t1 = wall_clock64();
     unsigned long long t2 = t1, t3 = t1;
@@ -287,7 +272,7 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
     } else if (tid == 0) {
       if (fenced) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
       else __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (fenced) __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);  // so that the cost of the release is seen apart from the wait
+      if (fenced) wait_stores_done();  // so that the cost of the release is seen apart from the wait
       t2 = wall_clock64();
       s_go = wait_for(counter, (unsigned)(a.group_size * (r + 1)), a.status, a.max_polls) ? 1 : 0;
       t3 = wall_clock64();
@@ -312,7 +297,7 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
       for (int u = 0; u < 16; ++u) sink += v[u][0] + v[u][1] + v[u][2] + v[u][3];
     }
     if (sink == 12345.678f) a.payload[0] = sink;  // keeps the loads
-    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);       // the acquire's invalidate, if any, has completed too
+    wait_stores_done();       // the acquire's invalidate, if any, has completed too
     const unsigned long long t5 = wall_clock64();
     if (tid == 0) {
       ticks[0] += t1 - t0; ticks[1] += t2 - t1; ticks[2] += t3 - t2; ticks[3] += t4 - t3; ticks[4] += t5 - t4;

@@ -471,7 +471,7 @@ def test_profiling_records_every_launch(ctx, P):
 
 
 # ---------------------------------------------------------------- every kernel variant
-@pytest.mark.parametrize("tile,ksplit", [(64, 1), (32, 1), (64, 2), (64, 4), (32, 8), (32, 2), (6, 4), (6, 8)])
+@pytest.mark.parametrize("tile,ksplit", [(64, 1), (32, 1), (64, 2), (64, 4), (32, 8), (32, 2), (6, 4), (6, 8), (65, 1), (33, 1)])
 def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit):
     """The launcher normally picks the node-tile height and k split from the level size; the
     tuning hook forces one variant for every level (leaf, internal, LSTM input and steps).
@@ -566,13 +566,28 @@ def test_generic_runtime_treelstm_program_is_bit_identical_to_the_specialised_pa
     g = A.Dfg(ctx)
     leaf, internal = treelstm_ops(g, B, t, w, h, c, N)
     assert g.acrobat_dfg_build_treelstm(w, int(w["V"]), leaf, internal) == A.OK
+    oh, oc = oracle.treelstm(w, nthreads=NT)
+    # The program numbers its nodes in the order it creates them, so inside a level the generic runtime lists
+    # them in another order than the specialised call (ascending arena row).  Levels that are cut into equal
+    # shares add a tile's pieces at share boundaries, which depend on where the tile sits in its level: both
+    # paths are within tolerance of the oracle, but bit-identical only with whole tiles (forced here first).
+    ctx.check(ctx.acrobat_set_tuning(64, 1, 0))
+    try:
+        ctx.check(g.acrobat_dfg_run(P.stream_handle()))
+        torch.cuda.synchronize()
+        h_ref, c_ref = P.run_treelstm(ctx, w)
+        assert np.array_equal(h.cpu().numpy(), h_ref) and np.array_equal(c.cpu().numpy(), c_ref)
+    finally:
+        ctx.check(ctx.acrobat_set_tuning(0, 0, 0))
+    h.fill_(float("nan")); c.fill_(float("nan"))
     ctx.check(g.acrobat_dfg_run(P.stream_handle()))
     torch.cuda.synchronize()
-    h_ref, c_ref = P.run_treelstm(ctx, w)
-    assert np.array_equal(h.cpu().numpy(), h_ref) and np.array_equal(c.cpu().numpy(), c_ref)
-    oh, oc = oracle.treelstm(w, nthreads=NT)
-    P.assert_close(h.cpu().numpy(), oh, "h")
-    P.assert_close(c.cpu().numpy(), oc, "c")
+    h_ref, c_ref = h.cpu().numpy().copy(), c.cpu().numpy().copy()
+    P.assert_close(h_ref, oh, "h")
+    P.assert_close(c_ref, oc, "c")
+    hs, cs = P.run_treelstm(ctx, w)
+    P.assert_close(hs, h_ref.astype(np.float64), "specialised vs generic h")
+    P.assert_close(cs, c_ref.astype(np.float64), "specialised vs generic c")
     # a second run of the same graph, and a run after clear + rebuild
     h.fill_(float("nan")); c.fill_(float("nan"))
     g.acrobat_dfg_clear()
@@ -902,7 +917,7 @@ def test_generic_runtime_lstm_program(ctx, P):
     oh, oc = oracle.varlen_lstm(w)
     P.assert_close(h.cpu().numpy(), oh, "h")
     P.assert_close(c.cpu().numpy(), oc, "c")
-    sh, sc = P.run_lstm(ctx, w)
+    sh, sc = P.run_lstm(ctx, w)  # H = 64: the specialised call also takes one launch per step here
     assert np.array_equal(h.cpu().numpy(), sh) and np.array_equal(c.cpu().numpy(), sc)
     g.close()
 

@@ -176,6 +176,20 @@ def acrobat_schedule_trees(trees: dict, vocab: int = -1):
     return rc, level_off[: n_levels.value + 1].copy(), level_nodes, lrow, rrow
 
 
+def prepared_schedule_trees(trees: dict, vocab: int = -1):
+    """-> a callable that runs acrobat_schedule_trees on `trees` with its arguments marshalled and its output
+    arrays allocated once, for timing the library call itself; it returns the C return code."""
+    st, keep = _trees_struct(trees)
+    N = int(keep[0][-1]) if keep[0].size else 0
+    out = [np.zeros(max(N, 0) + 1, np.int32)] + [np.empty(max(N, 0), np.int32) for _ in range(3)]
+    n_levels = C.c_int32(0)
+    args = (C.byref(st), vocab, C.byref(n_levels), *(_hp(a) for a in out))
+
+    def call(_keep=(st, keep, out, n_levels)):
+        return lib.acrobat_schedule_trees(*args)
+    return call
+
+
 def acrobat_schedule_seqs(lens):
     """-> (rc, level_off[n_levels+1], level_rows[sum len])"""
     lens = _i32(lens)

@@ -54,9 +54,14 @@ hipError_t static_scratch_for(int device, void** out) {
 struct acrobat_ctx {
   int device = 0;
   std::string err;
-  // last schedule (host)
+  // last schedule (host): level_off / level_nodes, or the tree scheduler's own lists (what `last` names)
   int32_t n_levels = 0;
   std::vector<int32_t> level_off, level_nodes;
+  TreeScheduler tree_scheduler;   // keeps its buffers from call to call
+  TreeSchedule tree_schedule;
+  std::vector<int32_t> leaf_tokens;
+  const std::vector<int32_t>* last_off = &level_off;
+  const std::vector<int32_t>* last_nodes = &level_nodes;
   // index staging: pinned host buffer -> device buffer, one copy per forward call
   int32_t* h_stage = nullptr;
   int32_t* h_stage_dev = nullptr;  // the staging buffer's address on the device side (kernels may read it in place)
@@ -280,6 +285,8 @@ int begin_call(acrobat_ctx* ctx) {
   if (!ctx) return ACROBAT_EINVAL;
   ctx->err.clear();
   ctx->records.clear();
+  ctx->last_off = &ctx->level_off;
+  ctx->last_nodes = &ctx->level_nodes;
   HIP_TRY(ctx, hipSetDevice(ctx->device));
   return ACROBAT_OK;
 }
@@ -446,10 +453,13 @@ int acrobat_schedule_trees(const acrobat_trees* trees, int32_t vocab, int32_t* n
                            int32_t* level_off, int32_t* level_nodes, int32_t* lrow, int32_t* rrow) {
   if (!trees || !n_levels || !level_off) return ACROBAT_EINVAL;
   try {
-    TreeSchedule s;
+    // buffers kept per thread: a call allocates nothing once they have grown to the batch size
+    static thread_local TreeScheduler scheduler;
+    static thread_local TreeSchedule s;
     std::string err;
-    const int rc = schedule_trees(*trees, vocab, s, err);
+    const int rc = scheduler.begin(*trees, vocab, s, nullptr, err);
     if (rc != ACROBAT_OK) return rc;
+    scheduler.finish(*trees, s);
     if (s.n_nodes > 0 && !level_nodes) return ACROBAT_EINVAL;
     *n_levels = s.n_levels;
     std::memcpy(level_off, s.level_off.data(), s.level_off.size() * sizeof(int32_t));
@@ -503,19 +513,35 @@ int treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, in
     if (!trees) return fail(ctx, ACROBAT_EINVAL, "trees is null");
     if (H <= 0 || D <= 0 || H % 32 || D % 32) return fail(ctx, ACROBAT_EINVAL, "H and D must be positive multiples of 32");
     if (V <= 0) return fail(ctx, ACROBAT_EINVAL, "V must be positive");
-    TreeSchedule s;
+    // Phase 1 of the schedule: the whole structure is validated (nothing is launched for malformed input),
+    // depths and level sizes are known and the leaves are listed with their tokens; phase 2 sorts the
+    // internal levels.
+    TreeSchedule& s = ctx->tree_schedule;
+    ctx->n_levels = 0;
+    ctx->last_off = &s.level_off;
+    ctx->last_nodes = &s.level_nodes;
     {
-      const int rc = schedule_trees(*trees, V, s, ctx->err);
-      if (rc != ACROBAT_OK) return rc;
+      const int rc = ctx->tree_scheduler.begin(*trees, V, s, &ctx->leaf_tokens, ctx->err);
+      if (rc != ACROBAT_OK) {
+        s.level_off.assign(1, 0);
+        s.level_nodes.clear();
+        return rc;
+      }
     }
     ctx->n_levels = s.n_levels;
-    ctx->level_off = s.level_off;
-    ctx->level_nodes = s.level_nodes;
     const int32_t N = s.n_nodes;
     if (N == 0) return ACROBAT_OK;
-    if (!d_emb || !d_Wleaf || !d_U || !d_h || !d_c) return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
+    if (!d_emb || !d_Wleaf || !d_U || !d_h || !d_c) {
+      ctx->tree_scheduler.finish(*trees, s);
+      return fail(ctx, ACROBAT_EINVAL, "a device pointer is null");
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
 
+    struct FinishOnExit {  // whatever happens below, acrobat_last_schedule reports the complete schedule
+      acrobat_ctx* ctx; const acrobat_trees* trees; bool done = false;
+      void now() { if (!done) ctx->tree_scheduler.finish(*trees, ctx->tree_schedule); done = true; }
+      ~FinishOnExit() { now(); }
+    } finish{ctx, trees};
     if ((double)5 * H * 2 * H >= 2147483648.0 || (double)5 * H * D >= 2147483648.0)
       return fail(ctx, ACROBAT_EINVAL, "weight matrix has 2^31 or more elements");
     if (noalloc && N > ACROBAT_NOALLOC_MAX_NODES)
@@ -528,6 +554,10 @@ int treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, in
     for (int32_t lv = 1; lv < s.n_levels; ++lv) n_wide = std::max(n_wide, s.level_off[lv + 1] - s.level_off[lv]);
     const bool unfused = !ctx->gather_fusion && !noalloc;
     const size_t n_iota = unfused ? (size_t)std::max(n_leaf, 2 * n_wide) : 0;
+    // (Uploading the leaf lists and launching level 0 before the internal levels are sorted was measured and
+    // dropped: the second upload sits behind the leaf kernel in stream order, so its three copy commands land
+    // between level 0 and level 1 - 0.731 instead of 0.691 ms per forward on 17 134 nodes - while the sort
+    // it would hide takes 20 us and is hidden anyway whenever a forward call is already queued.)
     int32_t* st = nullptr;     // pinned staging
     int32_t* d_idx = nullptr;  // its device copy
     SplitKWorkspace ws;
@@ -553,21 +583,33 @@ int treelstm_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t H, in
       d_idx = ctx->d_idx;
       ws = ctx->splitk;
     }
-    std::memcpy(st, s.level_nodes.data(), (size_t)N * sizeof(int32_t));
-    for (int32_t p = 0; p < n_leaf; ++p) st[N + p] = trees->token[s.level_nodes[p]];  // leaves gather by token
-    std::memcpy(st + N + n_leaf, s.lrow.data() + n_leaf, (size_t)(N - n_leaf) * sizeof(int32_t));
-    std::memcpy(st + 2 * (size_t)N, s.rrow.data(), (size_t)N * sizeof(int32_t));
-    for (size_t i = 0; i < n_iota; ++i) st[3 * (size_t)N + i] = (int32_t)i;
+    // staging layout: out row | first operand row (token at a leaf) | second operand row, N entries each
+    const size_t n_int = (size_t)(N - n_leaf);
+    auto stage_leaves = [&]() {
+      std::memcpy(st, s.level_nodes.data(), (size_t)n_leaf * sizeof(int32_t));
+      std::memcpy(st + N, ctx->leaf_tokens.data(), (size_t)n_leaf * sizeof(int32_t));  // leaves gather by token
+    };
+    auto stage_internal = [&]() {
+      std::memcpy(st + n_leaf, s.level_nodes.data() + n_leaf, n_int * sizeof(int32_t));
+      std::memcpy(st + N + n_leaf, s.lrow.data() + n_leaf, n_int * sizeof(int32_t));
+      std::memcpy(st + 2 * (size_t)N + n_leaf, s.rrow.data() + n_leaf, n_int * sizeof(int32_t));
+    };
+    auto copy_up = [&](size_t first, size_t count) {
+      return hipMemcpyAsync(d_idx + first, st + first, count * sizeof(int32_t), hipMemcpyHostToDevice, stream);
+    };
+    auto staging_in_flight = [&]() {  // the staging buffer may be rewritten once these uploads are through
+      if (stream_is_capturing(stream)) return hipSuccess;
+      const hipError_t e = hipEventRecord(noalloc ? ctx->fixed_done : ctx->stage_done, stream);
+      (noalloc ? ctx->fixed_pending : ctx->stage_pending) = true;
+      return e;
+    };
     if (unfused) TRY(reserve_scratch(ctx, std::max((size_t)n_leaf * D, 4 * (size_t)n_wide * H), stream));
-    if (noalloc) {
-      HIP_TRY(ctx, hipMemcpyAsync(d_idx, st, 3 * (size_t)N * sizeof(int32_t), hipMemcpyHostToDevice, stream));
-      if (!stream_is_capturing(stream)) {
-        HIP_TRY(ctx, hipEventRecord(ctx->fixed_done, stream));
-        ctx->fixed_pending = true;
-      }
-    } else {
-      TRY(upload_indices(ctx, 3 * (size_t)N + n_iota, stream));
-    }
+    finish.now();
+    stage_leaves();
+    stage_internal();
+    for (size_t i = 0; i < n_iota; ++i) st[3 * (size_t)N + i] = (int32_t)i;
+    HIP_TRY(ctx, copy_up(0, 3 * (size_t)N + n_iota));  // one upload (the second operands of level 0 are never read)
+    HIP_TRY(ctx, staging_in_flight());
     const int32_t* d_out = d_idx;
     const int32_t* d_ia = d_idx + N;
     const int32_t* d_ib = d_idx + 2 * (size_t)N;
@@ -655,14 +697,20 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
     if (!trees) return fail(ctx, ACROBAT_EINVAL, "trees is null");
     if (d != 64 && d != 128) return fail(ctx, ACROBAT_EINVAL, "only d == 64 and d == 128 are supported");
     if (V <= 0) return fail(ctx, ACROBAT_EINVAL, "V must be positive");
-    TreeSchedule s;
+    TreeSchedule& s = ctx->tree_schedule;
+    ctx->n_levels = 0;
+    ctx->last_off = &s.level_off;
+    ctx->last_nodes = &s.level_nodes;
     {
-      const int rc = schedule_trees(*trees, V, s, ctx->err);
-      if (rc != ACROBAT_OK) return rc;
+      const int rc = ctx->tree_scheduler.begin(*trees, V, s, nullptr, ctx->err);
+      if (rc != ACROBAT_OK) {
+        s.level_off.assign(1, 0);
+        s.level_nodes.clear();
+        return rc;
+      }
+      ctx->tree_scheduler.finish(*trees, s);
     }
     ctx->n_levels = s.n_levels;
-    ctx->level_off = s.level_off;
-    ctx->level_nodes = s.level_nodes;
     const int32_t N = s.n_nodes;
     if (N == 0) return ACROBAT_OK;
     if (!d_vec_tab || !d_mat_tab || !d_W || !d_WM || !d_vec || !d_mat)
@@ -1256,8 +1304,8 @@ int acrobat_last_schedule(const acrobat_ctx* ctx, int32_t* n_levels, const int32
                           const int32_t** level_nodes) {
   if (!ctx || !n_levels || !level_off || !level_nodes) return ACROBAT_EINVAL;
   *n_levels = ctx->n_levels;
-  *level_off = ctx->level_off.data();
-  *level_nodes = ctx->level_nodes.data();
+  *level_off = ctx->last_off->data();
+  *level_nodes = ctx->last_nodes->data();
   return ACROBAT_OK;
 }
 

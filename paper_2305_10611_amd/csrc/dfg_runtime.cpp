@@ -128,7 +128,9 @@ void Dfg::bucket(DfgBuckets& out, size_t first) const {
 
 int dfg_build_treelstm(Dfg& g, const acrobat_trees& tr, int32_t vocab, int32_t op_leaf, int32_t op_internal,
                        std::string& err) {
-  if (tr.n_trees < 0 || (tr.n_trees > 0 && (!tr.tree_off || !tr.left || !tr.right))) { err = "null structure array"; return ACROBAT_EINVAL; }
+  if (tr.n_trees < 0 || (tr.n_trees > 0 && !tr.tree_off)) { err = "null structure array"; return ACROBAT_EINVAL; }
+  // (a batch of empty trees has no nodes and needs no child arrays, as for schedule_trees)
+  if (tr.n_trees > 0 && tr.tree_off[tr.n_trees] > 0 && (!tr.left || !tr.right)) { err = "null structure array"; return ACROBAT_EINVAL; }
   struct Frame { int32_t node; int32_t stage; int32_t dl, nl; };  // local node, children done, left depth / node id
   std::vector<Frame> stack;
   for (int32_t t = 0; t < tr.n_trees; ++t) {

@@ -19,6 +19,24 @@ struct TreeSchedule {
 // Returns ACROBAT_OK / EINVAL / ESTRUCT; `err` explains a failure.
 int schedule_trees(const acrobat_trees& trees, int32_t vocab, TreeSchedule& out, std::string& err);
 
+// The same schedule in two phases with buffers that live across calls (a context owns one of these), so that
+// a forward call can launch level 0 while the host is still sorting the internal levels:
+//  begin()  validates the whole structure (nothing may be launched for malformed input), computes every
+//           node's depth, level_off, and the level-0 list: out.level_nodes[0 .. n_leaf) = the leaves by
+//           ascending id, their tokens in leaf_tokens (if not null; needs trees.token);
+//  finish() fills level_nodes / lrow / rrow of the internal levels.
+// `out` is resized, never shrunk to fit: its vectors keep their capacity from call to call.
+class TreeScheduler {
+ public:
+  int begin(const acrobat_trees& trees, int32_t vocab, TreeSchedule& out, std::vector<int32_t>* leaf_tokens, std::string& err);
+  void finish(const acrobat_trees& trees, TreeSchedule& out);
+
+ private:
+  int general_tree(const acrobat_trees& tr, int32_t t, int32_t vocab, std::string& err);
+  std::vector<int32_t> depth_, parent_, cursor_, count_;
+  std::vector<uint8_t> mark_;  // fast path: "has a parent"; general path: children still to come
+};
+
 struct SeqSchedule {
   int64_t n_rows = 0;
   int32_t n_levels = 0;

@@ -31,12 +31,18 @@ MEASURED_MFMA_TFLOPS = 155.0
 MEASURED_HBM_GBS = 5800.0
 
 # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summaries
-# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB per dispatch, factors from a plain copy of known size).
-# Hardware counters cannot be read from inside this process; workloads without a summary report null.
+# (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB per dispatch, factors from a plain copy of known size; averaged over
+# the launches that make up the dominant variant).  Hardware counters cannot be read from inside this process:
+# the figures are those of the library as of TRAFFIC_COMMIT and are reported with that label, not as live
+# measurements; a workload without a summary reports null.
+TRAFFIC_COMMIT = "b76ed52"
 MEASURED_TRAFFIC = {
-    ("treelstm_h512_256", "kind=2 tile=64"): (80.2e6, "profiles/treelstm_h512_256_cell_level_kernel.md"),
+    ("treelstm_h256_8x20", "kind=2 tile=6"): (3.64e6, "profiles/treelstm_h256_small_configs.md"),
+    ("treelstm_h256_64", "kind=2 tile=6"): (11.7e6, "profiles/treelstm_h256_small_configs.md"),
+    ("treelstm_h512_256", "kind=2 tile=64"): (120.4e6, "profiles/treelstm_h512_256_cell_level_kernel.md"),
     ("mvrnn_d64_64", "kind=3 tile=1"): (6.9e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md"),
-    ("lstm_h512_256", "kind=6 tile=6"): (12.3e6, "profiles/lstm_h512_256_cell_kernels.md"),
+    ("lstm_h512_256", "kind=13 tile=16"): (250.5e6, "profiles/lstm_h512_256_cell_kernels.md"),
+    ("lstm_h512_256", "kind=6 tile=6"): (12.3e6, "profiles/lstm_h512_256_cell_kernels.md (one launch per step, commit 138cebb)"),
 }
 
 
@@ -120,6 +126,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 0..4 (2 = headline)")
     ap.add_argument("--paper-grid", default=None, metavar="MODEL:SIZE:BATCH",
                     help="instead of --config: a mini-batch shaped like the paper's grid, e.g. treelstm:small:64")
+    ap.add_argument("--instances", type=int, default=None,
+                    help="with --config: the same recipe with this many trees / sequences (scaling runs)")
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
@@ -192,7 +200,7 @@ def main():
         w = paper_grid_workload(model, size, int(batch))
         args.config = -1
     else:
-        w = make_config(args.config)
+        w = make_config(args.config, n_instances=args.instances)
     kind = w["kind"]
     ctx = A.Context(0)
     if args.persistent == "off":
@@ -441,7 +449,7 @@ def main():
     traffic, traffic_src = MEASURED_TRAFFIC.get((w["name"], kname), (None, None))
     roofline = {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": traffic, "traffic_unit": "bytes/launch",
-                "traffic_source": traffic_src,
+                "traffic_source": traffic_src, "traffic_measured_at_commit": TRAFFIC_COMMIT if traffic else None,
                 "algorithmic_bytes_per_launch": round((units * bytes_per[dominant] + launches * weight_bytes[dominant]) / launches),
                 "kernel": kname, "launches_per_step": launches,
                 "units_per_step": units, "avg_launch_us": round(ms_sum / launches * 1e3, 2)}
@@ -456,6 +464,14 @@ def main():
             agg["datasheet"] += floor_ms(k, n, PEAK_FP32_MFMA_TFLOPS, PEAK_HBM_GBS)
             agg["measured_ceilings"] += floor_ms(k, n, MEASURED_MFMA_TFLOPS, MEASURED_HBM_GBS)
     agg = {key: round(v / t_device_ms, 4) for key, v in agg.items()}
+    # the dominant kernel is only part of the step: the same fraction for the whole step (every launch, the gaps
+    # between them, host scheduling and upload), so that the headline figure is not mistaken for it
+    if bound == "mfma":
+        whole = total_flops / (ms_per_step * 1e-3) / 1e12
+    else:
+        whole = sum(n * bytes_per[k] + weight_bytes[k] for k, lv, n, tile, ms, ks in per_launch if k in bytes_per) / (ms_per_step * 1e-3) / 1e9
+    roofline["whole_step"] = {"achieved": round(whole, 3), "frac": round(whole / peak, 4), "unit": unit,
+                              "sum_of_per_launch_floors_over_device_time": agg["datasheet"]}
 
     if args.verbose:
         print(f"{'kind':>4} {'lvl':>4} {'n':>6} {'tile':>4} {'ks':>3} {'us':>9} {'TFLOP/s':>8} {'%MFMA':>6} {'GB/s':>8} {'%HBM':>6} {'bound':>5}",

@@ -360,20 +360,22 @@ CONFIG_NAMES = (
 )
 
 
-def make_config(idx: int, seed: int | None = None):
-    """Build benchmark configuration ``idx`` (0..4)."""
+def make_config(idx: int, seed: int | None = None, n_instances: int | None = None):
+    """Build benchmark configuration ``idx`` (0..4).  n_instances: the same recipe with another number of
+    trees / sequences (scaling runs; the benchmark configurations proper use the default)."""
     s = SEED_BASE + idx if seed is None else seed
+    n = (8, 64, 256, 64, 256)[idx] if n_instances is None else int(n_instances)
     if idx == 0:
-        w = treelstm_workload(8, 20, 20, 256, 1000, "uniform", s)
+        w = treelstm_workload(n, 20, 20, 256, 1000, "uniform", s)
     elif idx == 1:
-        w = treelstm_workload(64, 10, 50, 256, 20000, "zipf1.1", s)
+        w = treelstm_workload(n, 10, 50, 256, 20000, "zipf1.1", s)
     elif idx == 2:
-        w = treelstm_workload(256, 10, 60, 512, 20000, "zipf1.1", s)
+        w = treelstm_workload(n, 10, 60, 512, 20000, "zipf1.1", s)
     elif idx == 3:
-        w = mvrnn_workload(64, 10, 40, 64, s)
+        w = mvrnn_workload(n, 10, 40, 64, s)
     elif idx == 4:
-        w = lstm_workload(256, 1, 100, 512, 512, s)
+        w = lstm_workload(n, 1, 100, 512, 512, s)
     else:
         raise IndexError(idx)
-    w["name"] = CONFIG_NAMES[idx]
+    w["name"] = CONFIG_NAMES[idx] if n_instances is None else f"{CONFIG_NAMES[idx]}_x{n}"
     return w

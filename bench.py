@@ -145,7 +145,7 @@ def main():
                     help="also time the forward call replayed from a captured HIP graph (index upload + every launch), "
                          "and what capturing and instantiating it costs; reported under \"graph_replay\"")
     ap.add_argument("--persistent", choices=("auto", "off"), default="auto",
-                    help="LSTM only: off = one launch per time step instead of one persistent launch for the recurrence")
+                    help="LSTM and MV-RNN (d = 64): off = one launch per time step / level instead of one persistent launch")
     ap.add_argument("--tuning", default=None, metavar="TILE,KSPLIT",
                     help="force one kernel variant for every cell level (acrobat_set_tuning), e.g. 64,1 or 65,1")
     ap.add_argument("--sync-probe", action="store_true",
@@ -239,9 +239,11 @@ def main():
             w, d, V, t["vec_tab"], t["mat_tab"], t["W"], t["WM"], o[0], o[1], 0, st)))
         sched = A.binding.prepared_schedule_trees(w, V)
         n_int = int((w["left"] >= 0).sum())
-        flops_per = {A.binding.K_MVRNN_LEVEL: 4.0 * d * d + 4.0 * d * d + 4.0 * d ** 3}
-        bytes_per = {A.binding.K_MVRNN_LEVEL: 12.0 * (d * d + d) + 12}
-        weight_bytes = {A.binding.K_MVRNN_LEVEL: 16.0 * d * d}
+        # one launch per level (K_MVRNN_LEVEL) or one launch for all internal levels (K_MVRNN_PERSISTENT): same work per node
+        node_flops, node_bytes = 4.0 * d * d + 4.0 * d * d + 4.0 * d ** 3, 12.0 * (d * d + d) + 12
+        flops_per = {A.binding.K_MVRNN_LEVEL: node_flops, A.binding.K_MVRNN_PERSISTENT: node_flops}
+        bytes_per = {A.binding.K_MVRNN_LEVEL: node_bytes, A.binding.K_MVRNN_PERSISTENT: node_bytes}
+        weight_bytes = {A.binding.K_MVRNN_LEVEL: 16.0 * d * d, A.binding.K_MVRNN_PERSISTENT: 16.0 * d * d}
         dominant = A.binding.K_MVRNN_LEVEL
         total_flops = n_int * flops_per[dominant]
         dtype, bound = "f32", "hbm"
@@ -425,8 +427,9 @@ def main():
     for i, r in enumerate(recs[0]):
         per_launch.append((r[0], r[1], r[2], r[4], float(np.mean([rr[i][3] for rr in recs])), r[5]))
     t_device_ms = sum(p[4] for p in per_launch)
-    if any(p[0] == A.binding.K_LSTM_PERSISTENT for p in per_launch):
-        dominant = A.binding.K_LSTM_PERSISTENT
+    for persistent_kind in (A.binding.K_LSTM_PERSISTENT, A.binding.K_MVRNN_PERSISTENT):
+        if any(p[0] == persistent_kind for p in per_launch):
+            dominant = persistent_kind
     K_REDUCE = A.binding.K_SPLITK_REDUCE
     t_reduce_ms = sum(p[4] for p in per_launch if p[0] == K_REDUCE)
     # dominant kernel = the variant of the dominant kind that accounts for most device time

@@ -177,9 +177,15 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
  * that acrobat_last_schedule reports; the workgroups keep W_h on chip for all steps and synchronise
  * among themselves through arrival counters in device memory.  Every wait inside that kernel is bounded
  * by max_polls polls of a counter (max_polls < 0: the default, about a quarter of a million): a
- * workgroup whose wait runs out raises a status word, all workgroups then leave at their next poll and
- * the kernel ends normally with incomplete outputs.  acrobat_device_status reports that: call it once the
- * stream has been synchronised; it returns ACROBAT_OK or ACROBAT_ETIMEOUT and clears the condition.
+ * workgroup whose wait runs out raises a status word (in pinned host memory; nothing touches it otherwise),
+ * all workgroups then leave at their next polls and the kernel ends normally with incomplete outputs.
+ * acrobat_device_status reports that: call it once the stream has been synchronised; it returns ACROBAT_OK
+ * or ACROBAT_ETIMEOUT and clears the condition.  Until it has been called the word stays raised and later
+ * persistent launches of the context give up at their first long wait too.
+ * The same switch covers acrobat_mvrnn_forward with d == 64: all internal levels then run in ONE launch in which
+ * a node waits for its own two children only (a flag word per node, polled with the same bound) instead of a
+ * whole level waiting for the previous one, provided every workgroup of that launch is resident at once and the
+ * call is not being captured into a graph (a captured call keeps one launch per level).
  * Nothing else may occupy the GPU's compute units for long while such a launch runs (another stream's
  * kernels delay the workgroups that are not yet resident; the bound turns a too long delay into
  * ACROBAT_ETIMEOUT instead of a hang). */
@@ -457,6 +463,7 @@ typedef struct {
 #define ACROBAT_K_GATHER 11
 #define ACROBAT_K_DFG_BUCKET 12 /* level = bucket index */
 #define ACROBAT_K_LSTM_PERSISTENT 13 /* all time steps of the recurrence in one launch; n = all rows */
+#define ACROBAT_K_MVRNN_PERSISTENT 14 /* all internal levels of an MV-RNN batch in one launch; n = internal nodes */
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 

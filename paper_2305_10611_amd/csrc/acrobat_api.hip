@@ -94,7 +94,11 @@ struct acrobat_ctx {
   bool persistent = true;           // acrobat_set_persistent
   int32_t max_polls = 1 << 18;      // bound of every wait inside a persistent kernel
   unsigned* d_sync = nullptr;       // [kPersistSyncWords]: the probe's flag lines | arrival counters | status
-  unsigned* h_status = nullptr;     // pinned; written by a copy behind every persistent launch
+  unsigned* h_status = nullptr;     // pinned host word that a kernel raises when one of its waits runs out
+  unsigned* h_status_dev = nullptr; // the same word's address on the device side
+  unsigned* d_node_flags = nullptr; // one word per arena row: the epoch of the call that last finished the node
+  size_t node_flags_cap = 0;
+  unsigned epoch = 0;               // of the last dataflow launch; never 0
   // profiling
   bool profiling = false;
   std::vector<acrobat_launch_record> records;
@@ -210,13 +214,16 @@ int reserve_splitk(acrobat_ctx* ctx, hipStream_t stream) {
 }
 
 constexpr int kSyncWords = kPersistSyncWords;  // the probe's flag lines, arrival counters, then the status word
+constexpr int kSyncWordsPadded = (kSyncWords + 3) / 4 * 4;
 
 int reserve_sync(acrobat_ctx* ctx, hipStream_t stream) {
   if (ctx->d_sync) return ACROBAT_OK;
   if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "stream capture: counters not allocated, run once without capture first");
-  HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_sync), kSyncWords * sizeof(unsigned)));
+  HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_sync), kSyncWordsPadded * sizeof(unsigned)));
+  HIP_TRY(ctx, hipMemset(ctx->d_sync, 0, kSyncWordsPadded * sizeof(unsigned)));
   HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), sizeof(unsigned), hipHostMallocDefault));
   *ctx->h_status = 0;
+  HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->h_status_dev), ctx->h_status, 0));
   return ACROBAT_OK;
 }
 
@@ -437,6 +444,7 @@ void acrobat_destroy(acrobat_ctx* ctx) {
   if (ctx->splitk.counters) (void)hipFree(ctx->splitk.counters);
   if (ctx->h_stage) (void)hipHostFree(ctx->h_stage);
   if (ctx->d_sync) (void)hipFree(ctx->d_sync);
+  if (ctx->d_node_flags) (void)hipFree(ctx->d_node_flags);
   if (ctx->h_status) (void)hipHostFree(ctx->h_status);
   if (ctx->d_zero_row) (void)hipFree(ctx->d_zero_row);
   if (ctx->h_scores) (void)hipHostFree(ctx->h_scores);
@@ -742,6 +750,47 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
       HIP_TRY(ctx, launch_mvrnn_leaf_copy(n_leaf, d, d_out, d_ia, d_vec_tab, d_mat_tab, d_vec, d_mat, stream, timer.ev));
       TRY(timer.end());
     }
+    // One launch for all internal levels where the kernel exists (d = 64) and every workgroup is resident at
+    // once: a node then waits for its own two children instead of a whole level for the previous one.
+    const int32_t n_internal = N - n_leaf;
+    // (Batches with very wide levels keep one launch per level: at 1 024 trees the single launch is 10 % slower,
+    // 0.54 vs 0.49 ms - its flag checks and write-through stores buy nothing where levels are bandwidth bound.)
+    int32_t widest = 0;
+    for (int32_t lv = 1; lv < s.n_levels; ++lv) widest = std::max(widest, s.level_off[lv + 1] - s.level_off[lv]);
+    const int df_wgs = ctx->persistent && ctx->mvrnn_variant == 0 && s.n_levels > 2 && widest <= 2048 &&
+                               !stream_is_capturing(stream)
+                           ? mvrnn_dataflow_workgroups(d, n_internal) : 0;
+    if (df_wgs > 0) {
+      TRY(reserve_sync(ctx, stream));
+      if ((size_t)N > ctx->node_flags_cap) {
+        const size_t cap = (size_t)N + (size_t)N / 2 + 1024;
+        if (ctx->d_node_flags) HIP_TRY(ctx, hipFree(ctx->d_node_flags));
+        ctx->d_node_flags = nullptr;
+        ctx->node_flags_cap = 0;
+        HIP_TRY(ctx, hipMalloc(reinterpret_cast<void**>(&ctx->d_node_flags), cap * sizeof(unsigned)));
+        HIP_TRY(ctx, hipMemsetAsync(ctx->d_node_flags, 0, cap * sizeof(unsigned), stream));
+        ctx->node_flags_cap = cap;
+      }
+      if (++ctx->epoch == 0) {  // wrapped: every stale word could pass for a fresh one
+        HIP_TRY(ctx, hipMemsetAsync(ctx->d_node_flags, 0, ctx->node_flags_cap * sizeof(unsigned), stream));
+        ctx->epoch = 1;
+      }
+      MvrnnLevelArgs a{};
+      a.n = n_internal;
+      a.d = d;
+      a.out_rows = d_out + n_leaf;
+      a.lsrc = d_ia + n_leaf;
+      a.rsrc = d_ib + n_leaf;
+      a.vec_tab = d_vec_tab; a.mat_tab = d_mat_tab;
+      a.W = d_W; a.WM = d_WM;
+      a.vec = d_vec; a.mat = d_mat;
+      a.flags = ctx->d_node_flags; a.epoch = ctx->epoch;
+      a.status = ctx->h_status_dev; a.max_polls = ctx->max_polls;
+      TRY(timer.begin(ACROBAT_K_MVRNN_PERSISTENT, 1, n_internal));
+      HIP_TRY(ctx, launch_mvrnn_dataflow(a, df_wgs, stream, timer.ev));
+      TRY(timer.end());
+      return timer.finish();
+    }
     for (int32_t lv = 1; lv < s.n_levels; ++lv) {
       const int32_t off = s.level_off[lv], n = s.level_off[lv + 1] - off;
       MvrnnLevelArgs a{};
@@ -841,13 +890,12 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       pa.slot_row0 = ctx->d_idx; pa.slot_len = ctx->d_idx + n_slots;
       pa.Wh = d_Wh; pa.xp = ctx->d_scratch; pa.h = d_h; pa.c = d_c;
       pa.h_bytes = (uint32_t)((size_t)R * H * sizeof(float));
-      pa.counters = ctx->d_sync + kPersistFlagWords; pa.status = ctx->d_sync + kSyncWords - 1;
+      pa.counters = ctx->d_sync + kPersistFlagWords; pa.status = ctx->h_status_dev;
       pa.max_polls = ctx->max_polls;
       TRY(timer.begin(ACROBAT_K_LSTM_PERSISTENT, 0, R));
       if (timer.tile()) *timer.tile() = 16;
       HIP_TRY(ctx, launch_lstm_persistent(pa, stream, timer.ev));
       TRY(timer.end());
-      HIP_TRY(ctx, hipMemcpyAsync(ctx->h_status, pa.status, sizeof(unsigned), hipMemcpyDeviceToHost, stream));
       return timer.finish();
     }
 
@@ -1374,13 +1422,12 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
     a.write_through = write_through != 0;
     a.store_floats = store_floats; a.load_floats = load_floats;
     a.payload = payload; a.flags = ctx->d_sync; a.counters = ctx->d_sync + kPersistFlagWords;
-    a.status = ctx->d_sync + kSyncWords - 1; a.max_polls = ctx->max_polls;
+    a.status = ctx->h_status_dev; a.max_polls = ctx->max_polls;
     a.ticks = ticks;
     LaunchEvents ev;
     ev.start = e0; ev.stop = e1;
     PROBE_TRY(launch_fill_u32(ctx->d_sync, 0u, kSyncWords, stream));
     PROBE_TRY(launch_sync_probe(a, stream, ev));
-    PROBE_TRY(hipMemcpyAsync(ctx->h_status, a.status, sizeof(unsigned), hipMemcpyDeviceToHost, stream));
     PROBE_TRY(hipStreamSynchronize(stream));
     float ms = 0.0f;
     PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));

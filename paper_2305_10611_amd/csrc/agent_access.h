@@ -32,6 +32,15 @@ __device__ __forceinline__ void store_agent_f4(__amdgpu_buffer_rsrc_t rsrc, unsi
 __device__ __forceinline__ unsigned load_agent(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// The status word of the kernels that wait for other workgroups lives in pinned host memory: it is only written
+// when a wait runs out and only read by workgroups that have been polling for a while, so the host sees it
+// without any copy and the ordinary case never touches it.
+__device__ __forceinline__ void raise_status(unsigned* status) {
+  __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ bool status_raised(const unsigned* status) {
+  return __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0;
+}
 // s_waitcnt vmcnt(0) (gfx9 encoding, the other counters at their maximum): every vector memory operation of
 // this wavefront, stores included, has completed.
 __device__ __forceinline__ void wait_stores_done() { __builtin_amdgcn_s_waitcnt(0x0F70); }

@@ -100,6 +100,10 @@ struct MvrnnLevelArgs {
   const float* vec_tab; const float* mat_tab;
   const float* W; const float* WM;  // [d,2d] each
   float* vec; float* mat;           // arena [rows,d], [rows,d,d]
+  // launch_mvrnn_dataflow only: one word per arena row, set to `epoch` by the node that owns the row once its
+  // state has been stored; the status word and the bound of every wait as for the other persistent kernels
+  unsigned* flags; unsigned epoch;
+  unsigned* status; int32_t max_polls;
 };
 // Same for two independent batches: one shared launch where the variants agree (then *tile / *ksplit
 // describe it and ev brackets it), else two launches in a row on the stream (ev.start on the first,
@@ -120,6 +124,14 @@ hipError_t launch_gather_rows(const GatherArgs& g, hipStream_t stream, const Lau
 
 hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32_t* tile,
                               const LaunchEvents& ev = LaunchEvents());
+
+// All internal levels of an MV-RNN batch (d = 64) in ONE launch: the lists hold every internal node in schedule
+// order; a node waits for its own two children only (a.flags / a.epoch), never for a whole level.
+// mvrnn_dataflow_workgroups: how many workgroups such a launch may have so that all are resident at once on the
+// current device (0: not available for this d); launch with exactly that many (or fewer).
+int mvrnn_dataflow_workgroups(int32_t d, int32_t n);
+hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, hipStream_t stream,
+                                 const LaunchEvents& ev = LaunchEvents());
 
 // Copies table rows `token[i]` into arena rows out_rows[i] (vector and matrix), i in [0,n).
 hipError_t launch_mvrnn_leaf_copy(int32_t n, int32_t d, const int32_t* out_rows, const int32_t* token,

@@ -29,6 +29,8 @@
 //    are issued before the current node's matrix instructions.
 #include "cell_kernels.h"
 
+#include "agent_access.h"
+
 namespace acrobat {
 namespace {
 
@@ -50,14 +52,34 @@ __device__ __forceinline__ float quad_sum(float x) {
   return x;
 }
 
+// 8-byte agent-scope accesses (see agent_access.h): one relaxed atomic each
+__device__ __forceinline__ floatx2 load_agent_f2(const float* p) {
+  const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return __builtin_bit_cast(floatx2, u);
+}
+__device__ __forceinline__ void store_agent_f2(float* p, floatx2 v) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), __builtin_bit_cast(unsigned long long, v), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+
 struct NodeRef {  // where one node's operands live and where its results go
   const float* mat;  // this wavefront's child matrix (left child for kh = 0, right for kh = 1)
   const float* vec;  // the OTHER child's vector
   size_t orow;
 };
 
+// DF (dataflow): ONE launch for all internal levels.  The list then holds every internal node in schedule
+// order, workgroup w takes list positions w, w + grid, ..., and a node waits only for its own two children:
+// every finished node announces itself in a flag word (the call's epoch number), the parent's workgroup polls
+// the two words, bounded, before it requests the operands.  No level boundary, no barrier among workgroups: a
+// batch takes (height of the tallest tree) x (one node's latency) instead of (levels) x (one launch).  Nothing
+// can deadlock as long as all workgroups are resident (the host checks): the earliest unfinished list position
+// only waits for earlier positions.  Children's states are stored write-through and read with agent-scope
+// loads, as everything that workgroups of one kernel hand to each other (agent_access.h).
+template <bool DF>
 __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArgs a) {
   __shared__ float s_v[2 * kD];  // B a | A b
+  __shared__ int s_go;
   __shared__ float s_red[2][2][16 * 64];  // [row block][k half of the writer][8 rows x even/odd x lane]
   __shared__ __attribute__((aligned(16))) float s_W[kD * kWld];
 
@@ -91,15 +113,49 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   };
   auto load_node = [&](const NodeRef& r, floatx2 (&x)[32], floatx2& vv) {
     const float* X = r.mat + lhi * kD + 2 * lcol;
+    if constexpr (DF) {  // a child may have been written by another workgroup of this launch
 #pragma unroll
-    for (int s = 0; s < 32; ++s) x[s] = *reinterpret_cast<const floatx2*>(X + 2 * s * kD);
-    vv = *reinterpret_cast<const floatx2*>(r.vec + 2 * lcol);
+      for (int s = 0; s < 32; ++s) x[s] = load_agent_f2(X + 2 * s * kD);
+      vv = load_agent_f2(r.vec + 2 * lcol);
+    } else {
+#pragma unroll
+      for (int s = 0; s < 32; ++s) x[s] = *reinterpret_cast<const floatx2*>(X + 2 * s * kD);
+      vv = *reinterpret_cast<const floatx2*>(r.vec + 2 * lcol);
+    }
+  };
+  // DF: have both children of the node announced themselves?  (wave-uniform; leaves are table rows: always)
+  auto children_done = [&](const RawIdx& i) {
+    bool ok = true;
+    if (i.ls >= 0) ok = ok && load_agent(a.flags + i.ls) == a.epoch;
+    if (i.rs >= 0) ok = ok && load_agent(a.flags + i.rs) == a.epoch;
+    return ok;
   };
 
   // one node: `x`, `vv` hold its operands; `xn`, `vvn` receive the next node's, whose indices
   // (`raw`) were fetched one iteration ago; the indices of the node after that are fetched now
+  // DF only: `cur_raw` names the current node's children, `have` says whether its operands were already
+  // requested (a wavefront requests the next node's operands early only if both children are done by then)
   auto process = [&](int node, NodeRef& cur, RawIdx& raw, floatx2 (&x)[32], floatx2& vv, floatx2 (&xn)[32],
-                     floatx2& vvn) {
+                     floatx2& vvn, RawIdx& cur_raw, bool& have) -> bool {
+    if constexpr (DF) {
+      if (tid == 0) {
+        int polls = 0;
+        bool ok = true;
+        while (!children_done(cur_raw)) {
+          if (++polls > a.max_polls) {
+            raise_status(a.status);
+            ok = false;
+            break;
+          }
+          if ((polls & 255) == 0 && status_raised(a.status)) { ok = false; break; }
+          __builtin_amdgcn_s_sleep(1);
+        }
+        s_go = ok ? 1 : 0;
+      }
+      __syncthreads();
+      if (!s_go) return false;  // a wait ran out here or elsewhere: drain
+      if (!have) load_node(cur, x, vv);
+    }
     // (indices past the end are clamped to the last node: a harmless re-read keeps the loop body
     // free of branches, so the compiler can leave these loads in flight)
     const int next2 = min(node + 2 * (int)gridDim.x, a.n - 1);
@@ -107,6 +163,7 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
     // waited for, before this point - they were requested a whole iteration ago)
     asm volatile("" : "+v"(raw.ls), "+v"(raw.rs), "+v"(raw.orow));
     const NodeRef nxt = resolve(raw);
+    const RawIdx nxt_raw = raw;
     raw = load_idx(next2);
 
     // ---- mat-vec rows 2*(16 mb + i) + lhi, i < 16: partial over this lane's two columns,
@@ -131,7 +188,9 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
     if ((lcol & 1) == 0) s_v[(kh ? 0 : kD) + 2 * (16 * mb + (lcol >> 1)) + lhi] = v[0];
 
     // ---- next node's operands: in flight during this node's matrix instructions
-    load_node(nxt, xn, vvn);
+    bool have_next = true;
+    if constexpr (DF) have_next = node + (int)gridDim.x < a.n && children_done(nxt_raw);
+    if (have_next) load_node(nxt, xn, vvn);
 
     // ---- P: 32 k-steps of two 32x32 blocks (even / odd output columns)
     floatx16 acc_e, acc_o;
@@ -170,7 +229,10 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
       for (int e = 0; e < 4; ++e) t += wk4[e] * s_v[vq * 32 + k * 4 + e];
     }
     t = quad_sum(t);
-    if (vq == 0) a.vec[cur.orow * kD + vr] = fast_tanh(t);
+    if (vq == 0) {
+      if constexpr (DF) __hip_atomic_store(a.vec + cur.orow * kD + vr, fast_tanh(t), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else a.vec[cur.orow * kD + vr] = fast_tanh(t);
+    }
 
     {
       float* P = a.mat + cur.orow * kDD;
@@ -184,11 +246,19 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
         floatx2 o;  // always (k half 0) + (k half 1)
         o[0] = kh ? other_e + mine_e : mine_e + other_e;
         o[1] = kh ? other_o + mine_o : mine_o + other_o;
-        *reinterpret_cast<floatx2*>(P + i * kD + 2 * lcol) = o;
+        if constexpr (DF) store_agent_f2(P + i * kD + 2 * lcol, o);
+        else *reinterpret_cast<floatx2*>(P + i * kD + 2 * lcol) = o;
       }
     }
-    __syncthreads();  // s_v / s_red are reused by the next node
+    if constexpr (DF) wait_stores_done();  // this wavefront's part of the node's state has been written through
+    __syncthreads();  // s_v / s_red are reused by the next node (DF: every wavefront's stores have completed)
+    if constexpr (DF) {
+      if (tid == 0) __hip_atomic_store(a.flags + cur.orow, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      cur_raw = nxt_raw;
+      have = have_next;
+    }
     cur = nxt;
+    return true;
   };
 
   int node = blockIdx.x;
@@ -214,9 +284,11 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
     wst[k] = *reinterpret_cast<const floatx4*>(a.W + (i >> 5) * (2 * kD) + (i & 31) * 4);
   }
   NodeRef cur = resolve(raw);
+  RawIdx cur_raw = raw;
   raw = raw_next;
   floatx2 x0[32], x1[32], vv0, vv1;
-  load_node(cur, x0, vv0);
+  bool have = !DF;  // DF: the first node's operands are requested once its children are known to be done
+  if (have) load_node(cur, x0, vv0);
   // W_M goes through the LDS buffer of W first: every wavefront picks its operand registers
   // (row 32 mb + lcol, columns 64 kh + 2 s + lhi) out of it, then W takes the buffer over
 #pragma unroll
@@ -234,10 +306,10 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
     *reinterpret_cast<floatx4*>(&s_W[(i >> 5) * kWld + (i & 31) * 4]) = wst[k];
   }
   while (true) {
-    process(node, cur, raw, x0, vv0, x1, vv1);
+    if (!process(node, cur, raw, x0, vv0, x1, vv1, cur_raw, have)) break;
     node += gridDim.x;
     if (node >= a.n) break;
-    process(node, cur, raw, x1, vv1, x0, vv0);
+    if (!process(node, cur, raw, x1, vv1, x0, vv0, cur_raw, have)) break;
     node += gridDim.x;
     if (node >= a.n) break;
   }
@@ -646,8 +718,25 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
   } else if (a.variant == 1) {
     launch_with_events(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else {
-    launch_with_events(mvrnn_level_kernel, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
+    launch_with_events(mvrnn_level_kernel<false>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
   }
+  return hipGetLastError();
+}
+
+int mvrnn_dataflow_workgroups(int32_t d, int32_t n) {
+  if (d != 64 || n <= 0) return 0;
+  int dev = 0, per_cu = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_level_kernel<true>, 256, 0) != hipSuccess) return 0;
+  const long resident = (long)per_cu * cus;
+  return (int)(n < resident ? n : resident);
+}
+
+hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, hipStream_t stream, const LaunchEvents& ev) {
+  if (a.n <= 0) return hipSuccess;
+  if (a.d != 64 || workgroups <= 0 || !a.flags || !a.status) return hipErrorInvalidValue;
+  launch_with_events(mvrnn_level_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
   return hipGetLastError();
 }
 

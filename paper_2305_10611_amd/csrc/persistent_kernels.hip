@@ -48,10 +48,10 @@ __device__ __forceinline__ bool wait_for_flags(const unsigned* line, int n, unsi
     const unsigned v = lane < n ? load_agent(line + lane) : target;
     if (__ballot(v < target) == 0) return true;
     if (++polls > max_polls) {
-      if (lane == 0) __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (lane == 0) raise_status(status);
       return false;
     }
-    if ((polls & 15) == 0 && load_agent(status) != 0) return false;
+    if ((polls & 255) == 0 && status_raised(status)) return false;
     __builtin_amdgcn_s_sleep(1);
   }
 }
@@ -62,10 +62,10 @@ __device__ __forceinline__ bool wait_for(const unsigned* counter, unsigned targe
   int polls = 0;
   while (load_agent(counter) < target) {
     if (++polls > max_polls) {
-      __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      raise_status(status);
       return false;
     }
-    if ((polls & 15) == 0 && load_agent(status) != 0) return false;
+    if ((polls & 255) == 0 && status_raised(status)) return false;
     __builtin_amdgcn_s_sleep(1);
   }
   return true;

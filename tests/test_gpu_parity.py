@@ -226,6 +226,59 @@ def test_mvrnn_streaming_variant(P, d, trees):
         c.close()
 
 
+@pytest.mark.parametrize("trees,lo,hi,seed", [(1, 2, 2, 50), (5, 1, 9, 51), (64, 10, 40, 52), (700, 1, 12, 53), (3, 60, 90, 54)])
+def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed):
+    """d = 64: every internal level in one launch, a node waiting for its own two children only (a flag per node).
+    Same schedule, same tolerances; bit-identical to one launch per level (a node's arithmetic is the same code)."""
+    import paper_2305_10611_amd as A
+    w = gen.mvrnn_workload(trees, lo, hi, 64, seed=seed)
+    ctx.acrobat_set_profiling(True)
+    try:
+        vec, mat = P.run_mvrnn(ctx, w, copy_leaves=0)
+        kinds = [r[0] for r in ctx.acrobat_last_profile()]
+    finally:
+        ctx.acrobat_set_profiling(False)
+    level_off, _ = ctx.acrobat_last_schedule()
+    one_launch = len(level_off) - 1 > 2
+    assert kinds == ([A.binding.K_MVRNN_PERSISTENT] if one_launch else [A.binding.K_MVRNN_LEVEL] * (len(level_off) - 2))
+    assert ctx.acrobat_device_status() == A.OK
+    check_tree_schedule(ctx, w)
+    ov, om = oracle.mvrnn(w, nthreads=NT)
+    internal = w["left"] >= 0
+    P.assert_close(vec[internal], ov[internal], "vec")
+    P.assert_close(mat[internal], om[internal], "mat")
+    vec2, mat2 = P.run_mvrnn(ctx, w, copy_leaves=0)  # again: a new epoch, the flags of the first call are stale
+    assert np.array_equal(vec2[internal], vec[internal]) and np.array_equal(mat2[internal], mat[internal])
+    ctx.acrobat_set_persistent(False)
+    try:
+        vec1, mat1 = P.run_mvrnn(ctx, w, copy_leaves=0)
+    finally:
+        ctx.acrobat_set_persistent(True)
+    assert np.array_equal(vec1[internal], vec[internal]) and np.array_equal(mat1[internal], mat[internal])
+
+
+def test_mvrnn_persistent_wait_that_runs_out_is_reported(P):
+    """As for the recurrence: with no polls allowed, a parent whose child is not finished yet gives up, the grid
+    drains, the kernel ends normally and the condition is reported once."""
+    import paper_2305_10611_amd as A
+    w = gen.mvrnn_workload(40, 20, 40, 64, seed=55)
+    c = A.Context(0)
+    try:
+        assert c.acrobat_set_persistent(True, 0) == A.OK
+        P.run_mvrnn(c, w, copy_leaves=0)
+        assert c.acrobat_device_status() == A.ETIMEOUT
+        assert c.acrobat_device_status() == A.OK
+        assert c.acrobat_set_persistent(True, -1) == A.OK
+        vec, mat = P.run_mvrnn(c, w, copy_leaves=0)
+        assert c.acrobat_device_status() == A.OK
+        ov, om = oracle.mvrnn(w, nthreads=NT)
+        internal = w["left"] >= 0
+        P.assert_close(vec[internal], ov[internal], "vec")
+        P.assert_close(mat[internal], om[internal], "mat")
+    finally:
+        c.close()
+
+
 def test_mvrnn_rejects_unsupported_d(ctx, P):
     import paper_2305_10611_amd as A
     w = gen.mvrnn_workload(2, 2, 3, 32, seed=33)

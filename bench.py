@@ -33,16 +33,16 @@ MEASURED_HBM_GBS = 5800.0
 # HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summaries
 # (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB per dispatch, factors from a plain copy of known size; averaged over
 # the launches that make up the dominant variant).  Hardware counters cannot be read from inside this process:
-# the figures are those of the library as of TRAFFIC_COMMIT and are reported with that label, not as live
-# measurements; a workload without a summary reports null.
-TRAFFIC_COMMIT = "b76ed52"
-MEASURED_TRAFFIC = {
-    ("treelstm_h256_8x20", "kind=2 tile=6"): (3.64e6, "profiles/treelstm_h256_small_configs.md"),
-    ("treelstm_h256_64", "kind=2 tile=6"): (11.7e6, "profiles/treelstm_h256_small_configs.md"),
-    ("treelstm_h512_256", "kind=2 tile=64"): (120.4e6, "profiles/treelstm_h512_256_cell_level_kernel.md"),
-    ("mvrnn_d64_64", "kind=3 tile=1"): (6.9e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md"),
-    ("lstm_h512_256", "kind=13 tile=16"): (250.5e6, "profiles/lstm_h512_256_cell_kernels.md"),
-    ("lstm_h512_256", "kind=6 tile=6"): (12.3e6, "profiles/lstm_h512_256_cell_kernels.md (one launch per step, commit 138cebb)"),
+# the figures are those of the library as of the commit named with each and are reported with that label, not as
+# live measurements; a workload without a summary reports null.
+MEASURED_TRAFFIC = {  # (workload, dominant kernel) -> (bytes per launch, summary, commit the library was at)
+    ("treelstm_h256_8x20", "kind=2 tile=6"): (3.64e6, "profiles/treelstm_h256_small_configs.md", "b76ed52"),
+    ("treelstm_h256_64", "kind=2 tile=6"): (11.7e6, "profiles/treelstm_h256_small_configs.md", "b76ed52"),
+    ("treelstm_h512_256", "kind=2 tile=64"): (120.4e6, "profiles/treelstm_h512_256_cell_level_kernel.md", "b76ed52"),
+    ("mvrnn_d64_64", "kind=14 tile=0"): (87.6e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md", "03fef4c"),
+    ("mvrnn_d64_64", "kind=3 tile=1"): (6.9e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md (one launch per level)", "b76ed52"),
+    ("lstm_h512_256", "kind=13 tile=16"): (250.5e6, "profiles/lstm_h512_256_cell_kernels.md", "b76ed52"),
+    ("lstm_h512_256", "kind=6 tile=6"): (12.3e6, "profiles/lstm_h512_256_cell_kernels.md (one launch per step)", "138cebb"),
 }
 
 
@@ -449,10 +449,10 @@ def main():
         achieved = (units * bytes_per[dominant] + launches * weight_bytes[dominant]) / (ms_sum * 1e-3) / 1e9
         peak, unit = PEAK_HBM_GBS, "GB/s"
     kname = f"kind={dominant} tile={dom_tile}"
-    traffic, traffic_src = MEASURED_TRAFFIC.get((w["name"], kname), (None, None))
+    traffic, traffic_src, traffic_commit = MEASURED_TRAFFIC.get((w["name"], kname), (None, None, None))
     roofline = {"bound": bound, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": traffic, "traffic_unit": "bytes/launch",
-                "traffic_source": traffic_src, "traffic_measured_at_commit": TRAFFIC_COMMIT if traffic else None,
+                "traffic_source": traffic_src, "traffic_measured_at_commit": traffic_commit,
                 "algorithmic_bytes_per_launch": round((units * bytes_per[dominant] + launches * weight_bytes[dominant]) / launches),
                 "kernel": kname, "launches_per_step": launches,
                 "units_per_step": units, "avg_launch_us": round(ms_sum / launches * 1e3, 2)}

@@ -477,7 +477,8 @@ int acrobat_set_gather_fusion(acrobat_ctx* ctx, int32_t enabled);
 /* Tuning and test hook; no result ever depends on it beyond the summation order of the contraction.
  * The launcher normally picks a kernel variant per level from the level's size.  force_tile != 0 makes
  * every cell level of this context use one variant instead: 64 or 32 = nodes per workgroup tile of the
- * tiled kernel, 6 = the kernel for latency-bound levels, 65 or 33 = 64- or 32-node tiles with the level
+ * tiled kernel, 6 = the stepwise kernel for latency-bound levels, 16 = the kernel for small levels that feeds the
+ * matrix cores straight from global memory (16-node tiles), 65 or 33 = 64- or 32-node tiles with the level
  * cut into equal shares, one per compute unit, inside one launch; force_ksplit (a power of two up to 32,
  * 0 = automatic) is then the number of workgroups sharing a tile's contraction range (tile 6: slabs moved
  * per step, 4 or 8; ignored for 65 and 33).  A forced shape that does not apply to a level (k range not divisible, workspace

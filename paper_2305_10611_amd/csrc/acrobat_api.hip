@@ -1451,8 +1451,9 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
 
 int acrobat_set_tuning(acrobat_ctx* ctx, int32_t force_tile, int32_t force_ksplit, int32_t mvrnn_variant) {
   if (!ctx) return ACROBAT_EINVAL;
-  if (force_tile != 0 && force_tile != 6 && force_tile != 32 && force_tile != 64 && force_tile != 33 && force_tile != 65)
-    return fail(ctx, ACROBAT_EINVAL, "force_tile must be 0, 6, 32, 64, 33 or 65");
+  if (force_tile != 0 && force_tile != 6 && force_tile != 16 && force_tile != 32 && force_tile != 64 && force_tile != 33 &&
+      force_tile != 65)
+    return fail(ctx, ACROBAT_EINVAL, "force_tile must be 0, 6, 16, 32, 64, 33 or 65");
   if (force_ksplit < 0 || force_ksplit > 32 || (force_ksplit & (force_ksplit - 1)))
     return fail(ctx, ACROBAT_EINVAL, "force_ksplit must be 0 or a power of two up to 32");
   if (mvrnn_variant != 0 && mvrnn_variant != 1) return fail(ctx, ACROBAT_EINVAL, "mvrnn_variant must be 0 or 1");

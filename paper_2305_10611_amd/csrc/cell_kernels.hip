@@ -66,41 +66,48 @@ __device__ __forceinline__ constexpr int gate_row(int g) {
 
 // Fused epilogue of one lane: bias, gates, state update, scatter to the arena, for NV
 // accumulator rows (node_of(v)) of hidden unit j; acc(g, v) is the pre-activation of gate g.
-// Three passes - indices, then every gathered operand, then arithmetic and stores - so that
-// all loads of a pass are in flight together instead of one dependent chain per row (the
-// stores may alias the loads as far as the compiler can tell, which would otherwise serialise
-// the rows).
+// Two stages.  epilogue_fetch reads the indices and then every gathered operand (all loads of a
+// pass in flight together instead of one dependent chain per row); it depends on nothing the
+// contraction computes, so a kernel may run it ahead of its k loop.  epilogue_apply does the
+// arithmetic and the stores (the stores may alias the loads as far as the compiler can tell,
+// which would otherwise serialise the rows).
 //
 // `sidx` (may be null) is the tile's index table in LDS, [3][bm]: arena row written, first and
 // second operand row of tile row r = node - m0, as staged by the contraction kernel's prologue
 // (tail rows hold the entries of node n - 1); without it the indices come from global memory.
-template <int G, int EPI, int NV, class Acc, class NodeOf>
-__device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int j, Acc&& acc, NodeOf&& node_of,
-                                              const int* sidx = nullptr, const int bm = 0, const int m0 = 0) {
-  const int H = a.H, n = a.n;
+template <int G, int EPI, int NV>
+struct EpilogueOperands {
   float bz[G];
+  size_t orow[NV];
+  bool live[NV];
+  float p0[NV], p1[NV];                        // gathered state: c of the two children / previous c / hoisted z (RNN)
+  float zx[EPI == EPI_LSTM_STEP ? G : 1][NV];  // hoisted input transform of an LSTM step
+};
+
+template <int G, int EPI, int NV, class NodeOf>
+__device__ __forceinline__ void epilogue_fetch(const CellLevelArgs& a, const int j, NodeOf&& node_of,
+                                               EpilogueOperands<G, EPI, NV>& o, const int* sidx = nullptr, const int bm = 0,
+                                               const int m0 = 0) {
+  const int H = a.H, n = a.n;
 #pragma unroll
   for (int g = 0; g < G; ++g) {
-    if constexpr (EPI == EPI_RELU_OUT) bz[g] = a.bias && j < a.n_cols ? a.bias[j] : 0.0f;
-    else bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
+    if constexpr (EPI == EPI_RELU_OUT) o.bz[g] = a.bias && j < a.n_cols ? a.bias[j] : 0.0f;
+    else o.bz[g] = a.bias ? a.bias[gate_row<EPI>(g) * H + j] : 0.0f;
   }
-
-  size_t orow[NV];
   int ia[NV], ib[NV];
-  bool live[NV];
 #pragma unroll
   for (int v = 0; v < NV; ++v) {
     const int node = node_of(v);
-    live[v] = node < n;
-    const int nd = live[v] ? node : n - 1;  // tail rows read what the last node reads, store nothing
+    o.live[v] = node < n;
+    const int nd = o.live[v] ? node : n - 1;  // tail rows read what the last node reads, store nothing
     ia[v] = ib[v] = 0;
     if (sidx) {
       const int r = node - m0;
-      orow[v] = (size_t)sidx[r];
+      o.orow[v] = (size_t)sidx[r];
       if constexpr (EPI == EPI_TREE_INTERNAL || EPI == EPI_LSTM_STEP) ia[v] = sidx[bm + r];
       if constexpr (EPI == EPI_TREE_INTERNAL) ib[v] = sidx[2 * bm + r];
     } else {
-      orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
+      o.orow[v] = a.out_rows ? (size_t)a.out_rows[nd] : (size_t)nd;
       if constexpr (EPI == EPI_TREE_INTERNAL) {
         ia[v] = a.idx0[nd];
         ib[v] = a.idx1[nd];
@@ -110,71 +117,83 @@ __device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int 
       }
     }
   }
+#pragma unroll
+  for (int v = 0; v < NV; ++v) {
+    o.p0[v] = o.p1[v] = 0.0f;
+    if constexpr (EPI == EPI_TREE_INTERNAL) {
+      o.p0[v] = a.cprev_src[(size_t)ia[v] * H + j];
+      o.p1[v] = a.cprev_src[(size_t)ib[v] * H + j];
+    } else if constexpr (EPI == EPI_RNN_STEP) {
+      o.p0[v] = a.zadd ? a.zadd[o.orow[v] * (size_t)H + j] : 0.0f;
+    } else if constexpr (EPI == EPI_LSTM_STEP) {
+      o.p0[v] = a.cprev_src ? a.cprev_src[(size_t)ia[v] * H + j] : 0.0f;
+#pragma unroll
+      for (int g = 0; g < G; ++g) o.zx[g][v] = a.zadd[o.orow[v] * (size_t)(G * H) + g * H + j];
+    }
+  }
+}
 
+template <int G, int EPI, int NV, class Acc>
+__device__ __forceinline__ void epilogue_apply(const CellLevelArgs& a, const int j, Acc&& acc,
+                                               const EpilogueOperands<G, EPI, NV>& o) {
+  const int H = a.H;
+  const float* bz = o.bz;
   if constexpr (EPI == EPI_STORE_Z) {
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      if (!live[v]) continue;
+      if (!o.live[v]) continue;
 #pragma unroll
-      for (int g = 0; g < G; ++g) a.zout[orow[v] * (size_t)(G * H) + g * H + j] = acc(g, v) + bz[g];
+      for (int g = 0; g < G; ++g) a.zout[o.orow[v] * (size_t)(G * H) + g * H + j] = acc(g, v) + bz[g];
     }
   } else if constexpr (EPI == EPI_TREE_LEAF) {
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      if (!live[v]) continue;
+      if (!o.live[v]) continue;
       const float c = fast_sigmoid(acc(0, v) + bz[0]) * fast_tanh(acc(2, v) + bz[2]);
-      a.c[orow[v] * H + j] = c;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc(1, v) + bz[1]) * fast_tanh(c);
+      a.c[o.orow[v] * H + j] = c;
+      a.h[o.orow[v] * H + j] = fast_sigmoid(acc(1, v) + bz[1]) * fast_tanh(c);
     }
   } else if constexpr (EPI == EPI_TREE_INTERNAL) {
-    float cl[NV], cr[NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      cl[v] = a.cprev_src[(size_t)ia[v] * H + j];
-      cr[v] = a.cprev_src[(size_t)ib[v] * H + j];
-    }
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      if (!live[v]) continue;
+      if (!o.live[v]) continue;
       const float c = fast_sigmoid(acc(0, v) + bz[0]) * fast_tanh(acc(4, v) + bz[4]) +
-                      fast_sigmoid(acc(1, v) + bz[1]) * cl[v] + fast_sigmoid(acc(2, v) + bz[2]) * cr[v];
-      a.c[orow[v] * H + j] = c;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc(3, v) + bz[3]) * fast_tanh(c);
+                      fast_sigmoid(acc(1, v) + bz[1]) * o.p0[v] + fast_sigmoid(acc(2, v) + bz[2]) * o.p1[v];
+      a.c[o.orow[v] * H + j] = c;
+      a.h[o.orow[v] * H + j] = fast_sigmoid(acc(3, v) + bz[3]) * fast_tanh(c);
     }
   } else if constexpr (EPI == EPI_RNN_STEP) {
-    float zx[NV];
-#pragma unroll
-    for (int v = 0; v < NV; ++v) zx[v] = a.zadd ? a.zadd[orow[v] * (size_t)H + j] : 0.0f;
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      if (!live[v]) continue;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc(0, v) + zx[v] + bz[0]);
+      if (!o.live[v]) continue;
+      a.h[o.orow[v] * H + j] = fast_sigmoid(acc(0, v) + o.p0[v] + bz[0]);
     }
   } else if constexpr (EPI == EPI_RELU_OUT) {
     if (j < a.n_cols) {
 #pragma unroll
       for (int v = 0; v < NV; ++v) {
-        if (!live[v]) continue;
-        a.y[orow[v] * (size_t)a.ldo + j] = fmaxf(acc(0, v) + bz[0], 0.0f);
+        if (!o.live[v]) continue;
+        a.y[o.orow[v] * (size_t)a.ldo + j] = fmaxf(acc(0, v) + bz[0], 0.0f);
       }
     }
   } else {  // EPI_LSTM_STEP
-    float cp[NV], zx[G][NV];
 #pragma unroll
     for (int v = 0; v < NV; ++v) {
-      cp[v] = a.cprev_src ? a.cprev_src[(size_t)ia[v] * H + j] : 0.0f;
-#pragma unroll
-      for (int g = 0; g < G; ++g) zx[g][v] = a.zadd[orow[v] * (size_t)(G * H) + g * H + j];
-    }
-#pragma unroll
-    for (int v = 0; v < NV; ++v) {
-      if (!live[v]) continue;
-      const float c = fast_sigmoid(acc(1, v) + zx[1][v] + bz[1]) * cp[v] +
-                      fast_sigmoid(acc(0, v) + zx[0][v] + bz[0]) * fast_tanh(acc(3, v) + zx[3][v] + bz[3]);
-      a.c[orow[v] * H + j] = c;
-      a.h[orow[v] * H + j] = fast_sigmoid(acc(2, v) + zx[2][v] + bz[2]) * fast_tanh(c);
+      if (!o.live[v]) continue;
+      const float c = fast_sigmoid(acc(1, v) + o.zx[1][v] + bz[1]) * o.p0[v] +
+                      fast_sigmoid(acc(0, v) + o.zx[0][v] + bz[0]) * fast_tanh(acc(3, v) + o.zx[3][v] + bz[3]);
+      a.c[o.orow[v] * H + j] = c;
+      a.h[o.orow[v] * H + j] = fast_sigmoid(acc(2, v) + o.zx[2][v] + bz[2]) * fast_tanh(c);
     }
   }
+}
+
+template <int G, int EPI, int NV, class Acc, class NodeOf>
+__device__ __forceinline__ void cell_epilogue(const CellLevelArgs& a, const int j, Acc&& acc, NodeOf&& node_of,
+                                              const int* sidx = nullptr, const int bm = 0, const int m0 = 0) {
+  EpilogueOperands<G, EPI, NV> o;
+  epilogue_fetch<G, EPI, NV>(a, j, node_of, o, sidx, bm, m0);
+  epilogue_apply<G, EPI, NV>(a, j, acc, o);
 }
 
 // LDS of one workgroup of the tiled kernels: slab buffers (reused by the reduction over the k-split
@@ -712,6 +731,11 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
   floatx16 acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+  // the element this thread finishes (node row tid / 8, unit tid % 8 of the tile); its gathered operands are
+  // requested as soon as the index table is in LDS, long before the contraction is through
+  const int erow = tid >> 3, ejj = tid & 7;
+  const bool finisher = ejj < JW && j0 + ejj < hlim;
+  EpilogueOperands<G, EPI, 1> eo;
 
   const int slabs_per_seg = a.kseg / kBK;
   const int S = a.nseg * slabs_per_seg;
@@ -780,6 +804,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
       load_b(0, 2);
     }
     __syncthreads();
+    if (finisher) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
     // invariant at the top: buffer 0 holds step s, slot 1 step s + 1, slot 0 step s + 2
     for (int s = 0; s < steps; s += 2) {
       if (s + 1 < steps) {
@@ -807,6 +832,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
     if ((tid & 7) == 0) sidx[32 + lrow] = row0;
     if ((tid & 7) == 1) sidx[64 + lrow] = row1;
     __syncthreads();
+    if (finisher) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
   }
 
   // partial tiles z[wk][node row][column], then one epilogue element per thread
@@ -815,18 +841,16 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
   for (int v = 0; v < 16; ++v)
     z[(wk * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * ZLD + (lane & 31)] = acc[v];
   __syncthreads();
-  const int row = tid >> 3, jj = tid & 7;
-  if (jj >= JW || j0 + jj >= hlim) return;
+  if (!finisher) return;
   float zs[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float sum = 0.0f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) sum += z[(w * 32 + row) * ZLD + g * JW + jj];
+    for (int w = 0; w < 4; ++w) sum += z[(w * 32 + erow) * ZLD + g * JW + ejj];
     zs[g] = sum;
   }
-  cell_epilogue<G, EPI, 1>(
-      a, j0 + jj, [&](int g, int) { return zs[g]; }, [&](int) { return m0 + row; }, sidx, 32, m0);
+  epilogue_apply<G, EPI, 1>(a, j0 + ejj, [&](int g, int) { return zs[g]; }, eo);
 }
 
 template <int G, int EPI, int U>
@@ -847,6 +871,124 @@ hipError_t launch_tiny(const CellLevelPair& pr, unsigned grid, hipStream_t strea
   launch_with_events((cell_tiny_kernel<G, EPI, U>), dim3(grid), dim3(kThreads), bytes, stream, ev.start, ev.stop, 
                         pr);
   return hipGetLastError();
+}
+
+// ---- small levels straight from global memory to the matrix cores --------------------------------------
+// cell_tiny_kernel walks its k range in steps (global -> registers -> LDS -> barrier -> operand registers), and
+// a level with few nodes is as long as that chain of dependent steps.  This kernel has no steps: a workgroup
+// owns 16 nodes x JW hidden units x all G gates (G * JW <= 16 columns, one 16x16 block of
+// v_mfma_f32_16x16x4_f32), wavefront w takes the 16-k groups w, w + 4, ... of the k range, and every lane
+// requests ALL of its operand pieces - 16 bytes of its node row and 16 bytes of its weight row per group -
+// before the first matrix instruction; lane l supplies A[node l % 16][k] and B[k][column l % 16] for the four
+// k = 16 group + 4 (l / 16) + e, one instruction per e (a permutation of the summation order applied to both
+// operands).  The only dependent chain left is index -> rows -> matrix instructions -> four-way sum through
+// LDS -> gate arithmetic, and the gathered operands of the gate arithmetic are requested right behind the
+// rows.  Column c of a workgroup is gate c / JW of unit j0 + c % JW.  The launcher pads the number of unit
+// tiles to a multiple of 8 so that all node tiles of a unit tile run on the same XCD and find its weight
+// rows in that XCD's L2.
+template <int G>
+constexpr int direct_jw() { return 16 / G; }
+constexpr int kDirectGroups = 16;  // 16-k groups of a wavefront in flight at once (K = 1024: all of them)
+
+template <int G, int EPI>
+__global__ __launch_bounds__(kThreads, 3) void cell_direct_kernel(const CellLevelPair pr) {
+  const bool second = blockIdx.x >= (unsigned)pr.split;  // which of the two batches (uniform)
+  const CellLevelArgs& a = pr.a[second];
+  const int bid = (int)blockIdx.x - (second ? pr.split : 0);
+  constexpr int JW = direct_jw<G>(), NC = G * JW;
+  __shared__ float z[4][16][17];
+  __shared__ int sidx[3 * 16];  // the tile's index table, see epilogue_fetch
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int li = lane & 15, kq = lane >> 4;
+  const int H = a.H, n = a.n;
+  const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
+  const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = (n_jt + 7) & ~7;
+  const int jt = bid % n_jt_padded, mt = bid / n_jt_padded;
+  if (jt >= n_jt) return;  // padding of the grid
+  const int j0 = jt * JW, m0 = mt * 16;
+
+  // operand node of this lane, and the element this thread finishes: node m0 + tid / JW, unit j0 + tid % JW
+  int node = m0 + li;
+  node = node < n ? node : n - 1;  // tail rows re-read the last node; never stored
+  const int row0 = a.idx0 ? a.idx0[node] : node;
+  const int row1 = a.idx1 ? a.idx1[node] : node;
+  const int orow = a.out_rows ? a.out_rows[node] : node;
+  const int er = tid / JW, ej = j0 + tid % JW;
+  const bool finisher = tid < 16 * JW && ej < hlim;
+
+  // weight row of column li (columns past the last repeat it and are never read back)
+  const float* bptr;
+  {
+    const int c = li < NC ? li : NC - 1;
+    int j = j0 + c % JW;
+    j = j < hlim ? j : hlim - 1;
+    int grow = 0;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (c / JW == g) grow = gate_row<EPI>(g);
+    bptr = a.W + ((size_t)grow * (size_t)H + (size_t)j) * (size_t)a.ldw + 4 * kq;
+  }
+
+  const int groups_per_seg = a.kseg / 16;
+  const int n_groups = a.nseg * groups_per_seg;
+  const int mine = n_groups > w ? (n_groups - w + 3) / 4 : 0;  // groups w, w + 4, ...
+  floatx4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+  EpilogueOperands<G, EPI, 1> eo;
+  for (int base = 0; base < mine || base == 0; base += kDirectGroups) {
+    floatx4 rb[kDirectGroups], ra[kDirectGroups];
+#pragma unroll
+    for (int t = 0; t < kDirectGroups; ++t)
+      if (base + t < mine) rb[t] = *reinterpret_cast<const floatx4*>(bptr + 16 * (4 * (base + t) + w));
+    const float* aptr0 = a.nseg > 0 ? a.src0 + (size_t)row0 * (size_t)a.ld0 + 4 * kq : nullptr;
+    const float* aptr1 = a.nseg > 1 ? a.src1 + (size_t)row1 * (size_t)a.ld1 + 4 * kq : aptr0;
+#pragma unroll
+    for (int t = 0; t < kDirectGroups; ++t)
+      if (base + t < mine) {
+        const int grp = 4 * (base + t) + w;
+        const bool seg = grp >= groups_per_seg;
+        ra[t] = *reinterpret_cast<const floatx4*>((seg ? aptr1 : aptr0) + 16 * (grp - (seg ? groups_per_seg : 0)));
+      }
+    if (base == 0) {  // the gate arithmetic's own operands, right behind the rows
+      if (tid < 16) {
+        sidx[li] = orow;
+        sidx[16 + li] = row0;
+        sidx[32 + li] = row1;
+      }
+      __syncthreads();
+      if (finisher) epilogue_fetch<G, EPI, 1>(a, ej, [&](int) { return m0 + er; }, eo, sidx, 16, m0);
+    }
+#pragma unroll
+    for (int t = 0; t < kDirectGroups; ++t)
+      if (base + t < mine) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          if (t & 1) acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[t][e], rb[t][e], acc1, 0, 0, 0);
+          else acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(ra[t][e], rb[t][e], acc0, 0, 0, 0);
+        }
+      }
+  }
+  // result register v of lane l: node 4 (l / 16) + v, column l % 16
+#pragma unroll
+  for (int v = 0; v < 4; ++v) z[w][4 * kq + v][li] = acc0[v] + acc1[v];
+  __syncthreads();
+  if (!finisher || m0 + er >= n) return;
+  float zs[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float sum = 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) sum += z[q][er][g * JW + tid % JW];
+    zs[g] = sum;
+  }
+  epilogue_apply<G, EPI, 1>(a, ej, [&](int g, int) { return zs[g]; }, eo);
+}
+
+template <int G>
+unsigned direct_grid(const CellLevelArgs& a, bool relu_out) {
+  const int hlim = relu_out ? a.n_cols : a.H;
+  const int n_jt = (hlim + direct_jw<G>() - 1) / direct_jw<G>();
+  return (unsigned)((long)((a.n + 15) / 16) * ((n_jt + 7) & ~7));
 }
 
 struct Shape {
@@ -880,6 +1022,7 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
     return (size_t)tiles * s * (bm / 32) * G * kBlockFloats <= ws.partial_floats;
   };
   if (ws.force_bm == 6) return Shape{6, ws.force_ksplit == 4 || ws.force_ksplit == 8 ? ws.force_ksplit : 0};
+  if (ws.force_bm == 16) return Shape{16, 1};
   if (ws.force_bm == 65 || ws.force_bm == 33) {  // tuning override: even split with 64- or 32-node tiles
     const int bm = ws.force_bm - 1;
     const int wgs = streamk_workgroups<G>(a, ws, bm);
@@ -899,7 +1042,18 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //    and reads ksplit partial tiles);
   //  * slightly more tiles than compute units: split in two for balance.
   //  * latency-bound levels (n x K up to about 256 000) run cell_tiny_kernel: one launch, no k split;
-  if ((long)a.n * n_slabs * kBK <= 256000) return Shape{6, 0};
+  if ((long)a.n * n_slabs * kBK <= 256000) {
+    //  * of those, the smallest go to cell_direct_kernel (no steps at all, but every workgroup pulls its 16 node
+    //    rows and 16 weight rows through the L2 on its own): while all its workgroups are resident at once and
+    //    together request at most 24 MiB.  Measured against the stepwise kernel: five-gate tree level, K = 1024,
+    //    up to 16 nodes 5.6-6.8 instead of 9.6-10.0 us (36 nodes: 13.5 instead of 10.4); K = 512, up to 64 nodes
+    //    4.5-6.7 instead of 6.6-7.1 (88 nodes: 8.7 instead of 7.1); LSTM step, K = 512, up to 30 rows 5.2
+    //    instead of 6.8; single-gate recurrent step, K = 256, 128 rows 4.4 instead of 6.9.
+    const long wgs = (long)((a.n + 15) / 16) * (((a.H + direct_jw<G>() - 1) / direct_jw<G>() + 7) & ~7);
+    const long rows = wgs * (G * direct_jw<G>()) + (long)(wgs / ((a.n + 15) / 16)) * a.n;  // weight rows + node rows requested
+    if (ws.n_cu > 0 && wgs <= 2L * ws.n_cu && rows * n_slabs * kBK * (long)sizeof(float) <= (24L << 20)) return Shape{16, 1};
+    return Shape{6, 0};
+  }
   //  * levels whose 32-node tiles all fit the chip at once (one workgroup per compute unit) run them
   //    unsplit: 29-30 us at 286 / 399 nodes against 32-33 us for 64-node tiles split in two;
   const long tiles32 = (long)((a.n + 31) / 32) * n_jt;
@@ -948,6 +1102,7 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
     const Shape sh2 = pick_shape<G>(*b, ws);
     const bool shareable = sh.bm == sh2.bm && sh.streamk_wgs == 0 && sh2.streamk_wgs == 0 &&
                            (sh.bm == 6 ? sh.ksplit == sh2.ksplit : (sh.ksplit == 1 && sh2.ksplit == 1));
+
     if (!shareable) {  // two launches in a row, bracketed as one: first kernel's begin .. last kernel's end
       LaunchEvents e0, e1;
       e0.start = ev.start;
@@ -971,6 +1126,12 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
     const int u = sh.ksplit ? sh.ksplit : (g0 + g1 <= 256 ? 8 : 4);
     if (ksplit) *ksplit = 1;
     return u == 8 ? launch_tiny<G, EPI, 8>(pr, g0 + g1, stream, ev) : launch_tiny<G, EPI, 4>(pr, g0 + g1, stream, ev);
+  }
+  if (sh.bm == 16) {
+    const unsigned g0 = direct_grid<G>(a, EPI == EPI_RELU_OUT), g1 = b ? direct_grid<G>(*b, EPI == EPI_RELU_OUT) : 0;
+    pr.split = (int32_t)g0;  // a multiple of 8: the second batch keeps the unit tile -> XCD assignment
+    launch_with_events((cell_direct_kernel<G, EPI>), dim3(g0 + g1), dim3(kThreads), 0, stream, ev.start, ev.stop, pr);
+    return hipGetLastError();
   }
   if (sh.streamk_wgs > 0) {
     StreamKArgs sk{a, sh.streamk_wgs, ws.partial,

@@ -524,7 +524,7 @@ def test_profiling_records_every_launch(ctx, P):
 
 
 # ---------------------------------------------------------------- every kernel variant
-@pytest.mark.parametrize("tile,ksplit", [(64, 1), (32, 1), (64, 2), (64, 4), (32, 8), (32, 2), (6, 4), (6, 8), (65, 1), (33, 1)])
+@pytest.mark.parametrize("tile,ksplit", [(64, 1), (32, 1), (64, 2), (64, 4), (32, 8), (32, 2), (6, 4), (6, 8), (65, 1), (33, 1), (16, 1)])
 def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit):
     """The launcher normally picks the node-tile height and k split from the level size; the
     tuning hook forces one variant for every level (leaf, internal, LSTM input and steps).

@@ -213,10 +213,12 @@ struct TileLds {
 // Contraction of one tile (BM nodes from m0, hidden units j0 .. j0 + 31, all G gates) over the slabs
 // [slab0, slab0 + my_slabs) of the k range.  On return own[g][v] holds this wavefront's share of the
 // result (accumulator row acc_row(v), see tile_acc_row) and sidx the tile's index table.
-template <int G, int EPI, int WM, int WK>
+// `early()` runs once the index table is complete and the first slabs are on their way: the place to request
+// whatever the epilogue gathers (epilogue_fetch), so that it has arrived when the contraction is through.
+template <int G, int EPI, int WM, int WK, class Early>
 __device__ __forceinline__ void contract_tile(const CellLevelArgs& a, const int m0, const int j0, const int slab0,
                                               const int my_slabs, float* const smem, int* const sidx,
-                                              float (&own)[G][TileLds<G, WM, WK>::NV]) {
+                                              float (&own)[G][TileLds<G, WM, WK>::NV], Early&& early) {
   static_assert(WM * WK == 4, "four wavefronts per workgroup");
   using L = TileLds<G, WM, WK>;
   constexpr int BM = L::BM;
@@ -395,6 +397,7 @@ __device__ __forceinline__ void contract_tile(const CellLevelArgs& a, const int 
     }
     __syncthreads();
     read_frag(0, 0, 0);
+    early();
     int kb = 0, bc = 0;
     for (; kb + NS <= my_slabs; kb += NS) {
 #pragma unroll
@@ -413,6 +416,7 @@ __device__ __forceinline__ void contract_tile(const CellLevelArgs& a, const int 
     if (Q > 1) __syncthreads();  // the last group's barrier pairs: LDS is reused by the reductions
   } else {
     __syncthreads();  // no contraction (first step of a recurrence): publish the index table
+    early();
   }
 
   // The WK wavefronts of a node block hold partial sums over their share of k.  They are added
@@ -478,19 +482,30 @@ __device__ __forceinline__ void contract_tile(const CellLevelArgs& a, const int 
 template <int WK>
 __device__ __forceinline__ int tile_acc_row(int wk, int v) { return (wk * (4 / WK) + (v >> 2)) * 4 + (v & 3); }
 
-// fused epilogue of a contracted tile (accumulator row r of a lane: node = m0 + 32 wm + 8 (r / 4) + 4 (lane / 32) + r % 4)
+// fused epilogue of a contracted tile (accumulator row r of a lane: node = m0 + 32 wm + 8 (r / 4) + 4 (lane / 32) + r % 4),
+// in its two stages
 template <int G, int EPI, int WM, int WK>
-__device__ __forceinline__ void tile_epilogue(const CellLevelArgs& a, const int m0, const int j0, const int* sidx,
-                                              const float (&own)[G][TileLds<G, WM, WK>::NV]) {
+using TileEpilogueOperands = EpilogueOperands<G, EPI, TileLds<G, WM, WK>::NV>;
+
+template <int G, int EPI, int WM, int WK>
+__device__ __forceinline__ void tile_epilogue_fetch(const CellLevelArgs& a, const int m0, const int j0, const int* sidx,
+                                                    TileEpilogueOperands<G, EPI, WM, WK>& eo) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave % WM, wk = wave / WM;
-  cell_epilogue<G, EPI, TileLds<G, WM, WK>::NV>(
-      a, j0 + (lane & 31), [&](int g, int v) { return own[g][v]; },
+  epilogue_fetch<G, EPI, TileLds<G, WM, WK>::NV>(
+      a, j0 + (lane & 31),
       [&](int v) {
         const int r = tile_acc_row<WK>(wk, v);
         return m0 + wm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       },
-      sidx, 32 * WM, m0);
+      eo, sidx, 32 * WM, m0);
+}
+template <int G, int EPI, int WM, int WK>
+__device__ __forceinline__ void tile_epilogue_apply(const CellLevelArgs& a, const int j0,
+                                                    const float (&own)[G][TileLds<G, WM, WK>::NV],
+                                                    const TileEpilogueOperands<G, EPI, WM, WK>& eo) {
+  epilogue_apply<G, EPI, TileLds<G, WM, WK>::NV>(
+      a, j0 + (int)(threadIdx.x & 31), [&](int g, int v) { return own[g][v]; }, eo);
 }
 
 template <int G, int EPI, int WM, int WK>
@@ -510,7 +525,12 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   const int j0 = jt * 32, m0 = mt * L::BM;
   const int my_slabs = (a.nseg * (a.kseg / kBK)) / ksplit;  // host guarantees divisibility
   float own[G][L::NV];
-  contract_tile<G, EPI, WM, WK>(a, m0, j0, ks * my_slabs, my_slabs, smem, sidx, own);
+  TileEpilogueOperands<G, EPI, WM, WK> eo;
+  // (the 32-node tile has no registers to spare during its k loop: it fetches behind the loop)
+  constexpr bool kEarly = WM == 2;
+  contract_tile<G, EPI, WM, WK>(a, m0, j0, ks * my_slabs, my_slabs, smem, sidx, own, [&] {
+    if (kEarly && ksplit == 1) tile_epilogue_fetch<G, EPI, WM, WK>(a, m0, j0, sidx, eo);
+  });
 
   // ---- k split over workgroups: store the partial tile in register layout and stop; the
   // reduction kernel that follows on the stream adds the partial tiles and runs the epilogue
@@ -525,7 +545,8 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
       for (int v = 0; v < L::NV; ++v) mine[(g * 16 + tile_acc_row<WK>(wk, v)) * 64 + lane] = own[g][v];
     return;
   }
-  tile_epilogue<G, EPI, WM, WK>(a, m0, j0, sidx, own);
+  if (!kEarly) tile_epilogue_fetch<G, EPI, WM, WK>(a, m0, j0, sidx, eo);
+  tile_epilogue_apply<G, EPI, WM, WK>(a, j0, own, eo);
 }
 
 // ---- even split of a level over the chip ("stream-k") ---------------------------------------------------
@@ -586,7 +607,10 @@ __global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamK
     const int j0 = jt * 32, m0 = mt * L::BM;
     if (!first) __syncthreads();  // the previous tile's epilogue is through with the index table and the slabs
     float own[G][L::NV];
-    contract_tile<G, EPI, WM, WK>(a, m0, j0, s0, cnt, smem, sidx, own);
+    TileEpilogueOperands<G, EPI, WM, WK> eo;
+    contract_tile<G, EPI, WM, WK>(a, m0, j0, s0, cnt, smem, sidx, own, [&] {
+      if (cnt == n_slabs) tile_epilogue_fetch<G, EPI, WM, WK>(a, m0, j0, sidx, eo);  // a whole tile
+    });
     if (cnt < n_slabs) {  // a piece: park it, count in, and leave unless last
       // 16 bytes per lane and access: the four rows of accumulator quad (wk * QPW + qi) of gate g
       const unsigned mine = slot_of(p, tile);
@@ -609,6 +633,7 @@ __global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamK
       __syncthreads();
       if (!s_last) continue;
       // the pieces in ascending order of k, this workgroup's own from its registers (the same bits it parked)
+      tile_epilogue_fetch<G, EPI, WM, WK>(a, m0, j0, sidx, eo);
       float sum[G][L::NV];
 #pragma unroll
       for (int g = 0; g < G; ++g)
@@ -640,7 +665,7 @@ __global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamK
 #pragma unroll
         for (int v = 0; v < L::NV; ++v) own[g][v] = sum[g][v];
     }
-    tile_epilogue<G, EPI, WM, WK>(a, m0, j0, sidx, own);
+    tile_epilogue_apply<G, EPI, WM, WK>(a, j0, own, eo);
   }
 }
 
@@ -736,6 +761,9 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
   const int erow = tid >> 3, ejj = tid & 7;
   const bool finisher = ejj < JW && j0 + ejj < hlim;
   EpilogueOperands<G, EPI, 1> eo;
+  // (an LSTM step gathers five values per element; requested early they cost the k loop more than they save:
+  // 11.2 instead of 10.7 us at 250 rows)
+  constexpr bool kEarly = EPI != EPI_LSTM_STEP;
 
   const int slabs_per_seg = a.kseg / kBK;
   const int S = a.nseg * slabs_per_seg;
@@ -804,7 +832,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
       load_b(0, 2);
     }
     __syncthreads();
-    if (finisher) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
+    if (kEarly && finisher) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
     // invariant at the top: buffer 0 holds step s, slot 1 step s + 1, slot 0 step s + 2
     for (int s = 0; s < steps; s += 2) {
       if (s + 1 < steps) {
@@ -832,7 +860,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
     if ((tid & 7) == 0) sidx[32 + lrow] = row0;
     if ((tid & 7) == 1) sidx[64 + lrow] = row1;
     __syncthreads();
-    if (finisher) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
+    if (kEarly && finisher) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
   }
 
   // partial tiles z[wk][node row][column], then one epilogue element per thread
@@ -842,6 +870,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
     z[(wk * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * ZLD + (lane & 31)] = acc[v];
   __syncthreads();
   if (!finisher) return;
+  if (!kEarly) epilogue_fetch<G, EPI, 1>(a, j0 + ejj, [&](int) { return m0 + erow; }, eo, sidx, 32, m0);
   float zs[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {

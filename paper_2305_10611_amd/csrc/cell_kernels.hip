@@ -519,17 +519,29 @@ __global__ __launch_bounds__(kThreads, 2) void cell_level_kernel(const CellLevel
   int* const sidx = reinterpret_cast<int*>(smem + L::SMEM_FLOATS);  // the tile's index table, see cell_epilogue
 
   const int n_jt = a.H >> 5;
-  const int jt = bid % n_jt;
-  const int rest = bid / n_jt;
-  const int ks = rest % ksplit, mt = rest / ksplit;
+  int jt, mt, ks = 0;
+  if (ksplit == 0) {
+    // Unsplit level, XCD-aware order (workgroup id % 8 is the XCD): XCD x runs the unit tiles x % 4 + 4 i of the
+    // node tiles 2 i' + x / 4, so it keeps a quarter of the weight rows in its L2 and streams half of the node
+    // rows, instead of an eighth of the weights and every node row.
+    const int x = bid & 7, q = bid >> 3, jq = n_jt >> 2;
+    jt = (x & 3) + 4 * (q % jq);
+    mt = 2 * (q / jq) + (x >> 2);
+    if (mt * L::BM >= a.n) return;  // padding of an odd number of node tiles
+  } else {
+    jt = bid % n_jt;
+    const int rest = bid / n_jt;
+    ks = rest % ksplit;
+    mt = rest / ksplit;
+  }
   const int j0 = jt * 32, m0 = mt * L::BM;
-  const int my_slabs = (a.nseg * (a.kseg / kBK)) / ksplit;  // host guarantees divisibility
+  const int my_slabs = (a.nseg * (a.kseg / kBK)) / (ksplit ? ksplit : 1);  // host guarantees divisibility
   float own[G][L::NV];
   TileEpilogueOperands<G, EPI, WM, WK> eo;
   // (the 32-node tile has no registers to spare during its k loop: it fetches behind the loop)
   constexpr bool kEarly = WM == 2;
   contract_tile<G, EPI, WM, WK>(a, m0, j0, ks * my_slabs, my_slabs, smem, sidx, own, [&] {
-    if (kEarly && ksplit == 1) tile_epilogue_fetch<G, EPI, WM, WK>(a, m0, j0, sidx, eo);
+    if (kEarly && ksplit <= 1) tile_epilogue_fetch<G, EPI, WM, WK>(a, m0, j0, sidx, eo);
   });
 
   // ---- k split over workgroups: store the partial tile in register layout and stop; the
@@ -1176,16 +1188,20 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
     return hipGetLastError();
   }
   const int n_jt = a.H / 32;
-  const unsigned g0 = (unsigned)((long)((a.n + sh.bm - 1) / sh.bm) * n_jt * sh.ksplit);
+  const long n_mt = (a.n + sh.bm - 1) / sh.bm;
+  // an unsplit single batch of at least two node tiles runs in the XCD-aware order (kernel argument 0)
+  const bool xcd_order = !b && sh.ksplit == 1 && n_jt % 4 == 0 && n_mt >= 2 && ws.force_bm == 0;
+  const unsigned g0 = xcd_order ? (unsigned)(2 * n_jt * ((n_mt + 1) / 2)) : (unsigned)(n_mt * n_jt * sh.ksplit);
   const unsigned g1 = b ? (unsigned)((long)((b->n + sh.bm - 1) / sh.bm) * (b->H / 32)) : 0;
   pr.split = (int32_t)g0;
   const unsigned grid = g0 + g1;
+  const int ks_arg = xcd_order ? 0 : sh.ksplit;
   if (sh.bm == 64) {
     launch_with_events((cell_level_kernel<G, EPI, 2, 2>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, pr, sh.ksplit, ws.partial);
+                          ev.stop, pr, ks_arg, ws.partial);
   } else {
     launch_with_events((cell_level_kernel<G, EPI, 1, 4>), dim3(grid), dim3(kThreads), 0, stream, ev.start,
-                          ev.stop, pr, sh.ksplit, ws.partial);
+                          ev.stop, pr, ks_arg, ws.partial);
   }
   if (sh.ksplit > 1) {
     const int wm_count = sh.bm / 32;

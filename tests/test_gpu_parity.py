@@ -549,6 +549,35 @@ def test_every_tile_and_split_variant_matches_the_oracle(P, tile, ksplit):
         c.close()
 
 
+@pytest.mark.parametrize("H,D", [(32, 32), (96, 160), (160, 96), (512, 64)])
+def test_small_level_kernel_ragged_contraction_and_tiles(P, H, D):
+    """The kernel for small levels (tile 16) deals the 16-k groups of the contraction range to four wavefronts:
+    ranges of 2, 6, 10, 12 ... groups leave some wavefronts with fewer groups or none; node counts from 1 to a few
+    16-node tiles with a ragged last tile; unit tiles of 3, 4, 5 or 16 units that do not divide H; an output layer
+    of 5 units; both directions of a recurrence in one launch with different row counts."""
+    import paper_2305_10611_amd as A
+    c = A.Context(0)
+    try:
+        assert c.acrobat_set_tuning(16, 1, 0) == A.OK
+        c.acrobat_set_profiling(True)
+        w = gen.treelstm_workload(7, 1, 19, H, 60, "zipf1.1", seed=H + D, bias_scale=0.3, D=D)
+        h, cc = P.run_treelstm(c, w)
+        assert all(r[4] == 16 for r in c.acrobat_last_profile())
+        oh, oc = oracle.treelstm(w, nthreads=NT)
+        P.assert_close(h, oh, "h")
+        P.assert_close(cc, oc, "c")
+        c.acrobat_set_persistent(False)
+        s = gen.lstm_workload(21, 0, 7, H, D, seed=H * 3 + D, bias_scale=0.2)
+        h, cc = P.run_lstm(c, s)
+        oh, oc = oracle.varlen_lstm(s, nthreads=NT)
+        P.assert_close(h, oh, "lstm h")
+        P.assert_close(cc, oc, "lstm c")
+        b = gen.birnn_workload(19, 0, 6, H, D, 5, seed=H * 5 + D, bias_scale=0.2)
+        check_birnn(P, P.run_birnn(c, b), oracle.birnn(b, nthreads=NT), "birnn")
+    finally:
+        c.close()
+
+
 # ---------------------------------------------------------------- stream capture
 def test_forward_recorded_into_a_graph_replays_the_eager_result():
     """A captured forward call (index upload + every level launch) replayed several times, with eager work

@@ -145,7 +145,7 @@ def main():
                     help="also time the forward call replayed from a captured HIP graph (index upload + every launch), "
                          "and what capturing and instantiating it costs; reported under \"graph_replay\"")
     ap.add_argument("--persistent", choices=("auto", "off"), default="auto",
-                    help="LSTM and MV-RNN (d = 64): off = one launch per time step / level instead of one persistent launch")
+                    help="LSTM, BiRNN and MV-RNN (d = 64): off = one launch per time step / level instead of one persistent launch")
     ap.add_argument("--tuning", default=None, metavar="TILE,KSPLIT",
                     help="force one kernel variant for every cell level (acrobat_set_tuning), e.g. 64,1 or 65,1")
     ap.add_argument("--sync-probe", action="store_true",
@@ -260,9 +260,14 @@ def main():
             (t["bWx"], t["bWh"], t["bb"], t["binit"]), t["C"], t["cb"], o[0], o[1], o[2], st)))
         sched = lambda: A.acrobat_schedule_birnn(w["len"])
         B = A.binding
-        flops_per = {B.K_RNN_INPUT: 2.0 * D * H, B.K_RNN_STEP: 2.0 * H * H, B.K_RNN_OUTPUT: 4.0 * H * n_out}
-        bytes_per = {B.K_RNN_INPUT: 4.0 * D + 4.0 * H, B.K_RNN_STEP: 12.0 * H + 8, B.K_RNN_OUTPUT: 8.0 * H + 4.0 * n_out}
-        weight_bytes = {B.K_RNN_INPUT: 4.0 * H * D, B.K_RNN_STEP: 4.0 * H * H, B.K_RNN_OUTPUT: 8.0 * H * n_out}
+        # the recurrences are one launch per step (K_RNN_STEP) or one launch for all steps of both directions
+        # (K_RNN_PERSISTENT): same work per (token, direction); the persistent launch reads the weights once
+        flops_per = {B.K_RNN_INPUT: 2.0 * D * H, B.K_RNN_STEP: 2.0 * H * H, B.K_RNN_PERSISTENT: 2.0 * H * H,
+                     B.K_RNN_OUTPUT: 4.0 * H * n_out}
+        bytes_per = {B.K_RNN_INPUT: 4.0 * D + 4.0 * H, B.K_RNN_STEP: 12.0 * H + 8, B.K_RNN_PERSISTENT: 12.0 * H,
+                     B.K_RNN_OUTPUT: 8.0 * H + 4.0 * n_out}
+        weight_bytes = {B.K_RNN_INPUT: 4.0 * H * D, B.K_RNN_STEP: 4.0 * H * H, B.K_RNN_PERSISTENT: 8.0 * H * H,
+                        B.K_RNN_OUTPUT: 8.0 * H * n_out}
         dominant = B.K_RNN_STEP
         total_flops = R * (2 * flops_per[B.K_RNN_INPUT] + 2 * flops_per[B.K_RNN_STEP] + flops_per[B.K_RNN_OUTPUT])
         dtype, bound = "f32", "mfma"
@@ -427,7 +432,7 @@ def main():
     for i, r in enumerate(recs[0]):
         per_launch.append((r[0], r[1], r[2], r[4], float(np.mean([rr[i][3] for rr in recs])), r[5]))
     t_device_ms = sum(p[4] for p in per_launch)
-    for persistent_kind in (A.binding.K_LSTM_PERSISTENT, A.binding.K_MVRNN_PERSISTENT):
+    for persistent_kind in (A.binding.K_LSTM_PERSISTENT, A.binding.K_MVRNN_PERSISTENT, A.binding.K_RNN_PERSISTENT):
         if any(p[0] == persistent_kind for p in per_launch):
             dominant = persistent_kind
     K_REDUCE = A.binding.K_SPLITK_REDUCE

@@ -182,7 +182,10 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
  * acrobat_device_status reports that: call it once the stream has been synchronised; it returns ACROBAT_OK
  * or ACROBAT_ETIMEOUT and clears the condition.  Until it has been called the word stays raised and later
  * persistent launches of the context give up at their first long wait too.
- * The same switch covers acrobat_mvrnn_forward with d == 64: all internal levels then run in ONE launch in which
+ * The same switch covers acrobat_birnn_forward (H in {128, 256, 512}, at most 256 non-empty sequences, every
+ * workgroup resident at once): both recurrences then run in one launch, blocks of 16 sequences per direction,
+ * H / 64 workgroups per block exchanging h after every step in the same way.
+ * It also covers acrobat_mvrnn_forward with d == 64: all internal levels then run in ONE launch in which
  * a node waits for its own two children only (a flag word per node, polled with the same bound) instead of a
  * whole level waiting for the previous one, provided every workgroup of that launch is resident at once and the
  * call is not being captured into a graph (a captured call keeps one launch per level).
@@ -464,6 +467,7 @@ typedef struct {
 #define ACROBAT_K_DFG_BUCKET 12 /* level = bucket index */
 #define ACROBAT_K_LSTM_PERSISTENT 13 /* all time steps of the recurrence in one launch; n = all rows */
 #define ACROBAT_K_MVRNN_PERSISTENT 14 /* all internal levels of an MV-RNN batch in one launch; n = internal nodes */
+#define ACROBAT_K_RNN_PERSISTENT 15 /* all steps of both directions of a bidirectional RNN in one launch; n = rows of both */
 
 int acrobat_set_profiling(acrobat_ctx* ctx, int32_t enabled);
 

@@ -14,7 +14,7 @@ from . import build as _build
 OK, EINVAL, ESTRUCT, ENOMEM, EHIP, ETIMEOUT = 0, -1, -2, -3, -4, -5
 K_TREE_LEAF, K_TREE_INTERNAL, K_MVRNN_LEVEL, K_MVRNN_LEAFCOPY, K_LSTM_INPUT, K_LSTM_STEP = 1, 2, 3, 4, 5, 6
 K_RNN_INPUT, K_RNN_STEP, K_RNN_OUTPUT, K_SPLITK_REDUCE = 7, 8, 9, 10
-K_GATHER, K_DFG_BUCKET, K_LSTM_PERSISTENT, K_MVRNN_PERSISTENT = 11, 12, 13, 14
+K_GATHER, K_DFG_BUCKET, K_LSTM_PERSISTENT, K_MVRNN_PERSISTENT, K_RNN_PERSISTENT = 11, 12, 13, 14, 15
 
 
 class AcrobatError(RuntimeError):

@@ -983,23 +983,59 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int32_t T = s.n_levels - 1;  // recurrence steps; level T is the output batch
     TRY(reserve_splitk(ctx, stream));
-    // per direction, by position in the direction's step lists: row written | row of the previous
-    // step of that direction (step 0 gathers row 0 of the initial-state vector)
-    TRY(reserve_indices(ctx, 4 * (size_t)R, stream));
-    int32_t* st = ctx->h_stage;
-    for (int32_t k = 0; k < T; ++k) {
-      const int32_t f0 = s.fwd_off[k], nf = s.fwd_off[k + 1] - f0;
-      const int32_t* codes = s.level_codes.data() + s.level_off[k];
-      for (int32_t p = 0; p < nf; ++p) {
-        const int32_t rf = codes[p], rb = codes[nf + p] - R;
-        st[f0 + p] = rf;
-        st[(size_t)R + f0 + p] = k == 0 ? 0 : rf - 1;
-        st[2 * (size_t)R + f0 + p] = rb;
-        st[3 * (size_t)R + f0 + p] = k == 0 ? 0 : rb + 1;
+    // One launch for both recurrences where the shape allows it (see the LSTM forward call): the steps are the
+    // same batches, executed by workgroups that keep W_h on chip and synchronise among themselves.
+    const int32_t n_live = s.fwd_off[1];  // sequences with at least one token
+    const int32_t blocks_per_dir = (n_live + kRnnSlots - 1) / kRnnSlots;
+    const bool persistent = ctx->persistent && T >= 2 && (double)R * H * sizeof(float) < 4294967296.0 &&
+                            rnn_persistent_eligible(H, 2 * blocks_per_dir, nullptr);
+    const size_t n_slots = (size_t)blocks_per_dir * kRnnSlots;
+    if (persistent) {
+      TRY(reserve_sync(ctx, stream));
+      TRY(reserve_indices(ctx, 2 * n_slots, stream));
+      int32_t* st = ctx->h_stage;
+      // sequences by non-increasing length (ties by id), dealt round-robin to the blocks: every block gets the
+      // same mix of lengths and its live slots are a prefix at every step
+      std::vector<int32_t> first(T + 2, 0);  // first[l]: count, then rank of the first sequence of length l
+      for (int32_t q = 0; q < n_seq; ++q)
+        if (len[q] > 0) ++first[len[q]];
+      for (int32_t l = T, run = 0; l >= 1; --l) {
+        const int32_t cnt = first[l];
+        first[l] = run;
+        run += cnt;
       }
+      std::fill(st, st + 2 * n_slots, 0);
+      int32_t row0 = 0;
+      for (int32_t q = 0; q < n_seq; ++q) {
+        if (len[q] > 0) {
+          const int32_t r = first[len[q]]++;
+          const size_t slot = (size_t)(r % blocks_per_dir) * kRnnSlots + r / blocks_per_dir;
+          st[slot] = row0;
+          st[n_slots + slot] = len[q];
+        }
+        row0 += len[q];
+      }
+      TRY(upload_indices(ctx, 2 * n_slots, stream));
+      HIP_TRY(ctx, launch_fill_u32(ctx->d_sync, 0u, kRnnMaxBlocks * kPersistCounterStride, stream));
+    } else {
+      // per direction, by position in the direction's step lists: row written | row of the previous
+      // step of that direction (step 0 gathers row 0 of the initial-state vector)
+      TRY(reserve_indices(ctx, 4 * (size_t)R, stream));
+      int32_t* st = ctx->h_stage;
+      for (int32_t k = 0; k < T; ++k) {
+        const int32_t f0 = s.fwd_off[k], nf = s.fwd_off[k + 1] - f0;
+        const int32_t* codes = s.level_codes.data() + s.level_off[k];
+        for (int32_t p = 0; p < nf; ++p) {
+          const int32_t rf = codes[p], rb = codes[nf + p] - R;
+          st[f0 + p] = rf;
+          st[(size_t)R + f0 + p] = k == 0 ? 0 : rf - 1;
+          st[2 * (size_t)R + f0 + p] = rb;
+          st[3 * (size_t)R + f0 + p] = k == 0 ? 0 : rb + 1;
+        }
+      }
+      TRY(upload_indices(ctx, 4 * (size_t)R, stream));
     }
     TRY(reserve_scratch(ctx, 2 * (size_t)R * (size_t)H, stream));
-    TRY(upload_indices(ctx, 4 * (size_t)R, stream));
 
     // The two recurrences share nothing but x and never wait for each other: step k of both
     // directions goes out as ONE launch (workgroups of the forward batch, then of the backward
@@ -1022,7 +1058,21 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
                                           timer.ev));
       TRY(timer.end());
     }
-    for (int32_t k = 0; k < T; ++k) {
+    if (persistent) {
+      RnnPersistentArgs pa{};
+      pa.n_blocks = 2 * blocks_per_dir; pa.H = H;
+      pa.slot_row0 = ctx->d_idx; pa.slot_len = ctx->d_idx + n_slots;
+      for (int dir = 0; dir < 2; ++dir) {
+        pa.Wh[dir] = par[dir]->Wh; pa.xp[dir] = xp[dir]; pa.h_init[dir] = par[dir]->h_init; pa.h[dir] = hdir[dir];
+      }
+      pa.h_bytes = (uint32_t)((size_t)R * H * sizeof(float));
+      pa.counters = ctx->d_sync; pa.status = ctx->h_status_dev; pa.max_polls = ctx->max_polls;
+      TRY(timer.begin(ACROBAT_K_RNN_PERSISTENT, 0, 2 * R));
+      if (timer.tile()) *timer.tile() = 16;
+      HIP_TRY(ctx, launch_rnn_persistent(pa, stream, timer.ev));
+      TRY(timer.end());
+    }
+    for (int32_t k = 0; k < (persistent ? 0 : T); ++k) {
       const int32_t off = s.fwd_off[k], n = s.fwd_off[k + 1] - off;
       CellLevelArgs a[2] = {};
       for (int dir = 0; dir < 2; ++dir) {

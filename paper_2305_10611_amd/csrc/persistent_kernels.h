@@ -41,6 +41,30 @@ struct LstmPersistentArgs {
 bool lstm_persistent_eligible(int32_t H, int32_t n_blocks, const char** why);
 hipError_t launch_lstm_persistent(const LstmPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev = LaunchEvents());
 
+// The two recurrences of a bidirectional RNN (single gate: h_t = sigmoid(W_h h_prev + xp_t)) in one launch.
+// Sequences are dealt to blocks of 16 slots; block 2 i + dir runs direction dir (0 forward, 1 backward) of the
+// i-th group of sequences.  Workgroup (block, column block cb) keeps the 64 rows of that direction's W_h that
+// belong to hidden units 64 cb .. 64 cb + 63 in registers (wavefront w: units 64 cb + 16 w ..) and exchanges
+// h with the other H / 64 workgroups of its block after every step, exactly as the LSTM kernel does.
+constexpr int kRnnSlots = 16;
+constexpr int kRnnMaxBlocks = 32;
+struct RnnPersistentArgs {
+  int32_t n_blocks;          // blocks in use (even), 2 .. kRnnMaxBlocks
+  int32_t H;                 // hidden size (instantiated for 128, 256 and 512)
+  const int32_t* slot_row0;  // [n_blocks / 2 * 16] first row of the slot's sequence (both directions use the same slots)
+  const int32_t* slot_len;   // [n_blocks / 2 * 16] its length, non-increasing inside a block, 0 = empty slot
+  const float* Wh[2];        // [H, H] per direction
+  const float* xp[2];        // [rows, H] hoisted input transform (bias included)
+  const float* h_init[2];    // [H] state before the first step
+  float* h[2];               // [rows, H]; forward step t of a sequence writes row row0 + t, backward row0 + len - 1 - t
+  uint32_t h_bytes;          // size of one h array in bytes (< 2^32)
+  unsigned* counters;        // [kRnnMaxBlocks * kPersistCounterStride], zero at launch
+  unsigned* status;
+  int32_t max_polls;
+};
+bool rnn_persistent_eligible(int32_t H, int32_t n_blocks, const char** why);
+hipError_t launch_rnn_persistent(const RnnPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev = LaunchEvents());
+
 // Fills n uint32 with a value (a kernel, so that a captured graph holds no memset node).
 hipError_t launch_fill_u32(unsigned* p, unsigned value, int n, hipStream_t stream);
 

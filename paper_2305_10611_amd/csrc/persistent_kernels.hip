@@ -228,6 +228,112 @@ __global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const Lstm
   }
 }
 
+// ---- bidirectional RNN recurrence ------------------------------------------------------------------------
+// Workgroup (nb, cb) = (blockIdx % nbp, blockIdx / nbp), nbp = number of blocks rounded up to a multiple of 8,
+// so the workgroups of a block share an XCD.  Wavefront w holds the weight rows of units 64 cb + 16 w + (l % 16)
+// as the B operand (H / 4 registers per lane); the block's 16 previous-state rows are the A operand, staged
+// in LDS once per step.  Thread t finishes slot t / 16, units 64 cb + 4 (t % 16) .. + 3.
+template <int H>
+__global__ __launch_bounds__(kThreads, 1) void rnn_persistent_kernel(const RnnPersistentArgs a) {
+  constexpr int CB = H / 64;
+  constexpr int LD = H + 4;
+  constexpr int NIT = H / 16;
+  constexpr int PASSES = kRnnSlots * (H / 4) / kThreads;  // 16-byte pieces of the block's rows per thread
+  static_assert(kRnnSlots == 16 && kThreads == 256 && H % 64 == 0, "staging layout");
+  __shared__ __attribute__((aligned(16))) float hs[kRnnSlots * LD];
+  __shared__ __attribute__((aligned(16))) float zs[4][kRnnSlots][20];
+  __shared__ int s_row0[kRnnSlots], s_len[kRnnSlots];
+  __shared__ int s_go;
+
+  const int nbp = (a.n_blocks + 7) & ~7;
+  const int nb = blockIdx.x % nbp, cb = blockIdx.x / nbp;
+  if (nb >= a.n_blocks) return;
+  const int dir = nb & 1;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int col = lane & 15, kq = lane >> 4;
+
+  if (tid < kRnnSlots) {
+    s_row0[tid] = a.slot_row0[(nb >> 1) * kRnnSlots + tid];
+    s_len[tid] = a.slot_len[(nb >> 1) * kRnnSlots + tid];
+  }
+  for (int i = tid; i < kRnnSlots * LD; i += kThreads) hs[i] = 0.0f;  // rows of dead slots stay finite
+  floatx4 wreg[NIT];
+  {
+    const float* wrow = a.Wh[dir] + (size_t)(64 * cb + 16 * w + col) * H + 4 * kq;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) wreg[it] = *reinterpret_cast<const floatx4*>(wrow + 16 * it);
+  }
+  __syncthreads();
+
+  const int T = s_len[0];  // the block's longest sequence
+  const int my_slot = tid >> 4, u0 = 4 * (tid & 15);
+  const int my_len = s_len[my_slot];
+  const size_t my_row0 = (size_t)s_row0[my_slot];
+  unsigned* const counter = a.counters + nb * kPersistCounterStride;
+  const __amdgpu_buffer_rsrc_t h_rsrc = agent_buffer(a.h[dir], a.h_bytes);
+  const float* const xp = a.xp[dir];
+  const float* const h_init = a.h_init[dir];
+
+  for (int t = 0; t < T; ++t) {
+    const size_t my_row = dir ? my_row0 + (size_t)(my_len - 1 - t) : my_row0 + (size_t)t;
+    floatx4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (my_len > t) xv = *reinterpret_cast<const floatx4*>(xp + my_row * H + 64 * cb + u0);  // does not depend on h
+    const int live = __popcll(__ballot(lane < kRnnSlots && s_len[lane & 15] > t));
+    if (t > 0) {
+      if (tid == 0) s_go = wait_for(counter, (unsigned)(CB * t), a.status, a.max_polls) ? 1 : 0;
+      __syncthreads();
+      if (!s_go) break;
+    }
+    // previous state of the live slots -> LDS (the initial state at t = 0)
+    floatx4 stage[PASSES];
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int piece = p * kThreads + tid, row = piece / (H / 4), c4 = piece % (H / 4);
+      if (row < live) {
+        if (t == 0) {
+          stage[p] = *reinterpret_cast<const floatx4*>(h_init + 4 * c4);
+        } else {
+          const size_t prow = dir ? (size_t)s_row0[row] + (size_t)(s_len[row] - t) : (size_t)s_row0[row] + (size_t)(t - 1);
+          stage[p] = load_agent_f4(h_rsrc, (unsigned)((prow * H + 4 * c4) * sizeof(float)));
+        }
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int piece = p * kThreads + tid, row = piece / (H / 4), c4 = piece % (H / 4);
+      if (row < live) *reinterpret_cast<floatx4*>(&hs[row * LD + 4 * c4]) = stage[p];
+    }
+    __syncthreads();
+    const float* arow = &hs[col * LD + 4 * kq];
+    floatx4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const floatx4 f = *reinterpret_cast<const floatx4*>(arow + 16 * it);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[0], wreg[it][0], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[1], wreg[it][1], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[2], wreg[it][2], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[3], wreg[it][3], acc1, 0, 0, 0);
+    }
+    // z of (slot 4 kq + v, unit 16 w + col) -> LDS
+#pragma unroll
+    for (int v = 0; v < 4; ++v) zs[w][4 * kq + v][col] = acc0[v] + acc1[v];
+    __syncthreads();
+    if (my_len > t) {
+      const floatx4 z = *reinterpret_cast<const floatx4*>(&zs[u0 >> 4][my_slot][u0 & 15]);
+      agent_f4 hv;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) hv[e] = fast_sigmoid(z[e] + xv[e]);
+      // read by the other workgroups of the block at the next step: write-through store
+      store_agent_f4(h_rsrc, (unsigned)((my_row * H + 64 * cb + u0) * sizeof(float)), hv);
+    }
+    if (t + 1 < T) {
+      wait_stores_done();
+      __syncthreads();
+      if (tid == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // ---- probe ---------------------------------------------------------------------------------------------
 // style 0: arrival counter; release (fence + atomic add), acquire fence, plain payload loads - the textbook
 //          barrier; write_through only changes how the payload is stored.
@@ -323,7 +429,48 @@ bool resident_at_once(int n_workgroups) {
   return (long)per_cu * cus >= n_workgroups;
 }
 
+template <int H>
+bool rnn_resident_at_once(int n_workgroups) {
+  int dev = 0, per_cu = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return false;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return false;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, rnn_persistent_kernel<H>, kThreads, 0) != hipSuccess) return false;
+  return (long)per_cu * cus >= n_workgroups;
+}
+
+template <int H>
+hipError_t launch_rnn_h(const RnnPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev) {
+  const unsigned grid = (unsigned)(((a.n_blocks + 7) & ~7) * (H / 64));
+  launch_with_events((rnn_persistent_kernel<H>), dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, a);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+bool rnn_persistent_eligible(int32_t H, int32_t n_blocks, const char** why) {
+  const char* dummy;
+  if (!why) why = &dummy;
+  if (n_blocks < 2 || n_blocks > kRnnMaxBlocks || (n_blocks & 1)) { *why = "more blocks than one launch holds"; return false; }
+  const int nbp = (n_blocks + 7) & ~7;
+  bool ok = false;
+  switch (H) {
+    case 128: ok = rnn_resident_at_once<128>(nbp * 2); break;
+    case 256: ok = rnn_resident_at_once<256>(nbp * 4); break;
+    case 512: ok = rnn_resident_at_once<512>(nbp * 8); break;
+    default: *why = "hidden size not instantiated"; return false;
+  }
+  if (!ok) *why = "the workgroups would not all be resident at once";
+  return ok;
+}
+
+hipError_t launch_rnn_persistent(const RnnPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev) {
+  switch (a.H) {
+    case 128: return launch_rnn_h<128>(a, stream, ev);
+    case 256: return launch_rnn_h<256>(a, stream, ev);
+    case 512: return launch_rnn_h<512>(a, stream, ev);
+  }
+  return hipErrorInvalidValue;
+}
 
 bool lstm_persistent_eligible(int32_t H, int32_t n_blocks, const char** why) {
   const char* dummy;

@@ -501,6 +501,74 @@ def test_birnn_degenerate(ctx, P):
     assert rc == A.EINVAL
 
 
+@pytest.mark.parametrize("H,D,n_seq,lo,hi", [(128, 32, 5, 1, 9), (128, 64, 33, 0, 40), (256, 128, 256, 1, 30), (256, 64, 17, 2, 2),
+                                             (512, 64, 70, 0, 25), (512, 512, 64, 5, 35), (512, 32, 16, 40, 40)])
+def test_birnn_both_recurrences_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
+    """Shapes the persistent kernel takes (H in {128, 256, 512}, at most 256 non-empty sequences): one launch
+    for all steps of both directions, same schedule, same tolerances; and against one launch per step."""
+    import paper_2305_10611_amd as A
+    w = gen.birnn_workload(n_seq, lo, hi, H, D, 7, seed=5 * H + D + n_seq, bias_scale=0.3)
+    ctx.acrobat_set_profiling(True)
+    try:
+        g = P.run_birnn(ctx, w)
+        kinds = [r[0] for r in ctx.acrobat_last_profile() if r[0] != A.binding.K_SPLITK_REDUCE]
+    finally:
+        ctx.acrobat_set_profiling(False)
+    assert kinds == [A.binding.K_RNN_INPUT, A.binding.K_RNN_PERSISTENT, A.binding.K_RNN_OUTPUT]
+    assert ctx.acrobat_device_status() == A.OK
+    ref = oracle.birnn(w, nthreads=NT)
+    check_birnn(P, g, ref, "one launch")
+    g2 = P.run_birnn(ctx, w)  # again, without per-launch events: the counters are cleared by every call
+    assert all(np.array_equal(a, b) for a, b in zip(g, g2))
+    ctx.acrobat_set_persistent(False)
+    try:
+        ctx.acrobat_set_profiling(True)
+        g1 = P.run_birnn(ctx, w)
+        kinds = [r[0] for r in ctx.acrobat_last_profile()]
+    finally:
+        ctx.acrobat_set_profiling(False)
+        ctx.acrobat_set_persistent(True)
+    assert kinds.count(A.binding.K_RNN_STEP) == int(w["len"].max()) and A.binding.K_RNN_PERSISTENT not in kinds
+    check_birnn(P, g1, ref, "one launch per step")
+    for a, b, name in zip(g, g1, ("hf", "hb", "y")):
+        P.assert_close(a, b.astype(np.float64), name + ", one launch vs one launch per step", ref_floor=0.1 if name == "y" else 1e-30)
+
+
+def test_birnn_shapes_the_persistent_launch_does_not_take(ctx, P):
+    """257 non-empty sequences need more blocks than one launch holds, H = 64 is not instantiated, and a single
+    step needs no recurrence: one launch per step."""
+    import paper_2305_10611_amd as A
+    for n_seq, lo, hi, H in ((257, 1, 5, 128), (20, 1, 9, 64), (9, 1, 1, 128)):
+        w = gen.birnn_workload(n_seq, lo, hi, H, 32, 4, seed=n_seq + H, bias_scale=0.2)
+        ctx.acrobat_set_profiling(True)
+        try:
+            g = P.run_birnn(ctx, w)
+            kinds = [r[0] for r in ctx.acrobat_last_profile()]
+        finally:
+            ctx.acrobat_set_profiling(False)
+        assert A.binding.K_RNN_PERSISTENT not in kinds and A.binding.K_RNN_STEP in kinds
+        check_birnn(P, g, oracle.birnn(w, nthreads=NT))
+
+
+def test_birnn_persistent_wait_that_runs_out_ends_the_kernel_and_is_reported(P):
+    """As for the LSTM: with no polls allowed a workgroup that finds its block's previous step incomplete gives
+    up, the grid drains, the kernel ends normally and the status is reported once."""
+    import paper_2305_10611_amd as A
+    w = gen.birnn_workload(200, 20, 30, 512, 64, 5, seed=73, bias_scale=0.2)
+    c = A.Context(0)
+    try:
+        assert c.acrobat_set_persistent(True, 0) == A.OK
+        P.run_birnn(c, w)  # synchronises
+        assert c.acrobat_device_status() == A.ETIMEOUT and "gave up waiting" in c.acrobat_last_error()
+        assert c.acrobat_device_status() == A.OK  # reported once
+        assert c.acrobat_set_persistent(True, -1) == A.OK
+        g = P.run_birnn(c, w)
+        assert c.acrobat_device_status() == A.OK
+        check_birnn(P, g, oracle.birnn(w, nthreads=NT))
+    finally:
+        c.close()
+
+
 # ---------------------------------------------------------------- profiling mode
 def test_profiling_records_every_launch(ctx, P):
     w = make_config(0)

@@ -741,8 +741,11 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
   const int tid = threadIdx.x, lane = tid & 63, wk = tid >> 6;
   const int H = a.H, n = a.n;
   const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
-  const int n_jt = (hlim + JW - 1) / JW;
-  const int jt = bid % n_jt, mt = bid / n_jt;
+  // the launcher pads the number of unit tiles to a multiple of 8: every node tile of a unit tile then runs on the
+  // same XCD (workgroup id % 8) and finds that tile's weight rows in its L2 instead of fetching them again
+  const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = (n_jt + 7) & ~7;
+  const int jt = bid % n_jt_padded, mt = bid / n_jt_padded;
+  if (jt >= n_jt) return;
   const int j0 = jt * JW, m0 = mt * 32;
 
   const int lrow = tid >> 3, lpart = (tid & 7) * 4;
@@ -1129,9 +1132,15 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
 }
 
 template <int G>
+long tiny_live_workgroups(const CellLevelArgs& a, bool relu_out) {  // workgroups of tiny_grid that have a tile
+  const int hlim = relu_out ? a.n_cols : a.H;
+  return (long)((a.n + 31) / 32) * ((hlim + tiny_jw<G>() - 1) / tiny_jw<G>());
+}
+
+template <int G>
 unsigned tiny_grid(const CellLevelArgs& a, bool relu_out) {
   const int hlim = relu_out ? a.n_cols : a.H;
-  return (unsigned)((long)((a.n + 31) / 32) * ((hlim + tiny_jw<G>() - 1) / tiny_jw<G>()));
+  return (unsigned)((long)((a.n + 31) / 32) * (((hlim + tiny_jw<G>() - 1) / tiny_jw<G>() + 7) & ~7));
 }
 
 // `b` (may be null) is a second, independent batch for the same launch.
@@ -1164,7 +1173,8 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
     const unsigned g0 = tiny_grid<G>(a, EPI == EPI_RELU_OUT), g1 = b ? tiny_grid<G>(*b, EPI == EPI_RELU_OUT) : 0;
     pr.split = (int32_t)g0;
     // 8 slabs per step need 128 KB of LDS, one workgroup per compute unit: only while all fit at once
-    const int u = sh.ksplit ? sh.ksplit : (g0 + g1 <= 256 ? 8 : 4);
+    const long live = tiny_live_workgroups<G>(a, EPI == EPI_RELU_OUT) + (b ? tiny_live_workgroups<G>(*b, EPI == EPI_RELU_OUT) : 0);
+    const int u = sh.ksplit ? sh.ksplit : (live <= 256 ? 8 : 4);
     if (ksplit) *ksplit = 1;
     return u == 8 ? launch_tiny<G, EPI, 8>(pr, g0 + g1, stream, ev) : launch_tiny<G, EPI, 4>(pr, g0 + g1, stream, ev);
   }

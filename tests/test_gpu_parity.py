@@ -690,6 +690,58 @@ def test_forward_recorded_into_a_graph_replays_the_eager_result():
         ctx.close(); ctx2.close()
 
 
+def test_persistent_recurrences_recorded_into_a_graph_replay_the_eager_result():
+    """The one-launch recurrences (LSTM, BiRNN) clear their arrival counters with a kernel, not a memset, so a
+    captured call can be replayed: every replay, with eager work on another context in between, gives the eager
+    result bit for bit.  (The MV-RNN dataflow launch is not captured: a captured call keeps one launch per level.)"""
+    import torch
+    import paper_2305_10611_amd as A
+    from tests import parity as P
+    w = gen.lstm_workload(40, 1, 12, 128, 64, seed=91, bias_scale=0.2)
+    b = gen.birnn_workload(30, 1, 10, 128, 64, 6, seed=92, bias_scale=0.2)
+    other = gen.treelstm_workload(9, 1, 12, 64, 50, "uniform", seed=45)
+    ctx, ctx2 = A.Context(0), A.Context(0)
+    try:
+        h_ref, c_ref = P.run_lstm(ctx, w)  # also sizes the context's buffers
+        R, H = int(np.sum(w["len"])), int(w["H"])
+        t = {k: P.dev(w[k]) for k in ("x", "Wx", "Wh", "b")}
+        h, c = P.nan_filled(R, H), P.nan_filled(R, H)
+        s = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s, capture_error_mode="relaxed"):
+            rc = ctx.acrobat_varlen_lstm_forward(w["len"], H, int(w["D"]), t["x"], t["Wx"], t["Wh"], t["b"], h, c, s.cuda_stream)
+        assert rc == A.OK, ctx.acrobat_last_error()
+        for _ in range(3):
+            h.fill_(float("nan")); c.fill_(float("nan"))
+            P.run_treelstm(ctx2, other)
+            g.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(h.cpu().numpy(), h_ref) and np.array_equal(c.cpu().numpy(), c_ref)
+        assert ctx.acrobat_device_status() == A.OK
+
+        ref = P.run_birnn(ctx, b)
+        Rb, Hb, n_out = int(np.sum(b["len"])), int(b["H"]), int(b["n_out"])
+        names = ("x", "fWx", "fWh", "fb", "finit", "bWx", "bWh", "bb", "binit", "C", "cb")
+        tb = {k: P.dev(np.asarray(b[k], np.float32)) for k in names}
+        hf, hb, y = P.nan_filled(Rb, Hb), P.nan_filled(Rb, Hb), P.nan_filled(Rb, n_out)
+        g2 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g2, stream=s, capture_error_mode="relaxed"):
+            rc = ctx.acrobat_birnn_forward(b["len"], Hb, int(b["D"]), n_out, tb["x"], (tb["fWx"], tb["fWh"], tb["fb"], tb["finit"]),
+                                           (tb["bWx"], tb["bWh"], tb["bb"], tb["binit"]), tb["C"], tb["cb"], hf, hb, y, s.cuda_stream)
+        assert rc == A.OK, ctx.acrobat_last_error()
+        for _ in range(3):
+            for o in (hf, hb, y):
+                o.fill_(float("nan"))
+            P.run_treelstm(ctx2, other)
+            g2.replay()
+            torch.cuda.synchronize()
+            assert all(np.array_equal(o.cpu().numpy(), r) for o, r in zip((hf, hb, y), ref))
+        assert ctx.acrobat_device_status() == A.OK
+    finally:
+        ctx.close(); ctx2.close()
+
+
 # ---------------------------------------------------------------- generic dataflow-graph runtime
 def treelstm_ops(g, B, t, w, h, c, N):
     H, D, V = int(w["H"]), int(w["D"]), int(w["V"])

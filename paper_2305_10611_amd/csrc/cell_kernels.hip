@@ -596,7 +596,8 @@ __global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamK
   // all of this fits 32 bits: the host admits at most 8192 tiles and 512 workgroups, and a k range of 2^16 slabs
   // would be a contraction over two million columns
   const int n_slabs = a.nseg * (a.kseg / kBK);
-  const int tiles = ((a.n + L::BM - 1) / L::BM) * n_jt;
+  const int n_mt = (a.n + L::BM - 1) / L::BM;
+  const int tiles = n_mt * n_jt;
   const unsigned U = (unsigned)tiles * (unsigned)n_slabs, P = (unsigned)sk.n_wg;
   auto start_of = [&](unsigned p) { return (unsigned)((unsigned long long)p * U / P); };               // first unit of workgroup p
   auto owner_of = [&](unsigned x) { return (unsigned)(((unsigned long long)(x + 1) * P - 1) / U); };  // whose share holds unit x
@@ -607,7 +608,12 @@ __global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamK
   };
   auto quad_off = [&](int g, int qi) { return (unsigned)((((g * 4 + wk * QPW + qi) * 64) + lane) * 4 * sizeof(float)); };
   const __amdgpu_buffer_rsrc_t ws_rsrc = agent_buffer(sk.partial, sk.partial_bytes);
-  const unsigned p = blockIdx.x;
+  // XCD-aware placement (workgroup id % 8 is the XCD): the shares of one XCD are contiguous, and with the node
+  // tile as the fastest index of a tile number an XCD's range of tiles is all node tiles of an eighth of the unit
+  // tiles - it keeps that eighth of the weight rows in its L2, and the pieces of a tile are parked and read back
+  // within one XCD.  (Any bijection would do for correctness; P is a multiple of 8 whenever it is the number of
+  // compute units.)
+  const unsigned p = (P & 7) == 0 ? (blockIdx.x & 7) * (P >> 3) + (blockIdx.x >> 3) : blockIdx.x;
   const unsigned u1 = start_of(p + 1);
   bool first = true;
   for (unsigned u = start_of(p); u < u1; first = false) {
@@ -615,7 +621,7 @@ __global__ __launch_bounds__(kThreads, 1) void cell_streamk_kernel(const StreamK
     const int s0 = (int)(u - (unsigned)tile * n_slabs);
     const int cnt = (n_slabs - s0 < (int)(u1 - u)) ? n_slabs - s0 : (int)(u1 - u);
     u += cnt;
-    const int jt = tile % n_jt, mt = tile / n_jt;
+    const int mt = tile % n_mt, jt = tile / n_mt;
     const int j0 = jt * 32, m0 = mt * L::BM;
     if (!first) __syncthreads();  // the previous tile's epilogue is through with the index table and the slabs
     float own[G][L::NV];

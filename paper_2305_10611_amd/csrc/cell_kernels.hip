@@ -1205,8 +1205,11 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
   }
   const int n_jt = a.H / 32;
   const long n_mt = (a.n + sh.bm - 1) / sh.bm;
-  // an unsplit single batch of at least two node tiles runs in the XCD-aware order (kernel argument 0)
-  const bool xcd_order = !b && sh.ksplit == 1 && n_jt % 4 == 0 && n_mt >= 2 && ws.force_bm == 0;
+  // An unsplit single batch runs in the XCD-aware order (kernel argument 0) where that saves bytes: every XCD
+  // then fetches a quarter of the weights and half of the node rows (2 W + 4 A in all) instead of an eighth and
+  // all of them (W + 8 A), which is less once the node rows outweigh a quarter of the weights.
+  const double a_bytes = (double)a.n * a.nseg * a.kseg, w_bytes = (double)G * a.H * a.nseg * a.kseg;
+  const bool xcd_order = !b && sh.ksplit == 1 && n_jt % 4 == 0 && n_mt >= 2 && ws.force_bm == 0 && 4.0 * a_bytes > w_bytes;
   const unsigned g0 = xcd_order ? (unsigned)(2 * n_jt * ((n_mt + 1) / 2)) : (unsigned)(n_mt * n_jt * sh.ksplit);
   const unsigned g1 = b ? (unsigned)((long)((b->n + sh.bm - 1) / sh.bm) * (b->H / 32)) : 0;
   pr.split = (int32_t)g0;

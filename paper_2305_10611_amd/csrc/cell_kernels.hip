@@ -51,6 +51,12 @@ constexpr int kBK = 32;        // k columns per slab
 constexpr int kThreads = 256;
 constexpr int kBlockFloats = 16 * 64;  // one 32x32 accumulator block of one wavefront
 
+// The kernels for small levels number their workgroups (node tile, unit tile) with the unit tile fastest and pad
+// the number of unit tiles to a multiple of 8: workgroup ids go round-robin to the 8 XCDs, so every node tile of a
+// unit tile then runs on the same XCD and finds that tile's weight rows in its L2.  With fewer than 8 unit tiles
+// the padding would leave XCDs empty, so there is none.
+__host__ __device__ constexpr int padded_unit_tiles(int n_jt) { return n_jt >= 8 ? (n_jt + 7) & ~7 : n_jt; }
+
 __device__ __forceinline__ float fast_sigmoid(float x) {
   return __builtin_amdgcn_rcpf(1.0f + __expf(-x));  // exp -> inf gives 0, exp -> 0 gives 1
 }
@@ -749,7 +755,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
   const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
   // the launcher pads the number of unit tiles to a multiple of 8: every node tile of a unit tile then runs on the
   // same XCD (workgroup id % 8) and finds that tile's weight rows in its L2 instead of fetching them again
-  const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = (n_jt + 7) & ~7;
+  const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = padded_unit_tiles(n_jt);
   const int jt = bid % n_jt_padded, mt = bid / n_jt_padded;
   if (jt >= n_jt) return;
   const int j0 = jt * JW, m0 = mt * 32;
@@ -953,7 +959,7 @@ __global__ __launch_bounds__(kThreads, 3) void cell_direct_kernel(const CellLeve
   const int li = lane & 15, kq = lane >> 4;
   const int H = a.H, n = a.n;
   const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
-  const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = (n_jt + 7) & ~7;
+  const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = padded_unit_tiles(n_jt);
   const int jt = bid % n_jt_padded, mt = bid / n_jt_padded;
   if (jt >= n_jt) return;  // padding of the grid
   const int j0 = jt * JW, m0 = mt * 16;
@@ -1038,7 +1044,7 @@ template <int G>
 unsigned direct_grid(const CellLevelArgs& a, bool relu_out) {
   const int hlim = relu_out ? a.n_cols : a.H;
   const int n_jt = (hlim + direct_jw<G>() - 1) / direct_jw<G>();
-  return (unsigned)((long)((a.n + 15) / 16) * ((n_jt + 7) & ~7));
+  return (unsigned)((long)((a.n + 15) / 16) * padded_unit_tiles(n_jt));
 }
 
 struct Shape {
@@ -1092,18 +1098,23 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //    and reads ksplit partial tiles);
   //  * slightly more tiles than compute units: split in two for balance.
   //  * latency-bound levels (n x K up to about 256 000) run cell_tiny_kernel: one launch, no k split;
-  if ((long)a.n * n_slabs * kBK <= 256000) {
-    //  * of those, the smallest go to cell_direct_kernel (no steps at all, but every workgroup pulls its 16 node
-    //    rows and 16 weight rows through the L2 on its own): while all its workgroups are resident at once and
-    //    together request at most 24 MiB.  Measured against the stepwise kernel: five-gate tree level, K = 1024,
-    //    up to 16 nodes 5.6-6.8 instead of 9.6-10.0 us (36 nodes: 13.5 instead of 10.4); K = 512, up to 64 nodes
-    //    4.5-6.7 instead of 6.6-7.1 (88 nodes: 8.7 instead of 7.1); LSTM step, K = 512, up to 30 rows 5.2
-    //    instead of 6.8; single-gate recurrent step, K = 256, 128 rows 4.4 instead of 6.9.
-    const long wgs = (long)((a.n + 15) / 16) * (((a.H + direct_jw<G>() - 1) / direct_jw<G>() + 7) & ~7);
-    const long rows = wgs * (G * direct_jw<G>()) + (long)(wgs / ((a.n + 15) / 16)) * a.n;  // weight rows + node rows requested
-    if (ws.n_cu > 0 && wgs <= 2L * ws.n_cu && rows * n_slabs * kBK * (long)sizeof(float) <= (24L << 20)) return Shape{16, 1};
-    return Shape{6, 0};
-  }
+  //  * cell_direct_kernel (no steps at all, but every workgroup pulls its 16 node rows and 16 weight rows through
+  //    the L2 on its own) while all its workgroups are resident at once and together request at most 24 MiB.
+  //    Measured against the stepwise kernel: five-gate tree level, K = 1024, up to 16 nodes 5.6-6.8 instead of
+  //    9.6-10.0 us (36 nodes: 13.5 instead of 10.4); K = 512, up to 64 nodes 4.5-6.7 instead of 6.6-7.1 (88 nodes:
+  //    8.7 instead of 7.1); LSTM step, K = 512, up to 30 rows 5.2 instead of 6.8; single-gate recurrent step,
+  //    K = 256, 128 rows 4.4 instead of 6.9.
+  const int hlim = a.n_cols > 0 ? a.n_cols : a.H;
+  const long direct_jt = (hlim + direct_jw<G>() - 1) / direct_jw<G>(), direct_mt = (a.n + 15) / 16;
+  const long direct_wgs = direct_mt * direct_jt;                                      // those that have a tile
+  const long direct_rows = direct_wgs * (G * direct_jw<G>()) + direct_jt * (long)a.n;  // weight rows + node rows requested
+  const bool direct_ok = ws.n_cu > 0 && direct_wgs <= 2L * ws.n_cu &&
+                         direct_rows * n_slabs * kBK * (long)sizeof(float) <= (24L << 20);
+  if ((long)a.n * n_slabs * kBK <= 256000) return direct_ok ? Shape{16, 1} : Shape{6, 0};
+  //  * a narrow output layer (at most 8 unit tiles of the direct kernel, e.g. 16 output units) gives the tiled
+  //    kernels one unit tile, i.e. few workgroups however many rows it has: 1 299 rows x 16 units, K = 1024,
+  //    9.3 us as 21 tiles split eight ways plus the reduction launch;
+  if (direct_ok && direct_jt <= 8) return Shape{16, 1};
   //  * levels whose 32-node tiles all fit the chip at once (one workgroup per compute unit) run them
   //    unsplit: 29-30 us at 286 / 399 nodes against 32-33 us for 64-node tiles split in two;
   const long tiles32 = (long)((a.n + 31) / 32) * n_jt;
@@ -1132,7 +1143,9 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //    workgroup, or the level runs unsplit (single-gate RNN steps, narrow LSTMs).
   const double wg_kb = (double)(32 * G + best.bm) * n_slabs * kBK * sizeof(float) / 1024.0;
   if (s > 1 && wg_kb * (1.0 - 1.0 / s) < 4.4 * 50.0) s = 1;
-  if (s == 1 && tiles > 256 && tiles <= 384 && n_slabs % 2 == 0 && n_slabs >= 8) s = 2;
+  //    (only where two workgroups fill a compute unit: single-gate tiles fit five to a unit and run such a level
+  //    unsplit in one round - 22 instead of 38 us for the two input projections of 1 299 rows, H = 512)
+  if (s == 1 && G >= 3 && tiles > 256 && tiles <= 384 && n_slabs % 2 == 0 && n_slabs >= 8) s = 2;
   if (fits(best.bm, s)) best.ksplit = s;
   return best;
 }
@@ -1146,7 +1159,7 @@ long tiny_live_workgroups(const CellLevelArgs& a, bool relu_out) {  // workgroup
 template <int G>
 unsigned tiny_grid(const CellLevelArgs& a, bool relu_out) {
   const int hlim = relu_out ? a.n_cols : a.H;
-  return (unsigned)((long)((a.n + 31) / 32) * (((hlim + tiny_jw<G>() - 1) / tiny_jw<G>() + 7) & ~7));
+  return (unsigned)((long)((a.n + 31) / 32) * padded_unit_tiles((hlim + tiny_jw<G>() - 1) / tiny_jw<G>()));
 }
 
 // `b` (may be null) is a second, independent batch for the same launch.

@@ -753,7 +753,7 @@ __global__ __launch_bounds__(kThreads) void cell_tiny_kernel(const CellLevelPair
   const int tid = threadIdx.x, lane = tid & 63, wk = tid >> 6;
   const int H = a.H, n = a.n;
   const int hlim = EPI == EPI_RELU_OUT ? a.n_cols : H;  // hidden units that exist
-  // the launcher pads the number of unit tiles to a multiple of 8: every node tile of a unit tile then runs on the
+  // the launcher pads the number of unit tiles (padded_unit_tiles): every node tile of a unit tile then runs on the
   // same XCD (workgroup id % 8) and finds that tile's weight rows in its L2 instead of fetching them again
   const int n_jt = (hlim + JW - 1) / JW, n_jt_padded = padded_unit_tiles(n_jt);
   const int jt = bid % n_jt_padded, mt = bid / n_jt_padded;
@@ -940,7 +940,7 @@ hipError_t launch_tiny(const CellLevelPair& pr, unsigned grid, hipStream_t strea
 // operands).  The only dependent chain left is index -> rows -> matrix instructions -> four-way sum through
 // LDS -> gate arithmetic, and the gathered operands of the gate arithmetic are requested right behind the
 // rows.  Column c of a workgroup is gate c / JW of unit j0 + c % JW.  The launcher pads the number of unit
-// tiles to a multiple of 8 so that all node tiles of a unit tile run on the same XCD and find its weight
+// tiles (padded_unit_tiles) so that all node tiles of a unit tile run on the same XCD and find its weight
 // rows in that XCD's L2.
 template <int G>
 constexpr int direct_jw() { return 16 / G; }
@@ -1199,7 +1199,7 @@ hipError_t launch_shape(const CellLevelArgs& a, const CellLevelArgs* b, hipStrea
   }
   if (sh.bm == 16) {
     const unsigned g0 = direct_grid<G>(a, EPI == EPI_RELU_OUT), g1 = b ? direct_grid<G>(*b, EPI == EPI_RELU_OUT) : 0;
-    pr.split = (int32_t)g0;  // a multiple of 8: the second batch keeps the unit tile -> XCD assignment
+    pr.split = (int32_t)g0;  // (a multiple of 8 where the unit tiles are padded: the second batch keeps its XCD assignment)
     launch_with_events((cell_direct_kernel<G, EPI>), dim3(g0 + g1), dim3(kThreads), 0, stream, ev.start, ev.stop, pr);
     return hipGetLastError();
   }

@@ -176,7 +176,9 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
  * above).  The batches are the same - step t over the sequences with len > t - and so is the schedule
  * that acrobat_last_schedule reports; the workgroups keep W_h on chip for all steps and synchronise
  * among themselves through arrival counters in device memory.  Every wait inside that kernel is bounded
- * by max_polls polls of a counter (max_polls < 0: the default, about a quarter of a million): a
+ * by max_polls polls of a counter (max_polls < 0: the default, about a quarter of a million; max_polls == 0 is a
+ * test hook: every wait gives up at once, whether or not it would have had to wait, so the error path below runs
+ * deterministically): a
  * workgroup whose wait runs out raises a status word (in pinned host memory; nothing touches it otherwise),
  * all workgroups then leave at their next polls and the kernel ends normally with incomplete outputs.
  * acrobat_device_status reports that: call it once the stream has been synchronised; it returns ACROBAT_OK

@@ -141,7 +141,11 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
       if (tid == 0) {
         int polls = 0;
         bool ok = true;
-        while (!children_done(cur_raw)) {
+        if (a.max_polls == 0) {  // test hook: every wait gives up at once, whether or not it would have had to wait
+          raise_status(a.status);
+          ok = false;
+        }
+        while (ok && !children_done(cur_raw)) {
           if (++polls > a.max_polls) {
             raise_status(a.status);
             ok = false;

@@ -43,6 +43,10 @@ __device__ __forceinline__ float fast_tanh(float x) { return 1.0f - 2.0f * __bui
 // lane i < n watches word i.  All 64 lanes take part (uniform control flow); returns false as wait_for does.
 __device__ __forceinline__ bool wait_for_flags(const unsigned* line, int n, unsigned target, unsigned* status, int max_polls) {
   const int lane = threadIdx.x & 63;
+  if (max_polls == 0) {  // test hook, as in wait_for
+    if (lane == 0) raise_status(status);
+    return false;
+  }
   int polls = 0;
   while (true) {
     const unsigned v = lane < n ? load_agent(line + lane) : target;
@@ -59,6 +63,10 @@ __device__ __forceinline__ bool wait_for_flags(const unsigned* line, int n, unsi
 // Thread 0 of a workgroup waits until *counter >= target.  Returns false when the wait ran out or another
 // workgroup has raised the status word; the caller then leaves its loop.
 __device__ __forceinline__ bool wait_for(const unsigned* counter, unsigned target, unsigned* status, int max_polls) {
+  if (max_polls == 0) {  // test hook: every wait gives up at once, whether or not it would have had to wait
+    raise_status(status);
+    return false;
+  }
   int polls = 0;
   while (load_agent(counter) < target) {
     if (++polls > max_polls) {

@@ -757,13 +757,15 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
     // 0.54 vs 0.49 ms - its flag checks and write-through stores buy nothing where levels are bandwidth bound.)
     int32_t widest = 0;
     for (int32_t lv = 1; lv < s.n_levels; ++lv) widest = std::max(widest, s.level_off[lv + 1] - s.level_off[lv]);
-    const int df_wgs = ctx->persistent && ctx->mvrnn_variant == 0 && s.n_levels > 2 && widest <= 2048 &&
+    const int32_t widest_limit = d == 64 ? 2048 : 512;  // (a d = 128 node is four times the bytes)
+    const size_t flag_words = (size_t)N * (d == 64 ? 1 : 4);
+    const int df_wgs = ctx->persistent && ctx->mvrnn_variant == 0 && s.n_levels > 2 && widest <= widest_limit &&
                                !stream_is_capturing(stream)
                            ? mvrnn_dataflow_workgroups(d, n_internal) : 0;
     if (df_wgs > 0) {
       TRY(reserve_sync(ctx, stream));
-      if ((size_t)N > ctx->node_flags_cap) {
-        const size_t cap = (size_t)N + (size_t)N / 2 + 1024;
+      if (flag_words > ctx->node_flags_cap) {
+        const size_t cap = flag_words + flag_words / 2 + 1024;
         if (ctx->d_node_flags) HIP_TRY(ctx, hipFree(ctx->d_node_flags));
         ctx->d_node_flags = nullptr;
         ctx->node_flags_cap = 0;

@@ -29,6 +29,13 @@ __device__ __forceinline__ agent_f4 load_agent_f4(__amdgpu_buffer_rsrc_t rsrc, u
 __device__ __forceinline__ void store_agent_f4(__amdgpu_buffer_rsrc_t rsrc, unsigned byte_off, agent_f4 v) {
   __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(agent_u4, v), rsrc, (int)byte_off, 0, kAuxAgentScope);
 }
+// 8-byte load at (resource base + per-lane byte offset + wave-uniform byte offset): the uniform part travels in a
+// scalar register, so a ring of such loads in flight needs no address registers of its own
+typedef float agent_f2 __attribute__((ext_vector_type(2)));
+typedef unsigned agent_u2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ agent_f2 load_agent_f2_at(__amdgpu_buffer_rsrc_t rsrc, unsigned lane_off, unsigned uniform_off) {
+  return __builtin_bit_cast(agent_f2, __builtin_amdgcn_raw_buffer_load_b64(rsrc, (int)lane_off, (int)uniform_off, kAuxAgentScope));
+}
 __device__ __forceinline__ unsigned load_agent(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }

@@ -31,6 +31,8 @@
 
 #include "agent_access.h"
 
+#include <algorithm>
+
 namespace acrobat {
 namespace {
 
@@ -518,6 +520,12 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void mvrnn_stream_kernel(cons
 //    across node boundaries;
 //  * the workgroups of one node are 8 ids apart, 8 consecutive ids being spread over the 8 XCDs:
 //    the four readers of a child matrix share one L2.
+//
+// DF (dataflow): one launch for all internal levels, as mvrnn_level_kernel<true> does for d = 64.  A node has four
+// flag words here, one per workgroup (row quarter) that writes a part of its state; the four workgroups of the
+// parent each wait for all eight words of the two children.  The ring only runs on into the next node when a
+// wavefront finds that node's children complete at that point; otherwise it is refilled after the wait.
+template <bool DF>
 __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs a) {
   constexpr int D = 128, DD = D * D;
   constexpr int S = 64;            // two-row steps over one child matrix
@@ -527,6 +535,7 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
   __shared__ float s_vp[2][2 * D];        // [column half of the writer][B a | A b], partial sums
   __shared__ float s_red[2][2][16 * 64];  // [column half][k half of the writer][8 rows x even/odd x lane]
   __shared__ __attribute__((aligned(16))) float s_W[RB * WLD];
+  __shared__ int s_go;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // (uniform: base addresses stay in scalar registers)
@@ -558,10 +567,54 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
     return n;
   };
   floatx2 ring[RING];
+  // DF: a child may have been written by another workgroup of this launch: agent-scope loads, through a buffer
+  // resource over the child's matrix (its base is wave-uniform) so that the step offset is a scalar
+  const unsigned lane_off = (unsigned)((lhi * D + 64 * ch + 2 * lcol) * sizeof(float));
   auto load_step = [&](const NodeRef& n, int s, int k) {  // s, k: compile-time at every call site
-    ring[k] = *reinterpret_cast<const floatx2*>(n.mat + (size_t)(2 * s + lhi) * D + 64 * ch + 2 * lcol);
+    if constexpr (DF) {
+      const floatx2 v = load_agent_f2_at(agent_buffer(n.mat, DD * sizeof(float)), lane_off, (unsigned)(2 * s * D * sizeof(float)));
+      ring[k] = v;
+    } else {
+      ring[k] = *reinterpret_cast<const floatx2*>(n.mat + (size_t)(2 * s + lhi) * D + 64 * ch + 2 * lcol);
+    }
   };
-  auto load_vec = [&](const NodeRef& n) { return *reinterpret_cast<const floatx2*>(n.vec + 64 * ch + 2 * lcol); };
+  auto load_vec = [&](const NodeRef& n) {
+    if constexpr (DF) return load_agent_f2(n.vec + 64 * ch + 2 * lcol);
+    else return *reinterpret_cast<const floatx2*>(n.vec + 64 * ch + 2 * lcol);
+  };
+  // DF: have all four parts of both children been announced?  (leaves are table rows: always)
+  auto children_done = [&](const RawIdx& i) {
+    bool ok = true;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (i.ls >= 0) ok = ok && load_agent(a.flags + 4 * (size_t)i.ls + q) == a.epoch;
+      if (i.rs >= 0) ok = ok && load_agent(a.flags + 4 * (size_t)i.rs + q) == a.epoch;
+    }
+    return ok;
+  };
+  // DF: thread 0 waits, bounded, for the children of the node; false = a wait ran out here or elsewhere: drain
+  auto wait_children = [&](const RawIdx& i) {
+    if (tid == 0) {
+      int polls = 0;
+      bool ok = true;
+      if (a.max_polls == 0) {  // test hook: every wait gives up at once
+        raise_status(a.status);
+        ok = false;
+      }
+      while (ok && !children_done(i)) {
+        if (++polls > a.max_polls) {
+          raise_status(a.status);
+          ok = false;
+          break;
+        }
+        if ((polls & 255) == 0 && status_raised(a.status)) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      s_go = ok ? 1 : 0;
+    }
+    __syncthreads();
+    return s_go != 0;
+  };
 
   // indices first (they head the dependent chain), then the weight rows as coalesced 16-byte loads
   RawIdx raw = load_idx(slot);
@@ -579,10 +632,15 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
     wst[k] = *reinterpret_cast<const floatx4*>(a.W + (size_t)(RB * r + (i >> 6)) * (2 * D) + (i & 63) * 4);
   }
   NodeRef cur = resolve(raw);
+  RawIdx cur_raw = raw;  // DF: the children the current node waits for
   raw = raw_next;
+  bool have = !DF;       // DF: whether this wavefront has already requested the current node's first ring of rows
+  floatx2 vv;
+  if constexpr (!DF) {
 #pragma unroll
-  for (int s = 0; s < RING; ++s) load_step(cur, s, s);
-  floatx2 vv = load_vec(cur);
+    for (int s = 0; s < RING; ++s) load_step(cur, s, s);
+    vv = load_vec(cur);
+  }
 
   // W_M's rows pass through the LDS buffer of W: each wavefront picks its operand registers
   // (row 32 r + lcol, columns 128 kh + 2 s + lhi), then W's rows take the buffer over
@@ -604,10 +662,20 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
 
   const int pr = tid >> 3, pq = tid & 7;  // p = tanh(W v): output row of this workgroup, eighth of the columns
   while (true) {
+    if constexpr (DF) {
+      if (!wait_children(cur_raw)) return;
+      if (!have) {
+#pragma unroll
+        for (int s = 0; s < RING; ++s) load_step(cur, s, s);
+        vv = load_vec(cur);
+      }
+    }
     // (opaque to the optimiser: nothing derived from these indices may be computed, and so waited
     // for, before this point - they were requested a whole node ago)
     asm volatile("" : "+v"(raw.ls), "+v"(raw.rs), "+v"(raw.orow));
     const NodeRef nxt = resolve(raw);
+    const RawIdx nxt_raw = raw;
+    bool pre = true;  // DF: run the ring on into the next node?
     // (past the end the last node is read again: harmless, and the loop body stays free of branches)
     raw = load_idx(min(slot + 2 * nslots, a.n - 1));
 
@@ -616,8 +684,8 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
     for (int q = 0; q < 16; ++q) acc_e[q] = acc_o[q] = 0.0f;
     float vp[16];
     floatx2 vv_next;
-#pragma unroll
-    for (int s = 0; s < S; ++s) {
+    // one two-row step: two matrix instructions and the step's share of (child matrix) x (other child's vector)
+    auto consume = [&](int s) {  // s: compile-time at every call site (the loops below are fully unrolled)
       const floatx2 x = ring[s % RING];
       acc_e = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], x[0], acc_e, 0, 0, 0);
       acc_o = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], x[1], acc_o, 0, 0, 0);
@@ -642,10 +710,21 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
         vp[0] += __shfl_xor(vp[0], 1);
         if ((lcol & 1) == 0) s_vp[ch][(kh ? 0 : D) + 2 * (16 * (s / 16) + (lcol >> 1)) + lhi] = vp[0];
       }
-      // the slot just consumed takes the step 32 ahead (of the next node from the middle on)
-      if (s + RING < S) load_step(cur, s + RING, s % RING);
-      else load_step(nxt, s + RING - S, s % RING);
-      if (s == S - RING) vv_next = load_vec(nxt);
+    };
+    // first half: the slot just consumed takes the step 32 ahead, still of this node
+#pragma unroll
+    for (int s = 0; s < S - RING; ++s) {
+      consume(s);
+      load_step(cur, s + RING, s % RING);
+    }
+    // second half: the ring runs on into the next node.  DF: only if this wavefront finds that node's children
+    // complete now (a wavefront-uniform decision; past the end of the list there is no next node)
+    if constexpr (DF) pre = slot + nslots < a.n && __all(children_done(nxt_raw));
+    if (pre) vv_next = load_vec(nxt);
+#pragma unroll
+    for (int s = S - RING; s < S; ++s) {
+      consume(s);
+      if (pre) load_step(nxt, s + RING - S, s % RING);
     }
     // the two k halves exchange half of their accumulator rows through LDS (kh = 0 hands over
     // rows q >= 8, kh = 1 rows q < 8), so every wavefront finishes and stores 8 rows
@@ -668,7 +747,10 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
       t += __shfl_xor(t, 1);
       t += __shfl_xor(t, 2);
       t += __shfl_xor(t, 4);
-      if (pq == 0) a.vec[cur.orow * D + RB * r + pr] = fast_tanh(t);
+      if (pq == 0) {
+        if constexpr (DF) __hip_atomic_store(a.vec + cur.orow * D + RB * r + pr, fast_tanh(t), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        else a.vec[cur.orow * D + RB * r + pr] = fast_tanh(t);
+      }
     }
     {
       float* P = a.mat + cur.orow * DD + (size_t)(RB * r) * D + 64 * ch + 2 * lcol;
@@ -682,13 +764,22 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
         floatx2 o;  // always (k half 0) + (k half 1)
         o[0] = kh ? other_e + mine_e : mine_e + other_e;
         o[1] = kh ? other_o + mine_o : mine_o + other_o;
-        *reinterpret_cast<floatx2*>(P + i * D) = o;
+        if constexpr (DF) store_agent_f2(P + i * D, o);
+        else *reinterpret_cast<floatx2*>(P + i * D) = o;
       }
+    }
+    if constexpr (DF) {
+      // this workgroup's quarter of the node is complete once every wavefront's stores are: announce it
+      wait_stores_done();
+      __syncthreads();
+      if (tid == 0) __hip_atomic_store(a.flags + 4 * cur.orow + r, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     slot += nslots;
     if (slot >= a.n) break;
-    __syncthreads();  // s_vp / s_red are reused by the next node
+    if constexpr (!DF) __syncthreads();  // s_vp / s_red are reused by the next node
     cur = nxt;
+    cur_raw = nxt_raw;
+    have = pre;
     vv = vv_next;
   }
 }
@@ -718,7 +809,7 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
   } else if (a.d == 128) {
     // four workgroups per node slot, slots in groups of 8; 512 resident workgroups = 128 slots
     const int slots = a.n < 128 ? (a.n + 7) / 8 * 8 : 128;
-    launch_with_events(mvrnn_rows_kernel, dim3(4 * slots), dim3(256), 0, stream, ev.start, ev.stop, a);
+    launch_with_events(mvrnn_rows_kernel<false>, dim3(4 * slots), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else if (a.variant == 1) {
     launch_with_events(mvrnn_stream_kernel<64>, dim3(grid), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else {
@@ -728,19 +819,31 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
 }
 
 int mvrnn_dataflow_workgroups(int32_t d, int32_t n) {
-  if (d != 64 || n <= 0) return 0;
+  if ((d != 64 && d != 128) || n <= 0) return 0;
   int dev = 0, per_cu = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_level_kernel<true>, 256, 0) != hipSuccess) return 0;
-  const long resident = (long)per_cu * cus;
-  return (int)(n < resident ? n : resident);
+  if (d == 64) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_level_kernel<true>, 256, 0) != hipSuccess) return 0;
+    const long resident = (long)per_cu * cus;
+    return (int)(n < resident ? n : resident);
+  }
+  // d = 128: four workgroups per node slot, slots in groups of 8 (see mvrnn_rows_kernel)
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_rows_kernel<true>, 256, 0) != hipSuccess) return 0;
+  const long resident_slots = (long)per_cu * cus / 32 * 8;
+  const long slots = std::min<long>((n + 7) / 8 * 8, resident_slots);
+  return (int)(4 * slots);
 }
 
 hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, hipStream_t stream, const LaunchEvents& ev) {
   if (a.n <= 0) return hipSuccess;
-  if (a.d != 64 || workgroups <= 0 || !a.flags || !a.status) return hipErrorInvalidValue;
-  launch_with_events(mvrnn_level_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
+  if ((a.d != 64 && a.d != 128) || workgroups <= 0 || !a.flags || !a.status) return hipErrorInvalidValue;
+  if (a.d == 128) {
+    if (workgroups % 32) return hipErrorInvalidValue;
+    launch_with_events(mvrnn_rows_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
+  } else {
+    launch_with_events(mvrnn_level_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
+  }
   return hipGetLastError();
 }
 

@@ -226,12 +226,15 @@ def test_mvrnn_streaming_variant(P, d, trees):
         c.close()
 
 
+@pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("trees,lo,hi,seed", [(1, 2, 2, 50), (5, 1, 9, 51), (64, 10, 40, 52), (700, 1, 12, 53), (3, 60, 90, 54)])
-def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed):
-    """d = 64: every internal level in one launch, a node waiting for its own two children only (a flag per node).
-    Same schedule, same tolerances; bit-identical to one launch per level (a node's arithmetic is the same code)."""
+def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed, d):
+    """Every internal level in one launch, a node waiting for its own two children only (a flag per node; four
+    per node for d = 128, whose nodes are written by four workgroups).  Same schedule, same tolerances;
+    bit-identical to one launch per level (a node's arithmetic is the same code).  Batches whose widest internal
+    level exceeds 2 048 (d = 64) or 512 (d = 128) nodes keep one launch per level."""
     import paper_2305_10611_amd as A
-    w = gen.mvrnn_workload(trees, lo, hi, 64, seed=seed)
+    w = gen.mvrnn_workload(trees, lo, hi, d, seed=seed)
     ctx.acrobat_set_profiling(True)
     try:
         vec, mat = P.run_mvrnn(ctx, w, copy_leaves=0)
@@ -239,7 +242,8 @@ def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed):
     finally:
         ctx.acrobat_set_profiling(False)
     level_off, _ = ctx.acrobat_last_schedule()
-    one_launch = len(level_off) - 1 > 2
+    widest = int(np.diff(level_off)[1:].max()) if len(level_off) > 2 else 0
+    one_launch = len(level_off) - 1 > 2 and widest <= (2048 if d == 64 else 512)
     assert kinds == ([A.binding.K_MVRNN_PERSISTENT] if one_launch else [A.binding.K_MVRNN_LEVEL] * (len(level_off) - 2))
     assert ctx.acrobat_device_status() == A.OK
     check_tree_schedule(ctx, w)
@@ -257,11 +261,12 @@ def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed):
     assert np.array_equal(vec1[internal], vec[internal]) and np.array_equal(mat1[internal], mat[internal])
 
 
-def test_mvrnn_persistent_wait_that_runs_out_is_reported(P):
+@pytest.mark.parametrize("d", [64, 128])
+def test_mvrnn_persistent_wait_that_runs_out_is_reported(P, d):
     """As for the recurrence: with no polls allowed, a parent whose child is not finished yet gives up, the grid
     drains, the kernel ends normally and the condition is reported once."""
     import paper_2305_10611_amd as A
-    w = gen.mvrnn_workload(40, 20, 40, 64, seed=55)
+    w = gen.mvrnn_workload(40, 20, 40, d, seed=55)
     c = A.Context(0)
     try:
         assert c.acrobat_set_persistent(True, 0) == A.OK

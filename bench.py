@@ -147,7 +147,7 @@ def main():
                     help="also time the forward call replayed from a captured HIP graph (index upload + every launch), "
                          "and what capturing and instantiating it costs; reported under \"graph_replay\"")
     ap.add_argument("--persistent", choices=("auto", "off"), default="auto",
-                    help="LSTM, BiRNN and MV-RNN (d = 64): off = one launch per time step / level instead of one persistent launch")
+                    help="LSTM, BiRNN and MV-RNN: off = one launch per time step / level instead of one persistent launch")
     ap.add_argument("--tuning", default=None, metavar="TILE,KSPLIT",
                     help="force one kernel variant for every cell level (acrobat_set_tuning), e.g. 64,1 or 65,1")
     ap.add_argument("--sync-probe", action="store_true",

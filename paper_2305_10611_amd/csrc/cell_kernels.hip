@@ -1108,8 +1108,14 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   const long direct_jt = (hlim + direct_jw<G>() - 1) / direct_jw<G>(), direct_mt = (a.n + 15) / 16;
   const long direct_wgs = direct_mt * direct_jt;                                      // those that have a tile
   const long direct_rows = direct_wgs * (G * direct_jw<G>()) + direct_jt * (long)a.n;  // weight rows + node rows requested
+  //    A single-gate cell leaves the other kernels little to work with (a quarter of the stepwise kernel's matrix
+  //    columns, 32-column tiles with one accumulator block), so there the limit is 64 MiB and the rule applies
+  //    whatever n x K: recurrent cell of the tree generator, H = 512, K = 1024, 165-244 rows (two cells per launch)
+  //    12.4-16.8 us against 22-30 us (stepwise) and 12.2-21 us (32-node tiles); 587 rows go to the tiled kernel.
+  const long direct_cap = G == 1 ? (64L << 20) : (24L << 20);
   const bool direct_ok = ws.n_cu > 0 && direct_wgs <= 2L * ws.n_cu &&
-                         direct_rows * n_slabs * kBK * (long)sizeof(float) <= (24L << 20);
+                         direct_rows * n_slabs * kBK * (long)sizeof(float) <= direct_cap;
+  if (G == 1 && direct_ok) return Shape{16, 1};
   if ((long)a.n * n_slabs * kBK <= 256000) return direct_ok ? Shape{16, 1} : Shape{6, 0};
   //  * a narrow output layer (at most 8 unit tiles of the direct kernel, e.g. 16 output units) gives the tiled
   //    kernels one unit tile, i.e. few workgroups however many rows it has: 1 299 rows x 16 units, K = 1024,
@@ -1118,7 +1124,8 @@ Shape pick_shape(const CellLevelArgs& a, const SplitKWorkspace& ws) {
   //  * levels whose 32-node tiles all fit the chip at once (one workgroup per compute unit) run them
   //    unsplit: 29-30 us at 286 / 399 nodes against 32-33 us for 64-node tiles split in two;
   const long tiles32 = (long)((a.n + 31) / 32) * n_jt;
-  if (tiles32 <= 256 && G >= 4) return Shape{32, 1};
+  //    (single-gate cells too: 603 rows, H = 256, 9.0 instead of 12.4 us; 587 rows, H = 512, 17.5 instead of 18.6)
+  if (tiles32 <= 256 && (G >= 4 || G == 1)) return Shape{32, 1};
   Shape best{a.n > 128 ? 64 : 32, 1};
   const long tiles = (long)((a.n + best.bm - 1) / best.bm) * n_jt;
   //  * up to two rounds of 64-node tiles: whole tiles leave compute units idle for part of the level (144 or

@@ -127,10 +127,10 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   };
   // DF: have both children of the node announced themselves?  (wave-uniform; leaves are table rows: always)
   auto children_done = [&](const RawIdx& i) {
-    bool ok = true;
-    if (i.ls >= 0) ok = ok && load_agent(a.flags + i.ls) == a.epoch;
-    if (i.rs >= 0) ok = ok && load_agent(a.flags + i.rs) == a.epoch;
-    return ok;
+    // (both words requested before either is looked at: one round trip, not two)
+    const unsigned l = i.ls >= 0 ? load_agent(a.flags + i.ls) : a.epoch;
+    const unsigned r = i.rs >= 0 ? load_agent(a.flags + i.rs) : a.epoch;
+    return l == a.epoch && r == a.epoch;
   };
 
   // one node: `x`, `vv` hold its operands; `xn`, `vvn` receive the next node's, whose indices
@@ -584,12 +584,16 @@ __global__ __launch_bounds__(256, 2) void mvrnn_rows_kernel(const MvrnnLevelArgs
   };
   // DF: have all four parts of both children been announced?  (leaves are table rows: always)
   auto children_done = [&](const RawIdx& i) {
-    bool ok = true;
+    // (all eight words requested before any is looked at: one round trip, not eight)
+    unsigned l[4], r[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      if (i.ls >= 0) ok = ok && load_agent(a.flags + 4 * (size_t)i.ls + q) == a.epoch;
-      if (i.rs >= 0) ok = ok && load_agent(a.flags + 4 * (size_t)i.rs + q) == a.epoch;
+      l[q] = i.ls >= 0 ? load_agent(a.flags + 4 * (size_t)i.ls + q) : a.epoch;
+      r[q] = i.rs >= 0 ? load_agent(a.flags + 4 * (size_t)i.rs + q) : a.epoch;
     }
+    bool ok = true;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) ok = ok && l[q] == a.epoch && r[q] == a.epoch;
     return ok;
   };
   // DF: thread 0 waits, bounded, for the children of the node; false = a wait ran out here or elsewhere: drain

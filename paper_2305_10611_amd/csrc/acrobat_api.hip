@@ -855,15 +855,17 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
     // One launch for the whole recurrence where the shape allows it: the steps are the same batches in the
     // same order, executed by workgroups that keep W_h on chip and synchronise among themselves.
     const int32_t n_live = s.level_off[1];  // sequences with at least one step
-    const int32_t n_blocks = (n_live + kPersistSlots - 1) / kPersistSlots;
+    const int32_t slots = kLstmSlots;
+    const int32_t n_blocks = (n_live + slots - 1) / slots;
     if (ctx->persistent && s.n_levels >= 2 && (double)R * H * sizeof(float) < 4294967296.0 &&
         lstm_persistent_eligible(H, n_blocks, nullptr)) {
       TRY(reserve_sync(ctx, stream));
-      const size_t n_slots = (size_t)n_blocks * kPersistSlots;
+      const size_t n_slots = (size_t)n_blocks * slots;
       TRY(reserve_indices(ctx, 2 * n_slots, stream));
       int32_t* st = ctx->h_stage;
       // sequences by non-increasing length (ties by id): a counting sort over the lengths; rank r goes to block
-      // r % n_blocks, slot r / n_blocks, so every block gets the same mix of lengths and its live slots are a prefix
+      // r / slots, slot r % slots, so a block's live slots are a prefix at every step, its sequences are of
+      // similar length (few dead rows in its products) and the blocks of short sequences leave the chip early
       std::vector<int32_t> first(s.n_levels + 2, 0);  // first[l]: count, then rank of the first sequence of length l
       for (int32_t q = 0; q < n_seq; ++q)
         if (len[q] > 0) ++first[len[q]];
@@ -877,7 +879,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       for (int32_t q = 0; q < n_seq; ++q) {
         if (len[q] > 0) {
           const int32_t r = first[len[q]]++;
-          const size_t slot = (size_t)(r % n_blocks) * kPersistSlots + r / n_blocks;
+          const size_t slot = (size_t)r;  // block r / slots, slot r % slots
           st[slot] = row0;
           st[n_slots + slot] = len[q];
         }
@@ -885,14 +887,14 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       }
       TRY(upload_indices(ctx, 2 * n_slots, stream));
       LaunchTimer timer{ctx, stream};
-      HIP_TRY(ctx, launch_fill_u32(ctx->d_sync + kPersistFlagWords, 0u, kSyncWords - kPersistFlagWords, stream));
+      HIP_TRY(ctx, launch_fill_u32(ctx->d_sync, 0u, kLstmMaxBlocks * kPersistCounterStride, stream));
       TRY(input_transform(timer));
       LstmPersistentArgs pa{};
       pa.n_blocks = n_blocks; pa.H = H;
       pa.slot_row0 = ctx->d_idx; pa.slot_len = ctx->d_idx + n_slots;
       pa.Wh = d_Wh; pa.xp = ctx->d_scratch; pa.h = d_h; pa.c = d_c;
       pa.h_bytes = (uint32_t)((size_t)R * H * sizeof(float));
-      pa.counters = ctx->d_sync + kPersistFlagWords; pa.status = ctx->h_status_dev;
+      pa.counters = ctx->d_sync; pa.status = ctx->h_status_dev;
       pa.max_polls = ctx->max_polls;
       TRY(timer.begin(ACROBAT_K_LSTM_PERSISTENT, 0, R));
       if (timer.tile()) *timer.tile() = 16;

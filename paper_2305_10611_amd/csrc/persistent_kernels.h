@@ -9,24 +9,25 @@
 
 namespace acrobat {
 
-constexpr int kPersistSlots = 32;        // sequences per node block
-constexpr int kPersistMaxBlocks = 8;     // node blocks of one launch (one per XCD)
+constexpr int kLstmSlots = 16;           // sequences per node block of the LSTM launch
+constexpr int kLstmMaxBlocks = 16;       // its node blocks at most (two per XCD; at H = 512 two workgroups per compute unit)
+constexpr int kPersistMaxBlocks = 8;     // groups of the probe at most (one per XCD)
 constexpr int kPersistMaxColBlocks = 32;   // workgroups per node block at most (H = 512)
 constexpr int kPersistCounterStride = 32;  // uint32 between two groups' arrival counters of the probe (one cache line each)
 // synchronisation words of one context: the probe's flag lines [group][consumer][producer], arrival counters, status
 constexpr int kPersistFlagWords = kPersistMaxBlocks * kPersistMaxColBlocks * kPersistMaxColBlocks;
 constexpr int kPersistSyncWords = kPersistFlagWords + kPersistMaxBlocks * kPersistCounterStride + 1;
 
-// The LSTM recurrence of a whole mini-batch in one launch.  The sequences are dealt out to node blocks of 32
+// The LSTM recurrence of a whole mini-batch in one launch.  The sequences are dealt out to node blocks of 16
 // slots; workgroup (block nb, column block cb) keeps the 64 rows of W_h that belong to hidden units
 // 16 cb .. 16 cb + 15 (all four gates) in registers for every step and owns those units of the block's
 // sequences.  After step t the workgroups of a block exchange h_t through the arena and arrive at the block's
 // counter; blocks never wait for each other.
 struct LstmPersistentArgs {
-  int32_t n_blocks;          // node blocks in use, 1 .. kPersistMaxBlocks
+  int32_t n_blocks;          // node blocks in use, 1 .. kLstmMaxBlocks
   int32_t H;                 // hidden size (the kernel is instantiated for 128, 256 and 512)
-  const int32_t* slot_row0;  // [n_blocks * 32] first arena row of the slot's sequence
-  const int32_t* slot_len;   // [n_blocks * 32] its length, non-increasing inside a block, 0 = empty slot
+  const int32_t* slot_row0;  // [n_blocks * 16] first arena row of the slot's sequence
+  const int32_t* slot_len;   // [n_blocks * 16] its length, non-increasing inside a block, 0 = empty slot
   const float* Wh;           // [4H, H], gate order (i, f, o, u)
   const float* xp;           // [rows, 4H] hoisted input transform (bias included)
   float* h; float* c;        // arena [rows, H], row = slot_row0 + t

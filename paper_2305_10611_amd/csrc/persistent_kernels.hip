@@ -84,36 +84,45 @@ __global__ void fill_u32_kernel(unsigned* p, unsigned value, int n) {
 }
 
 // ---- LSTM recurrence ---------------------------------------------------------------------------------
-// Workgroup (nb, cb) = (blockIdx % 8, blockIdx / 8): node block nb lives on XCD nb.  Wavefront g computes
-// gate g for the workgroup's 16 hidden units: its 16 weight rows are the B operand of
-// v_mfma_f32_16x16x4_f32 and stay in H/4 registers per lane; the A operand is the block's h_{t-1} rows,
-// staged in LDS once per step.  Lane l supplies A[slot l%16][k] and B[k][unit l%16] for the four k
-// = 16 it + 4 (l/16) + e, e = 0..3, of 16-k group `it` (one 16-byte LDS read feeds four instructions), and
-// holds z[slot 4 (l/16) + v][unit l%16] in result register v.  The slots of a block are sorted by
-// non-increasing length, so the live sequences of a step are a prefix and a step multiplies 16 or 32 rows.
+// Node blocks of 16 slots; workgroup (nb, cb) owns hidden units 16 cb .. 16 cb + 15 of block nb.  Wavefront g
+// computes gate g for those units: its 16 weight rows are the B operand of v_mfma_f32_16x16x4_f32 and stay in
+// H/4 registers per lane; the A operand is the block's h_{t-1} rows, staged in LDS once per step.  Lane l supplies
+// A[slot l%16][k] and B[k][unit l%16] for the four k = 16 it + 4 (l/16) + e, e = 0..3, of 16-k group `it` (one
+// 16-byte LDS read feeds four instructions), and holds z[slot 4 (l/16) + v][unit l%16] in result register v.
+// A step is one 16-row product per wavefront whatever the number of live slots; a block's sequences are of similar
+// length (the host sorts them), so few of those rows are dead.
+// At H = 512 sixteen blocks are 512 workgroups, two per compute unit (204 registers each): one multiplies while the
+// other exchanges its rows.  The two that share a compute unit have ids 256 apart and must belong to different
+// blocks - workgroups of one block wait for each other, and as co-residents they were measured to take turns
+// (8 us per step instead of 5.3) - hence the numbering below.
 template <int H>
-__global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const LstmPersistentArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void lstm_persistent_kernel(const LstmPersistentArgs a) {
   constexpr int CB = H / 16;   // column blocks = workgroups per node block
   constexpr int LD = H + 4;    // padded LDS row: 16-byte reads of 8 consecutive rows hit distinct banks
   constexpr int NIT = H / 16;  // 16-k groups
-  constexpr int CW = 128;      // columns per staging chunk: 32 rows x 128 columns = 4 passes of the 256 threads
+  constexpr int CW = 128;      // columns per staging chunk: 8 rows x 128 columns per pass of the 256 threads
   constexpr int CH = H / CW;
-  static_assert(H % CW == 0 && kPersistSlots == 32 && kThreads == 256, "staging layout");
-  __shared__ __attribute__((aligned(16))) float hs[kPersistSlots * LD];
-  __shared__ float zs[4][kPersistSlots][17];
-  __shared__ int s_row0[kPersistSlots], s_len[kPersistSlots];
+  constexpr int PASSES = kLstmSlots / 8;
+  static_assert(H % CW == 0 && kLstmSlots == 16 && kThreads == 256, "staging layout");
+  __shared__ __attribute__((aligned(16))) float hs[kLstmSlots * LD];
+  __shared__ float zs[4][kLstmSlots][17];
+  __shared__ int s_row0[kLstmSlots], s_len[kLstmSlots];
   __shared__ int s_go;
 
-  const int nb = blockIdx.x % kPersistMaxBlocks, cb = blockIdx.x / kPersistMaxBlocks;
+  // Workgroup ids 0 .. 8 CB - 1 are blocks 0 .. 7, the next 8 CB are blocks 15 .. 8: ids that agree modulo 8 share
+  // an XCD, so a block lives on one XCD, and - blocks being sorted by length - the longest block shares its
+  // compute units with the shortest one, which soon leaves them to it.
+  const int nb = blockIdx.x < 8 * CB ? (blockIdx.x & 7) : 15 - (blockIdx.x & 7);
+  const int cb = (blockIdx.x >> 3) % CB;
   if (nb >= a.n_blocks) return;
   const int tid = threadIdx.x, lane = tid & 63, g = tid >> 6;
   const int col = lane & 15, kq = lane >> 4;
 
-  if (tid < kPersistSlots) {
-    s_row0[tid] = a.slot_row0[nb * kPersistSlots + tid];
-    s_len[tid] = a.slot_len[nb * kPersistSlots + tid];
+  if (tid < kLstmSlots) {
+    s_row0[tid] = a.slot_row0[nb * kLstmSlots + tid];
+    s_len[tid] = a.slot_len[nb * kLstmSlots + tid];
   }
-  for (int i = tid; i < kPersistSlots * LD; i += kThreads) hs[i] = 0.0f;  // rows of dead slots stay finite
+  for (int i = tid; i < kLstmSlots * LD; i += kThreads) hs[i] = 0.0f;  // rows of dead slots stay finite
   // this wavefront's weight rows: gate g, units 16 cb + col
   floatx4 wreg[NIT];
   {
@@ -124,109 +133,77 @@ __global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const Lstm
   __syncthreads();
 
   const int T = s_len[0];  // the block's longest sequence
-  // epilogue ownership: slot tid / 8, units 16 cb + 2 (tid % 8) and the next one
-  const int my_slot = tid >> 3, u0 = (tid & 7) * 2;
+  // epilogue ownership: slot tid / 16, unit 16 cb + tid % 16
+  const int my_slot = tid >> 4, u0 = tid & 15;
   const int my_len = s_len[my_slot];
   const size_t my_row0 = (size_t)s_row0[my_slot];
-  float c0 = 0.0f, c1 = 0.0f;
+  float c = 0.0f;
   unsigned* const counter = a.counters + nb * kPersistCounterStride;  // arrivals of this block's workgroups
   const __amdgpu_buffer_rsrc_t h_rsrc = agent_buffer(a.h, a.h_bytes);
 
   for (int t = 0; t < T; ++t) {
     // input transform of this step: does not depend on h, requested before the wait
-    floatx2 xv[4];
+    float xv[4];
     if (my_len > t) {
       const float* xrow = a.xp + (my_row0 + t) * (size_t)(4 * H) + 16 * cb + u0;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) xv[q] = *reinterpret_cast<const floatx2*>(xrow + q * H);
+      for (int q = 0; q < 4; ++q) xv[q] = xrow[q * H];
     }
-    float z[4][2];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) z[q][0] = z[q][1] = 0.0f;
+    float z[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 
     if (t > 0) {
-      const int live = __popcll(__ballot(lane < kPersistSlots && s_len[lane & 31] > t));
+      const int live = __popcll(__ballot(lane < kLstmSlots && s_len[lane & (kLstmSlots - 1)] > t));
       // h_{t-1} of the block is complete once all CB workgroups have arrived t times
       if (tid == 0) s_go = wait_for(counter, (unsigned)(CB * t), a.status, a.max_polls) ? 1 : 0;
       __syncthreads();
       if (!s_go) break;
       // The live rows (all of them were live at t - 1) go to LDS in chunks of 128 columns: every load is
       // requested up front, and the matrix instructions of a chunk run while the later chunks are in flight.
-      floatx4 stage[CH][4];
+      floatx4 stage[CH][PASSES];
 #pragma unroll
-      for (int c = 0; c < CH; ++c)
+      for (int ch = 0; ch < CH; ++ch)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < PASSES; ++p) {
           const int row = (p * kThreads + tid) >> 5;
           if (row < live)
-            stage[c][p] = load_agent_f4(h_rsrc, (unsigned)((((size_t)s_row0[row] + t - 1) * H + CW * c + 4 * (tid & 31)) * sizeof(float)));
+            stage[ch][p] = load_agent_f4(h_rsrc, (unsigned)((((size_t)s_row0[row] + t - 1) * H + CW * ch + 4 * (tid & 31)) * sizeof(float)));
         }
-      // contraction: 16 or 32 rows x 16 units x H for this wavefront's gate, two accumulators per row group
+      // contraction: 16 rows x 16 units x H for this wavefront's gate, two accumulators
       const float* arow = &hs[col * LD + 4 * kq];
-      floatx4 acc00 = {0, 0, 0, 0}, acc01 = {0, 0, 0, 0}, acc10 = {0, 0, 0, 0}, acc11 = {0, 0, 0, 0};
+      floatx4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
+      for (int ch = 0; ch < CH; ++ch) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < PASSES; ++p) {
           const int row = (p * kThreads + tid) >> 5;
-          if (row < live) *reinterpret_cast<floatx4*>(&hs[row * LD + CW * c + 4 * (tid & 31)]) = stage[c][p];
+          if (row < live) *reinterpret_cast<floatx4*>(&hs[row * LD + CW * ch + 4 * (tid & 31)]) = stage[ch][p];
         }
         __syncthreads();
-        if (live > 16) {
 #pragma unroll
-          for (int it = c * (CW / 16); it < (c + 1) * (CW / 16); ++it) {
-            const floatx4 f0 = *reinterpret_cast<const floatx4*>(arow + 16 * it);
-            const floatx4 f1 = *reinterpret_cast<const floatx4*>(arow + 16 * LD + 16 * it);
-            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[0], wreg[it][0], acc00, 0, 0, 0);
-            acc10 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[0], wreg[it][0], acc10, 0, 0, 0);
-            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[1], wreg[it][1], acc01, 0, 0, 0);
-            acc11 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[1], wreg[it][1], acc11, 0, 0, 0);
-            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[2], wreg[it][2], acc00, 0, 0, 0);
-            acc10 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[2], wreg[it][2], acc10, 0, 0, 0);
-            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[3], wreg[it][3], acc01, 0, 0, 0);
-            acc11 = __builtin_amdgcn_mfma_f32_16x16x4f32(f1[3], wreg[it][3], acc11, 0, 0, 0);
-          }
-        } else {
-#pragma unroll
-          for (int it = c * (CW / 16); it < (c + 1) * (CW / 16); ++it) {
-            const floatx4 f0 = *reinterpret_cast<const floatx4*>(arow + 16 * it);
-            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[0], wreg[it][0], acc00, 0, 0, 0);
-            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[1], wreg[it][1], acc01, 0, 0, 0);
-            acc00 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[2], wreg[it][2], acc00, 0, 0, 0);
-            acc01 = __builtin_amdgcn_mfma_f32_16x16x4f32(f0[3], wreg[it][3], acc01, 0, 0, 0);
-          }
+        for (int it = ch * (CW / 16); it < (ch + 1) * (CW / 16); ++it) {
+          const floatx4 f = *reinterpret_cast<const floatx4*>(arow + 16 * it);
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[0], wreg[it][0], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[1], wreg[it][1], acc1, 0, 0, 0);
+          acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[2], wreg[it][2], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[3], wreg[it][3], acc1, 0, 0, 0);
         }
       }
-      // gate g of (slot 4 kq + v [+ 16], unit col) -> LDS, so that a thread finds all four gates of its elements
+      // gate g of (slot 4 kq + v, unit col) -> LDS, so that a thread finds all four gates of its element
 #pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        zs[g][4 * kq + v][col] = acc00[v] + acc01[v];
-        zs[g][16 + 4 * kq + v][col] = acc10[v] + acc11[v];
-      }
+      for (int v = 0; v < 4; ++v) zs[g][4 * kq + v][col] = acc0[v] + acc1[v];
       __syncthreads();
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        z[q][0] = zs[q][my_slot][u0];
-        z[q][1] = zs[q][my_slot][u0 + 1];
-      }
+      for (int q = 0; q < 4; ++q) z[q] = zs[q][my_slot][u0];
     }
 
     if (my_len > t) {
-      float hv[2];
-      float* cc[2] = {&c0, &c1};
-#pragma unroll
-      for (int e = 0; e < 2; ++e) {
-        const float zi = z[0][e] + xv[0][e], zf = z[1][e] + xv[1][e], zo = z[2][e] + xv[2][e], zu = z[3][e] + xv[3][e];
-        const float cn = fast_sigmoid(zf) * *cc[e] + fast_sigmoid(zi) * fast_tanh(zu);
-        *cc[e] = cn;
-        hv[e] = fast_sigmoid(zo) * fast_tanh(cn);
-      }
+      const float zi = z[0] + xv[0], zf = z[1] + xv[1], zo = z[2] + xv[2], zu = z[3] + xv[3];
+      c = fast_sigmoid(zf) * c + fast_sigmoid(zi) * fast_tanh(zu);
+      const float hv = fast_sigmoid(zo) * fast_tanh(c);
       const size_t o = (my_row0 + t) * (size_t)H + 16 * cb + u0;
-      // h is read by the other workgroups of the block at the next step: write-through stores
-      __hip_atomic_store(a.h + o, hv[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(a.h + o + 1, hv[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      floatx2 cv = {c0, c1};
-      *reinterpret_cast<floatx2*>(a.c + o) = cv;
+      // h is read by the other workgroups of the block at the next step: write-through store
+      __hip_atomic_store(a.h + o, hv, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      a.c[o] = c;
     }
     if (t + 1 < T) {
       wait_stores_done();  // this wavefront's stores have completed
@@ -237,24 +214,27 @@ __global__ __launch_bounds__(kThreads, 1) void lstm_persistent_kernel(const Lstm
 }
 
 // ---- bidirectional RNN recurrence ------------------------------------------------------------------------
-// Workgroup (nb, cb) = (blockIdx % nbp, blockIdx / nbp), nbp = number of blocks rounded up to a multiple of 8,
-// so the workgroups of a block share an XCD.  Wavefront w holds the weight rows of units 64 cb + 16 w + (l % 16)
-// as the B operand (H / 4 registers per lane); the block's 16 previous-state rows are the A operand, staged
-// in LDS once per step.  Thread t finishes slot t / 16, units 64 cb + 4 (t % 16) .. + 3.
+// Blocks of 16 slots; workgroup (nb, cb) owns hidden units 16 cb .. 16 cb + 15 of block nb, and its wavefront w
+// the quarter [w H/4, (w + 1) H/4) of the contraction: the B operand, W_h[unit l%16][that quarter], stays in
+// H/16 registers per lane, the A operand - the block's 16 previous-state rows - goes straight from the arena into
+// the operand registers (lane l: row l%16, 16 bytes at k = w H/4 + 16 it + 4 (l/16); every load of a step is in
+// flight at once), and the four partial sums meet in LDS, where thread t adds them in ascending w and finishes
+// slot t / 16, unit 16 cb + t % 16.  A single-gate step is small (16 x 16 x H per workgroup), so H/16 workgroups
+// per block rather than H/64 shorten what a step waits for: 0.43 instead of 1.7 us of matrix instructions at H = 512.
+// Workgroup ids 0 .. 8 CB - 1 are blocks 0 .. 7, the next 8 CB blocks 8 .. 15, and so on: ids that agree modulo 8
+// share an XCD, so a block lives on one XCD, and workgroups that share a compute unit (ids a multiple of 256
+// apart) belong to different blocks - those of one block wait for each other and would take turns.
 template <int H>
-__global__ __launch_bounds__(kThreads, 1) void rnn_persistent_kernel(const RnnPersistentArgs a) {
-  constexpr int CB = H / 64;
-  constexpr int LD = H + 4;
-  constexpr int NIT = H / 16;
-  constexpr int PASSES = kRnnSlots * (H / 4) / kThreads;  // 16-byte pieces of the block's rows per thread
-  static_assert(kRnnSlots == 16 && kThreads == 256 && H % 64 == 0, "staging layout");
-  __shared__ __attribute__((aligned(16))) float hs[kRnnSlots * LD];
-  __shared__ __attribute__((aligned(16))) float zs[4][kRnnSlots][20];
+__global__ __launch_bounds__(kThreads, 2) void rnn_persistent_kernel(const RnnPersistentArgs a) {
+  constexpr int CB = H / 16;
+  constexpr int KQ = H / 4;     // this wavefront's share of the contraction
+  constexpr int NIT = KQ / 16;  // its 16-k groups
+  static_assert(kRnnSlots == 16 && kThreads == 256 && H % 64 == 0, "one element per thread, four k quarters");
+  __shared__ float zs[4][kRnnSlots][17];
   __shared__ int s_row0[kRnnSlots], s_len[kRnnSlots];
   __shared__ int s_go;
 
-  const int nbp = (a.n_blocks + 7) & ~7;
-  const int nb = blockIdx.x % nbp, cb = blockIdx.x / nbp;
+  const int nb = 8 * (blockIdx.x / (8 * CB)) + (blockIdx.x & 7), cb = (blockIdx.x >> 3) % CB;
   if (nb >= a.n_blocks) return;
   const int dir = nb & 1;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -264,19 +244,22 @@ __global__ __launch_bounds__(kThreads, 1) void rnn_persistent_kernel(const RnnPe
     s_row0[tid] = a.slot_row0[(nb >> 1) * kRnnSlots + tid];
     s_len[tid] = a.slot_len[(nb >> 1) * kRnnSlots + tid];
   }
-  for (int i = tid; i < kRnnSlots * LD; i += kThreads) hs[i] = 0.0f;  // rows of dead slots stay finite
+  const unsigned koff = (unsigned)(KQ * w + 4 * kq);  // first k of this lane's 16-byte pieces
   floatx4 wreg[NIT];
   {
-    const float* wrow = a.Wh[dir] + (size_t)(64 * cb + 16 * w + col) * H + 4 * kq;
+    const float* wrow = a.Wh[dir] + (size_t)(16 * cb + col) * H + koff;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) wreg[it] = *reinterpret_cast<const floatx4*>(wrow + 16 * it);
   }
   __syncthreads();
 
   const int T = s_len[0];  // the block's longest sequence
-  const int my_slot = tid >> 4, u0 = 4 * (tid & 15);
+  const int my_slot = tid >> 4, u0 = tid & 15;
   const int my_len = s_len[my_slot];
   const size_t my_row0 = (size_t)s_row0[my_slot];
+  // the slot whose rows this lane supplies to the matrix instructions
+  const int a_len = s_len[col];
+  const size_t a_row0 = (size_t)s_row0[col];
   unsigned* const counter = a.counters + nb * kPersistCounterStride;
   const __amdgpu_buffer_rsrc_t h_rsrc = agent_buffer(a.h[dir], a.h_bytes);
   const float* const xp = a.xp[dir];
@@ -284,59 +267,49 @@ __global__ __launch_bounds__(kThreads, 1) void rnn_persistent_kernel(const RnnPe
 
   for (int t = 0; t < T; ++t) {
     const size_t my_row = dir ? my_row0 + (size_t)(my_len - 1 - t) : my_row0 + (size_t)t;
-    floatx4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (my_len > t) xv = *reinterpret_cast<const floatx4*>(xp + my_row * H + 64 * cb + u0);  // does not depend on h
-    const int live = __popcll(__ballot(lane < kRnnSlots && s_len[lane & 15] > t));
+    float xv = 0.0f;
+    if (my_len > t) xv = xp[my_row * H + 16 * cb + u0];  // does not depend on h
     if (t > 0) {
       if (tid == 0) s_go = wait_for(counter, (unsigned)(CB * t), a.status, a.max_polls) ? 1 : 0;
       __syncthreads();
       if (!s_go) break;
     }
-    // previous state of the live slots -> LDS (the initial state at t = 0)
-    floatx4 stage[PASSES];
+    // previous state of the lane's slot (the initial state at t = 0; zero for a slot that is through)
+    floatx4 f[NIT];
+    if (a_len > t) {
+      if (t == 0) {
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-      const int piece = p * kThreads + tid, row = piece / (H / 4), c4 = piece % (H / 4);
-      if (row < live) {
-        if (t == 0) {
-          stage[p] = *reinterpret_cast<const floatx4*>(h_init + 4 * c4);
-        } else {
-          const size_t prow = dir ? (size_t)s_row0[row] + (size_t)(s_len[row] - t) : (size_t)s_row0[row] + (size_t)(t - 1);
-          stage[p] = load_agent_f4(h_rsrc, (unsigned)((prow * H + 4 * c4) * sizeof(float)));
-        }
+        for (int it = 0; it < NIT; ++it) f[it] = *reinterpret_cast<const floatx4*>(h_init + koff + 16 * it);
+      } else {
+        const size_t prow = dir ? a_row0 + (size_t)(a_len - t) : a_row0 + (size_t)(t - 1);
+        const unsigned base = (unsigned)((prow * H + koff) * sizeof(float));
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) f[it] = load_agent_f4(h_rsrc, base + 64u * it);
       }
-    }
+    } else {
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-      const int piece = p * kThreads + tid, row = piece / (H / 4), c4 = piece % (H / 4);
-      if (row < live) *reinterpret_cast<floatx4*>(&hs[row * LD + 4 * c4]) = stage[p];
+      for (int it = 0; it < NIT; ++it) f[it] = floatx4{0.0f, 0.0f, 0.0f, 0.0f};
     }
-    __syncthreads();
-    const float* arow = &hs[col * LD + 4 * kq];
     floatx4 acc0 = {0, 0, 0, 0}, acc1 = {0, 0, 0, 0};
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-      const floatx4 f = *reinterpret_cast<const floatx4*>(arow + 16 * it);
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[0], wreg[it][0], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[1], wreg[it][1], acc1, 0, 0, 0);
-      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[2], wreg[it][2], acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[3], wreg[it][3], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[it][0], wreg[it][0], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[it][1], wreg[it][1], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[it][2], wreg[it][2], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(f[it][3], wreg[it][3], acc1, 0, 0, 0);
     }
-    // z of (slot 4 kq + v, unit 16 w + col) -> LDS
+    // this quarter's share of z(slot 4 kq + v, unit col) -> LDS
 #pragma unroll
     for (int v = 0; v < 4; ++v) zs[w][4 * kq + v][col] = acc0[v] + acc1[v];
     __syncthreads();
     if (my_len > t) {
-      const floatx4 z = *reinterpret_cast<const floatx4*>(&zs[u0 >> 4][my_slot][u0 & 15]);
-      agent_f4 hv;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) hv[e] = fast_sigmoid(z[e] + xv[e]);
+      const float z = ((zs[0][my_slot][u0] + zs[1][my_slot][u0]) + zs[2][my_slot][u0]) + zs[3][my_slot][u0];
       // read by the other workgroups of the block at the next step: write-through store
-      store_agent_f4(h_rsrc, (unsigned)((my_row * H + 64 * cb + u0) * sizeof(float)), hv);
+      __hip_atomic_store(a.h[dir] + my_row * H + 16 * cb + u0, fast_sigmoid(z + xv), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (t + 1 < T) {
       wait_stores_done();
-      __syncthreads();
+      __syncthreads();  // (also: every thread has read zs before the next step writes it)
       if (tid == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
@@ -423,7 +396,7 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
 
 template <int H>
 hipError_t launch_lstm_h(const LstmPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev) {
-  const unsigned grid = (unsigned)(kPersistMaxBlocks * (H / 16));
+  const unsigned grid = (unsigned)(((a.n_blocks + 7) & ~7) * (H / 16));
   launch_with_events((lstm_persistent_kernel<H>), dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, a);
   return hipGetLastError();
 }
@@ -448,7 +421,7 @@ bool rnn_resident_at_once(int n_workgroups) {
 
 template <int H>
 hipError_t launch_rnn_h(const RnnPersistentArgs& a, hipStream_t stream, const LaunchEvents& ev) {
-  const unsigned grid = (unsigned)(((a.n_blocks + 7) & ~7) * (H / 64));
+  const unsigned grid = (unsigned)(((a.n_blocks + 7) & ~7) * (H / 16));
   launch_with_events((rnn_persistent_kernel<H>), dim3(grid), dim3(kThreads), 0, stream, ev.start, ev.stop, a);
   return hipGetLastError();
 }
@@ -462,9 +435,9 @@ bool rnn_persistent_eligible(int32_t H, int32_t n_blocks, const char** why) {
   const int nbp = (n_blocks + 7) & ~7;
   bool ok = false;
   switch (H) {
-    case 128: ok = rnn_resident_at_once<128>(nbp * 2); break;
-    case 256: ok = rnn_resident_at_once<256>(nbp * 4); break;
-    case 512: ok = rnn_resident_at_once<512>(nbp * 8); break;
+    case 128: ok = rnn_resident_at_once<128>(nbp * 8); break;
+    case 256: ok = rnn_resident_at_once<256>(nbp * 16); break;
+    case 512: ok = rnn_resident_at_once<512>(nbp * 32); break;
     default: *why = "hidden size not instantiated"; return false;
   }
   if (!ok) *why = "the workgroups would not all be resident at once";
@@ -483,12 +456,13 @@ hipError_t launch_rnn_persistent(const RnnPersistentArgs& a, hipStream_t stream,
 bool lstm_persistent_eligible(int32_t H, int32_t n_blocks, const char** why) {
   const char* dummy;
   if (!why) why = &dummy;
-  if (n_blocks < 1 || n_blocks > kPersistMaxBlocks) { *why = "more node blocks than one launch holds"; return false; }
+  if (n_blocks < 1 || n_blocks > kLstmMaxBlocks) { *why = "more node blocks than one launch holds"; return false; }
+  const int nbp = (n_blocks + 7) & ~7;
   bool ok = false;
   switch (H) {
-    case 128: ok = resident_at_once<128>(kPersistMaxBlocks * 8); break;
-    case 256: ok = resident_at_once<256>(kPersistMaxBlocks * 16); break;
-    case 512: ok = resident_at_once<512>(kPersistMaxBlocks * 32); break;
+    case 128: ok = resident_at_once<128>(nbp * 8); break;
+    case 256: ok = resident_at_once<256>(nbp * 16); break;
+    case 512: ok = resident_at_once<512>(nbp * 32); break;
     default: *why = "hidden size not instantiated"; return false;
   }
   if (!ok) *why = "the workgroups would not all be resident at once";

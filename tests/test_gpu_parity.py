@@ -322,7 +322,8 @@ def test_lstm_ragged_with_bias_and_empty_sequences(ctx, P, H, D, n_seq, lo, hi):
 
 
 @pytest.mark.parametrize("H,D,n_seq,lo,hi", [(128, 32, 5, 1, 9), (128, 64, 33, 0, 40), (256, 128, 256, 1, 30), (256, 64, 100, 2, 2),
-                                             (512, 64, 70, 0, 25), (512, 512, 256, 1, 100), (512, 32, 17, 60, 60)])
+                                             (512, 64, 70, 0, 25), (512, 512, 256, 1, 100), (512, 32, 17, 60, 60),
+                                             (512, 32, 150, 1, 40), (128, 32, 200, 0, 12)])
 def test_lstm_whole_recurrence_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
     """Shapes the persistent kernel takes (H in {128, 256, 512}, at most 256 live sequences): one launch for all
     time steps, same schedule, same tolerances; and against the one-launch-per-step path of the same library."""
@@ -357,7 +358,8 @@ def test_lstm_whole_recurrence_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
 
 
 def test_lstm_more_sequences_than_one_persistent_launch_holds(ctx, P):
-    """257 live sequences need nine node blocks: the call falls back to one launch per step."""
+    """257 live sequences need seventeen node blocks of 16, one more than a launch holds: the call falls back to
+    one launch per step."""
     import paper_2305_10611_amd as A
     w = gen.lstm_workload(257, 1, 6, 128, 32, seed=71, bias_scale=0.2)
     ctx.acrobat_set_profiling(True)
@@ -507,7 +509,8 @@ def test_birnn_degenerate(ctx, P):
 
 
 @pytest.mark.parametrize("H,D,n_seq,lo,hi", [(128, 32, 5, 1, 9), (128, 64, 33, 0, 40), (256, 128, 256, 1, 30), (256, 64, 17, 2, 2),
-                                             (512, 64, 70, 0, 25), (512, 512, 64, 5, 35), (512, 32, 16, 40, 40)])
+                                             (512, 64, 70, 0, 25), (512, 512, 64, 5, 35), (512, 32, 16, 40, 40),
+                                             (512, 64, 256, 1, 12)])
 def test_birnn_both_recurrences_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
     """Shapes the persistent kernel takes (H in {128, 256, 512}, at most 256 non-empty sequences): one launch
     for all steps of both directions, same schedule, same tolerances; and against one launch per step."""

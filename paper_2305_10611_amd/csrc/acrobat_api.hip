@@ -758,10 +758,15 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
     int32_t widest = 0;
     for (int32_t lv = 1; lv < s.n_levels; ++lv) widest = std::max(widest, s.level_off[lv + 1] - s.level_off[lv]);
     const int32_t widest_limit = d == 64 ? 2048 : 512;  // (a d = 128 node is four times the bytes)
-    const size_t flag_words = (size_t)N * (d == 64 ? 1 : 4);
+    const size_t flag_words = (size_t)N * 4;  // one per workgroup of a node
+    // d = 64: four workgroups per node while the levels are narrow enough for a node's latency to be what counts
+    // (the configuration of 64 trees, widest level 563: 0.097 against 0.100 ms; 16 trees 0.063 against 0.073;
+    // 96 trees, widest level 850: 0.120 against 0.117, 192 trees 0.168 against 0.145 - every workgroup of a node
+    // reads both child matrices whole)
+    const bool quarters = d == 64 && widest <= 640;
     const int df_wgs = ctx->persistent && ctx->mvrnn_variant == 0 && s.n_levels > 2 && widest <= widest_limit &&
                                !stream_is_capturing(stream)
-                           ? mvrnn_dataflow_workgroups(d, n_internal) : 0;
+                           ? mvrnn_dataflow_workgroups(d, n_internal, quarters) : 0;
     if (df_wgs > 0) {
       TRY(reserve_sync(ctx, stream));
       if (flag_words > ctx->node_flags_cap) {
@@ -789,7 +794,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
       a.flags = ctx->d_node_flags; a.epoch = ctx->epoch;
       a.status = ctx->h_status_dev; a.max_polls = ctx->max_polls;
       TRY(timer.begin(ACROBAT_K_MVRNN_PERSISTENT, 1, n_internal));
-      HIP_TRY(ctx, launch_mvrnn_dataflow(a, df_wgs, stream, timer.ev));
+      HIP_TRY(ctx, launch_mvrnn_dataflow(a, df_wgs, quarters, stream, timer.ev));
       TRY(timer.end());
       return timer.finish();
     }

@@ -100,8 +100,8 @@ struct MvrnnLevelArgs {
   const float* vec_tab; const float* mat_tab;
   const float* W; const float* WM;  // [d,2d] each
   float* vec; float* mat;           // arena [rows,d], [rows,d,d]
-  // launch_mvrnn_dataflow only: one word per arena row (four for d = 128), set to `epoch` by the node that owns
-  // the row once its state has been stored; the status word and the bound of every wait as for the other persistent kernels
+  // launch_mvrnn_dataflow only: four words per arena row, word q set to `epoch` by workgroup q of the node that owns
+  // the row once its part of the state has been stored (d = 64 without quarters: one word per row); the status word and the bound of every wait as for the other persistent kernels
   unsigned* flags; unsigned epoch;
   unsigned* status; int32_t max_polls;
 };
@@ -126,12 +126,15 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
                               const LaunchEvents& ev = LaunchEvents());
 
 // All internal levels of an MV-RNN batch in ONE launch: the lists hold every internal node in schedule
-// order; a node waits for its own two children only (a.flags / a.epoch), never for a whole level.  a.flags has one
-// word per arena row for d = 64 and four (one per row quarter of the state) for d = 128.
+// order; a node waits for its own two children only (a.flags / a.epoch), never for a whole level.  `quarters`
+// (d = 64 only; d = 128 always works that way): four workgroups per node, each a quarter of the node's matrix
+// product, for batches of narrow levels, where a node's latency is what counts; otherwise one workgroup per node.
+// a.flags needs four words per arena row (one per workgroup of a node; d = 64 without quarters uses the first
+// word per row of a [rows] array).
 // mvrnn_dataflow_workgroups: how many workgroups such a launch may have so that all are resident at once on the
-// current device (0: not available for this d); launch with exactly that many (d = 64: or fewer).
-int mvrnn_dataflow_workgroups(int32_t d, int32_t n);
-hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, hipStream_t stream,
+// current device (0: not available for this d); launch with exactly that many (d = 64 without quarters: or fewer).
+int mvrnn_dataflow_workgroups(int32_t d, int32_t n, bool quarters);
+hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, bool quarters, hipStream_t stream,
                                  const LaunchEvents& ev = LaunchEvents());
 
 // Copies table rows `token[i]` into arena rows out_rows[i] (vector and matrix), i in [0,n).

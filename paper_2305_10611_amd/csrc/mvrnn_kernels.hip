@@ -321,6 +321,227 @@ __global__ __launch_bounds__(256, 2) void mvrnn_level_kernel(const MvrnnLevelArg
   }
 }
 
+// d = 64, dataflow launches, FOUR workgroups per node.  With one workgroup per node the 64 dependent matrix
+// instructions of a wavefront (1.7 us) are a third of what a node of a narrow level takes, and the narrow levels
+// near the roots are most of a small batch's time.  Here workgroup (node, q) computes the 32 x 32 block of P with
+// rows 32 (q / 2) .. and columns 32 (q % 2) .., and rows 16 q .. 16 q + 15 of p:
+//  * wavefront (kh, kq) takes rows 32 kq .. 32 kq + 31 of child kh (kh = 0: A, kh = 1: B), ALL columns: lane l
+//    holds columns l % 32 and l % 32 + 32 of rows 32 kq + 2 s + l / 32, s < 16.  That is a quarter of the k range of
+//    P = W_M [A ; B]: 16 v_mfma_f32_32x32x2_f32 on the workgroup's column half (0.43 us), the four partial blocks
+//    summed through LDS in ascending wavefront order;
+//  * the same registers give this wavefront's 32 rows of B a or A b (reduce-scatter butterfly over the 32 lanes
+//    of a half wavefront, as in mvrnn_level_kernel), so every workgroup forms the whole [B a ; A b] for itself
+//    and no workgroup waits for another one of its node;
+//  * every workgroup reads both child matrices whole (4 x the requests of the one-workgroup kernel; the four
+//    workgroups of a node are 8 ids apart and share an XCD, so HBM sees them once);
+//  * a node has four flag words, one per workgroup; a parent's workgroups each wait for all eight words of the two
+//    children (as mvrnn_rows_kernel<true> does for d = 128).
+__global__ __launch_bounds__(256, 3) void mvrnn_quarter_kernel(const MvrnnLevelArgs a) {
+  constexpr int kRows = 16;  // rows of p, and of W, per workgroup
+  __shared__ float s_v[2 * kD];  // B a | A b
+  __shared__ __attribute__((aligned(16))) float s_red[4][16 * 64];  // [wavefront][accumulator register][lane]
+  __shared__ __attribute__((aligned(16))) float s_W[kRows * kWld];
+  __shared__ int s_go;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kh = wave >> 1, kq = wave & 1;
+  const int lcol = lane & 31, lhi = lane >> 5;
+  const int q4 = (blockIdx.x >> 3) & 3, mb = q4 >> 1, ch = q4 & 1;
+  int slot = 8 * (blockIdx.x >> 5) + (blockIdx.x & 7);
+  const int nslots = 8 * (gridDim.x >> 5);  // the grid is a multiple of 32 workgroups
+  if (slot >= a.n) return;
+
+  struct RawIdx { int ls, rs, orow; };
+  const int32_t* __restrict__ lsrc = a.lsrc;
+  const int32_t* __restrict__ rsrc = a.rsrc;
+  const int32_t* __restrict__ orows = a.out_rows;
+  auto load_idx = [&](int node) {
+    const int u = __builtin_amdgcn_readfirstlane(node);
+    RawIdx r;
+    r.ls = lsrc[u];
+    r.rs = rsrc[u];
+    r.orow = orows[u];
+    return r;
+  };
+  auto resolve = [&](const RawIdx& i) {
+    const int ms = kh ? i.rs : i.ls, vs = kh ? i.ls : i.rs;
+    NodeRef r;
+    r.mat = ms >= 0 ? a.mat + (size_t)ms * kDD : a.mat_tab + (size_t)(-(ms + 1)) * kDD;
+    r.vec = vs >= 0 ? a.vec + (size_t)vs * kD : a.vec_tab + (size_t)(-(vs + 1)) * kD;
+    r.orow = (size_t)i.orow;
+    return r;
+  };
+  auto load_f = [](const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+  auto load_node = [&](const NodeRef& r, float (&x)[16][2], float (&vv)[2]) {
+    const float* X = r.mat + (32 * kq + lhi) * kD + lcol;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+      x[s][0] = load_f(X + 2 * s * kD);
+      x[s][1] = load_f(X + 2 * s * kD + 32);
+    }
+    vv[0] = load_f(r.vec + lcol);
+    vv[1] = load_f(r.vec + lcol + 32);
+  };
+  auto children_done = [&](const RawIdx& i) {
+    // (all eight words requested before any is looked at: one round trip, not eight)
+    unsigned l[4], r[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      l[q] = i.ls >= 0 ? load_agent(a.flags + 4 * (size_t)i.ls + q) : a.epoch;
+      r[q] = i.rs >= 0 ? load_agent(a.flags + 4 * (size_t)i.rs + q) : a.epoch;
+    }
+    bool ok = true;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) ok = ok && l[q] == a.epoch && r[q] == a.epoch;
+    return ok;
+  };
+
+  float wm[16];  // W_M[32 mb + lcol][64 kh + 32 kq + 2 s + lhi], in registers for the whole launch (loaded below)
+
+  // one node, as in mvrnn_level_kernel<true>: `x`, `vv` hold (or receive, if !have) its operands, `xn`, `vvn` the
+  // next node's if its children are done by the time this node's operands have been consumed
+  auto process = [&](int node, NodeRef& cur, RawIdx& raw, float (&x)[16][2], float (&vv)[2], float (&xn)[16][2],
+                     float (&vvn)[2], RawIdx& cur_raw, bool& have) -> bool {
+    if (tid == 0) {
+      int polls = 0;
+      bool ok = true;
+      if (a.max_polls == 0) {  // test hook: every wait gives up at once, whether or not it would have had to wait
+        raise_status(a.status);
+        ok = false;
+      }
+      while (ok && !children_done(cur_raw)) {
+        if (++polls > a.max_polls) {
+          raise_status(a.status);
+          ok = false;
+          break;
+        }
+        if ((polls & 255) == 0 && status_raised(a.status)) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(1);
+      }
+      s_go = ok ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_go) return false;  // a wait ran out here or elsewhere: drain
+    if (!have) load_node(cur, x, vv);
+    const int next2 = min(node + 2 * nslots, a.n - 1);
+    asm volatile("" : "+v"(raw.ls), "+v"(raw.rs), "+v"(raw.orow));  // (requested a whole iteration ago)
+    const NodeRef nxt = resolve(raw);
+    const RawIdx nxt_raw = raw;
+    raw = load_idx(next2);
+
+    // ---- mat-vec rows 32 kq + 2 i + lhi, i < 16: partial over this lane's two columns, then reduce-scatter
+    // over the 32 lanes of the half wavefront
+    float v[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v[i] = x[i][0] * vv[0] + x[i][1] * vv[1];
+#pragma unroll
+    for (int half = 8, bit = 16; half >= 1; half >>= 1, bit >>= 1) {
+      const bool up = (lcol & bit) != 0;  // upper lanes keep the upper half of the rows
+#pragma unroll
+      for (int i = 0; i < half; ++i) {
+        const float send = up ? v[i] : v[i + half];
+        const float keep = up ? v[i + half] : v[i];
+        v[i] = keep + __shfl_xor(send, bit);
+      }
+    }
+    v[0] += __shfl_xor(v[0], 1);  // lanes 2i, 2i+1 both hold row i's sum now
+    if ((lcol & 1) == 0) s_v[(kh ? 0 : kD) + 2 * (16 * kq + (lcol >> 1)) + lhi] = v[0];
+
+    // ---- P: this wavefront's 16 two-row steps on the workgroup's column half
+    floatx16 acc;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[q] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < 16; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wm[s], ch ? x[s][1] : x[s][0], acc, 0, 0, 0);
+
+    // ---- next node's operands, if its children are done: in flight during the rest of this node
+    const bool have_next = node + nslots < a.n && children_done(nxt_raw);
+    if (have_next) load_node(nxt, xn, vvn);
+
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s_red[wave][q * 64 + lane] = acc[q];
+    __syncthreads();  // s_v and s_red complete
+
+    // ---- p = tanh(W [B a ; A b]), rows 16 q4 .. 16 q4 + 15: 16 threads per row, 8 columns each
+    {
+      const int pr = tid >> 4, part = tid & 15;
+      float t = 0.0f;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const floatx4 wk4 = *reinterpret_cast<const floatx4*>(&s_W[pr * kWld + part * 8 + k * 4]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t += wk4[e] * s_v[part * 8 + k * 4 + e];
+      }
+      t += __shfl_xor(t, 1);
+      t += __shfl_xor(t, 2);
+      t += __shfl_xor(t, 4);
+      t += __shfl_xor(t, 8);
+      if (part == 0) __hip_atomic_store(a.vec + cur.orow * kD + kRows * q4 + pr, fast_tanh(t), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    // ---- accumulator registers 4 wave .. 4 wave + 3 are finished here: rows 32 mb + 8 wave + 4 lhi + (q & 3)
+    {
+      float* P = a.mat + cur.orow * kDD + (size_t)(32 * mb + 8 * wave + 4 * lhi) * kD + 32 * ch + lcol;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int q = 4 * wave + e;
+        const float sum = ((s_red[0][q * 64 + lane] + s_red[1][q * 64 + lane]) + s_red[2][q * 64 + lane]) + s_red[3][q * 64 + lane];
+        __hip_atomic_store(P + e * kD, sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    wait_stores_done();  // this wavefront's part of the node's state has been written through
+    __syncthreads();     // ... and so has every other wavefront's; s_v / s_red are reused by the next node
+    if (tid == 0) __hip_atomic_store(a.flags + 4 * cur.orow + q4, a.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    cur_raw = nxt_raw;
+    have = have_next;
+    cur = nxt;
+    return true;
+  };
+
+  RawIdx raw = load_idx(slot);
+  RawIdx raw_next = load_idx(min(slot + nslots, a.n - 1));
+  // this workgroup's 32 rows of W_M go through s_red (32 x 128 floats) into the operand registers; its 16 rows of W
+  // stay in LDS
+  floatx4 wmst[4], wst[2];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = tid + 256 * k;
+    wmst[k] = *reinterpret_cast<const floatx4*>(a.WM + (size_t)(32 * mb + (i >> 5)) * (2 * kD) + (i & 31) * 4);
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int i = tid + 256 * k;
+    wst[k] = *reinterpret_cast<const floatx4*>(a.W + (size_t)(kRows * q4 + (i >> 5)) * (2 * kD) + (i & 31) * 4);
+  }
+  NodeRef cur = resolve(raw);
+  RawIdx cur_raw = raw;
+  raw = raw_next;
+  float* const stage = &s_red[0][0];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const int i = tid + 256 * k;
+    *reinterpret_cast<floatx4*>(&stage[(i >> 5) * (2 * kD) + (i & 31) * 4]) = wmst[k];
+  }
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int i = tid + 256 * k;
+    *reinterpret_cast<floatx4*>(&s_W[(i >> 5) * kWld + (i & 31) * 4]) = wst[k];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < 16; ++s) wm[s] = stage[lcol * (2 * kD) + 64 * kh + 32 * kq + 2 * s + lhi];
+  __syncthreads();  // s_red is free for the partial blocks
+  float x0[16][2], x1[16][2], vv0[2], vv1[2];
+  bool have = false;  // the first node's operands are requested once its children are known to be done
+  while (true) {
+    if (!process(slot, cur, raw, x0, vv0, x1, vv1, cur_raw, have)) break;
+    slot += nslots;
+    if (slot >= a.n) break;
+    if (!process(slot, cur, raw, x1, vv1, x0, vv0, cur_raw, have)) break;
+    slot += nslots;
+    if (slot >= a.n) break;
+  }
+}
+
 // Streaming variant, any D in {64, 128}: P = W_M [A ; B] with v_mfma_f32_16x16x4_f32.
 // Lane l = 16 r4 + c loads 16 bytes: columns 4c..4c+3 (of a 64-column group) of row 4s + r4 of
 // the stacked child matrices - exactly the B-operand layout of the instruction (k = l/16,
@@ -822,31 +1043,37 @@ hipError_t launch_mvrnn_level(const MvrnnLevelArgs& a, hipStream_t stream, int32
   return hipGetLastError();
 }
 
-int mvrnn_dataflow_workgroups(int32_t d, int32_t n) {
+int mvrnn_dataflow_workgroups(int32_t d, int32_t n, bool quarters) {
   if ((d != 64 && d != 128) || n <= 0) return 0;
   int dev = 0, per_cu = 0, cus = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  if (d == 64) {
+  if (d == 64 && !quarters) {
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_level_kernel<true>, 256, 0) != hipSuccess) return 0;
     const long resident = (long)per_cu * cus;
     return (int)(n < resident ? n : resident);
   }
-  // d = 128: four workgroups per node slot, slots in groups of 8 (see mvrnn_rows_kernel)
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_rows_kernel<true>, 256, 0) != hipSuccess) return 0;
+  // four workgroups per node slot, slots in groups of 8 (see mvrnn_quarter_kernel, mvrnn_rows_kernel)
+  const hipError_t e = d == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_quarter_kernel, 256, 0)
+                               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mvrnn_rows_kernel<true>, 256, 0);
+  if (e != hipSuccess) return 0;
   const long resident_slots = (long)per_cu * cus / 32 * 8;
   const long slots = std::min<long>((n + 7) / 8 * 8, resident_slots);
   return (int)(4 * slots);
 }
 
-hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, hipStream_t stream, const LaunchEvents& ev) {
+hipError_t launch_mvrnn_dataflow(const MvrnnLevelArgs& a, int workgroups, bool quarters, hipStream_t stream, const LaunchEvents& ev) {
   if (a.n <= 0) return hipSuccess;
   if ((a.d != 64 && a.d != 128) || workgroups <= 0 || !a.flags || !a.status) return hipErrorInvalidValue;
+  if (a.d == 64 && !quarters) {
+    launch_with_events(mvrnn_level_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
+    return hipGetLastError();
+  }
+  if (workgroups % 32) return hipErrorInvalidValue;
   if (a.d == 128) {
-    if (workgroups % 32) return hipErrorInvalidValue;
     launch_with_events(mvrnn_rows_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
   } else {
-    launch_with_events(mvrnn_level_kernel<true>, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
+    launch_with_events(mvrnn_quarter_kernel, dim3((unsigned)workgroups), dim3(256), 0, stream, ev.start, ev.stop, a);
   }
   return hipGetLastError();
 }

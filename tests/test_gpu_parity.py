@@ -229,10 +229,11 @@ def test_mvrnn_streaming_variant(P, d, trees):
 @pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("trees,lo,hi,seed", [(1, 2, 2, 50), (5, 1, 9, 51), (64, 10, 40, 52), (700, 1, 12, 53), (3, 60, 90, 54)])
 def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed, d):
-    """Every internal level in one launch, a node waiting for its own two children only (a flag per node; four
-    per node for d = 128, whose nodes are written by four workgroups).  Same schedule, same tolerances;
-    bit-identical to one launch per level (a node's arithmetic is the same code).  Batches whose widest internal
-    level exceeds 2 048 (d = 64) or 512 (d = 128) nodes keep one launch per level."""
+    """Every internal level in one launch, a node waiting for its own two children only (four flags per node, one
+    per workgroup that writes a part of its state).  Same schedule, same tolerances; at d = 128 bit-identical to one
+    launch per level (a node's arithmetic is the same code), at d = 64 equal within the tolerances (the single launch
+    cuts a node's contraction into four parts instead of two).  Batches whose widest internal level exceeds 2 048
+    (d = 64) or 512 (d = 128) nodes keep one launch per level."""
     import paper_2305_10611_amd as A
     w = gen.mvrnn_workload(trees, lo, hi, d, seed=seed)
     ctx.acrobat_set_profiling(True)
@@ -258,15 +259,22 @@ def test_mvrnn_all_levels_in_one_launch(ctx, P, trees, lo, hi, seed, d):
         vec1, mat1 = P.run_mvrnn(ctx, w, copy_leaves=0)
     finally:
         ctx.acrobat_set_persistent(True)
-    assert np.array_equal(vec1[internal], vec[internal]) and np.array_equal(mat1[internal], mat[internal])
+    if d == 128:
+        assert np.array_equal(vec1[internal], vec[internal]) and np.array_equal(mat1[internal], mat[internal])
+    else:
+        P.assert_close(vec1[internal], ov[internal], "vec, one launch per level")
+        P.assert_close(mat1[internal], om[internal], "mat, one launch per level")
+        P.assert_close(vec[internal], vec1[internal].astype(np.float64), "vec, one launch vs one launch per level")
+        P.assert_close(mat[internal], mat1[internal].astype(np.float64), "mat, one launch vs one launch per level")
 
 
-@pytest.mark.parametrize("d", [64, 128])
-def test_mvrnn_persistent_wait_that_runs_out_is_reported(P, d):
+@pytest.mark.parametrize("d,trees", [(64, 40), (64, 200), (128, 40)])
+def test_mvrnn_persistent_wait_that_runs_out_is_reported(P, d, trees):
     """As for the recurrence: with no polls allowed, a parent whose child is not finished yet gives up, the grid
-    drains, the kernel ends normally and the condition is reported once."""
+    drains, the kernel ends normally and the condition is reported once.  (d = 64: 40 trees run four workgroups per
+    node, 200 trees - a widest level of more than 640 nodes - one.)"""
     import paper_2305_10611_amd as A
-    w = gen.mvrnn_workload(40, 20, 40, d, seed=55)
+    w = gen.mvrnn_workload(trees, 20, 40, d, seed=55)
     c = A.Context(0)
     try:
         assert c.acrobat_set_persistent(True, 0) == A.OK
@@ -1077,8 +1085,12 @@ def test_generic_runtime_mvrnn_program(ctx, P, d):
     P.assert_close(vec.cpu().numpy()[internal], ov[internal], "vec")
     P.assert_close(mat.cpu().numpy()[internal], om[internal], "mat")
     assert torch.isnan(vec[torch.from_numpy(~internal).cuda()]).all()  # leaves are read in place, never copied
-    # same kernels, same batches (one per height) as the specialised entry point: the same bits
-    sv, sm = P.run_mvrnn(ctx, w, copy_leaves=0)
+    # same kernels, same batches (one per height) as the specialised entry point with one launch per level: the same bits
+    ctx.acrobat_set_persistent(False)
+    try:
+        sv, sm = P.run_mvrnn(ctx, w, copy_leaves=0)
+    finally:
+        ctx.acrobat_set_persistent(True)
     assert np.array_equal(vec.cpu().numpy()[internal], sv[internal]) and np.array_equal(mat.cpu().numpy()[internal], sm[internal])
     boff, order, bops = g.acrobat_dfg_schedule()
     level_off, _ = ctx.acrobat_last_schedule()

@@ -40,7 +40,7 @@ MEASURED_TRAFFIC = {  # (workload, dominant kernel) -> (bytes per launch, summar
     ("treelstm_h256_8x20", "kind=2 tile=6"): (3.64e6, "profiles/treelstm_h256_small_configs.md (stepwise kernel on every level)", "b76ed52"),
     ("treelstm_h256_64", "kind=2 tile=6"): (9.3e6, "profiles/treelstm_h256_small_configs.md", "e1d1bbb"),
     ("treelstm_h512_256", "kind=2 tile=64"): (80.0e6, "profiles/treelstm_h512_256_cell_level_kernel.md", "90fe6c3"),
-    ("mvrnn_d64_64", "kind=14 tile=0"): (87.6e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md", "03fef4c"),
+    ("mvrnn_d64_64", "kind=14 tile=0"): (81.6e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md", "0f6c915"),
     ("mvrnn_d64_64", "kind=3 tile=1"): (6.9e6, "profiles/mvrnn_d64_64_mvrnn_level_kernel.md (one launch per level)", "b76ed52"),
     ("lstm_h512_256", "kind=13 tile=16"): (227.9e6, "profiles/lstm_h512_256_cell_kernels.md", "2065830"),
     ("lstm_h512_256", "kind=6 tile=6"): (12.3e6, "profiles/lstm_h512_256_cell_kernels.md (one launch per step)", "138cebb"),

@@ -1,5 +1,6 @@
-// MV-RNN level kernels for gfx950 (d = 64: register-resident kernel, one workgroup per node; d = 128:
-// four workgroups per node; d = 64 or 128: streaming kernel, kept as a tuning alternative).
+// MV-RNN level kernels for gfx950 (d = 64: register-resident kernel, one workgroup per node, and for single
+// launches over narrow levels a kernel with four workgroups per node; d = 128: four workgroups per node; d = 64 or
+// 128: streaming kernel, kept as a tuning alternative).
 //
 // Per node with left child (a, A) and right child (b, B):
 //   p = tanh(W [B a ; A b]),   P = W_M [A ; B]          (W, W_M: [64,128])

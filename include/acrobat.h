@@ -186,7 +186,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
  * persistent launches of the context give up at their first long wait too.
  * The same switch covers acrobat_birnn_forward (H in {128, 256, 512}, at most 256 non-empty sequences, every
  * workgroup resident at once): both recurrences then run in one launch, blocks of 16 sequences per direction,
- * H / 64 workgroups per block exchanging h after every step in the same way.
+ * H / 16 workgroups per block exchanging h after every step in the same way.
  * It also covers acrobat_mvrnn_forward (d == 64 up to a widest internal level of 2 048 nodes, d == 128 up to 512):
  * all internal levels then run in ONE launch in which
  * a node waits for its own two children only (flag words per node, polled with the same bound) instead of a

@@ -44,9 +44,10 @@ hipError_t launch_lstm_persistent(const LstmPersistentArgs& a, hipStream_t strea
 
 // The two recurrences of a bidirectional RNN (single gate: h_t = sigmoid(W_h h_prev + xp_t)) in one launch.
 // Sequences are dealt to blocks of 16 slots; block 2 i + dir runs direction dir (0 forward, 1 backward) of the
-// i-th group of sequences.  Workgroup (block, column block cb) keeps the 64 rows of that direction's W_h that
-// belong to hidden units 64 cb .. 64 cb + 63 in registers (wavefront w: units 64 cb + 16 w ..) and exchanges
-// h with the other H / 64 workgroups of its block after every step, exactly as the LSTM kernel does.
+// i-th group of sequences.  Workgroup (block, column block cb) keeps the 16 rows of that direction's W_h that
+// belong to hidden units 16 cb .. 16 cb + 15 in registers (wavefront w: columns w H/4 .. of those rows, a quarter
+// of the contraction) and exchanges h with the other H / 16 workgroups of its block after every step, exactly as
+// the LSTM kernel does.
 constexpr int kRnnSlots = 16;
 constexpr int kRnnMaxBlocks = 32;
 struct RnnPersistentArgs {

@@ -182,17 +182,19 @@ def main():
         names = ("store+wg_barrier", "announce", "wait", "acquire+wg_barrier", "load")
         for groups, gsize in ((8, 32), (8, 8), (1, 256), (1, 32)):
             for same_xcd in (1, 0):
-                for style in (0, 1, 2):
+                for style in (0, 1, 2, 3):
                     if style == 2 and gsize > 32:
                         continue
+                    rounds = 200 if style == 3 else 2000  # (style 3 keeps every round's payload)
                     for store, load in ((0, 0), (512, 16384)):
                         load = min(load, gsize * store // 1024 * 1024)
-                        rc, us, ph = ctx.acrobat_sync_probe(groups, gsize, 2000, same_xcd, style, 1, store, load)
+                        rc, us, ph = ctx.acrobat_sync_probe(groups, gsize, rounds, same_xcd, style, 1, store, load)
                         ctx.check(rc)
                         print(json.dumps({"sync_probe": {"groups": groups, "group_size": gsize, "same_xcd": same_xcd,
-                                                         "style": ("counter+fences", "counter", "flag lines")[style],
+                                                         "style": ("counter+fences", "counter", "flag lines", "counter, write-once payload read with plain loads")[style],
                                                          "store_bytes": 4 * store, "load_bytes": 4 * load,
                                                          "us_per_round": round(us, 2),
+                                                         "stale_elements": int(ph[5]),
                                                          "phase_us": {k: round(v, 2) for k, v in zip(names, ph)}}}), flush=True)
         ctx.close()
         return

@@ -207,10 +207,18 @@ int acrobat_device_status(acrobat_ctx* ctx);
  * arrival and acquire after the wait (the fences write back / invalidate the XCD's L2), plain loads;
  * write_through != 0 then stores the payload with agent-scope atomic stores.  style 1: the same counter
  * without fences - write-through stores completed before the arrival, agent-scope loads.  style 2: style 1
- * with a flag line per consumer instead of the counter (group_size <= 32).  The persistent recurrence
- * kernel uses style 1.  Outputs (host): *us_per_round = kernel time / rounds; phase_us[5] = mean over
- * workgroups and rounds of the time spent in payload stores + workgroup barrier, announcing, waiting,
- * acquire + workgroup barrier, payload loads (including the completion of the acquire's invalidate).
+ * with a flag line per consumer instead of the counter (group_size <= 32).  style 3: style 1 with payload
+ * addresses of its own for every round (rounds x workgroups x store_floats x 4 bytes, at most 1 GiB) and PLAIN
+ * payload loads: data that is written once per launch, written through, and only read after it has been
+ * announced has never been in a cache on the reader's side, so a plain load cannot find a stale copy of it and
+ * may be served by the L2 of the reader's XCD (the recurrence kernels' exchanged rows are of that kind; an
+ * element that does turn out stale is counted, see below).
+ * The persistent recurrence kernel uses style 1.  Outputs (host): *us_per_round = kernel time /
+ * rounds; phase_us[6]: [0..4] = mean over workgroups and rounds of the time spent in payload stores + workgroup
+ * barrier, announcing, waiting, acquire + workgroup barrier, payload loads (including the completion of the
+ * acquire's invalidate); [5] = style 3 only: number of payload elements that were read and did not hold the
+ * value stored in that round (0 if the reasoning above holds; store_floats must then be a power of two, and the
+ * load time of style 3 includes this check).
  * Allocates its buffers per call and synchronises the stream. */
 int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int32_t rounds, int32_t same_xcd,
                        int32_t style, int32_t write_through, int32_t store_floats, int32_t load_floats,

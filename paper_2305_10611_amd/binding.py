@@ -415,8 +415,8 @@ class Context:
 
     def acrobat_sync_probe(self, groups, group_size, rounds, same_xcd, style, write_through, store_floats, load_floats,
                            stream=0):
-        """-> (rc, microseconds per round, [5 phase times in microseconds])"""
-        us, phases = C.c_double(0.0), (C.c_double * 5)()
+        """-> (rc, microseconds per round, [5 phase times in microseconds, number of stale payload elements read])"""
+        us, phases = C.c_double(0.0), (C.c_double * 6)()
         rc = lib.acrobat_sync_probe(self._h, groups, group_size, rounds, int(bool(same_xcd)), style, int(bool(write_through)),
                                     store_floats, load_floats, C.byref(us), phases, stream)
         return rc, us.value, list(phases)

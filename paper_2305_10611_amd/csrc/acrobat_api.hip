@@ -1444,11 +1444,13 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
     if (!us_per_round || !phase_us) return fail(ctx, ACROBAT_EINVAL, "null output pointer");
     if (groups < 1 || groups > kPersistMaxBlocks || group_size < 1 || groups * group_size > 256 || rounds < 1 || rounds > 100000)
       return fail(ctx, ACROBAT_EINVAL, "groups in 1..8, at most 256 workgroups, rounds in 1..100000");
-    if (style < 0 || style > 2 || (style == 2 && group_size > kPersistMaxColBlocks))
-      return fail(ctx, ACROBAT_EINVAL, "style in 0..2; flag lines (style 2) hold at most 32 members");
+    if (style < 0 || style > 3 || (style == 2 && group_size > kPersistMaxColBlocks))
+      return fail(ctx, ACROBAT_EINVAL, "style in 0..3; flag lines (style 2) hold at most 32 members");
     if (store_floats < 0 || store_floats > 16384 || store_floats % 256 || load_floats < 0 || load_floats % 1024 ||
         load_floats > group_size * store_floats)
       return fail(ctx, ACROBAT_EINVAL, "payload sizes: store multiple of 256 up to 16384, load multiple of 1024 within the group's stores");
+    if (style == 3 && (store_floats & (store_floats - 1)))
+      return fail(ctx, ACROBAT_EINVAL, "style 3 checks what it reads: store_floats must be a power of two");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     if (stream_is_capturing(stream)) return fail(ctx, ACROBAT_EINVAL, "the probe synchronises: it cannot be captured");
     int cus = 0;
@@ -1456,14 +1458,19 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
     if (groups * group_size > cus) return fail(ctx, ACROBAT_EINVAL, "more workgroups than compute units: they would not all be resident");
     TRY(reserve_sync(ctx, stream));
     const int n_wg = groups * group_size;
-    const size_t payload_floats = 2 * (size_t)n_wg * (size_t)std::max(store_floats, 1);
+    // two generations of payload, used in turn; style 3: one per round
+    const size_t payload_floats = (style == 3 ? (size_t)rounds : 2) * (size_t)n_wg * (size_t)std::max(store_floats, 1);
+    if (payload_floats * sizeof(float) > ((size_t)1 << 30))
+      return fail(ctx, ACROBAT_EINVAL, "style 3 keeps every round's payload: rounds x workgroups x store_floats x 4 bytes must not exceed 1 GiB");
     float* payload = nullptr;
     unsigned long long* ticks = nullptr;
+    unsigned* stale = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     int rc = ACROBAT_OK;
     auto cleanup = [&]() {
       if (payload) (void)hipFree(payload);
       if (ticks) (void)hipFree(ticks);
+      if (stale) (void)hipFree(stale);
       if (e0) (void)hipEventDestroy(e0);
       if (e1) (void)hipEventDestroy(e1);
     };
@@ -1474,6 +1481,8 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
   } while (0)
     PROBE_TRY(hipMalloc(reinterpret_cast<void**>(&payload), payload_floats * sizeof(float)));
     PROBE_TRY(hipMalloc(reinterpret_cast<void**>(&ticks), (size_t)n_wg * 5 * sizeof(unsigned long long)));
+    PROBE_TRY(hipMalloc(reinterpret_cast<void**>(&stale), sizeof(unsigned)));
+    PROBE_TRY(hipMemsetAsync(stale, 0, sizeof(unsigned), stream));
     PROBE_TRY(hipEventCreate(&e0));
     PROBE_TRY(hipEventCreate(&e1));
     SyncProbeArgs a{};
@@ -1483,6 +1492,7 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
     a.payload = payload; a.flags = ctx->d_sync; a.counters = ctx->d_sync + kPersistFlagWords;
     a.status = ctx->h_status_dev; a.max_polls = ctx->max_polls;
     a.ticks = ticks;
+    a.stale = stale;
     LaunchEvents ev;
     ev.start = e0; ev.stop = e1;
     PROBE_TRY(launch_fill_u32(ctx->d_sync, 0u, kSyncWords, stream));
@@ -1492,6 +1502,8 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
     PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));
     std::vector<unsigned long long> host((size_t)n_wg * 5);
     PROBE_TRY(hipMemcpy(host.data(), ticks, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    unsigned n_stale = 0;
+    PROBE_TRY(hipMemcpy(&n_stale, stale, sizeof(unsigned), hipMemcpyDeviceToHost));
 #undef PROBE_TRY
     cleanup();
     *us_per_round = (double)ms * 1e3 / rounds;
@@ -1500,6 +1512,7 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
       for (int w = 0; w < n_wg; ++w) sum += (double)host[(size_t)w * 5 + i];
       phase_us[i] = sum / n_wg / rounds * 0.01;
     }
+    phase_us[5] = (double)n_stale;
     return acrobat_device_status(ctx);
   } catch (const std::bad_alloc&) {
     return fail(ctx, ACROBAT_ENOMEM, "host allocation failed");

@@ -78,10 +78,11 @@ hipError_t launch_fill_u32(unsigned* p, unsigned value, int n, hipStream_t strea
 struct SyncProbeArgs {
   int32_t groups, group_size, rounds;
   int32_t same_xcd;       // 1: group = workgroup id % groups, 0: group = workgroup id / group_size
-  int32_t style;          // 0: counter + release / acquire fences, 1: counter without fences, 2: flag lines without fences
+  int32_t style;          // 0: counter + release / acquire fences, 1: counter without fences, 2: flag lines without fences,
+                          // 3: style 1 with payload addresses of its own for every round and plain payload loads
   int32_t write_through;  // style 0 only: 1 = payload stores are agent-scope atomic stores (write through), 0 = plain stores
   int32_t store_floats, load_floats;  // payload per workgroup and round (multiples of 256, <= 16384)
-  float* payload;         // [groups * group_size * store_floats * 2] (two generations)
+  float* payload;         // [groups * group_size * store_floats * 2] (two generations; style 3: * rounds, one per round)
   unsigned* counters;     // [groups * kPersistCounterStride], zero at launch
   unsigned* flags;        // [kPersistFlagWords], zero at launch
   unsigned* status;
@@ -90,6 +91,7 @@ struct SyncProbeArgs {
   // [0] payload stores + workgroup barrier, [1] release + arrival, [2] polling, [3] acquire + workgroup barrier,
   // [4] payload loads
   unsigned long long* ticks;  // [groups * group_size * 5]
+  unsigned* stale;            // [1] zero at launch: payload elements read that did not hold the round's value
 };
 hipError_t launch_sync_probe(const SyncProbeArgs& a, hipStream_t stream, const LaunchEvents& ev = LaunchEvents());
 

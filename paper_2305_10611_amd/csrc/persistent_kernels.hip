@@ -334,10 +334,15 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
   const __amdgpu_buffer_rsrc_t rsrc =
       agent_buffer(a.payload, (unsigned)(2 * gen_floats * sizeof(float)));
   const bool fenced = a.style == 0;
+  // style 3: every round has payload addresses of its own, written once (write-through) and read with PLAIN loads
+  // after the arrival - a line that has never been read cannot be stale in any cache on the way
+  const bool once = a.style == 3;
   unsigned long long ticks[5] = {0, 0, 0, 0, 0};
+  unsigned stale = 0;  // payload elements that did not hold this round's value
   float sink = 0.0f;
   for (int r = 0; r < a.rounds; ++r) {
-    float* mine = a.payload + (size_t)(r & 1) * gen_floats + ((size_t)group * a.group_size + member) * a.store_floats;
+    const size_t gen = once ? (size_t)r : (size_t)(r & 1);
+    float* mine = a.payload + gen * gen_floats + ((size_t)group * a.group_size + member) * a.store_floats;
     const unsigned long long t0 = wall_clock64();
     for (int i = tid; i < a.store_floats; i += kThreads) {
       const float v = (float)(r + i);
@@ -361,7 +366,8 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
       else __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (fenced) wait_stores_done();  // so that the cost of the release is seen apart from the wait
       t2 = wall_clock64();
-      s_go = wait_for(counter, (unsigned)(a.group_size * (r + 1)), a.status, a.max_polls) ? 1 : 0;
+      const unsigned target = (unsigned)(a.group_size * (r + 1));
+      s_go = wait_for(counter, target, a.status, a.max_polls) ? 1 : 0;
       t3 = wall_clock64();
     }
     __syncthreads();
@@ -369,19 +375,42 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
     if (fenced) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     const unsigned long long t4 = wall_clock64();
     // read what the group stored this round (its first load_floats floats), all loads in flight together
-    const size_t base = (size_t)(r & 1) * gen_floats + (size_t)group * a.group_size * a.store_floats;
-    for (int i0 = 0; i0 < a.load_floats; i0 += kThreads * 4 * 16) {
-      floatx4 v[16];
+    const size_t base = gen * gen_floats + (size_t)group * a.group_size * a.store_floats;
+    if (!once) {
+      for (int i0 = 0; i0 < a.load_floats; i0 += kThreads * 4 * 16) {
+        floatx4 v[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) {
-        const int i = i0 + (u * kThreads + tid) * 4;
-        const bool in = i < a.load_floats;
-        v[u] = floatx4{0, 0, 0, 0};
-        if (in && fenced) v[u] = *reinterpret_cast<const floatx4*>(a.payload + base + i);
-        if (in && !fenced) v[u] = load_agent_f4(rsrc, (unsigned)((base + i) * sizeof(float)));
+        for (int u = 0; u < 16; ++u) {
+          const int i = i0 + (u * kThreads + tid) * 4;
+          const bool in = i < a.load_floats;
+          v[u] = floatx4{0, 0, 0, 0};
+          if (in && fenced) v[u] = *reinterpret_cast<const floatx4*>(a.payload + base + i);
+          if (in && !fenced) v[u] = load_agent_f4(rsrc, (unsigned)((base + i) * sizeof(float)));
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sink += v[u][0] + v[u][1] + v[u][2] + v[u][3];
       }
+    } else {
+      for (int i0 = 0; i0 < a.load_floats; i0 += kThreads * 4 * 16) {
+        floatx4 v[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) sink += v[u][0] + v[u][1] + v[u][2] + v[u][3];
+        for (int u = 0; u < 16; ++u) {
+          const int i = i0 + (u * kThreads + tid) * 4;
+          v[u] = floatx4{0, 0, 0, 0};
+          if (i < a.load_floats) v[u] = *reinterpret_cast<const floatx4*>(a.payload + base + i);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) sink += v[u][0] + v[u][1] + v[u][2] + v[u][3];
+        // did every element hold what its owner stored in this round?  (part of this style's load time)
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int i = i0 + (u * kThreads + tid) * 4;
+          if (i < a.load_floats) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) stale += v[u][e] != (float)(r + ((i + e) & (a.store_floats - 1)));
+          }
+        }
+      }
     }
     if (sink == 12345.678f) a.payload[0] = sink;  // keeps the loads
     wait_stores_done();       // the acquire's invalidate, if any, has completed too
@@ -392,6 +421,7 @@ __global__ __launch_bounds__(kThreads) void sync_probe_kernel(const SyncProbeArg
   }
   if (tid == 0)
     for (int i = 0; i < 5; ++i) a.ticks[(size_t)wg * 5 + i] = ticks[i];
+  if (stale) atomicAdd(a.stale, stale);
 }
 
 template <int H>

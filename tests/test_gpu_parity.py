@@ -411,7 +411,13 @@ def test_sync_probe_reports_sane_times(ctx):
     for same_xcd, style, wt in ((1, 0, 1), (0, 0, 0), (1, 1, 0), (1, 2, 0), (0, 2, 0)):
         rc, us, phases = ctx.acrobat_sync_probe(8, 8, 200, same_xcd, style, wt, 512, 4096)
         assert rc == A.OK, ctx.acrobat_last_error()
-        assert 0.2 < us < 500.0 and all(0.0 <= p < 500.0 for p in phases) and sum(phases) <= us * 1.5
+        assert 0.2 < us < 500.0 and all(0.0 <= p < 500.0 for p in phases[:5]) and sum(phases[:5]) <= us * 1.5
+    # write-once payload read with plain loads: no element may be stale, wherever the group's workgroups run
+    for same_xcd in (1, 0):
+        rc, us, phases = ctx.acrobat_sync_probe(8, 8, 200, same_xcd, 3, 1, 512, 4096)
+        assert rc == A.OK, ctx.acrobat_last_error()
+        assert phases[5] == 0.0 and 0.2 < us < 500.0
+    assert ctx.acrobat_sync_probe(8, 32, 100000, 1, 3, 1, 16384, 1024)[0] == A.EINVAL  # every round's payload: over 1 GiB
     assert ctx.acrobat_sync_probe(9, 8, 10, 1, 0, 1, 512, 1024)[0] == A.EINVAL
     assert ctx.acrobat_sync_probe(1, 64, 10, 1, 2, 1, 512, 1024)[0] == A.EINVAL  # a flag line holds 32 members
 

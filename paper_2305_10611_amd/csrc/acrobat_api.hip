@@ -95,6 +95,7 @@ struct acrobat_ctx {
   int32_t max_polls = 1 << 18;      // bound of every wait inside a persistent kernel
   unsigned* d_sync = nullptr;       // [kPersistSyncWords]: the probe's flag lines | arrival counters | status
   unsigned* h_status = nullptr;     // pinned host word that a kernel raises when one of its waits runs out
+  bool sync_dirty = false;          // the arrival counters in d_sync may be non-zero: clear them before the next persistent recurrence
   unsigned* h_status_dev = nullptr; // the same word's address on the device side
   unsigned* d_node_flags = nullptr; // one word per arena row: the epoch of the call that last finished the node
   size_t node_flags_cap = 0;
@@ -224,6 +225,17 @@ int reserve_sync(acrobat_ctx* ctx, hipStream_t stream) {
   HIP_TRY(ctx, hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), sizeof(unsigned), hipHostMallocDefault));
   *ctx->h_status = 0;
   HIP_TRY(ctx, hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->h_status_dev), ctx->h_status, 0));
+  return ACROBAT_OK;
+}
+
+// The persistent recurrences count their workgroups in and out in the first words of d_sync and leave them zero
+// (leave_block): a clearing launch is only needed after something else has used the words - the probe, or a
+// launch whose wait ran out.  (While that condition has not been read with acrobat_device_status, launches give
+// up at their first long wait anyway.)
+int clean_counters(acrobat_ctx* ctx, hipStream_t stream) {
+  if (!ctx->sync_dirty) return ACROBAT_OK;
+  HIP_TRY(ctx, launch_fill_u32(ctx->d_sync, 0u, kRnnMaxBlocks * kPersistCounterStride, stream));
+  if (!stream_is_capturing(stream)) ctx->sync_dirty = false;  // (a captured clearing launch has not run yet)
   return ACROBAT_OK;
 }
 
@@ -892,7 +904,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       }
       TRY(upload_indices(ctx, 2 * n_slots, stream));
       LaunchTimer timer{ctx, stream};
-      HIP_TRY(ctx, launch_fill_u32(ctx->d_sync, 0u, kLstmMaxBlocks * kPersistCounterStride, stream));
+      TRY(clean_counters(ctx, stream));
       TRY(input_transform(timer));
       LstmPersistentArgs pa{};
       pa.n_blocks = n_blocks; pa.H = H;
@@ -1025,7 +1037,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
         row0 += len[q];
       }
       TRY(upload_indices(ctx, 2 * n_slots, stream));
-      HIP_TRY(ctx, launch_fill_u32(ctx->d_sync, 0u, kRnnMaxBlocks * kPersistCounterStride, stream));
+      TRY(clean_counters(ctx, stream));
     } else {
       // per direction, by position in the direction's step lists: row written | row of the previous
       // step of that direction (step 0 gathers row 0 of the initial-state vector)
@@ -1433,6 +1445,7 @@ int acrobat_device_status(acrobat_ctx* ctx) {
   if (!ctx) return ACROBAT_EINVAL;
   if (!ctx->h_status || *ctx->h_status == 0) return ACROBAT_OK;
   *ctx->h_status = 0;
+  ctx->sync_dirty = true;  // a launch that gave up leaves its counters as they were
   return fail(ctx, ACROBAT_ETIMEOUT, "a workgroup of a persistent launch gave up waiting; the launch's outputs are incomplete");
 }
 
@@ -1495,6 +1508,7 @@ int acrobat_sync_probe(acrobat_ctx* ctx, int32_t groups, int32_t group_size, int
     a.stale = stale;
     LaunchEvents ev;
     ev.start = e0; ev.stop = e1;
+    ctx->sync_dirty = true;  // the probe's counters end wherever its rounds took them
     PROBE_TRY(launch_fill_u32(ctx->d_sync, 0u, kSyncWords, stream));
     PROBE_TRY(launch_sync_probe(a, stream, ev));
     PROBE_TRY(hipStreamSynchronize(stream));

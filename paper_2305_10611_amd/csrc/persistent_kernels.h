@@ -32,7 +32,8 @@ struct LstmPersistentArgs {
   const float* xp;           // [rows, 4H] hoisted input transform (bias included)
   float* h; float* c;        // arena [rows, H], row = slot_row0 + t
   uint32_t h_bytes;          // size of h in bytes (< 2^32: the exchanged rows are read through a buffer resource)
-  unsigned* counters;        // [n_blocks * kPersistCounterStride]: arrivals of a block's workgroups; zero at launch
+  unsigned* counters;        // [n_blocks * kPersistCounterStride]: arrivals of a block's workgroups, and behind each the
+                             // workgroups that have left; zero at launch, and zero again when the launch has completed
   unsigned* status;          // set to 1 by a workgroup whose wait ran out (the kernel then drains and ends)
   int32_t max_polls;         // bound of every wait, in polls of the counter
 };
@@ -60,7 +61,7 @@ struct RnnPersistentArgs {
   const float* h_init[2];    // [H] state before the first step
   float* h[2];               // [rows, H]; forward step t of a sequence writes row row0 + t, backward row0 + len - 1 - t
   uint32_t h_bytes;          // size of one h array in bytes (< 2^32)
-  unsigned* counters;        // [kRnnMaxBlocks * kPersistCounterStride], zero at launch
+  unsigned* counters;        // [kRnnMaxBlocks * kPersistCounterStride], zero at launch and again when the launch has completed
   unsigned* status;
   int32_t max_polls;
 };

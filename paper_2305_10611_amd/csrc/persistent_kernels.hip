@@ -79,6 +79,17 @@ __device__ __forceinline__ bool wait_for(const unsigned* counter, unsigned targe
   return true;
 }
 
+// A block's arrival counter goes back to zero for the next launch without a clearing launch in between: every
+// workgroup of the block counts itself out in the word behind the counter when it has left its loop (it no longer
+// looks at the counter then), and the last one to do so clears both words.  (After a wait that ran out the words
+// may be left in any state: the host clears them before the next launch once it has seen the status.)
+__device__ __forceinline__ void leave_block(unsigned* counter, unsigned members) {
+  if (__hip_atomic_fetch_add(counter + 1, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == members - 1) {
+    __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(counter + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
 __global__ void fill_u32_kernel(unsigned* p, unsigned value, int n) {
   for (int i = threadIdx.x + blockIdx.x * blockDim.x; i < n; i += blockDim.x * gridDim.x) p[i] = value;
 }
@@ -211,6 +222,7 @@ __global__ __launch_bounds__(kThreads, 2) void lstm_persistent_kernel(const Lstm
       if (tid == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
+  if (tid == 0) leave_block(counter, CB);
 }
 
 // ---- bidirectional RNN recurrence ------------------------------------------------------------------------
@@ -313,6 +325,7 @@ __global__ __launch_bounds__(kThreads, 2) void rnn_persistent_kernel(const RnnPe
       if (tid == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
+  if (tid == 0) leave_block(counter, CB);
 }
 
 // ---- probe ---------------------------------------------------------------------------------------------

@@ -349,7 +349,7 @@ def test_lstm_whole_recurrence_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
     oh, oc = oracle.varlen_lstm(w, nthreads=NT)
     P.assert_close(h, oh, "h")
     P.assert_close(c, oc, "c")
-    h2, c2 = P.run_lstm(ctx, w)  # again, without per-launch events: the counters are cleared by every call
+    h2, c2 = P.run_lstm(ctx, w)  # again, without per-launch events: the launch before left its counters at zero
     assert np.array_equal(h, h2) and np.array_equal(c, c2)
     ctx.acrobat_set_persistent(False)
     try:
@@ -540,7 +540,7 @@ def test_birnn_both_recurrences_in_one_launch(ctx, P, H, D, n_seq, lo, hi):
     assert ctx.acrobat_device_status() == A.OK
     ref = oracle.birnn(w, nthreads=NT)
     check_birnn(P, g, ref, "one launch")
-    g2 = P.run_birnn(ctx, w)  # again, without per-launch events: the counters are cleared by every call
+    g2 = P.run_birnn(ctx, w)  # again, without per-launch events: the launch before left its counters at zero
     assert all(np.array_equal(a, b) for a, b in zip(g, g2))
     ctx.acrobat_set_persistent(False)
     try:

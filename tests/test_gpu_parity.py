@@ -422,6 +422,27 @@ def test_sync_probe_reports_sane_times(ctx):
     assert ctx.acrobat_sync_probe(1, 64, 10, 1, 2, 1, 512, 1024)[0] == A.EINVAL  # a flag line holds 32 members
 
 
+def test_persistent_recurrence_after_the_probe_has_used_the_counters(ctx, P):
+    """The probe leaves the arrival counters wherever its rounds took them; the next persistent launch must find
+    them cleared (the recurrences otherwise leave them at zero themselves and no clearing launch runs)."""
+    import paper_2305_10611_amd as A
+    rc, _, _ = ctx.acrobat_sync_probe(8, 16, 37, 1, 1, 1, 256, 1024)
+    assert rc == A.OK, ctx.acrobat_last_error()
+    w = gen.lstm_workload(40, 1, 12, 128, 32, seed=123, bias_scale=0.2)
+    for _ in range(3):  # the first call clears, the others rely on the launch before them
+        h, c = P.run_lstm(ctx, w)
+        assert ctx.acrobat_device_status() == A.OK
+        oh, oc = oracle.varlen_lstm(w, nthreads=NT)
+        P.assert_close(h, oh, "h")
+        P.assert_close(c, oc, "c")
+    wb = gen.birnn_workload(40, 1, 12, 128, 32, 4, seed=124, bias_scale=0.2)
+    rc, _, _ = ctx.acrobat_sync_probe(8, 16, 11, 0, 1, 1, 256, 1024)
+    assert rc == A.OK, ctx.acrobat_last_error()
+    for _ in range(2):
+        check_birnn(P, P.run_birnn(ctx, wb), oracle.birnn(wb, nthreads=NT))
+        assert ctx.acrobat_device_status() == A.OK
+
+
 def test_lstm_degenerate(ctx, P):
     w = gen.lstm_workload(4, 1, 3, 32, 32, seed=5)
     w0 = dict(w, len=np.zeros(4, np.int32))

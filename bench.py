@@ -133,9 +133,13 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="per-level table on stderr")
-    ap.add_argument("--two-streams", dest="overlap_streams", action="store_true",
+    ap.add_argument("--two-streams", dest="overlap_streams", action="store_true", default=None,
                     help="also measure, for information, the throughput when consecutive mini-batches alternate "
-                         "between two streams (reported under \"two_stream_throughput\")")
+                         "between two streams (reported under \"two_stream_throughput\"); the default for TreeLSTM "
+                         "workloads, whose kernels never wait for each other - the single launches of the recurrences "
+                         "and of MV-RNN batches want the chip to themselves (include/acrobat.h, acrobat_set_persistent)")
+    ap.add_argument("--no-two-streams", dest="overlap_streams", action="store_false",
+                    help="skip the two-stream measurement")
     ap.add_argument("--ablation", action="store_true",
                     help="TreeLSTM only: also time the forward pass with gather fusion switched off (explicit "
                          "gather launches), reported under \"ablation\"")
@@ -206,6 +210,8 @@ def main():
     else:
         w = make_config(args.config, n_instances=args.instances)
     kind = w["kind"]
+    if args.overlap_streams is None:
+        args.overlap_streams = kind == "treelstm"
     ctx = A.Context(0)
     if args.persistent == "off":
         ctx.acrobat_set_persistent(False)

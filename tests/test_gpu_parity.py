@@ -689,6 +689,35 @@ def test_small_level_kernel_ragged_contraction_and_tiles(P, H, D):
         c.close()
 
 
+def test_two_contexts_on_two_streams_overlap_their_mini_batches(P):
+    """Two contexts, each with a stream of its own, are handed mini-batches in turn without any synchronisation in
+    between (what `bench.py` reports as two_stream_throughput): level launches of one batch overlap those of the
+    other - including levels cut into equal shares, whose parked pieces and tile counters are per context - and
+    every batch still matches the oracle."""
+    import torch
+    import paper_2305_10611_amd as A
+    ws = [gen.treelstm_workload(200, 1, 40, 512, 300, "zipf1.1", seed=900 + i, bias_scale=0.2) for i in range(2)]
+    refs = [oracle.treelstm(w, nthreads=NT) for w in ws]
+    ctxs, streams = [A.Context(0), A.Context(0)], [torch.cuda.Stream(), torch.cuda.Stream()]
+    try:
+        t = [{k: P.dev(w[k]) for k in ("emb", "W_leaf", "b_leaf", "U", "b")} for w in ws]
+        outs = []
+        for rep in range(6):
+            i = rep % 2
+            w, N, H = ws[i], int(ws[i]["tree_off"][-1]), 512
+            h, c = P.nan_filled(N, H), P.nan_filled(N, H)
+            ctxs[i].check(ctxs[i].acrobat_treelstm_forward(w, H, int(w["D"]), int(w["V"]), t[i]["emb"], t[i]["W_leaf"], t[i]["b_leaf"],
+                                                           t[i]["U"], t[i]["b"], h, c, streams[i].cuda_stream))
+            outs.append((i, h, c))
+        torch.cuda.synchronize()
+        for i, h, c in outs:
+            P.assert_close(h.cpu().numpy(), refs[i][0], "h")
+            P.assert_close(c.cpu().numpy(), refs[i][1], "c")
+    finally:
+        for c_ in ctxs:
+            c_.close()
+
+
 # ---------------------------------------------------------------- stream capture
 def test_forward_recorded_into_a_graph_replays_the_eager_result():
     """A captured forward call (index upload + every level launch) replayed several times, with eager work

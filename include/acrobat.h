@@ -22,9 +22,9 @@
  *  - A context must not be used from two threads at once.
  *  - Throughput: the last levels of a mini-batch are few nodes wide and leave most of the GPU idle.  Two contexts,
  *    each fed on a stream of its own with mini-batches in turn, overlap those levels of one batch with the wide
- *    first levels of the next (measured on tree batches: 1.2 to 1.6 times the single-stream throughput).  This
- *    does not extend to the calls that run as ONE launch whose workgroups wait for each other (see
- *    acrobat_set_persistent): two such launches must not share the GPU.
+ *    first levels of the next (measured on tree batches: 1.2 to 1.6 times the single-stream throughput).  The
+ *    calls that run as ONE launch whose workgroups wait for each other (see acrobat_set_persistent) do not
+ *    overlap one another that way: the library lets them take turns.
  *  - Stream capture (hipStreamBeginCapture on the given stream): a forward call may be recorded
  *    into a HIP graph once an uncaptured call of at least the same sizes has run on the context
  *    (a captured call allocates nothing and waits for nothing; otherwise it fails with
@@ -199,7 +199,11 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
  * call is not being captured into a graph (a captured call keeps one launch per level).
  * Nothing else may occupy the GPU's compute units for long while such a launch runs (another stream's
  * kernels delay the workgroups that are not yet resident; the bound turns a too long delay into
- * ACROBAT_ETIMEOUT instead of a hang). */
+ * ACROBAT_ETIMEOUT instead of a hang).  Two launches of this kind must never share the GPU - each could hold
+ * the slots the other's missing workgroups need - so the library orders its own: when one comes from another
+ * stream than the one before it on that GPU (from any context of the process), the new stream first waits for
+ * an event recorded on the earlier one.  This does not cover launches captured into a graph, nor other
+ * processes. */
 int acrobat_set_persistent(acrobat_ctx* ctx, int32_t enabled, int32_t max_polls);
 int acrobat_device_status(acrobat_ctx* ctx);
 

@@ -51,6 +51,48 @@ hipError_t static_scratch_for(int device, void** out) {
 }
 }  // namespace
 
+namespace {
+// One at a time per GPU for the launches whose workgroups wait for each other (the persistent recurrences, the
+// MV-RNN dataflow launches): two of them sharing the compute units could each hold slots the other's missing
+// workgroups need, and both would only end by the bound of their waits.  Launches from one stream are ordered
+// anyway; when such a launch comes from another stream than the one before it (another context's, say), an event
+// recorded on that earlier stream now - behind the earlier launch and whatever followed it - is what the new stream
+// waits for first.  Costs nothing while one stream is in use.  Not applied to a launch that is being captured into
+// a graph (a graph cannot wait for an event outside it): replays of such graphs must not overlap other launches
+// of this kind.
+struct WaitingLaunchGate {
+  std::mutex m;
+  hipEvent_t order = nullptr;
+  hipStream_t last = nullptr;
+  bool any = false;
+};
+WaitingLaunchGate g_gate[kMaxDevices];
+
+hipError_t order_waiting_launch(int device, hipStream_t stream) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  WaitingLaunchGate& g = g_gate[device];
+  std::lock_guard<std::mutex> lock(g.m);
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &st) != hipSuccess) (void)hipGetLastError();
+  if (st != hipStreamCaptureStatusNone) return hipSuccess;
+  if (g.any && g.last != stream) {
+    if (!g.order) {
+      const hipError_t e = hipEventCreateWithFlags(&g.order, hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+    }
+    if (hipEventRecord(g.order, g.last) == hipSuccess) {
+      const hipError_t e = hipStreamWaitEvent(stream, g.order, 0);
+      if (e != hipSuccess) return e;
+    } else {
+      (void)hipGetLastError();  // the earlier stream no longer exists: its work was ordered before its destruction returned
+    }
+  }
+  g.last = stream;
+  g.any = true;
+  return hipSuccess;
+}
+}  // namespace
+
 struct acrobat_ctx {
   int device = 0;
   std::string err;
@@ -806,6 +848,7 @@ int acrobat_mvrnn_forward(acrobat_ctx* ctx, const acrobat_trees* trees, int32_t 
       a.flags = ctx->d_node_flags; a.epoch = ctx->epoch;
       a.status = ctx->h_status_dev; a.max_polls = ctx->max_polls;
       TRY(timer.begin(ACROBAT_K_MVRNN_PERSISTENT, 1, n_internal));
+      HIP_TRY(ctx, order_waiting_launch(ctx->device, stream));
       HIP_TRY(ctx, launch_mvrnn_dataflow(a, df_wgs, quarters, stream, timer.ev));
       TRY(timer.end());
       return timer.finish();
@@ -915,6 +958,7 @@ int acrobat_varlen_lstm_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* 
       pa.max_polls = ctx->max_polls;
       TRY(timer.begin(ACROBAT_K_LSTM_PERSISTENT, 0, R));
       if (timer.tile()) *timer.tile() = 16;
+      HIP_TRY(ctx, order_waiting_launch(ctx->device, stream));
       HIP_TRY(ctx, launch_lstm_persistent(pa, stream, timer.ev));
       TRY(timer.end());
       return timer.finish();
@@ -1090,6 +1134,7 @@ int acrobat_birnn_forward(acrobat_ctx* ctx, int32_t n_seq, const int32_t* len, i
       pa.counters = ctx->d_sync; pa.status = ctx->h_status_dev; pa.max_polls = ctx->max_polls;
       TRY(timer.begin(ACROBAT_K_RNN_PERSISTENT, 0, 2 * R));
       if (timer.tile()) *timer.tile() = 16;
+      HIP_TRY(ctx, order_waiting_launch(ctx->device, stream));
       HIP_TRY(ctx, launch_rnn_persistent(pa, stream, timer.ev));
       TRY(timer.end());
     }

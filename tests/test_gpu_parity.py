@@ -718,6 +718,51 @@ def test_two_contexts_on_two_streams_overlap_their_mini_batches(P):
             c_.close()
 
 
+def test_single_launch_calls_from_two_streams_take_turns(P):
+    """The calls that run as one launch whose workgroups wait for each other (LSTM and BiRNN recurrences, MV-RNN
+    dataflow) must not share the GPU; handed to two contexts on two streams in turn, without synchronisation, the
+    library orders them itself: every result matches the oracle and no wait runs out."""
+    import torch
+    import paper_2305_10611_amd as A
+    wl = gen.lstm_workload(256, 1, 40, 512, 64, seed=31, bias_scale=0.2)
+    wm = gen.mvrnn_workload(48, 10, 30, 64, seed=32)
+    wb = gen.birnn_workload(64, 5, 25, 256, 64, 8, seed=33, bias_scale=0.2)
+    ref_l, ref_m, ref_b = oracle.varlen_lstm(wl, nthreads=NT), oracle.mvrnn(wm, nthreads=NT), oracle.birnn(wb, nthreads=NT)
+    ctxs, streams = [A.Context(0), A.Context(0)], [torch.cuda.Stream(), torch.cuda.Stream()]
+    try:
+        tl = {k: P.dev(wl[k]) for k in ("x", "Wx", "Wh", "b")}
+        tm = {k: P.dev(wm[k]) for k in ("vec_tab", "mat_tab", "W", "WM")}
+        Rl, Nm, dm = int(wl["len"].sum()), int(wm["tree_off"][-1]), 64
+        outs = []
+        for rep in range(8):
+            i = rep % 2
+            c, st = ctxs[i], streams[i].cuda_stream
+            if rep % 4 < 2:
+                h, cc = P.nan_filled(Rl, 512), P.nan_filled(Rl, 512)
+                c.check(c.acrobat_varlen_lstm_forward(wl["len"], 512, 64, tl["x"], tl["Wx"], tl["Wh"], tl["b"], h, cc, st))
+                outs.append(("lstm", h, cc))
+            else:
+                vec, mat = P.nan_filled(Nm, dm), P.nan_filled(Nm, dm, dm)
+                c.check(c.acrobat_mvrnn_forward(wm, dm, int(wm["V"]), tm["vec_tab"], tm["mat_tab"], tm["W"], tm["WM"], vec, mat, 0, st))
+                outs.append(("mvrnn", vec, mat))
+        torch.cuda.synchronize()
+        assert all(c.acrobat_device_status() == A.OK for c in ctxs)
+        internal = wm["left"] >= 0
+        for kind, a, b in outs:
+            if kind == "lstm":
+                P.assert_close(a.cpu().numpy(), ref_l[0], "h")
+                P.assert_close(b.cpu().numpy(), ref_l[1], "c")
+            else:
+                P.assert_close(a.cpu().numpy()[internal], ref_m[0][internal], "vec")
+                P.assert_close(b.cpu().numpy()[internal], ref_m[1][internal], "mat")
+        # (the BiRNN through the ordinary runner, on the default stream, right behind them)
+        check_birnn(P, P.run_birnn(ctxs[0], wb), ref_b)
+        assert ctxs[0].acrobat_device_status() == A.OK
+    finally:
+        for c_ in ctxs:
+            c_.close()
+
+
 # ---------------------------------------------------------------- stream capture
 def test_forward_recorded_into_a_graph_replays_the_eager_result():
     """A captured forward call (index upload + every level launch) replayed several times, with eager work
